@@ -1,0 +1,248 @@
+"""Pins for the oracle's target and draft forwards: library routines (torch CPU float64),
+special cases, and invariances that the method's definition implies."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+import torch
+import torch.nn.functional as F
+
+from oracle import dflash_oracle as O
+from synth import inputs as si
+from tests.helpers import W64, tiny_workload
+
+
+# ---- an independent reference built from torch library routines -------------------------
+def _t(x):
+    return torch.from_numpy(np.asarray(x, dtype=np.float64))
+
+
+def _rope_complex(x, pos, theta):
+    # x [T, H, hd] -> complex rotation of (x_i, x_{i+hd/2})
+    hd = x.shape[-1]
+    z = torch.complex(x[..., : hd // 2], x[..., hd // 2:])
+    freq = theta ** (-torch.arange(0, hd, 2, dtype=torch.float64) / hd)
+    rot = torch.polar(torch.ones(len(pos), hd // 2, dtype=torch.float64), _t(pos)[:, None] * freq[None])
+    z = z * rot[:, None, :]
+    return torch.cat([z.real, z.imag], -1)
+
+
+def torch_layer(W, m, pre, h, pos, causal, extra_kv=None):
+    """One decoder layer on rows h [T, D] that attend to each other (causal or not) and,
+    when given, to extra K/V rows (all visible), using SDPA."""
+    T = h.shape[0]
+    a = F.rms_norm(h, (m.d_model,), _t(W(pre + "g1")), m.rms_eps)
+    q = F.linear(a, _t(W(pre + "wq"))).view(T, m.n_q_heads, m.head_dim)
+    k = F.linear(a, _t(W(pre + "wk"))).view(T, m.n_kv_heads, m.head_dim)
+    v = F.linear(a, _t(W(pre + "wv"))).view(T, m.n_kv_heads, m.head_dim)
+    if m.qk_norm:
+        q = F.rms_norm(q, (m.head_dim,), _t(W(pre + "qn")), m.rms_eps)
+        k = F.rms_norm(k, (m.head_dim,), _t(W(pre + "kn")), m.rms_eps)
+    q, k = _rope_complex(q, pos, m.rope_theta), _rope_complex(k, pos, m.rope_theta)
+    mask = None
+    if extra_kv is not None:
+        ek, ev = extra_kv
+        n = ek.shape[0]
+        k = torch.cat([_t(ek), k], 0)
+        v = torch.cat([_t(ev), v], 0)
+        mask = torch.ones(T, n + T, dtype=torch.bool)
+        if causal:
+            mask[:, n:] = torch.tril(torch.ones(T, T, dtype=torch.bool))
+        o = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None],
+                                           v.permute(1, 0, 2)[None], attn_mask=mask, enable_gqa=True)
+    else:
+        o = F.scaled_dot_product_attention(q.permute(1, 0, 2)[None], k.permute(1, 0, 2)[None],
+                                           v.permute(1, 0, 2)[None], is_causal=causal, enable_gqa=True)
+    o = o[0].permute(1, 0, 2).reshape(T, -1)
+    h = h + F.linear(o, _t(W(pre + "wo")))
+    a2 = F.rms_norm(h, (m.d_model,), _t(W(pre + "g2")), m.rms_eps)
+    h = h + F.linear(F.silu(F.linear(a2, _t(W(pre + "wg")))) * F.linear(a2, _t(W(pre + "wu"))),
+                     _t(W(pre + "wd")))
+    return h
+
+
+def torch_target(W, m, tokens):
+    h = _t(W("E"))[torch.as_tensor(np.asarray(tokens, dtype=np.int64))]
+    pos = np.arange(len(tokens))
+    hs = []
+    for l in range(m.n_layers):
+        h = torch_layer(W, m, f"L{l}.", h, pos, causal=True)
+        hs.append(h)
+    logits = F.linear(F.rms_norm(h, (m.d_model,), _t(W("gf")), m.rms_eps), _t(W("lm")))
+    return logits.numpy(), [x.numpy() for x in hs]
+
+
+CASES = [dict(qk_norm=False, kv_heads=4), dict(qk_norm=True, kv_heads=2)]
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_target_sequence_form_matches_torch_library(case):
+    w = tiny_workload(seed=3, n_layers=3, vocab=200, taps=(0, 2), **case)
+    wt, _ = si.make_weights(w, 1)
+    W = W64(wt)
+    toks = si.make_prompts(replace(w, ctx_min=23, ctx_max=23))[0]
+    kv = O.KVList(3, w.target.n_kv_heads, 64, 64)
+    logits, taps = O.target_forward_sequence(W, w.target, toks, kv, w.tap_layers)
+    ref_logits, ref_h = torch_target(W, w.target, toks)
+    assert np.allclose(logits, ref_logits, atol=1e-10)
+    assert np.allclose(taps[:, 0], ref_h[0], atol=1e-10)        # tap = residual stream after the layer
+    assert np.allclose(taps[:, 1], ref_h[2], atol=1e-10)
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_token_loop_equals_sequence_form_and_single_token_calls(case):
+    w = tiny_workload(seed=4, n_layers=2, vocab=300, taps=(1,), **case)
+    wt, _ = si.make_weights(w, 1)
+    W = W64(wt)
+    toks = si.make_prompts(replace(w, ctx_min=19, ctx_max=19))[0]
+    m = w.target
+    kv_a = O.KVList(2, m.n_kv_heads, 64, 32)
+    la, ta = O.target_forward_sequence(W, m, toks, kv_a, w.tap_layers)
+    # (i) prefix through the cache, then a block of 8 tokens in one call
+    kv_b = O.KVList(2, m.n_kv_heads, 64, 32)
+    lb0, tb0 = O.target_forward_tokens(W, m, toks[:11], 0, kv_b, w.tap_layers)
+    lb1, tb1 = O.target_forward_tokens(W, m, toks[11:], 11, kv_b, w.tap_layers)
+    assert np.allclose(np.concatenate([lb0, lb1]), la, atol=1e-11)
+    assert np.allclose(np.concatenate([tb0, tb1]), ta, atol=1e-11)
+    for l in range(2):
+        assert np.allclose(kv_a.k[l][:19], kv_b.k[l][:19], atol=1e-12)
+        assert np.allclose(kv_a.v[l][:19], kv_b.v[l][:19], atol=1e-12)
+    # (ii) strictly one token per call: the plain autoregressive decoder
+    kv_c = O.KVList(2, m.n_kv_heads, 64, 32)
+    rows = [O.target_forward_tokens(W, m, [int(t)], i, kv_c, w.tap_layers)[0][0] for i, t in enumerate(toks)]
+    assert np.allclose(np.stack(rows), la, atol=1e-11)
+    assert np.allclose(np.stack(rows[11:]), lb1, atol=1e-12)
+
+
+def _draft_setup(seed, n_ctx, case, draft_layers=2, B=6):
+    w = tiny_workload(seed=seed, n_layers=3, draft_layers=draft_layers, vocab=256, block=B,
+                      taps=(0, 1), **case)
+    wt, wd = si.make_weights(w, 1)
+    Wt, Wd = W64(wt), W64(wd)
+    st = O.SeqState(w.target, w.draft, 64)
+    toks = si.make_prompts(replace(w, ctx_min=max(n_ctx, 1), ctx_max=max(n_ctx, 1)))[0]
+    if n_ctx > 0:
+        O.prefill(Wt, Wd, w.target, w.draft, w.tap_layers, toks, st)
+    else:
+        st.anchor = int(toks[0])
+    return w, Wt, Wd, st
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_draft_without_context_is_a_plain_bidirectional_transformer(case):
+    w, Wt, Wd, st = _draft_setup(5, 0, case)
+    md, B = w.draft, w.block_size
+    got = O.draft_block_forward(Wd, md, st.anchor, 0, st.ctx, B, w.mask_token_id)
+    toks = np.array([st.anchor] + [w.mask_token_id] * (B - 1))
+    h = _t(Wd("E"))[torch.as_tensor(toks)]
+    for i in range(md.n_layers):
+        h = torch_layer(Wd, md, f"L{i}.", h, np.arange(B), causal=False)
+    ref = F.linear(F.rms_norm(h, (md.d_model,), _t(Wd("gf")), md.rms_eps), _t(Wd("lm"))).numpy()
+    assert np.allclose(got, ref, atol=1e-10)
+
+
+@pytest.mark.parametrize("case", CASES)
+def test_draft_with_context_matches_library_attention_over_concatenated_kv(case):
+    """K = [W_K H_t ; W_K H_d] (Appendix A.3): the context rows enter as extra, fully visible
+    K/V rows of every layer; the fused feature itself is checked against F.linear + rms_norm."""
+    w, Wt, Wd, st = _draft_setup(6, 13, case)
+    md, mt, B, n = w.draft, w.target, w.block_size, st.n
+    got = O.draft_block_forward(Wd, md, st.anchor, n, st.ctx, B, w.mask_token_id)
+    # rebuild the context K/V independently from the torch target's hidden states
+    toks = si.make_prompts(replace(w, ctx_min=13, ctx_max=13))[0]
+    _, hs = torch_target(Wt, mt, toks)
+    cat = torch.cat([_t(hs[l]) for l in w.tap_layers], -1)              # ascending layer order
+    H_t = F.rms_norm(F.linear(cat, _t(Wd("wc"))), (md.d_model,), _t(Wd("gc")), md.rms_eps)
+    btoks = np.array([st.anchor] + [w.mask_token_id] * (B - 1))
+    h = _t(Wd("E"))[torch.as_tensor(btoks)]
+    for i in range(md.n_layers):
+        pre = f"L{i}."
+        ek = F.linear(H_t, _t(Wd(pre + "wk"))).view(n, md.n_kv_heads, md.head_dim)
+        ev = F.linear(H_t, _t(Wd(pre + "wv"))).view(n, md.n_kv_heads, md.head_dim)
+        if md.qk_norm:
+            ek = F.rms_norm(ek, (md.head_dim,), _t(Wd(pre + "kn")), md.rms_eps)
+        ek = _rope_complex(ek, np.arange(n), md.rope_theta)
+        assert np.allclose(st.ctx.k[i][:n], ek.numpy(), atol=1e-10)
+        assert np.allclose(st.ctx.v[i][:n], ev.numpy(), atol=1e-10)
+        h = torch_layer(Wd, md, pre, h, np.arange(n, n + B), causal=False,
+                        extra_kv=(ek.numpy(), ev.numpy()))
+    ref = F.linear(F.rms_norm(h, (md.d_model,), _t(Wd("gf")), md.rms_eps), _t(Wd("lm"))).numpy()
+    assert np.allclose(got, ref, atol=1e-10)
+
+
+def test_joint_softmax_equals_lse_merge_of_context_and_block_parts():
+    rng = np.random.default_rng(8)
+
+    class M:
+        n_q_heads, n_kv_heads, head_dim = 4, 2, 32
+    n, B = 21, 5
+    q = rng.standard_normal((4, 32))
+    K = rng.standard_normal((n + B, 2, 32))
+    V = rng.standard_normal((n + B, 2, 32))
+    joint = O._attend(M, q, K, V)
+    for h in range(4):
+        g = h // 2
+        s = torch.from_numpy(K[:, g] @ q[h] / np.sqrt(32))
+        parts = []
+        for sl in (slice(0, n), slice(n, n + B)):
+            lse = torch.logsumexp(s[sl], 0)
+            o = torch.softmax(s[sl], 0) @ torch.from_numpy(V[sl, g])
+            parts.append((lse, o))
+        tot = torch.logsumexp(torch.stack([parts[0][0], parts[1][0]]), 0)
+        merged = sum(torch.exp(l - tot) * o for l, o in parts)
+        assert np.allclose(joint[h], merged.numpy(), atol=1e-12)
+
+
+def test_draft_invariant_to_context_slot_order_and_wc_scale():
+    case = CASES[1]
+    w, Wt, Wd, st = _draft_setup(9, 17, case)
+    md, B, n = w.draft, w.block_size, st.n
+    base = O.draft_block_forward(Wd, md, st.anchor, n, st.ctx, B, w.mask_token_id)
+    # (a) context rows carry their position inside K (RoPE applied before caching): storing them
+    # in another order changes nothing
+    perm = np.random.default_rng(0).permutation(n)
+    ctx2 = O.KVList(md.n_layers, md.n_kv_heads, md.head_dim, 64)
+    for i in range(md.n_layers):
+        ctx2.k[i][:n] = st.ctx.k[i][:n][perm]
+        ctx2.v[i][:n] = st.ctx.v[i][:n][perm]
+    ctx2.n = n
+    assert np.allclose(O.draft_block_forward(Wd, md, st.anchor, n, ctx2, B, w.mask_token_id), base, atol=1e-11)
+    # (b) the fused feature is normalised: scaling W_c leaves H_t, hence the draft, unchanged
+    taps = np.random.default_rng(1).standard_normal((4, 2, w.target.d_model))
+    h1 = O.fuse_taps(Wd, md, taps)
+    Wd2 = lambda name: (3.0 * Wd(name) if name == "wc" else Wd(name))
+    md0 = replace(md, rms_eps=0.0)
+    assert np.allclose(O.fuse_taps(Wd2, md0, taps), O.fuse_taps(Wd, md0, taps), atol=1e-12)
+    assert h1.shape == (4, md.d_model)
+    # (c) the context only ever enters through K/V: dropping every context row of V and K
+    # (n = 0) must equal the plain bidirectional block
+    ctx0 = O.KVList(md.n_layers, md.n_kv_heads, md.head_dim, 8)
+    d0 = O.draft_block_forward(Wd, md, st.anchor, 0, ctx0, B, w.mask_token_id)
+    assert not np.allclose(d0, base, atol=1e-6)
+
+
+def test_block_rows_see_each_other_bidirectionally():
+    """Changing the LAST slot's input must change the FIRST mask slot's output (no causal mask
+    in the draft), whereas in the target an earlier row never sees a later one."""
+    w, Wt, Wd, st = _draft_setup(10, 9, CASES[0], draft_layers=1)
+    md, B, n = w.draft, w.block_size, st.n
+    base = O.draft_block_forward(Wd, md, st.anchor, n, st.ctx, B, w.mask_token_id)
+
+    def Wd_alt(name):               # perturb only the mask embedding -> rows 1..B-1 change input
+        a = Wd(name)
+        if name == "E":
+            a = a.copy()
+            a[w.mask_token_id] += 0.05
+        return a
+    alt = O.draft_block_forward(Wd_alt, md, st.anchor, n, st.ctx, B, w.mask_token_id)
+    assert np.abs(alt[0] - base[0]).max() > 1e-6        # anchor row sees the masks after it
+    kv1 = O.KVList(3, w.target.n_kv_heads, 64, 64)
+    kv2 = O.KVList(3, w.target.n_kv_heads, 64, 64)
+    a1, _ = O.target_forward_tokens(Wt, w.target, [5, 6, 7, 8], 0, kv1, ())
+    a2, _ = O.target_forward_tokens(Wt, w.target, [5, 6, 7, 9], 0, kv2, ())
+    assert np.array_equal(a1[:3], a2[:3]) and not np.allclose(a1[3], a2[3])
+
+
+def test_tap_layers_follow_the_paper():
+    assert si.tap_layers_for(36, 5) == (1, 9, 17, 25, 33)      # second layer .. third-to-last
+    assert si.workload(1).tap_layers == (0,)
