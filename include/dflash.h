@@ -1,0 +1,178 @@
+/*
+ * dflash.h -- C ABI of the DFlash speculative-decoding step for one MI355X (gfx950).
+ *
+ * One step of the method (arxiv 2602.06036, Section 3.1 and Section 4.1) is four calls, always in
+ * this order, all enqueued on the caller's HIP stream without host synchronisation:
+ *
+ *     dflash_draft_block -> dflash_verify -> dflash_accept -> dflash_kv_commit
+ *
+ * Conventions
+ *   - Every pointer is marked (host) or (device).  Device memory is owned by the caller (weights,
+ *     packed blobs, KV pools, workspace, inputs, outputs) and must stay valid until the enqueued
+ *     work has finished.  The library allocates no device memory.
+ *   - Return value: DFLASH_OK or a negative DFLASH_E* code.  Errors that the host can see
+ *     (null pointers, sizes, unsupported shapes) are reported before anything is enqueued;
+ *     dflash_last_error() then gives a message.  Conditions only the device can see (a sequence
+ *     that outgrew its pages, a page id outside the pool) raise a sticky device flag that
+ *     dflash_device_status() reads; the offending rows are skipped, never accessed out of bounds.
+ *   - Linear maps are given as [out_features, in_features] row-major (y = W x, the paper's
+ *     notation), in the model's dtype; norm gains are fp32.
+ *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
+ *   - Block layout (Section 4.2): slot 0 of every block is the clean anchor token (the previous
+ *     step's bonus token) at position seq_lens[s]; slots 1..B-1 are the drafted tokens.
+ */
+#ifndef DFLASH_H
+#define DFLASH_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+#define DFLASH_PAGE_SIZE 16      /* tokens per KV page (fixed: one page is one 16-wide MFMA tile) */
+#define DFLASH_MAX_BLOCK 16      /* largest block size B */
+#define DFLASH_MAX_TAPS 8
+
+enum { DFLASH_F32 = 0, DFLASH_BF16 = 1 };
+enum {
+  DFLASH_OK = 0,
+  DFLASH_EINVAL = -1,      /* bad argument or unsupported shape */
+  DFLASH_ECAPACITY = -2,   /* sequence length + block exceeds the pages of the block table */
+  DFLASH_EWORKSPACE = -3,  /* workspace / pool / blob buffer too small */
+  DFLASH_EHIP = -4         /* a HIP call failed */
+};
+enum { DFLASH_POOL_TARGET = 0, DFLASH_POOL_DRAFT = 1 };
+
+/* Shape of one model (target decoder or draft model); Section 5 "Implementation". */
+typedef struct {
+  int32_t n_layers, d_model, n_q_heads, n_kv_heads, head_dim, d_ffn, vocab;
+  float rope_theta, rms_eps;
+  int32_t qk_norm; /* 1: per-head RMSNorm on q and k before RoPE */
+  int32_t dtype;   /* DFLASH_F32 | DFLASH_BF16: storage type of weights, activations fed to GEMMs, KV */
+} dflash_dims;
+
+/* One Transformer layer's weights (device), canonical layout. */
+typedef struct {
+  const void *wq, *wk, *wv, *wo; /* [Hq*hd, D], [Hkv*hd, D], [Hkv*hd, D], [D, Hq*hd] */
+  const void *wg, *wu, *wd;      /* [F, D], [F, D], [D, F] */
+  const float *g1, *g2;          /* [D] pre-attention / pre-FFN RMSNorm gains */
+  const float *qn, *kn;          /* [hd] per-head q / k norm gains (ignored unless qk_norm) */
+} dflash_layer_weights;
+
+/* Runtime geometry and caller-owned buffers. */
+typedef struct {
+  int32_t block_size;        /* B, 2..DFLASH_MAX_BLOCK */
+  int32_t max_seqs;          /* largest n_seqs of any call */
+  int32_t max_pages_per_seq; /* row length of the block table */
+  int32_t n_pages;           /* pages in each pool; page ids are 0..n_pages-1 in both pools */
+  int32_t n_taps;            /* tapped target layers (Section 5: 5) */
+  int32_t tap_layers[DFLASH_MAX_TAPS]; /* 0-based, ascending; the layer's output is tapped */
+  int32_t mask_token_id;     /* id whose embedding fills the masked slots */
+  void *target_kv_pool;      /* (device) dflash_kv_pool_bytes(target, n_pages) bytes */
+  void *draft_kv_pool;       /* (device) dflash_kv_pool_bytes(draft, n_pages) bytes */
+  void *workspace;           /* (device) dflash_workspace_bytes() bytes, 256-byte aligned */
+  size_t workspace_bytes;
+} dflash_runtime;
+
+/* Per-call batch description. */
+typedef struct {
+  int32_t n_seqs;             /* S */
+  int32_t max_seq_len;        /* (host) upper bound on seq_lens[s] over the batch; sizes launch grids only */
+  int32_t *seq_lens;          /* (device) [S] committed length n_s; updated by dflash_kv_commit */
+  const int32_t *block_table; /* (device) [S, max_pages_per_seq] page ids; pages covering n_s + B tokens must be valid */
+  int32_t *anchor;            /* (device) [S] clean token at position n_s; updated by dflash_kv_commit */
+} dflash_batch;
+
+typedef struct dflash_ctx dflash_ctx;
+
+/* ---- sizes ------------------------------------------------------------------------------- */
+size_t dflash_target_blob_bytes(const dflash_dims *target);
+size_t dflash_draft_blob_bytes(const dflash_dims *draft, int32_t n_taps, int32_t d_target);
+size_t dflash_kv_pool_bytes(const dflash_dims *model, int32_t n_pages);
+size_t dflash_workspace_bytes(const dflash_dims *target, const dflash_dims *draft, const dflash_runtime *rt);
+
+/* ---- one-time weight packing (device -> device, enqueued on stream) ---------------------------
+ * Rewrites canonical weights into the library's streaming layout inside a caller-owned blob:
+ * Q/K/V rows concatenated, gate/up rows interleaved in groups of 16 so SwiGLU fuses into the GEMM
+ * epilogue, and for bf16 every matrix cut into 16x32 tiles stored in MFMA operand order.  The
+ * canonical copies may be freed once the stream has finished.  Shared embedding and LM head
+ * (Section 4.2) live in the target blob and are used by the draft as well. */
+int dflash_pack_target_head(const dflash_dims *target, const void *embed /*(device) [V,D]*/,
+                            const void *lm_head /*(device) [V,D]*/, const float *final_gain /*(device) [D]*/,
+                            void *blob, void *stream);
+int dflash_pack_target_layer(const dflash_dims *target, int32_t layer, const dflash_layer_weights *w /*(host struct)*/,
+                             void *blob, void *stream);
+/* W_c is [D, n_taps*D_target] (Appendix A.3), g_c its RMSNorm gain, final_gain the draft's final norm. */
+int dflash_pack_draft_head(const dflash_dims *draft, int32_t n_taps, int32_t d_target, const void *w_c,
+                           const float *g_c, const float *final_gain, void *blob, void *stream);
+int dflash_pack_draft_layer(const dflash_dims *draft, int32_t n_taps, int32_t d_target, int32_t layer,
+                            const dflash_layer_weights *w, void *blob, void *stream);
+
+/* ---- context ----------------------------------------------------------------------------- */
+/* Validates shapes and buffer sizes and records pointers; touches no device memory except
+ * clearing the device status word (one synchronous 4-byte copy). */
+int dflash_create(const dflash_dims *target, const void *target_blob, const dflash_dims *draft,
+                  const void *draft_blob, const dflash_runtime *rt, dflash_ctx **out);
+int dflash_destroy(dflash_ctx *ctx);
+const char *dflash_last_error(const dflash_ctx *ctx); /* ctx may be NULL: message of the last failed create/pack/size call */
+/* Synchronises `stream`, returns and clears the sticky device status (0, or DFLASH_ECAPACITY). */
+int dflash_device_status(dflash_ctx *ctx, void *stream);
+
+/* ---- the step ------------------------------------------------------------------------------ */
+/* Draft (Section 4.1 "Parallel diffusion drafting", Appendix A.3): one forward pass of the draft
+ * model over the block [anchor, mask x (B-1)] at positions n_s .. n_s+B-1.  Block rows attend without
+ * mask to the n_s cached context-feature K/V rows of each draft layer and to all B block rows.
+ * temperature == 0: draft_tokens[s,j] = argmax of slot j's logits (ties -> lowest id);
+ * temperature  > 0: a draw from softmax(logits/temperature) by Gumbel-max with the counter-based
+ * generator keyed by *rng_key.  draft_tokens (device) [S,B] out, slot 0 = anchor.
+ * logits_out (device, nullable) [S,B,V] fp32 receives the draft logits (row j = slot j). */
+int dflash_draft_block(dflash_ctx *ctx, const dflash_batch *batch, float temperature,
+                       const uint64_t *rng_key /*(device) [1], nullable when temperature == 0*/,
+                       int32_t *draft_tokens, float *logits_out, void *stream);
+
+/* Verify (Section 3.1): one causal forward of the target over tokens[s,0..B-1] at positions
+ * n_s .. n_s+B-1 against the paged KV cache; row j sees cache rows 0..n_s-1 and block rows <= j.
+ * Writes the B new K/V rows of every layer into the target pool (speculatively: they become
+ * visible only when dflash_kv_commit advances seq_lens) and the tapped hidden states into the
+ * workspace.  tgt_argmax (device) [S,B]: greedy token after row j.  logits_out (device, nullable)
+ * [S,B,V] fp32. */
+int dflash_verify(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *tokens /*(device) [S,B]*/,
+                  int32_t *tgt_argmax, float *logits_out, void *stream);
+
+/* Accept (Section 3.1: tau = accept_len + 1 in [1, B], bonus token included).
+ * temperature == 0: accept_len[s] = largest a with draft_tokens[s,j] == tgt_argmax[s,j-1] for all
+ * 1 <= j <= a; out_tokens[s] = d_1..d_a, tgt_argmax[s,a], then -1 padding.
+ * temperature  > 0: speculative sampling on the logits the preceding dflash_draft_block and
+ * dflash_verify calls left in the workspace: slot j accepted iff u[s,j] * q_j(d_j) < p_{j-1}(d_j);
+ * first rejected slot is replaced by a draw from normalise(max(p - q, 0)); all accepted -> bonus
+ * draw from the last row.  uniforms (device) [S,B] fp32 in [0,1). */
+int dflash_accept(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *draft_tokens,
+                  const int32_t *tgt_argmax, float temperature, const float *uniforms /*nullable when greedy*/,
+                  const uint64_t *rng_key /*(device) [1], nullable when greedy*/,
+                  int32_t *accept_len /*(device) [S] out*/, int32_t *out_tokens /*(device) [S,B] out*/, void *stream);
+
+/* Commit / rollback (Section 4.1, Appendix A.3): fuses the tapped hidden states of the block rows,
+ * H_t = RMSNorm(W_c [taps]), projects them with every draft layer's W_K, W_V (k-norm, RoPE at the
+ * row's position) into the draft pool at positions n_s .. n_s+B-1, then advances
+ * seq_lens[s] += accept_len[s] + 1 and sets anchor[s] = out_tokens[s, accept_len[s]].
+ * Rows beyond the accepted prefix stay in the pools but are invisible (rolled back) and are
+ * overwritten by the next step.  accept_len[s] = -1 commits nothing for sequence s (length and anchor
+ * unchanged): an idle slot of the batch, or a prompt that ended in an earlier prefill chunk.  kv_slots_out (device, nullable) [S,B] int64: page*16+offset of
+ * each committed row, -1 for rolled-back rows. */
+int dflash_kv_commit(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *accept_len,
+                     const int32_t *out_tokens, int64_t *kv_slots_out, void *stream);
+
+/* ---- cache import / export (state migration, tests) ------------------------------------------ */
+/* Copies rows [start, start+count) of sequence `seq` of one layer between the paged pool and
+ * canonical fp32 buffers k, v (device) [count, Hkv, hd].  K rows are stored post-RoPE. */
+int dflash_kv_read(dflash_ctx *ctx, const dflash_batch *batch, int32_t pool, int32_t layer, int32_t seq,
+                   int32_t start, int32_t count, float *k, float *v, void *stream);
+int dflash_kv_write(dflash_ctx *ctx, const dflash_batch *batch, int32_t pool, int32_t layer, int32_t seq,
+                    int32_t start, int32_t count, const float *k, const float *v, void *stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DFLASH_H */

@@ -307,13 +307,14 @@ def _mix64(z: np.ndarray) -> np.ndarray:
 
 
 def counter_uniform(key: int, seq: int, slot: int, purpose: int, idx: np.ndarray) -> np.ndarray:
-    """u in (0,1) with 24 random bits: counter c = (((seq*64 + slot)*4 + purpose) << 32) | idx,
-    z = mix64(key + 0x9E3779B97F4A7C15 * (c + 1)) (mod 2^64), u = ((z >> 40) + 0.5) / 2^24."""
+    """u in (0,1) with 23 random bits: counter c = (((seq*64 + slot)*4 + purpose) << 32) | idx,
+    z = mix64(key + 0x9E3779B97F4A7C15 * (c + 1)) (mod 2^64), u = ((z >> 41) + 0.5) / 2^23
+    (23 bits keep x + 0.5 exact in single precision as well)."""
     with np.errstate(over="ignore"):
         hi = np.uint64((((seq * 64 + slot) * 4 + purpose) << 32) & _M64)
         c = hi | np.asarray(idx, dtype=np.uint64)
         z = _mix64(np.uint64(key & _M64) + np.uint64(0x9E3779B97F4A7C15) * (c + np.uint64(1)))
-    return ((z >> np.uint64(40)).astype(np.float64) + 0.5) * 2.0 ** -24
+    return ((z >> np.uint64(41)).astype(np.float64) + 0.5) * 2.0 ** -23
 
 
 def gumbel_scores(logw: np.ndarray, key: int, seq: int, slot: int, purpose: int) -> np.ndarray:

@@ -1,0 +1,240 @@
+"""Thin ctypes binding of the C ABI in include/dflash.h.
+
+Argument marshalling only: every step of the speculative-decoding path runs inside the HIP
+library.  PyTorch is used for device allocations and the current HIP stream, nothing else.
+The binding fails loudly when the library has not been built (python -m paper_2602_06036_amd.build).
+"""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from typing import Dict, Optional, Sequence
+
+import torch
+
+_HERE = os.path.dirname(os.path.abspath(__file__))
+LIB_PATH = os.path.join(_HERE, "libdflash.so")
+
+DFLASH_F32, DFLASH_BF16 = 0, 1
+DFLASH_OK, DFLASH_EINVAL, DFLASH_ECAPACITY, DFLASH_EWORKSPACE, DFLASH_EHIP = 0, -1, -2, -3, -4
+DFLASH_POOL_TARGET, DFLASH_POOL_DRAFT = 0, 1
+PAGE_SIZE, MAX_TAPS = 16, 8
+
+EXPORTS = [
+    "dflash_target_blob_bytes", "dflash_draft_blob_bytes", "dflash_kv_pool_bytes", "dflash_workspace_bytes",
+    "dflash_pack_target_head", "dflash_pack_target_layer", "dflash_pack_draft_head", "dflash_pack_draft_layer",
+    "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
+    "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
+    "dflash_kv_read", "dflash_kv_write",
+]
+
+
+class Dims(C.Structure):
+    _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
+               [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("qk_norm", C.c_int32), ("dtype", C.c_int32)]
+
+
+class LayerWeights(C.Structure):
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "qn", "kn")]
+
+
+class Runtime(C.Structure):
+    _fields_ = [("block_size", C.c_int32), ("max_seqs", C.c_int32), ("max_pages_per_seq", C.c_int32), ("n_pages", C.c_int32),
+                ("n_taps", C.c_int32), ("tap_layers", C.c_int32 * MAX_TAPS), ("mask_token_id", C.c_int32),
+                ("target_kv_pool", C.c_void_p), ("draft_kv_pool", C.c_void_p), ("workspace", C.c_void_p),
+                ("workspace_bytes", C.c_size_t)]
+
+
+class Batch(C.Structure):
+    _fields_ = [("n_seqs", C.c_int32), ("max_seq_len", C.c_int32), ("seq_lens", C.c_void_p), ("block_table", C.c_void_p),
+                ("anchor", C.c_void_p)]
+
+
+class DFlashError(RuntimeError):
+    def __init__(self, code: int, msg: str):
+        super().__init__(f"dflash error {code}: {msg}")
+        self.code = code
+
+
+_lib = None
+
+
+def lib() -> C.CDLL:
+    global _lib
+    if _lib is None:
+        if not os.path.exists(LIB_PATH):
+            raise ImportError(f"{LIB_PATH} is missing: build it with `python -m paper_2602_06036_amd.build` "
+                              "(there is no CPU fallback)")
+        l = C.CDLL(LIB_PATH)
+        P, I, F = C.c_void_p, C.c_int32, C.c_float
+        l.dflash_target_blob_bytes.restype = C.c_size_t
+        l.dflash_target_blob_bytes.argtypes = [C.POINTER(Dims)]
+        l.dflash_draft_blob_bytes.restype = C.c_size_t
+        l.dflash_draft_blob_bytes.argtypes = [C.POINTER(Dims), I, I]
+        l.dflash_kv_pool_bytes.restype = C.c_size_t
+        l.dflash_kv_pool_bytes.argtypes = [C.POINTER(Dims), I]
+        l.dflash_workspace_bytes.restype = C.c_size_t
+        l.dflash_workspace_bytes.argtypes = [C.POINTER(Dims), C.POINTER(Dims), C.POINTER(Runtime)]
+        l.dflash_pack_target_head.argtypes = [C.POINTER(Dims), P, P, P, P, P]
+        l.dflash_pack_target_layer.argtypes = [C.POINTER(Dims), I, C.POINTER(LayerWeights), P, P]
+        l.dflash_pack_draft_head.argtypes = [C.POINTER(Dims), I, I, P, P, P, P, P]
+        l.dflash_pack_draft_layer.argtypes = [C.POINTER(Dims), I, I, I, C.POINTER(LayerWeights), P, P]
+        l.dflash_create.argtypes = [C.POINTER(Dims), P, C.POINTER(Dims), P, C.POINTER(Runtime), C.POINTER(P)]
+        l.dflash_destroy.argtypes = [P]
+        l.dflash_last_error.restype = C.c_char_p
+        l.dflash_last_error.argtypes = [P]
+        l.dflash_device_status.argtypes = [P, P]
+        l.dflash_draft_block.argtypes = [P, C.POINTER(Batch), F, P, P, P, P]
+        l.dflash_verify.argtypes = [P, C.POINTER(Batch), P, P, P, P]
+        l.dflash_accept.argtypes = [P, C.POINTER(Batch), P, P, F, P, P, P, P, P]
+        l.dflash_kv_commit.argtypes = [P, C.POINTER(Batch), P, P, P, P]
+        l.dflash_kv_read.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
+        l.dflash_kv_write.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
+        for name in EXPORTS:
+            if name not in ("dflash_target_blob_bytes", "dflash_draft_blob_bytes", "dflash_kv_pool_bytes",
+                            "dflash_workspace_bytes", "dflash_last_error"):
+                getattr(l, name).restype = C.c_int
+        _lib = l
+    return _lib
+
+
+def make_dims(m, dtype: str) -> Dims:
+    """m: any object with the ModelDims attributes."""
+    return Dims(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn, m.vocab,
+                float(m.rope_theta), float(m.rms_eps), int(bool(m.qk_norm)),
+                DFLASH_BF16 if dtype == "bf16" else DFLASH_F32)
+
+
+def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
+    if t is None:
+        return None
+    assert t.is_cuda and t.is_contiguous()
+    return t.data_ptr()
+
+
+def _stream() -> int:
+    return torch.cuda.current_stream().cuda_stream
+
+
+def _check(rc: int, ctx=None):
+    if rc != DFLASH_OK:
+        raise DFlashError(rc, lib().dflash_last_error(ctx).decode())
+
+
+def _layer_struct(w: Dict[str, torch.Tensor]) -> LayerWeights:
+    return LayerWeights(*[_ptr(w.get(k)) for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "qn", "kn")])
+
+
+class Engine:
+    """Owns the device buffers (torch tensors) that the C library works on, and the context."""
+
+    def __init__(self, target, draft, dtype: str, block_size: int, max_seqs: int, max_pages_per_seq: int,
+                 n_pages: int, tap_layers: Sequence[int], mask_token_id: int, device: str = "cuda:0"):
+        self.l = lib()
+        self.device = torch.device(device)
+        self.dtype = dtype
+        self.target, self.draft = target, draft
+        self.td, self.dd = make_dims(target, dtype), make_dims(draft, dtype)
+        self.B, self.max_seqs, self.max_pages_per_seq, self.n_pages = block_size, max_seqs, max_pages_per_seq, n_pages
+        self.n_taps = len(tap_layers)
+        rt = Runtime()
+        rt.block_size, rt.max_seqs, rt.max_pages_per_seq, rt.n_pages = block_size, max_seqs, max_pages_per_seq, n_pages
+        rt.n_taps = self.n_taps
+        for i, t in enumerate(tap_layers):
+            rt.tap_layers[i] = int(t)
+        rt.mask_token_id = mask_token_id
+        self.rt = rt
+        tb = self.l.dflash_target_blob_bytes(C.byref(self.td))
+        db = self.l.dflash_draft_blob_bytes(C.byref(self.dd), self.n_taps, target.d_model)
+        if tb == 0 or db == 0:
+            _check(DFLASH_EINVAL)
+        self.target_blob = torch.empty(tb, dtype=torch.uint8, device=self.device)
+        self.draft_blob = torch.empty(db, dtype=torch.uint8, device=self.device)
+        self.ctx = None
+
+    # ---- weights -------------------------------------------------------------------------------
+    def pack_target_head(self, embed, lm_head, final_gain):
+        _check(self.l.dflash_pack_target_head(C.byref(self.td), _ptr(embed), _ptr(lm_head), _ptr(final_gain),
+                                              _ptr(self.target_blob), _stream()))
+
+    def pack_target_layer(self, layer: int, w: Dict[str, torch.Tensor]):
+        s = _layer_struct(w)
+        _check(self.l.dflash_pack_target_layer(C.byref(self.td), layer, C.byref(s), _ptr(self.target_blob), _stream()))
+
+    def pack_draft_head(self, w_c, g_c, final_gain):
+        _check(self.l.dflash_pack_draft_head(C.byref(self.dd), self.n_taps, self.target.d_model, _ptr(w_c), _ptr(g_c),
+                                             _ptr(final_gain), _ptr(self.draft_blob), _stream()))
+
+    def pack_draft_layer(self, layer: int, w: Dict[str, torch.Tensor]):
+        s = _layer_struct(w)
+        _check(self.l.dflash_pack_draft_layer(C.byref(self.dd), self.n_taps, self.target.d_model, layer, C.byref(s),
+                                              _ptr(self.draft_blob), _stream()))
+
+    # ---- context -------------------------------------------------------------------------------
+    def create(self):
+        tp = self.l.dflash_kv_pool_bytes(C.byref(self.td), self.n_pages)
+        dp = self.l.dflash_kv_pool_bytes(C.byref(self.dd), self.n_pages)
+        ws = self.l.dflash_workspace_bytes(C.byref(self.td), C.byref(self.dd), C.byref(self.rt))
+        if tp == 0 or dp == 0 or ws == 0:
+            _check(DFLASH_EINVAL)
+        self.target_pool = torch.zeros(tp, dtype=torch.uint8, device=self.device)
+        self.draft_pool = torch.zeros(dp, dtype=torch.uint8, device=self.device)
+        self.workspace = torch.zeros(ws, dtype=torch.uint8, device=self.device)
+        self.rt.target_kv_pool, self.rt.draft_kv_pool = _ptr(self.target_pool), _ptr(self.draft_pool)
+        self.rt.workspace, self.rt.workspace_bytes = _ptr(self.workspace), ws
+        torch.cuda.synchronize(self.device)
+        h = C.c_void_p()
+        _check(self.l.dflash_create(C.byref(self.td), _ptr(self.target_blob), C.byref(self.dd), _ptr(self.draft_blob),
+                                    C.byref(self.rt), C.byref(h)))
+        self.ctx = h
+        return self
+
+    def close(self):
+        if self.ctx is not None:
+            self.l.dflash_destroy(self.ctx)
+            self.ctx = None
+
+    def batch(self, seq_lens: torch.Tensor, block_table: torch.Tensor, anchor: torch.Tensor, max_seq_len: int) -> Batch:
+        assert seq_lens.dtype == torch.int32 and block_table.dtype == torch.int32 and anchor.dtype == torch.int32
+        assert block_table.shape == (seq_lens.shape[0], self.max_pages_per_seq)
+        return Batch(int(seq_lens.shape[0]), int(max_seq_len), _ptr(seq_lens), _ptr(block_table), _ptr(anchor))
+
+    def device_status(self):
+        _check(self.l.dflash_device_status(self.ctx, _stream()), self.ctx)
+
+
+# ---- the four calls of the step (same names as the C ABI) ------------------------------------------
+def dflash_draft_block(e: Engine, batch: Batch, draft_tokens: torch.Tensor, temperature: float = 0.0,
+                       rng_key: Optional[torch.Tensor] = None, logits_out: Optional[torch.Tensor] = None):
+    _check(e.l.dflash_draft_block(e.ctx, C.byref(batch), float(temperature), _ptr(rng_key), _ptr(draft_tokens),
+                                  _ptr(logits_out), _stream()), e.ctx)
+
+
+def dflash_verify(e: Engine, batch: Batch, tokens: torch.Tensor, tgt_argmax: torch.Tensor,
+                  logits_out: Optional[torch.Tensor] = None):
+    _check(e.l.dflash_verify(e.ctx, C.byref(batch), _ptr(tokens), _ptr(tgt_argmax), _ptr(logits_out), _stream()), e.ctx)
+
+
+def dflash_accept(e: Engine, batch: Batch, draft_tokens: torch.Tensor, tgt_argmax: torch.Tensor, accept_len: torch.Tensor,
+                  out_tokens: torch.Tensor, temperature: float = 0.0, uniforms: Optional[torch.Tensor] = None,
+                  rng_key: Optional[torch.Tensor] = None):
+    _check(e.l.dflash_accept(e.ctx, C.byref(batch), _ptr(draft_tokens), _ptr(tgt_argmax), float(temperature), _ptr(uniforms),
+                             _ptr(rng_key), _ptr(accept_len), _ptr(out_tokens), _stream()), e.ctx)
+
+
+def dflash_kv_commit(e: Engine, batch: Batch, accept_len: torch.Tensor, out_tokens: torch.Tensor,
+                     kv_slots_out: Optional[torch.Tensor] = None):
+    _check(e.l.dflash_kv_commit(e.ctx, C.byref(batch), _ptr(accept_len), _ptr(out_tokens), _ptr(kv_slots_out), _stream()), e.ctx)
+
+
+def dflash_kv_read(e: Engine, batch: Batch, pool: int, layer: int, seq: int, start: int, count: int):
+    m = e.target if pool == DFLASH_POOL_TARGET else e.draft
+    k = torch.empty((count, m.n_kv_heads, m.head_dim), dtype=torch.float32, device=e.device)
+    v = torch.empty_like(k)
+    _check(e.l.dflash_kv_read(e.ctx, C.byref(batch), pool, layer, seq, start, count, _ptr(k), _ptr(v), _stream()), e.ctx)
+    return k, v
+
+
+def dflash_kv_write(e: Engine, batch: Batch, pool: int, layer: int, seq: int, start: int, k: torch.Tensor, v: torch.Tensor):
+    assert k.dtype == torch.float32 and v.dtype == torch.float32 and k.shape == v.shape
+    _check(e.l.dflash_kv_write(e.ctx, C.byref(batch), pool, layer, seq, start, int(k.shape[0]), _ptr(k), _ptr(v), _stream()), e.ctx)

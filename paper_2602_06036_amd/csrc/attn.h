@@ -1,0 +1,118 @@
+// Block attention over the paged cache, split along the context ("split-KV") with a deterministic
+// log-sum-exp merge.  Used for both halves of the step:
+//   verify (Section 3.1): causal -- block row j sees positions 0 .. n_s + j
+//   draft  (Section 4.2, Appendix A.3): no mask -- every block row sees the n_s context-feature rows
+//                                       and all B block rows (positions 0 .. n_s + B - 1)
+// In both cases the block's own K/V rows have already been written to the pool at n_s .. n_s+B-1.
+#pragma once
+#include "common.h"
+
+struct AttnArgs {
+  int n_q_heads, n_kv_heads, head_dim;
+  int layer;     // layer inside the pool
+  int causal;
+  int chunk;     // context tokens per split (multiple of 64)
+  int n_splits;
+  float scale;   // 1/sqrt(head_dim)
+};
+
+// partial results: for pr = (m*Hq + hq)*n_splits + split : ml[pr] = (running max, sum exp), o[pr*hd + d]
+// (o unnormalised, relative to the running max)
+
+// ------------------------------------------------------------------------------------------------
+// Generic kernel (any storage type; plain ALU math).  grid (n_splits, Hkv, S), block 256.
+// A wavefront takes query rows r = wave, wave+4, ... of the B*group rows that share this kv head.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void attn_partial_simple_kernel(const T* __restrict__ q, const T* __restrict__ pool,
+                                                                  SeqGeom geo, AttnArgs aa, float* __restrict__ part_o,
+                                                                  float2* __restrict__ part_ml) {
+  const int split = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int hd = aa.head_dim, B = geo.block_size;
+  const int group = aa.n_q_heads / aa.n_kv_heads;
+  const int rows = B * group;
+  const int n_s = geo.seq_lens[s];
+  const int cap = geo.max_pages_per_seq * DF_PAGE;
+  const int n_tok = min(n_s + B, cap);
+  const int c0 = split * aa.chunk;
+  const int c1 = min(n_tok, c0 + aa.chunk);
+  __shared__ float qs[4][128];
+  const int32_t* table = geo.block_table + (size_t)s * geo.max_pages_per_seq;
+
+  for (int r = wave; r < rows; r += 4) {
+    const int slot = r / group, hq = kvh * group + r % group;
+    const int m = s * B + slot;
+    const size_t pr = ((size_t)m * aa.n_q_heads + hq) * aa.n_splits + split;
+    const T* qrow = q + ((size_t)m * aa.n_q_heads + hq) * hd;
+    for (int d = lane; d < hd; d += 64) qs[wave][d] = Store<T>::to(qrow[d]);
+    // (same wavefront writes and reads qs[wave]; LDS ops of one wavefront complete in order)
+    const int last_vis = aa.causal ? min(n_s + slot, n_tok - 1) : n_tok - 1;
+    float m_run = -INFINITY, l_run = 0.f, o0 = 0.f, o1 = 0.f;
+    for (int t0 = c0; t0 < c1; t0 += 64) {
+      const int pos = t0 + lane;
+      const bool vis = pos < c1 && pos <= last_vis;
+      int page = -1;
+      if (vis) page = table[pos / DF_PAGE];
+      const bool ok = vis && page >= 0 && page < geo.n_pages;
+      float sc = -INFINITY;
+      if (ok) {
+        const T* kb = pool + kv_head_base(aa.layer, geo.n_pages, page, aa.n_kv_heads, kvh, hd);
+        const int key = pos % DF_PAGE;
+        float acc = 0.f;
+        for (int d = 0; d < hd; d += 8) {
+          const T* kp = kb + k_in_page(key, d);
+#pragma unroll
+          for (int e = 0; e < 8; ++e) acc += qs[wave][d + e] * Store<T>::to(kp[e]);
+        }
+        sc = acc * aa.scale;
+      }
+      const float tmax = wave_reduce_max(sc);
+      if (tmax == -INFINITY) continue;   // uniform across the wavefront
+      const float m_new = fmaxf(m_run, tmax);
+      const float corr = (m_run == -INFINITY) ? 0.f : expf(m_run - m_new);
+      const float p = ok ? expf(sc - m_new) : 0.f;
+      l_run = l_run * corr + wave_reduce_sum(p);
+      o0 *= corr;
+      o1 *= corr;
+      m_run = m_new;
+      const int n_in_tile = min(64, c1 - t0);
+      for (int kk = 0; kk < n_in_tile; ++kk) {
+        const float pk = __shfl(p, kk, 64);
+        if (pk == 0.f) continue;         // uniform
+        const int kpos = t0 + kk;
+        const int pg = table[kpos / DF_PAGE];
+        const T* vb = pool + kv_head_base(aa.layer, geo.n_pages, pg, aa.n_kv_heads, kvh, hd) + DF_PAGE * hd;
+        const int key = kpos % DF_PAGE;
+        if (lane < hd) o0 += pk * Store<T>::to(vb[v_in_page(key, lane)]);
+        if (lane + 64 < hd) o1 += pk * Store<T>::to(vb[v_in_page(key, lane + 64)]);
+      }
+    }
+    if (lane == 0) part_ml[pr] = make_float2(m_run, l_run);
+    if (lane < hd) part_o[pr * hd + lane] = o0;
+    if (lane + 64 < hd) part_o[pr * hd + lane + 64] = o1;
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Merge of the splits in ascending split order; grid (M*Hq), block 128.
+// Output in GEMM operand layout, row length Hq*hd.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
+                                                         T* __restrict__ out, int n_q_heads, int hd, int n_splits) {
+  const int row = blockIdx.x;  // m*Hq + hq
+  const int m = row / n_q_heads, hq = row % n_q_heads;
+  const int d = threadIdx.x;
+  float mx = -INFINITY;
+  for (int c = 0; c < n_splits; ++c) mx = fmaxf(mx, part_ml[(size_t)row * n_splits + c].x);
+  float L = 0.f, o = 0.f;
+  for (int c = 0; c < n_splits; ++c) {
+    const float2 ml = part_ml[(size_t)row * n_splits + c];
+    if (ml.y <= 0.f) continue;
+    const float w = expf(ml.x - mx);
+    L += ml.y * w;
+    if (d < hd) o += w * part_o[((size_t)row * n_splits + c) * hd + d];
+  }
+  if (d < hd) out[tile_index<T>(m, hq * hd + d, n_q_heads * hd)] = Store<T>::from(L > 0.f ? o / L : 0.f);
+}

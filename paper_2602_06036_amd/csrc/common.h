@@ -1,0 +1,87 @@
+// Shared device/host helpers of the DFlash HIP path: storage types, tile and KV-page layouts.
+#pragma once
+#include <hip/hip_runtime.h>
+#include <stdint.h>
+
+typedef uint16_t bf16_t;  // raw bfloat16 bits
+typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
+typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+
+#define DF_WAVE 64
+#define DF_PAGE 16
+
+__host__ __device__ __forceinline__ float bf16_bits_to_float(bf16_t b) {
+  union { uint32_t u; float f; } c;
+  c.u = (uint32_t)b << 16;
+  return c.f;
+}
+// round-to-nearest-even; inputs are finite on this path
+__host__ __device__ __forceinline__ bf16_t float_to_bf16_bits(float f) {
+  union { uint32_t u; float f; } c;
+  c.f = f;
+  uint32_t u = c.u;
+  u += 0x7FFFu + ((u >> 16) & 1u);
+  return (bf16_t)(u >> 16);
+}
+
+template <typename T> struct Store;
+template <> struct Store<float> {
+  static __host__ __device__ __forceinline__ float from(float f) { return f; }
+  static __host__ __device__ __forceinline__ float to(float v) { return v; }
+};
+template <> struct Store<bf16_t> {
+  static __host__ __device__ __forceinline__ bf16_t from(float f) { return float_to_bf16_bits(f); }
+  static __host__ __device__ __forceinline__ float to(bf16_t v) { return bf16_bits_to_float(v); }
+};
+
+// ---- GEMM operand layout -----------------------------------------------------------------------
+// A matrix of `rows` x K (K contiguous in the canonical form).  fp32: plain row-major.  bf16: cut into
+// 16-row x 32-column tiles; a tile is 1 KB holding, for lane = (k%32)/8*16 + r%16 of a 64-wide
+// wavefront, the 8 consecutive k values that lane feeds to v_mfma_f32_16x16x32_bf16.  Tiles of one
+// 16-row band are consecutive along K, so a wavefront streams a band as contiguous 1 KB loads.
+template <typename T> __host__ __device__ __forceinline__ size_t tile_index(int r, int k, int K);
+template <> __host__ __device__ __forceinline__ size_t tile_index<float>(int r, int k, int K) {
+  return (size_t)r * K + k;
+}
+template <> __host__ __device__ __forceinline__ size_t tile_index<bf16_t>(int r, int k, int K) {
+  return ((size_t)(r >> 4) * (K >> 5) + (k >> 5)) * 512 + (size_t)(((((k & 31) >> 3) << 4) + (r & 15)) * 8 + (k & 7));
+}
+// rows that a buffer in this layout must provide for M logical rows
+template <typename T> __host__ __device__ __forceinline__ int tile_rows(int M) { return M; }
+template <> __host__ __device__ __forceinline__ int tile_rows<bf16_t>(int M) { return (M + 15) & ~15; }
+
+// ---- KV page layout ----------------------------------------------------------------------------
+// A pool holds, per layer, n_pages pages; a page holds for each kv head 16 keys then 16 values:
+//   pool[layer][page][kv_head][K|V][16*hd]
+// K part: [hd/8][16 keys][8 dims]   -> a 16-key x 32-dim MFMA A-operand tile is 1 KB contiguous
+// V part: [hd/16][4][16 dims][4 keys] -> lane (dim%16, key/4) of the P.V MFMA reads 4 keys contiguously
+__host__ __device__ __forceinline__ int k_in_page(int key, int d) { return (d >> 3) * 128 + key * 8 + (d & 7); }
+__host__ __device__ __forceinline__ int v_in_page(int key, int d) {
+  return (d >> 4) * 256 + (key >> 2) * 64 + (d & 15) * 4 + (key & 3);
+}
+__host__ __device__ __forceinline__ size_t kv_head_base(int layer, int n_pages, int page, int n_kv_heads, int kvh, int hd) {
+  return ((((size_t)layer * n_pages + page) * n_kv_heads + kvh) * 2) * (size_t)(DF_PAGE * hd);
+}
+
+struct SeqGeom {          // passed by value to kernels that walk the page table
+  const int32_t* seq_lens;
+  const int32_t* block_table;
+  int32_t max_pages_per_seq;
+  int32_t n_pages;
+  int32_t block_size;
+  int32_t* status;        // sticky device status word
+};
+
+#define DF_STATUS_CAPACITY 1
+
+__device__ __forceinline__ float wave_reduce_sum(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o, 64);
+  return v;
+}
+__device__ __forceinline__ float wave_reduce_max(float v) {
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o, 64));
+  return v;
+}

@@ -1,0 +1,700 @@
+// C ABI of the DFlash speculative-decoding step (see include/dflash.h) and the host-side
+// orchestration that enqueues the gfx950 kernels.  No device memory is allocated here.
+#include "../../include/dflash.h"
+
+#include <hip/hip_runtime.h>
+#include <math.h>
+#include <stdarg.h>
+#include <stdio.h>
+#include <string.h>
+
+#include <algorithm>
+#include <new>
+
+#include "attn.h"
+#include "attn_mfma.h"
+#include "common.h"
+#include "gemm.h"
+#include "misc.h"
+
+namespace {
+
+thread_local char g_err[512] = "";
+
+int fail(char* dst, int code, const char* fmt, ...) {
+  va_list ap;
+  va_start(ap, fmt);
+  vsnprintf(g_err, sizeof g_err, fmt, ap);
+  va_end(ap);
+  if (dst) memcpy(dst, g_err, sizeof g_err);
+  return code;
+}
+
+inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
+inline size_t esize(int dtype) { return dtype == DFLASH_BF16 ? 2 : 4; }
+inline int round_rows(int dtype, int M) { return dtype == DFLASH_BF16 ? (M + 15) & ~15 : M; }
+
+struct LayerOff {
+  size_t wqkv, wo, wgu, wd, g1, g2, qn, kn, end;
+};
+
+LayerOff layer_layout(const dflash_dims& d) {
+  const size_t es = esize(d.dtype);
+  const size_t qd = (size_t)d.n_q_heads * d.head_dim, kd = (size_t)d.n_kv_heads * d.head_dim;
+  LayerOff o;
+  size_t off = 0;
+  o.wqkv = off; off += align256((qd + 2 * kd) * d.d_model * es);
+  o.wo = off;   off += align256((size_t)d.d_model * qd * es);
+  o.wgu = off;  off += align256((size_t)2 * d.d_ffn * d.d_model * es);
+  o.wd = off;   off += align256((size_t)d.d_model * d.d_ffn * es);
+  o.g1 = off;   off += align256((size_t)d.d_model * 4);
+  o.g2 = off;   off += align256((size_t)d.d_model * 4);
+  o.qn = off;   off += align256((size_t)d.head_dim * 4);
+  o.kn = off;   off += align256((size_t)d.head_dim * 4);
+  o.end = off;
+  return o;
+}
+
+struct TargetLayout {
+  size_t embed, lm, gf, layer0, total;
+  LayerOff lo;
+};
+TargetLayout target_layout(const dflash_dims& d) {
+  const size_t es = esize(d.dtype);
+  TargetLayout t;
+  size_t off = 0;
+  t.embed = off; off += align256((size_t)d.vocab * d.d_model * es);
+  t.lm = off;    off += align256((size_t)d.vocab * d.d_model * es);
+  t.gf = off;    off += align256((size_t)d.d_model * 4);
+  t.layer0 = off;
+  t.lo = layer_layout(d);
+  t.total = off + t.lo.end * d.n_layers;
+  return t;
+}
+
+struct DraftLayout {
+  size_t wc, gc, gf, wkv_all, layer0, total;
+  LayerOff lo;
+};
+DraftLayout draft_layout(const dflash_dims& d, int n_taps, int d_target) {
+  const size_t es = esize(d.dtype);
+  const size_t kd = (size_t)d.n_kv_heads * d.head_dim;
+  DraftLayout t;
+  size_t off = 0;
+  t.wc = off;      off += align256((size_t)d.d_model * n_taps * d_target * es);
+  t.gc = off;      off += align256((size_t)d.d_model * 4);
+  t.gf = off;      off += align256((size_t)d.d_model * 4);
+  t.wkv_all = off; off += align256((size_t)d.n_layers * 2 * kd * d.d_model * es);
+  t.layer0 = off;
+  t.lo = layer_layout(d);
+  t.total = off + t.lo.end * d.n_layers;
+  return t;
+}
+
+int check_dims(const dflash_dims* d, const char* who) {
+  if (!d) return fail(nullptr, DFLASH_EINVAL, "%s dims: null", who);
+  if (d->dtype != DFLASH_F32 && d->dtype != DFLASH_BF16) return fail(nullptr, DFLASH_EINVAL, "%s: dtype must be DFLASH_F32 or DFLASH_BF16", who);
+  if (d->n_layers < 1 || d->d_model < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 1 || d->vocab < 1)
+    return fail(nullptr, DFLASH_EINVAL, "%s: non-positive dimension", who);
+  if (d->n_q_heads % d->n_kv_heads) return fail(nullptr, DFLASH_EINVAL, "%s: n_q_heads must be a multiple of n_kv_heads", who);
+  if (d->head_dim > 128 || d->head_dim < 16 || d->head_dim % 16) return fail(nullptr, DFLASH_EINVAL, "%s: head_dim must be a multiple of 16 in [16,128]", who);
+  const int qd = d->n_q_heads * d->head_dim;
+  if (d->dtype == DFLASH_BF16) {
+    if (d->d_model % 32 || d->d_ffn % 32 || qd % 32 || d->vocab % 16)
+      return fail(nullptr, DFLASH_EINVAL, "%s: bf16 needs d_model, d_ffn, Hq*hd multiples of 32 and vocab a multiple of 16", who);
+  } else {
+    if (d->d_model % 8 || d->d_ffn % 16 || qd % 8) return fail(nullptr, DFLASH_EINVAL, "%s: fp32 needs d_model, Hq*hd multiples of 8 and d_ffn a multiple of 16", who);
+  }
+  if (!(d->rope_theta > 1.f) || !(d->rms_eps >= 0.f)) return fail(nullptr, DFLASH_EINVAL, "%s: bad rope_theta / rms_eps", who);
+  return DFLASH_OK;
+}
+
+// ---- attention split policy -----------------------------------------------------------------------
+struct SplitPlan {
+  int n_splits, chunk;
+  int bound;  // >= n_splits for this and every smaller max_tokens (sizes the partial buffers)
+};
+SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens) {
+  const int target_wgs = 1024, max_splits = 64;
+  int splits = (target_wgs + S * n_kv_heads - 1) / (S * n_kv_heads);
+  const int by_len = (max_tokens + 63) / 64;
+  splits = std::max(1, std::min(splits, std::min(by_len, max_splits)));
+  int chunk = (max_tokens + splits - 1) / splits;
+  chunk = (chunk + 63) & ~63;
+  SplitPlan p;
+  p.bound = splits;
+  p.chunk = chunk;
+  p.n_splits = (max_tokens + chunk - 1) / chunk;
+  return p;
+}
+
+// ---- workspace ------------------------------------------------------------------------------------
+struct Workspace {
+  size_t status, h, a, qkv, q, o, act, taps, fuse, ht, kvctx, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, total;
+};
+Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
+  const size_t es = esize(t.dtype);
+  const int M = rt.max_seqs * rt.block_size;
+  const size_t Mr = round_rows(t.dtype, M);
+  const size_t qd = (size_t)std::max(t.n_q_heads * t.head_dim, d.n_q_heads * d.head_dim);
+  const size_t nqkv = std::max((size_t)(t.n_q_heads + 2 * t.n_kv_heads) * t.head_dim, (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim);
+  const size_t F = std::max(t.d_ffn, d.d_ffn);
+  const size_t D = t.d_model;
+  Workspace w;
+  size_t off = 0;
+  auto take = [&](size_t bytes) { size_t r = off; off += align256(bytes); return r; };
+  w.status = take(256);
+  w.h = take((size_t)M * D * 4);
+  w.a = take(Mr * D * es);
+  w.qkv = take((size_t)M * nqkv * 4);
+  w.q = take((size_t)M * qd * es);
+  w.o = take(Mr * qd * es);
+  w.act = take(Mr * F * es);
+  w.taps = take(Mr * (size_t)rt.n_taps * D * es);
+  w.fuse = take((size_t)M * D * 4);
+  w.ht = take(Mr * D * es);
+  w.kvctx = take((size_t)M * d.n_layers * 2 * d.n_kv_heads * d.head_dim * 4);
+  w.logits_d = take((size_t)M * t.vocab * 4);
+  w.logits_t = take((size_t)M * t.vocab * 4);
+  // attention partials: worst case over batch sizes and both models
+  size_t part_rows = 0;
+  const int max_tokens = rt.max_pages_per_seq * DFLASH_PAGE_SIZE;
+  for (int S = 1; S <= rt.max_seqs; ++S) {
+    for (const dflash_dims* m : {&t, &d}) {
+      const SplitPlan p = plan_splits(S, m->n_kv_heads, max_tokens);
+      part_rows = std::max(part_rows, (size_t)S * rt.block_size * m->n_q_heads * p.bound);
+    }
+  }
+  const size_t hd = std::max(t.head_dim, d.head_dim);
+  w.part_o = take(part_rows * hd * 4);
+  w.part_ml = take(part_rows * 8);
+  w.stats_p = take((size_t)M * 8);
+  w.stats_q = take((size_t)M * 8);
+  w.total = off;
+  return w;
+}
+
+int check_runtime(const dflash_dims* t, const dflash_dims* d, const dflash_runtime* rt) {
+  if (!rt) return fail(nullptr, DFLASH_EINVAL, "runtime: null");
+  if (rt->block_size < 2 || rt->block_size > DFLASH_MAX_BLOCK) return fail(nullptr, DFLASH_EINVAL, "block_size must be in [2,%d]", DFLASH_MAX_BLOCK);
+  if (rt->max_seqs < 1 || rt->max_pages_per_seq < 1 || rt->n_pages < 1) return fail(nullptr, DFLASH_EINVAL, "max_seqs, max_pages_per_seq, n_pages must be positive");
+  if (rt->n_taps < 1 || rt->n_taps > DFLASH_MAX_TAPS) return fail(nullptr, DFLASH_EINVAL, "n_taps must be in [1,%d]", DFLASH_MAX_TAPS);
+  for (int i = 0; i < rt->n_taps; ++i) {
+    if (rt->tap_layers[i] < 0 || rt->tap_layers[i] >= t->n_layers || (i && rt->tap_layers[i] <= rt->tap_layers[i - 1]))
+      return fail(nullptr, DFLASH_EINVAL, "tap_layers must be ascending layer indices of the target");
+  }
+  if (rt->mask_token_id < 0 || rt->mask_token_id >= t->vocab) return fail(nullptr, DFLASH_EINVAL, "mask_token_id outside the vocabulary");
+  if (t->dtype != d->dtype) return fail(nullptr, DFLASH_EINVAL, "target and draft must share the dtype");
+  if (t->d_model != d->d_model || t->vocab != d->vocab) return fail(nullptr, DFLASH_EINVAL, "draft shares embedding and LM head: d_model and vocab must match the target");
+  if (t->dtype == DFLASH_BF16 && ((size_t)rt->n_taps * t->d_model) % 32) return fail(nullptr, DFLASH_EINVAL, "n_taps*d_model must be a multiple of 32");
+  for (const dflash_dims* m : {t, d})
+    if (rt->block_size * (m->n_q_heads / m->n_kv_heads) > 64) return fail(nullptr, DFLASH_EINVAL, "block_size * (n_q_heads/n_kv_heads) must not exceed 64");
+  return DFLASH_OK;
+}
+
+}  // namespace
+
+struct dflash_ctx {
+  dflash_dims t, d;
+  dflash_runtime rt;
+  TargetLayout tl;
+  DraftLayout dl;
+  Workspace ws;
+  const char* tblob;
+  const char* dblob;
+  char* wsp;
+  char err[512];
+};
+
+namespace {
+
+#define CTX_FAIL(ctx, code, ...) fail((ctx)->err, code, __VA_ARGS__)
+
+template <typename T>
+struct Engine {
+  dflash_ctx* c;
+  hipStream_t st;
+  int hip_err = 0;
+
+  void check() {
+    hipError_t e = hipGetLastError();
+    if (e != hipSuccess && !hip_err) {
+      hip_err = 1;
+      fail(c->err, DFLASH_EHIP, "HIP launch failed: %s", hipGetErrorString(e));
+    }
+  }
+  template <typename P> P* ws(size_t off) { return reinterpret_cast<P*>(c->wsp + off); }
+  int32_t* status() { return ws<int32_t>(c->ws.status); }
+
+  SeqGeom geom(const dflash_batch* b) {
+    SeqGeom g;
+    g.seq_lens = b->seq_lens;
+    g.block_table = b->block_table;
+    g.max_pages_per_seq = c->rt.max_pages_per_seq;
+    g.n_pages = c->rt.n_pages;
+    g.block_size = c->rt.block_size;
+    g.status = status();
+    return g;
+  }
+
+  // ---- GEMM dispatch ------------------------------------------------------------------------------
+  void gemm(const T* W, const T* A, int M, int N, int K, int epi, EpiArgs ep);
+
+  void rmsnorm(const float* x, const float* gain, T* out, int M, int D, float eps) {
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(M), dim3(256), 0, st, x, gain, out, D, eps);
+    check();
+  }
+
+  void attention(const dflash_dims& m, const T* pool, int layer, const dflash_batch* b, bool causal);
+
+  // one Transformer layer on the M block rows held in ws.h
+  void layer(const dflash_dims& m, const char* lbase, const LayerOff& lo, T* pool, int l, const dflash_batch* b, bool causal) {
+    const int S = b->n_seqs, B = c->rt.block_size, M = S * B, D = m.d_model;
+    const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, nqkv = qd + 2 * kd;
+    float* h = ws<float>(c->ws.h);
+    T* a = ws<T>(c->ws.a);
+    float* qkv = ws<float>(c->ws.qkv);
+    T* q = ws<T>(c->ws.q);
+    T* o = ws<T>(c->ws.o);
+    T* act = ws<T>(c->ws.act);
+    rmsnorm(h, reinterpret_cast<const float*>(lbase + lo.g1), a, M, D, m.rms_eps);
+    EpiArgs e{qkv, nqkv, nullptr, 0};
+    gemm(reinterpret_cast<const T*>(lbase + lo.wqkv), a, M, nqkv, D, EPI_STORE, e);
+    RopeArgs ra;
+    ra.n_q_heads = m.n_q_heads; ra.n_kv_heads = m.n_kv_heads; ra.head_dim = m.head_dim;
+    ra.q_off = 0; ra.k_off = qd; ra.v_off = qd + kd;
+    ra.qk_norm = m.qk_norm; ra.eps = m.rms_eps; ra.log_theta = log((double)m.rope_theta); ra.layer = l;
+    hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, m.n_q_heads + 2 * m.n_kv_heads), dim3(64), 0, st, qkv, nqkv,
+                       reinterpret_cast<const float*>(lbase + lo.qn), reinterpret_cast<const float*>(lbase + lo.kn), q, pool,
+                       geom(b), ra);
+    check();
+    attention(m, pool, l, b, causal);
+    EpiArgs e2{h, D, nullptr, 0};
+    gemm(reinterpret_cast<const T*>(lbase + lo.wo), o, M, D, qd, EPI_RESID, e2);
+    rmsnorm(h, reinterpret_cast<const float*>(lbase + lo.g2), a, M, D, m.rms_eps);
+    EpiArgs e3{nullptr, 0, act, m.d_ffn};
+    gemm(reinterpret_cast<const T*>(lbase + lo.wgu), a, M, 2 * m.d_ffn, D, EPI_SWIGLU, e3);
+    EpiArgs e4{h, D, nullptr, 0};
+    gemm(reinterpret_cast<const T*>(lbase + lo.wd), act, M, D, m.d_ffn, EPI_RESID, e4);
+  }
+
+  void lm_head(const float* final_gain, float eps, int M, float* logits) {
+    const dflash_dims& t = c->t;
+    T* a = ws<T>(c->ws.a);
+    rmsnorm(ws<float>(c->ws.h), final_gain, a, M, t.d_model, eps);
+    EpiArgs e{logits, t.vocab, nullptr, 0};
+    gemm(reinterpret_cast<const T*>(c->tblob + c->tl.lm), a, M, t.vocab, t.d_model, EPI_STORE, e);
+  }
+
+  int draft_block(const dflash_batch* b, float temperature, const uint64_t* rng_key, int32_t* draft_tokens, float* logits_out) {
+    const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+    const dflash_dims& d = c->d;
+    hipLaunchKernelGGL(build_block_kernel, dim3((M + 255) / 256), dim3(256), 0, st, b->anchor, draft_tokens, S, B, c->rt.mask_token_id);
+    check();
+    hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), draft_tokens,
+                       ws<float>(c->ws.h), d.d_model, d.vocab, status());
+    check();
+    for (int i = 0; i < d.n_layers; ++i)
+      layer(d, c->dblob + c->dl.layer0 + c->dl.lo.end * i, c->dl.lo, reinterpret_cast<T*>(c->rt.draft_kv_pool), i, b, false);
+    float* logits = ws<float>(c->ws.logits_d);
+    lm_head(reinterpret_cast<const float*>(c->dblob + c->dl.gf), d.rms_eps, M, logits);
+    const int mode = temperature > 0.f ? 1 : 0;
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(1024), 0, st, logits, d.vocab, B, draft_tokens, 1, mode,
+                       mode ? 1.0f / temperature : 1.0f, rng_key);
+    check();
+    if (logits_out) {
+      if (hipMemcpyAsync(logits_out, logits, (size_t)M * d.vocab * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return CTX_FAIL(c, DFLASH_EHIP, "logits copy failed");
+    }
+    return hip_err ? DFLASH_EHIP : DFLASH_OK;
+  }
+
+  int verify(const dflash_batch* b, const int32_t* tokens, int32_t* tgt_argmax, float* logits_out) {
+    const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+    const dflash_dims& t = c->t;
+    hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), tokens,
+                       ws<float>(c->ws.h), t.d_model, t.vocab, status());
+    check();
+    int tap = 0;
+    for (int l = 0; l < t.n_layers; ++l) {
+      layer(t, c->tblob + c->tl.layer0 + c->tl.lo.end * l, c->tl.lo, reinterpret_cast<T*>(c->rt.target_kv_pool), l, b, true);
+      if (tap < c->rt.n_taps && c->rt.tap_layers[tap] == l) {
+        hipLaunchKernelGGL(tap_copy_kernel<T>, dim3(M), dim3(256), 0, st, ws<float>(c->ws.h), ws<T>(c->ws.taps), t.d_model, tap,
+                           c->rt.n_taps * t.d_model);
+        check();
+        ++tap;
+      }
+    }
+    float* logits = ws<float>(c->ws.logits_t);
+    lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits);
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(1024), 0, st, logits, t.vocab, B, tgt_argmax, 0, 0, 1.0f,
+                       (const uint64_t*)nullptr);
+    check();
+    if (logits_out) {
+      if (hipMemcpyAsync(logits_out, logits, (size_t)M * t.vocab * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
+        return CTX_FAIL(c, DFLASH_EHIP, "logits copy failed");
+    }
+    return hip_err ? DFLASH_EHIP : DFLASH_OK;
+  }
+
+  int accept(const dflash_batch* b, const int32_t* draft_tokens, const int32_t* tgt_argmax, float temperature, const float* uniforms,
+             const uint64_t* rng_key, int32_t* accept_len, int32_t* out_tokens) {
+    const int S = b->n_seqs, B = c->rt.block_size, M = S * B, V = c->t.vocab;
+    if (temperature <= 0.f) {
+      hipLaunchKernelGGL(accept_greedy_kernel, dim3((S + 63) / 64), dim3(64), 0, st, draft_tokens, tgt_argmax, S, B, accept_len, out_tokens);
+      check();
+    } else {
+      const float inv_T = 1.0f / temperature;
+      hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, ws<float>(c->ws.logits_t), V, inv_T, ws<float2>(c->ws.stats_p));
+      check();
+      hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, ws<float>(c->ws.logits_d), V, inv_T, ws<float2>(c->ws.stats_q));
+      check();
+      hipLaunchKernelGGL(accept_sampling_kernel, dim3(S), dim3(1024), 0, st, ws<float>(c->ws.logits_t), ws<float>(c->ws.logits_d),
+                         ws<float2>(c->ws.stats_p), ws<float2>(c->ws.stats_q), draft_tokens, uniforms, rng_key, V, B, inv_T,
+                         accept_len, out_tokens);
+      check();
+    }
+    return hip_err ? DFLASH_EHIP : DFLASH_OK;
+  }
+
+  int commit(const dflash_batch* b, const int32_t* accept_len, const int32_t* out_tokens, int64_t* kv_slots) {
+    const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+    const dflash_dims& d = c->d;
+    const int D = d.d_model, kd = d.n_kv_heads * d.head_dim, nkv = d.n_layers * 2 * kd;
+    float* fuse = ws<float>(c->ws.fuse);
+    T* ht = ws<T>(c->ws.ht);
+    float* kvctx = ws<float>(c->ws.kvctx);
+    EpiArgs e{fuse, D, nullptr, 0};
+    gemm(reinterpret_cast<const T*>(c->dblob + c->dl.wc), ws<T>(c->ws.taps), M, D, c->rt.n_taps * c->t.d_model, EPI_STORE, e);
+    rmsnorm(fuse, reinterpret_cast<const float*>(c->dblob + c->dl.gc), ht, M, D, d.rms_eps);
+    EpiArgs e2{kvctx, nkv, nullptr, 0};
+    gemm(reinterpret_cast<const T*>(c->dblob + c->dl.wkv_all), ht, M, nkv, D, EPI_STORE, e2);
+    for (int i = 0; i < d.n_layers; ++i) {
+      RopeArgs ra;
+      ra.n_q_heads = 0; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = d.head_dim;
+      ra.q_off = 0; ra.k_off = i * 2 * kd; ra.v_off = i * 2 * kd + kd;
+      ra.qk_norm = d.qk_norm; ra.eps = d.rms_eps; ra.log_theta = log((double)d.rope_theta); ra.layer = i;
+      const char* lbase = c->dblob + c->dl.layer0 + c->dl.lo.end * i;
+      hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, 2 * d.n_kv_heads), dim3(64), 0, st, kvctx, nkv, (const float*)nullptr,
+                         reinterpret_cast<const float*>(lbase + c->dl.lo.kn), (T*)nullptr, reinterpret_cast<T*>(c->rt.draft_kv_pool),
+                         geom(b), ra);
+      check();
+    }
+    hipLaunchKernelGGL(commit_update_kernel, dim3((S + 63) / 64), dim3(64), 0, st, geom(b), b->seq_lens, b->anchor, accept_len,
+                       out_tokens, S, kv_slots);
+    check();
+    return hip_err ? DFLASH_EHIP : DFLASH_OK;
+  }
+};
+
+// ---- GEMM dispatch ----------------------------------------------------------------------------------
+template <int NT, int MT>
+void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep) {
+  const dim3 grid((N / 16) / NT, ((M + 15) / 16 + MT - 1) / MT), block(256);
+  switch (epi) {
+    case EPI_STORE: hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, ep); break;
+    case EPI_RESID: hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, EPI_RESID>), grid, block, 0, st, W, A, M, N, K, ep); break;
+    default:
+      if constexpr (NT >= 2) hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, ep);
+      break;
+  }
+}
+
+template <>
+void Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep) {
+  const int nt = N / 16;
+  if (M <= 16) {
+    if (nt % 4 == 0) launch_bf16<4, 1>(st, W, A, M, N, K, epi, ep);
+    else if (nt % 2 == 0) launch_bf16<2, 1>(st, W, A, M, N, K, epi, ep);
+    else launch_bf16<1, 1>(st, W, A, M, N, K, epi, ep);
+  } else {
+    if (nt % 2 == 0) launch_bf16<2, 4>(st, W, A, M, N, K, epi, ep);
+    else launch_bf16<1, 4>(st, W, A, M, N, K, epi, ep);
+  }
+  check();
+}
+
+template <>
+void Engine<float>::gemm(const float* W, const float* A, int M, int N, int K, int epi, EpiArgs ep) {
+  const int cols = epi == EPI_SWIGLU ? N / 2 : N;
+  const dim3 grid((cols + 3) / 4), block(256);
+  switch (epi) {
+    case EPI_STORE: hipLaunchKernelGGL(gemm_f32_kernel<EPI_STORE>, grid, block, 0, st, W, A, M, N, K, ep); break;
+    case EPI_RESID: hipLaunchKernelGGL(gemm_f32_kernel<EPI_RESID>, grid, block, 0, st, W, A, M, N, K, ep); break;
+    default: hipLaunchKernelGGL(gemm_f32_kernel<EPI_SWIGLU>, grid, block, 0, st, W, A, M, N, K, ep); break;
+  }
+  check();
+}
+
+template <typename T>
+void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const dflash_batch* b, bool causal) {
+  const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+  const int max_tokens = std::min(b->max_seq_len + B, c->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
+  const SplitPlan p = plan_splits(S, m.n_kv_heads, max_tokens);
+  AttnArgs aa;
+  aa.n_q_heads = m.n_q_heads; aa.n_kv_heads = m.n_kv_heads; aa.head_dim = m.head_dim; aa.layer = layer;
+  aa.causal = causal ? 1 : 0; aa.chunk = p.chunk; aa.n_splits = p.n_splits; aa.scale = 1.0f / sqrtf((float)m.head_dim);
+  float* part_o = ws<float>(c->ws.part_o);
+  float2* part_ml = ws<float2>(c->ws.part_ml);
+  if (!attn_mfma_launch<T>(st, ws<T>(c->ws.q), pool, geom(b), aa, S, part_o, part_ml))
+    hipLaunchKernelGGL(attn_partial_simple_kernel<T>, dim3(p.n_splits, m.n_kv_heads, S), dim3(256), 0, st, ws<T>(c->ws.q), pool, geom(b),
+                       aa, part_o, part_ml);
+  check();
+  hipLaunchKernelGGL(attn_merge_kernel<T>, dim3(M * m.n_q_heads), dim3(128), 0, st, part_o, part_ml, ws<T>(c->ws.o), m.n_q_heads,
+                     m.head_dim, p.n_splits);
+  check();
+}
+
+// ---- packing helpers -----------------------------------------------------------------------------------
+template <typename T>
+int pack_rows(hipStream_t st, PackSrc ps, int K, int total_rows, void* dst) {
+  const size_t chunks = (size_t)total_rows * (K / 8);
+  hipLaunchKernelGGL(pack_kernel<T>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, ps, K, total_rows, reinterpret_cast<T*>(dst));
+  return hipGetLastError() == hipSuccess ? DFLASH_OK : fail(nullptr, DFLASH_EHIP, "pack launch failed");
+}
+int pack_any(int dtype, hipStream_t st, PackSrc ps, int K, int rows, void* dst) {
+  return dtype == DFLASH_BF16 ? pack_rows<bf16_t>(st, ps, K, rows, dst) : pack_rows<float>(st, ps, K, rows, dst);
+}
+PackSrc one(const void* p, int rows) {
+  PackSrc s{};
+  s.src[0] = p; s.rows[0] = rows; s.n_src = 1; s.mode = 0;
+  return s;
+}
+int copy_f32(hipStream_t st, void* dst, const float* src, size_t n) {
+  return hipMemcpyAsync(dst, src, n * 4, hipMemcpyDeviceToDevice, st) == hipSuccess ? DFLASH_OK : fail(nullptr, DFLASH_EHIP, "gain copy failed");
+}
+
+int pack_layer_common(const dflash_dims& d, const LayerOff& lo, char* lbase, const dflash_layer_weights* w, hipStream_t st) {
+  if (!w || !w->wq || !w->wk || !w->wv || !w->wo || !w->wg || !w->wu || !w->wd || !w->g1 || !w->g2)
+    return fail(nullptr, DFLASH_EINVAL, "layer weights: null pointer");
+  if (d.qk_norm && (!w->qn || !w->kn)) return fail(nullptr, DFLASH_EINVAL, "layer weights: qk_norm set but qn/kn null");
+  const int qd = d.n_q_heads * d.head_dim, kd = d.n_kv_heads * d.head_dim;
+  int rc;
+  PackSrc qkv{};
+  qkv.src[0] = w->wq; qkv.src[1] = w->wk; qkv.src[2] = w->wv;
+  qkv.rows[0] = qd; qkv.rows[1] = kd; qkv.rows[2] = kd; qkv.n_src = 3; qkv.mode = 0;
+  if ((rc = pack_any(d.dtype, st, qkv, d.d_model, qd + 2 * kd, lbase + lo.wqkv))) return rc;
+  if ((rc = pack_any(d.dtype, st, one(w->wo, d.d_model), qd, d.d_model, lbase + lo.wo))) return rc;
+  PackSrc gu{};
+  gu.src[0] = w->wg; gu.src[1] = w->wu; gu.rows[0] = gu.rows[1] = d.d_ffn; gu.n_src = 2; gu.mode = 1;
+  if ((rc = pack_any(d.dtype, st, gu, d.d_model, 2 * d.d_ffn, lbase + lo.wgu))) return rc;
+  if ((rc = pack_any(d.dtype, st, one(w->wd, d.d_model), d.d_ffn, d.d_model, lbase + lo.wd))) return rc;
+  if ((rc = copy_f32(st, lbase + lo.g1, w->g1, d.d_model))) return rc;
+  if ((rc = copy_f32(st, lbase + lo.g2, w->g2, d.d_model))) return rc;
+  if (d.qk_norm) {
+    if ((rc = copy_f32(st, lbase + lo.qn, w->qn, d.head_dim))) return rc;
+    if ((rc = copy_f32(st, lbase + lo.kn, w->kn, d.head_dim))) return rc;
+  }
+  return DFLASH_OK;
+}
+
+template <typename T>
+int run_kv_copy(dflash_ctx* ctx, const dflash_batch* b, int pool, int layer, int seq, int start, int count, float* k, float* v, int dir,
+                hipStream_t st) {
+  const dflash_dims& m = pool == DFLASH_POOL_TARGET ? ctx->t : ctx->d;
+  Engine<T> e{ctx, st};
+  T* p = reinterpret_cast<T*>(pool == DFLASH_POOL_TARGET ? ctx->rt.target_kv_pool : ctx->rt.draft_kv_pool);
+  hipLaunchKernelGGL(kv_copy_kernel<T>, dim3(count, m.n_kv_heads), dim3(128), 0, st, p, e.geom(b), layer, m.n_kv_heads, m.head_dim, seq,
+                     start, k, v, dir);
+  e.check();
+  return e.hip_err ? DFLASH_EHIP : DFLASH_OK;
+}
+
+int check_batch(dflash_ctx* ctx, const dflash_batch* b) {
+  if (!ctx) return fail(nullptr, DFLASH_EINVAL, "ctx: null");
+  if (!b || !b->seq_lens || !b->block_table || !b->anchor) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: null pointer");
+  if (b->n_seqs < 1 || b->n_seqs > ctx->rt.max_seqs) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: n_seqs %d outside [1,%d]", b->n_seqs, ctx->rt.max_seqs);
+  if (b->max_seq_len < 0) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: negative max_seq_len");
+  if ((int64_t)b->max_seq_len + ctx->rt.block_size > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE)
+    return CTX_FAIL(ctx, DFLASH_ECAPACITY, "batch: max_seq_len %d + block %d exceeds the %d tokens a block-table row covers", b->max_seq_len,
+                    ctx->rt.block_size, ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
+  return DFLASH_OK;
+}
+
+}  // namespace
+
+// =====================================================================================================
+extern "C" {
+
+size_t dflash_target_blob_bytes(const dflash_dims* target) {
+  if (check_dims(target, "target")) return 0;
+  return target_layout(*target).total;
+}
+size_t dflash_draft_blob_bytes(const dflash_dims* draft, int32_t n_taps, int32_t d_target) {
+  if (check_dims(draft, "draft") || n_taps < 1 || d_target < 1) return 0;
+  return draft_layout(*draft, n_taps, d_target).total;
+}
+size_t dflash_kv_pool_bytes(const dflash_dims* m, int32_t n_pages) {
+  if (check_dims(m, "model") || n_pages < 1) return 0;
+  return (size_t)m->n_layers * n_pages * m->n_kv_heads * 2 * DFLASH_PAGE_SIZE * m->head_dim * esize(m->dtype);
+}
+size_t dflash_workspace_bytes(const dflash_dims* target, const dflash_dims* draft, const dflash_runtime* rt) {
+  if (check_dims(target, "target") || check_dims(draft, "draft") || check_runtime(target, draft, rt)) return 0;
+  return workspace_layout(*target, *draft, *rt).total;
+}
+
+int dflash_pack_target_head(const dflash_dims* target, const void* embed, const void* lm_head, const float* final_gain, void* blob,
+                            void* stream) {
+  int rc;
+  if ((rc = check_dims(target, "target"))) return rc;
+  if (!embed || !lm_head || !final_gain || !blob) return fail(nullptr, DFLASH_EINVAL, "pack_target_head: null pointer");
+  const TargetLayout tl = target_layout(*target);
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)blob;
+  if (hipMemcpyAsync(base + tl.embed, embed, (size_t)target->vocab * target->d_model * esize(target->dtype), hipMemcpyDeviceToDevice, st) != hipSuccess)
+    return fail(nullptr, DFLASH_EHIP, "embedding copy failed");
+  if ((rc = pack_any(target->dtype, st, one(lm_head, target->vocab), target->d_model, target->vocab, base + tl.lm))) return rc;
+  return copy_f32(st, base + tl.gf, final_gain, target->d_model);
+}
+
+int dflash_pack_target_layer(const dflash_dims* target, int32_t layer, const dflash_layer_weights* w, void* blob, void* stream) {
+  int rc;
+  if ((rc = check_dims(target, "target"))) return rc;
+  if (!blob || layer < 0 || layer >= target->n_layers) return fail(nullptr, DFLASH_EINVAL, "pack_target_layer: bad layer or blob");
+  const TargetLayout tl = target_layout(*target);
+  return pack_layer_common(*target, tl.lo, (char*)blob + tl.layer0 + tl.lo.end * layer, w, (hipStream_t)stream);
+}
+
+int dflash_pack_draft_head(const dflash_dims* draft, int32_t n_taps, int32_t d_target, const void* w_c, const float* g_c,
+                           const float* final_gain, void* blob, void* stream) {
+  int rc;
+  if ((rc = check_dims(draft, "draft"))) return rc;
+  if (!w_c || !g_c || !final_gain || !blob || n_taps < 1 || d_target < 1) return fail(nullptr, DFLASH_EINVAL, "pack_draft_head: bad argument");
+  if (draft->dtype == DFLASH_BF16 && ((size_t)n_taps * d_target) % 32) return fail(nullptr, DFLASH_EINVAL, "n_taps*d_target must be a multiple of 32");
+  const DraftLayout dl = draft_layout(*draft, n_taps, d_target);
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)blob;
+  if ((rc = pack_any(draft->dtype, st, one(w_c, draft->d_model), n_taps * d_target, draft->d_model, base + dl.wc))) return rc;
+  if ((rc = copy_f32(st, base + dl.gc, g_c, draft->d_model))) return rc;
+  return copy_f32(st, base + dl.gf, final_gain, draft->d_model);
+}
+
+int dflash_pack_draft_layer(const dflash_dims* draft, int32_t n_taps, int32_t d_target, int32_t layer, const dflash_layer_weights* w,
+                            void* blob, void* stream) {
+  int rc;
+  if ((rc = check_dims(draft, "draft"))) return rc;
+  if (!blob || layer < 0 || layer >= draft->n_layers || n_taps < 1 || d_target < 1) return fail(nullptr, DFLASH_EINVAL, "pack_draft_layer: bad argument");
+  const DraftLayout dl = draft_layout(*draft, n_taps, d_target);
+  hipStream_t st = (hipStream_t)stream;
+  char* base = (char*)blob;
+  if ((rc = pack_layer_common(*draft, dl.lo, base + dl.layer0 + dl.lo.end * layer, w, st))) return rc;
+  // second copy of this layer's W_K, W_V rows inside the all-layers matrix used at commit
+  const int kd = draft->n_kv_heads * draft->head_dim;
+  PackSrc kv{};
+  kv.src[0] = w->wk; kv.src[1] = w->wv; kv.rows[0] = kv.rows[1] = kd; kv.n_src = 2; kv.mode = 0;
+  char* dst = base + dl.wkv_all + (size_t)layer * 2 * kd * draft->d_model * esize(draft->dtype);
+  return pack_any(draft->dtype, st, kv, draft->d_model, 2 * kd, dst);
+}
+
+int dflash_create(const dflash_dims* target, const void* target_blob, const dflash_dims* draft, const void* draft_blob,
+                  const dflash_runtime* rt, dflash_ctx** out) {
+  int rc;
+  if (!out) return fail(nullptr, DFLASH_EINVAL, "create: out is null");
+  *out = nullptr;
+  if ((rc = check_dims(target, "target")) || (rc = check_dims(draft, "draft")) || (rc = check_runtime(target, draft, rt))) return rc;
+  if (!target_blob || !draft_blob) return fail(nullptr, DFLASH_EINVAL, "create: null blob");
+  if (!rt->target_kv_pool || !rt->draft_kv_pool || !rt->workspace) return fail(nullptr, DFLASH_EINVAL, "create: null pool or workspace");
+  if (((uintptr_t)rt->workspace & 255) || ((uintptr_t)rt->target_kv_pool & 255) || ((uintptr_t)rt->draft_kv_pool & 255) ||
+      ((uintptr_t)target_blob & 255) || ((uintptr_t)draft_blob & 255))
+    return fail(nullptr, DFLASH_EINVAL, "create: buffers must be 256-byte aligned");
+  if ((draft->n_layers * 2 * draft->n_kv_heads * draft->head_dim) % 16) return fail(nullptr, DFLASH_EINVAL, "draft K/V width must be a multiple of 16");
+  const Workspace ws = workspace_layout(*target, *draft, *rt);
+  if (rt->workspace_bytes < ws.total) return fail(nullptr, DFLASH_EWORKSPACE, "create: workspace has %zu bytes, %zu needed", rt->workspace_bytes, ws.total);
+  dflash_ctx* c = new (std::nothrow) dflash_ctx;
+  if (!c) return fail(nullptr, DFLASH_EINVAL, "create: out of host memory");
+  c->t = *target; c->d = *draft; c->rt = *rt;
+  c->tl = target_layout(*target);
+  c->dl = draft_layout(*draft, rt->n_taps, target->d_model);
+  c->ws = ws;
+  c->tblob = (const char*)target_blob; c->dblob = (const char*)draft_blob; c->wsp = (char*)rt->workspace;
+  c->err[0] = 0;
+  if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {
+    delete c;
+    return fail(nullptr, DFLASH_EHIP, "create: cannot clear the device status word");
+  }
+  *out = c;
+  return DFLASH_OK;
+}
+
+int dflash_destroy(dflash_ctx* ctx) {
+  delete ctx;
+  return DFLASH_OK;
+}
+
+const char* dflash_last_error(const dflash_ctx* ctx) { return ctx ? ctx->err : g_err; }
+
+int dflash_device_status(dflash_ctx* ctx, void* stream) {
+  if (!ctx) return fail(nullptr, DFLASH_EINVAL, "ctx: null");
+  int32_t v = 0;
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "stream synchronise failed");
+  if (hipMemcpy(&v, ctx->wsp + ctx->ws.status, 4, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "status read failed");
+  if (v) {
+    if (hipMemset(ctx->wsp + ctx->ws.status, 0, 4) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "status clear failed");
+    return CTX_FAIL(ctx, DFLASH_ECAPACITY, "device: a row addressed a page outside the block table / pool, or a token id outside the vocabulary");
+  }
+  return DFLASH_OK;
+}
+
+#define DISPATCH(ctx, call)                                                        \
+  ((ctx)->t.dtype == DFLASH_BF16 ? Engine<bf16_t>{(ctx), (hipStream_t)stream}.call \
+                                 : Engine<float>{(ctx), (hipStream_t)stream}.call)
+
+int dflash_draft_block(dflash_ctx* ctx, const dflash_batch* batch, float temperature, const uint64_t* rng_key, int32_t* draft_tokens,
+                       float* logits_out, void* stream) {
+  int rc;
+  if ((rc = check_batch(ctx, batch))) return rc;
+  if (!draft_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "draft_block: draft_tokens is null");
+  if (!(temperature >= 0.f)) return CTX_FAIL(ctx, DFLASH_EINVAL, "draft_block: negative temperature");
+  if (temperature > 0.f && !rng_key) return CTX_FAIL(ctx, DFLASH_EINVAL, "draft_block: sampling needs rng_key");
+  return DISPATCH(ctx, draft_block(batch, temperature, rng_key, draft_tokens, logits_out));
+}
+
+int dflash_verify(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* tokens, int32_t* tgt_argmax, float* logits_out, void* stream) {
+  int rc;
+  if ((rc = check_batch(ctx, batch))) return rc;
+  if (!tokens || !tgt_argmax) return CTX_FAIL(ctx, DFLASH_EINVAL, "verify: null tokens or tgt_argmax");
+  return DISPATCH(ctx, verify(batch, tokens, tgt_argmax, logits_out));
+}
+
+int dflash_accept(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* draft_tokens, const int32_t* tgt_argmax, float temperature,
+                  const float* uniforms, const uint64_t* rng_key, int32_t* accept_len, int32_t* out_tokens, void* stream) {
+  int rc;
+  if ((rc = check_batch(ctx, batch))) return rc;
+  if (!draft_tokens || !tgt_argmax || !accept_len || !out_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: null pointer");
+  if (!(temperature >= 0.f)) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: negative temperature");
+  if (temperature > 0.f && (!uniforms || !rng_key)) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: sampling needs uniforms and rng_key");
+  return DISPATCH(ctx, accept(batch, draft_tokens, tgt_argmax, temperature, uniforms, rng_key, accept_len, out_tokens));
+}
+
+int dflash_kv_commit(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* accept_len, const int32_t* out_tokens, int64_t* kv_slots_out,
+                     void* stream) {
+  int rc;
+  if ((rc = check_batch(ctx, batch))) return rc;
+  if (!accept_len || !out_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "kv_commit: null pointer");
+  return DISPATCH(ctx, commit(batch, accept_len, out_tokens, kv_slots_out));
+}
+
+static int kv_copy_checked(dflash_ctx* ctx, const dflash_batch* batch, int32_t pool, int32_t layer, int32_t seq, int32_t start, int32_t count,
+                           float* k, float* v, int dir, void* stream) {
+  int rc;
+  if ((rc = check_batch(ctx, batch))) return rc;
+  if (pool != DFLASH_POOL_TARGET && pool != DFLASH_POOL_DRAFT) return CTX_FAIL(ctx, DFLASH_EINVAL, "kv copy: bad pool");
+  const dflash_dims& m = pool == DFLASH_POOL_TARGET ? ctx->t : ctx->d;
+  if (layer < 0 || layer >= m.n_layers || seq < 0 || seq >= batch->n_seqs || start < 0 || count < 0 || !k || !v)
+    return CTX_FAIL(ctx, DFLASH_EINVAL, "kv copy: bad layer, seq, range or pointer");
+  if ((int64_t)start + count > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE) return CTX_FAIL(ctx, DFLASH_ECAPACITY, "kv copy: range beyond the block table");
+  if (count == 0) return DFLASH_OK;
+  return ctx->t.dtype == DFLASH_BF16 ? run_kv_copy<bf16_t>(ctx, batch, pool, layer, seq, start, count, k, v, dir, (hipStream_t)stream)
+                                     : run_kv_copy<float>(ctx, batch, pool, layer, seq, start, count, k, v, dir, (hipStream_t)stream);
+}
+
+int dflash_kv_read(dflash_ctx* ctx, const dflash_batch* batch, int32_t pool, int32_t layer, int32_t seq, int32_t start, int32_t count,
+                   float* k, float* v, void* stream) {
+  return kv_copy_checked(ctx, batch, pool, layer, seq, start, count, k, v, 0, stream);
+}
+int dflash_kv_write(dflash_ctx* ctx, const dflash_batch* batch, int32_t pool, int32_t layer, int32_t seq, int32_t start, int32_t count,
+                    const float* k, const float* v, void* stream) {
+  return kv_copy_checked(ctx, batch, pool, layer, seq, start, count, const_cast<float*>(k), const_cast<float*>(v), 1, stream);
+}
+
+}  // extern "C"

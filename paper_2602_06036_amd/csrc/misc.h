@@ -1,0 +1,370 @@
+// Small memory-bound kernels of the step: embedding gather, RMSNorm, q/k-norm + RoPE + KV page
+// write, tap copy, row argmax / Gumbel-max, acceptance, commit bookkeeping, weight packing and
+// KV import/export.
+#pragma once
+#include "common.h"
+
+// ---- block assembly + embedding gather -------------------------------------------------------
+// tokens_out[s, 0] = anchor[s], tokens_out[s, j>0] = mask_id   (Section 4.2: clean anchor + masks)
+__global__ void build_block_kernel(const int32_t* __restrict__ anchor, int32_t* __restrict__ tokens_out, int S, int B,
+                                   int mask_id) {
+  const int i = blockIdx.x * blockDim.x + threadIdx.x;
+  if (i < S * B) tokens_out[i] = (i % B == 0) ? anchor[i / B] : mask_id;
+}
+
+// h[m, :] = float(E[tokens[m], :]); ids outside the vocabulary raise the status flag and read row 0
+template <typename T>
+__global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
+                                                    float* __restrict__ h, int D, int vocab, int32_t* status) {
+  const int m = blockIdx.x;
+  int tok = tokens[m];
+  if (tok < 0 || tok >= vocab) {
+    if (threadIdx.x == 0) atomicOr(status, DF_STATUS_CAPACITY);
+    tok = 0;
+  }
+  const T* src = E + (size_t)tok * D;
+  for (int d = threadIdx.x; d < D; d += blockDim.x) h[(size_t)m * D + d] = Store<T>::to(src[d]);
+}
+
+// ---- RMSNorm: fp32 rows [M, D] -> storage type in GEMM operand layout ----------------------------
+template <typename T>
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
+                                                      T* __restrict__ out, int D, float eps) {
+  const int m = blockIdx.x;
+  const float* row = x + (size_t)m * D;
+  float ss = 0.f;
+  for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
+    const float4 v = *reinterpret_cast<const float4*>(row + d);
+    ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
+  }
+  __shared__ float part[4];
+  ss = wave_reduce_sum(ss);
+  if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+  __syncthreads();
+  const float tot = part[0] + part[1] + part[2] + part[3];
+  const float rstd = 1.0f / sqrtf(tot / (float)D + eps);
+  for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
+    const float4 v = *reinterpret_cast<const float4*>(row + d);
+    const float4 g = *reinterpret_cast<const float4*>(gain + d);
+    T* dst = out + tile_index<T>(m, d, D);   // 4 consecutive k stay inside one 8-chunk
+    dst[0] = Store<T>::from(v.x * rstd * g.x);
+    dst[1] = Store<T>::from(v.y * rstd * g.y);
+    dst[2] = Store<T>::from(v.z * rstd * g.z);
+    dst[3] = Store<T>::from(v.w * rstd * g.w);
+  }
+}
+
+// ---- tap copy: taps[m, t*D + d] = storage(h[m, d]) in GEMM operand layout (row length n_taps*D) ---
+template <typename T>
+__global__ __launch_bounds__(256) void tap_copy_kernel(const float* __restrict__ h, T* __restrict__ taps, int D, int t,
+                                                       int K_total) {
+  const int m = blockIdx.x;
+  for (int d = threadIdx.x; d < D; d += blockDim.x)
+    taps[tile_index<T>(m, t * D + d, K_total)] = Store<T>::from(h[(size_t)m * D + d]);
+}
+
+// ---- q/k RMSNorm + RoPE + cache write ------------------------------------------------------------
+// One wavefront per (row m, head); lane i owns the rotate-half pair (i, i + hd/2) [hd <= 128].
+// Input row: fp32 [.. q heads | k heads | v heads ..] starting at in + m*in_ld.
+// q heads -> q_out [M, Hq, hd] row-major storage type; k/v heads -> page of position seq_len + slot.
+// Angles are formed in double precision (pos * theta^(-2i/hd), reduced by sincos) so that long
+// contexts do not lose phase accuracy.
+struct RopeArgs {
+  int n_q_heads, n_kv_heads, head_dim;
+  int q_off, k_off, v_off;  // element offsets inside an input row
+  int qk_norm;
+  float eps;
+  double log_theta;
+  int layer;                // layer index inside the pool
+};
+
+template <typename T>
+__global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ in, int in_ld, const float* __restrict__ qn,
+                                                      const float* __restrict__ kn, T* __restrict__ q_out,
+                                                      T* __restrict__ pool, SeqGeom geo, RopeArgs ra) {
+  const int m = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+  const int hd = ra.head_dim, half = hd >> 1;
+  const int s = m / geo.block_size, slot = m % geo.block_size;
+  const int pos = geo.seq_lens[s] + slot;
+  const bool is_q = head < ra.n_q_heads;
+  const bool is_k = !is_q && head < ra.n_q_heads + ra.n_kv_heads;
+  const int kvh = is_q ? 0 : (is_k ? head - ra.n_q_heads : head - ra.n_q_heads - ra.n_kv_heads);
+  const float* src = in + (size_t)m * in_ld + (is_q ? ra.q_off + head * hd : (is_k ? ra.k_off : ra.v_off) + kvh * hd);
+  const bool active = lane < half;
+  float x1 = active ? src[lane] : 0.f, x2 = active ? src[lane + half] : 0.f;
+  if (!is_q) {
+    const int pidx = pos / DF_PAGE;
+    int page = -1;
+    if (pos >= 0 && pidx < geo.max_pages_per_seq) page = geo.block_table[(size_t)s * geo.max_pages_per_seq + pidx];
+    if (page < 0 || page >= geo.n_pages) {
+      if (lane == 0) atomicOr(geo.status, DF_STATUS_CAPACITY);
+      return;
+    }
+    T* base = pool + kv_head_base(ra.layer, geo.n_pages, page, ra.n_kv_heads, kvh, hd);
+    const int key = pos % DF_PAGE;
+    if (!is_k) {
+      if (active) {
+        base[DF_PAGE * hd + v_in_page(key, lane)] = Store<T>::from(x1);
+        base[DF_PAGE * hd + v_in_page(key, lane + half)] = Store<T>::from(x2);
+      }
+      return;
+    }
+    if (ra.qk_norm) {
+      const float ss = wave_reduce_sum(x1 * x1 + x2 * x2);
+      const float rstd = 1.0f / sqrtf(ss / (float)hd + ra.eps);
+      if (active) { x1 *= rstd * kn[lane]; x2 *= rstd * kn[lane + half]; }
+    }
+    if (active) {
+      double sn, cs;
+      sincos((double)pos * exp(-ra.log_theta * (2.0 * lane / hd)), &sn, &cs);
+      const float c = (float)cs, sf = (float)sn;
+      base[k_in_page(key, lane)] = Store<T>::from(x1 * c - x2 * sf);
+      base[k_in_page(key, lane + half)] = Store<T>::from(x2 * c + x1 * sf);
+    }
+    return;
+  }
+  if (ra.qk_norm) {
+    const float ss = wave_reduce_sum(x1 * x1 + x2 * x2);
+    const float rstd = 1.0f / sqrtf(ss / (float)hd + ra.eps);
+    if (active) { x1 *= rstd * qn[lane]; x2 *= rstd * qn[lane + half]; }
+  }
+  if (active) {
+    double sn, cs;
+    sincos((double)pos * exp(-ra.log_theta * (2.0 * lane / hd)), &sn, &cs);
+    const float c = (float)cs, sf = (float)sn;
+    T* dst = q_out + ((size_t)m * ra.n_q_heads + head) * hd;
+    dst[lane] = Store<T>::from(x1 * c - x2 * sf);
+    dst[lane + half] = Store<T>::from(x2 * c + x1 * sf);
+  }
+}
+
+// ---- row argmax (ties -> lowest index), optionally of logit/T + Gumbel noise ---------------------
+__device__ __forceinline__ uint64_t mix64(uint64_t z) {
+  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
+  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
+  return z ^ (z >> 31);
+}
+// u in (0,1), 23 bits (so that x + 0.5 is exact in fp32): counter c = (((seq*64 + slot)*4 + purpose) << 32) | idx
+__device__ __forceinline__ float counter_uniform(uint64_t key, int seq, int slot, int purpose, uint32_t idx) {
+  const uint64_t c = ((uint64_t)(((uint32_t)seq * 64u + (uint32_t)slot) * 4u + (uint32_t)purpose) << 32) | idx;
+  const uint64_t z = mix64(key + 0x9E3779B97F4A7C15ull * (c + 1ull));
+  return ((float)(z >> 41) + 0.5f) * 1.1920928955078125e-7f;  // 2^-23
+}
+__device__ __forceinline__ float gumbel(float u) { return -logf(-logf(u)); }
+
+__device__ __forceinline__ void argmax_combine(float& bv, int& bi, float v, int i) {
+  if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
+}
+
+// block-wide (1024 threads) argmax; result valid in thread 0
+__device__ __forceinline__ void block_argmax(float& bv, int& bi) {
+  __shared__ float sv[16];
+  __shared__ int si[16];
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(bv, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    argmax_combine(bv, bi, ov, oi);
+  }
+  const int wave = threadIdx.x >> 6, nw = blockDim.x >> 6;
+  if ((threadIdx.x & 63) == 0) { sv[wave] = bv; si[wave] = bi; }
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    for (int w = 1; w < nw; ++w) argmax_combine(bv, bi, sv[w], si[w]);
+  }
+}
+
+// mode 0: greedy.  mode 1: draft sampling, score = logit * inv_T + Gumbel(key, seq, slot, purpose 0).
+// Writes out[m] unless (skip_slot0 && slot == 0).
+__global__ __launch_bounds__(1024) void argmax_rows_kernel(const float* __restrict__ logits, int V, int B, int32_t* __restrict__ out,
+                                                           int skip_slot0, int mode, float inv_T,
+                                                           const uint64_t* __restrict__ rng_key) {
+  const int m = blockIdx.x, slot = m % B, seq = m / B;
+  if (skip_slot0 && slot == 0) return;
+  const float* row = logits + (size_t)m * V;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  const uint64_t key = mode ? rng_key[0] : 0ull;
+  for (int i = threadIdx.x; i < V; i += blockDim.x) {
+    float v = row[i];
+    if (mode) v = v * inv_T + gumbel(counter_uniform(key, seq, slot, 0, (uint32_t)i));
+    argmax_combine(bv, bi, v, i);
+  }
+  block_argmax(bv, bi);
+  if (threadIdx.x == 0) out[m] = bi;
+}
+
+// ---- greedy acceptance (Section 3.1) ---------------------------------------------------------------
+__global__ void accept_greedy_kernel(const int32_t* __restrict__ draft, const int32_t* __restrict__ tgt, int S, int B,
+                                     int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= S) return;
+  const int32_t* d = draft + (size_t)s * B;
+  const int32_t* t = tgt + (size_t)s * B;
+  int a = 0;
+  while (a + 1 < B && d[a + 1] == t[a]) ++a;
+  accept_len[s] = a;
+  for (int j = 0; j < B; ++j) out_tokens[(size_t)s * B + j] = (j < a) ? d[j + 1] : (j == a ? t[a] : -1);
+}
+
+// ---- speculative sampling ---------------------------------------------------------------------------
+// per-row softmax statistics of logits * inv_T: stats[m] = (max, log-sum-exp)
+__global__ __launch_bounds__(1024) void row_lse_kernel(const float* __restrict__ logits, int V, float inv_T,
+                                                       float2* __restrict__ stats) {
+  const int m = blockIdx.x;
+  const float* row = logits + (size_t)m * V;
+  __shared__ float sh[16];
+  float mx = -INFINITY;
+  for (int i = threadIdx.x; i < V; i += blockDim.x) mx = fmaxf(mx, row[i] * inv_T);
+  mx = wave_reduce_max(mx);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = mx;
+  __syncthreads();
+  mx = sh[0];
+  for (int w = 1; w < (int)(blockDim.x >> 6); ++w) mx = fmaxf(mx, sh[w]);
+  __syncthreads();
+  float sum = 0.f;
+  for (int i = threadIdx.x; i < V; i += blockDim.x) sum += expf(row[i] * inv_T - mx);
+  sum = wave_reduce_sum(sum);
+  if ((threadIdx.x & 63) == 0) sh[threadIdx.x >> 6] = sum;
+  __syncthreads();
+  if (threadIdx.x == 0) {
+    float tot = 0.f;
+    for (int w = 0; w < (int)(blockDim.x >> 6); ++w) tot += sh[w];
+    stats[m] = make_float2(mx, mx + logf(tot));
+  }
+}
+
+// One block per sequence.  Thread 0 walks the slots: slot j accepted iff u_j * q_j(d_j) < p_{j-1}(d_j).
+// Then the whole block draws the final token by Gumbel-max over
+//   first rejected slot j: log max(p_{j-1} - q_j, 0)   (purpose 1, slot j)
+//   none rejected:         log p_{B-1}                 (purpose 2, slot B)
+__global__ __launch_bounds__(1024) void accept_sampling_kernel(const float* __restrict__ p_logits, const float* __restrict__ q_logits,
+                                                               const float2* __restrict__ p_stats, const float2* __restrict__ q_stats,
+                                                               const int32_t* __restrict__ draft, const float* __restrict__ uniforms,
+                                                               const uint64_t* __restrict__ rng_key, int V, int B, float inv_T,
+                                                               int32_t* __restrict__ accept_len, int32_t* __restrict__ out_tokens) {
+  const int s = blockIdx.x;
+  __shared__ int sh_a;
+  if (threadIdx.x == 0) {
+    int a = B - 1;
+    for (int j = 1; j < B; ++j) {
+      const int d = draft[(size_t)s * B + j];
+      const size_t mp = (size_t)s * B + j - 1, mq = (size_t)s * B + j;
+      const float p = expf(p_logits[mp * V + d] * inv_T - p_stats[mp].y);
+      const float q = expf(q_logits[mq * V + d] * inv_T - q_stats[mq].y);
+      if (!(uniforms[(size_t)s * B + j] * q < p)) { a = j - 1; break; }
+    }
+    sh_a = a;
+  }
+  __syncthreads();
+  const int a = sh_a;
+  const bool bonus = (a == B - 1);
+  // a rejection at slot j gives a = j-1 <= B-2, so a == B-1 means every slot was accepted
+  const uint64_t key = rng_key[0];
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  if (bonus) {
+    const size_t mp = (size_t)s * B + (B - 1);
+    for (int i = threadIdx.x; i < V; i += blockDim.x) {
+      const float v = p_logits[mp * V + i] * inv_T - p_stats[mp].y + gumbel(counter_uniform(key, s, B, 2, (uint32_t)i));
+      argmax_combine(bv, bi, v, i);
+    }
+  } else {
+    const int j = a + 1;
+    const size_t mp = (size_t)s * B + j - 1, mq = (size_t)s * B + j;
+    for (int i = threadIdx.x; i < V; i += blockDim.x) {
+      const float p = expf(p_logits[mp * V + i] * inv_T - p_stats[mp].y);
+      const float q = expf(q_logits[mq * V + i] * inv_T - q_stats[mq].y);
+      const float r = p - q;
+      if (r > 0.f) {
+        const float v = logf(r) + gumbel(counter_uniform(key, s, j, 1, (uint32_t)i));
+        argmax_combine(bv, bi, v, i);
+      }
+    }
+  }
+  block_argmax(bv, bi);
+  if (threadIdx.x == 0) {
+    accept_len[s] = a;
+    for (int j = 0; j < B; ++j)
+      out_tokens[(size_t)s * B + j] = (j < a) ? draft[(size_t)s * B + j + 1] : (j == a ? bi : -1);
+  }
+}
+
+// ---- commit bookkeeping ----------------------------------------------------------------------------
+__global__ void commit_update_kernel(SeqGeom geo, int32_t* __restrict__ seq_lens, int32_t* __restrict__ anchor,
+                                     const int32_t* __restrict__ accept_len, const int32_t* __restrict__ out_tokens, int S,
+                                     int64_t* __restrict__ kv_slots) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s >= S) return;
+  const int B = geo.block_size;
+  const int n = seq_lens[s];
+  int a = accept_len[s];
+  a = max(-1, min(a, B - 1));   // -1: nothing of this sequence is committed, anchor kept
+  if (kv_slots) {
+    for (int j = 0; j < B; ++j) {
+      int64_t slot = -1;
+      const int pos = n + j, pidx = pos / DF_PAGE;
+      if (j <= a && pidx < geo.max_pages_per_seq) {
+        const int page = geo.block_table[(size_t)s * geo.max_pages_per_seq + pidx];
+        if (page >= 0 && page < geo.n_pages) slot = (int64_t)page * DF_PAGE + pos % DF_PAGE;
+      }
+      kv_slots[(size_t)s * B + j] = slot;
+    }
+  }
+  if (a >= 0) anchor[s] = out_tokens[(size_t)s * B + a];
+  seq_lens[s] = n + a + 1;
+}
+
+// ---- weight packing ---------------------------------------------------------------------------------
+// dst row r of the packed matrix comes from source matrix/row:
+//   mode 0 (concat):      sources stacked in order
+//   mode 1 (interleave):  16 rows of src0, 16 rows of src1, 16 rows of src0, ...
+struct PackSrc {
+  const void* src[3];
+  int rows[3];
+  int n_src;
+  int mode;
+};
+template <typename T>
+__global__ __launch_bounds__(256) void pack_kernel(PackSrc ps, int K, int total_rows, T* __restrict__ dst) {
+  const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 8-element chunk
+  const int chunks_per_row = K >> 3;
+  const size_t n_chunks = (size_t)total_rows * chunks_per_row;
+  if (chunk >= n_chunks) return;
+  const int r = (int)(chunk / chunks_per_row), k = (int)(chunk % chunks_per_row) * 8;
+  int si = 0, sr = r;
+  if (ps.mode == 1) {
+    si = (r >> 4) & 1;
+    sr = ((r >> 5) << 4) + (r & 15);
+  } else {
+    while (si + 1 < ps.n_src && sr >= ps.rows[si]) { sr -= ps.rows[si]; ++si; }
+  }
+  const T* s = reinterpret_cast<const T*>(ps.src[si]) + (size_t)sr * K + k;
+  T* d = dst + tile_index<T>(r, k, K);
+#pragma unroll
+  for (int i = 0; i < 8; ++i) d[i] = s[i];
+}
+
+// ---- KV import / export -------------------------------------------------------------------------------
+// dir 0: pool -> canonical fp32 [count, Hkv, hd]; dir 1: canonical -> pool
+template <typename T>
+__global__ __launch_bounds__(128) void kv_copy_kernel(T* __restrict__ pool, SeqGeom geo, int layer, int n_kv_heads, int hd, int seq,
+                                                      int start, float* __restrict__ k, float* __restrict__ v, int dir) {
+  const int pos = start + blockIdx.x, kvh = blockIdx.y;
+  const int pidx = pos / DF_PAGE;
+  if (pidx >= geo.max_pages_per_seq) return;
+  const int page = geo.block_table[(size_t)seq * geo.max_pages_per_seq + pidx];
+  if (page < 0 || page >= geo.n_pages) return;
+  T* base = pool + kv_head_base(layer, geo.n_pages, page, n_kv_heads, kvh, hd);
+  const int key = pos % DF_PAGE;
+  const size_t row = ((size_t)blockIdx.x * n_kv_heads + kvh) * hd;
+  for (int d = threadIdx.x; d < hd; d += blockDim.x) {
+    if (dir == 0) {
+      k[row + d] = Store<T>::to(base[k_in_page(key, d)]);
+      v[row + d] = Store<T>::to(base[DF_PAGE * hd + v_in_page(key, d)]);
+    } else {
+      base[k_in_page(key, d)] = Store<T>::from(k[row + d]);
+      base[DF_PAGE * hd + v_in_page(key, d)] = Store<T>::from(v[row + d]);
+    }
+  }
+}

@@ -1,0 +1,147 @@
+"""Test-side driver of the HIP path: uploads seeded weights, packs them, prefills by chunked
+verification with forced commits, runs speculative steps through the C ABI, and moves cache state
+between the oracle's per-sequence lists and the paged pools."""
+from __future__ import annotations
+
+from typing import Dict, List, Optional, Sequence
+
+import numpy as np
+import torch
+
+import paper_2602_06036_amd as dfl
+from paper_2602_06036_amd import binding as B
+from synth import inputs as si
+
+
+def to_dev(arr: np.ndarray, dev) -> torch.Tensor:
+    if arr.dtype == np.uint16:                                   # bf16 bit patterns
+        return torch.from_numpy(arr.view(np.int16)).to(dev).view(torch.bfloat16)
+    return torch.from_numpy(arr).to(dev)
+
+
+class GpuModel:
+    def __init__(self, w: si.Workload, wt: si.Weights, wd: si.Weights, max_len: int, n_seqs: Optional[int] = None,
+                 shuffle_pages: bool = True, device: str = "cuda:0", max_seqs: Optional[int] = None):
+        self.w = w
+        self.dev = torch.device(device)
+        self.S = n_seqs or w.n_seqs
+        self.Bk = w.block_size
+        table, n_pages = si.make_block_table(w if self.S == w.n_seqs else _with_seqs(w, self.S), max_len, shuffle_pages)
+        self.table_host = table
+        self.e = dfl.Engine(w.target, w.draft, w.dtype, w.block_size, max_seqs or self.S, table.shape[1], n_pages,
+                            w.tap_layers, w.mask_token_id, device)
+        e = self.e
+        e.pack_target_head(to_dev(wt.raw("E"), self.dev), to_dev(wt.raw("lm"), self.dev), to_dev(wt.raw("gf"), self.dev))
+        for l in range(w.target.n_layers):
+            e.pack_target_layer(l, {k: to_dev(wt.raw(f"L{l}.{k}"), self.dev) for k in si.LAYER_MATS + si.LAYER_GAINS})
+            torch.cuda.synchronize(self.dev)
+        e.pack_draft_head(to_dev(wd.raw("wc"), self.dev), to_dev(wd.raw("gc"), self.dev), to_dev(wd.raw("gf"), self.dev))
+        for l in range(w.draft.n_layers):
+            e.pack_draft_layer(l, {k: to_dev(wd.raw(f"L{l}.{k}"), self.dev) for k in si.LAYER_MATS + si.LAYER_GAINS})
+            torch.cuda.synchronize(self.dev)
+        torch.cuda.synchronize(self.dev)
+        e.create()
+        self.block_table = torch.from_numpy(table).to(self.dev)
+        self.seq_lens = torch.zeros(self.S, dtype=torch.int32, device=self.dev)
+        self.anchor = torch.zeros(self.S, dtype=torch.int32, device=self.dev)
+        self.host_lens = np.zeros(self.S, dtype=np.int64)
+        V = w.target.vocab
+        self.draft_tokens = torch.zeros((self.S, self.Bk), dtype=torch.int32, device=self.dev)
+        self.tgt_argmax = torch.zeros_like(self.draft_tokens)
+        self.accept_len = torch.zeros(self.S, dtype=torch.int32, device=self.dev)
+        self.out_tokens = torch.zeros_like(self.draft_tokens)
+        self.kv_slots = torch.zeros((self.S, self.Bk), dtype=torch.int64, device=self.dev)
+        self.logits_d = torch.zeros((self.S, self.Bk, V), dtype=torch.float32, device=self.dev)
+        self.logits_t = torch.zeros_like(self.logits_d)
+
+    def batch(self):
+        return self.e.batch(self.seq_lens, self.block_table, self.anchor, int(self.host_lens.max()))
+
+    # ---- prefill by chunked verification with forced commits ---------------------------------------
+    def prefill(self, prompts: Sequence[np.ndarray]) -> np.ndarray:
+        S, Bk = self.S, self.Bk
+        lens = np.array([len(p) for p in prompts])
+        n_chunks = int((lens.max() + Bk - 1) // Bk)
+        for c in range(n_chunks):
+            toks = np.zeros((S, Bk), dtype=np.int32)
+            r = np.clip(lens - c * Bk, 0, Bk)
+            for s in range(S):
+                toks[s, : r[s]] = prompts[s][c * Bk: c * Bk + r[s]]
+            tokens = torch.from_numpy(toks).to(self.dev)
+            b = self.batch()
+            dfl.dflash_verify(self.e, b, tokens, self.tgt_argmax)
+            acc = torch.from_numpy((r - 1).astype(np.int32)).to(self.dev)
+            dfl.dflash_kv_commit(self.e, b, acc, self.tgt_argmax)
+            self.host_lens += r
+        torch.cuda.synchronize(self.dev)
+        self.e.device_status()
+        assert np.array_equal(self.seq_lens.cpu().numpy(), self.host_lens)
+        return self.anchor.cpu().numpy().copy()
+
+    # ---- one speculative step --------------------------------------------------------------------------
+    def step(self, proposals: Optional[np.ndarray] = None, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None,
+             key: int = 0, want_logits: bool = True) -> Dict[str, np.ndarray]:
+        b = self.batch()
+        rng = torch.tensor([key], dtype=torch.int64, device=self.dev) if temperature > 0 else None
+        dfl.dflash_draft_block(self.e, b, self.draft_tokens, temperature, rng, self.logits_d if want_logits else None)
+        drafted = self.draft_tokens.cpu().numpy().copy()
+        if proposals is not None:
+            blk = drafted.copy()
+            blk[:, 1:] = proposals
+            self.draft_tokens.copy_(torch.from_numpy(blk).to(self.dev))
+        dfl.dflash_verify(self.e, b, self.draft_tokens, self.tgt_argmax, self.logits_t if want_logits else None)
+        u = torch.from_numpy(np.ascontiguousarray(uniforms, dtype=np.float32)).to(self.dev) if uniforms is not None else None
+        dfl.dflash_accept(self.e, b, self.draft_tokens, self.tgt_argmax, self.accept_len, self.out_tokens, temperature, u, rng)
+        lens_before = self.host_lens.copy()
+        dfl.dflash_kv_commit(self.e, b, self.accept_len, self.out_tokens, self.kv_slots)
+        torch.cuda.synchronize(self.dev)
+        self.e.device_status()
+        a = self.accept_len.cpu().numpy().copy()
+        self.host_lens = lens_before + a + 1
+        assert np.array_equal(self.seq_lens.cpu().numpy(), self.host_lens)
+        out = dict(drafted=drafted, block=self.draft_tokens.cpu().numpy().copy(), tgt_argmax=self.tgt_argmax.cpu().numpy().copy(),
+                   accept_len=a, out_tokens=self.out_tokens.cpu().numpy().copy(), kv_slots=self.kv_slots.cpu().numpy().copy(),
+                   lens_before=lens_before, anchor=self.anchor.cpu().numpy().copy())
+        if want_logits:
+            out["logits_d"] = self.logits_d.cpu().numpy().copy()
+            out["logits_t"] = self.logits_t.cpu().numpy().copy()
+        return out
+
+    # ---- cache state in canonical form -----------------------------------------------------------------------
+    def read_kv(self, pool: int, layer: int, seq: int, start: int, count: int):
+        k, v = dfl.dflash_kv_read(self.e, self.batch(), pool, layer, seq, start, count)
+        torch.cuda.synchronize(self.dev)
+        return k.cpu().numpy(), v.cpu().numpy()
+
+    def write_kv(self, pool: int, layer: int, seq: int, start: int, k: np.ndarray, v: np.ndarray):
+        dfl.dflash_kv_write(self.e, self.batch(), pool, layer, seq, start,
+                            torch.from_numpy(np.ascontiguousarray(k, dtype=np.float32)).to(self.dev),
+                            torch.from_numpy(np.ascontiguousarray(v, dtype=np.float32)).to(self.dev))
+
+    def load_state(self, states) -> None:
+        """Teacher forcing / synthetic state: copy each oracle SeqState (lists of K/V rows, length,
+        anchor) into the paged pools."""
+        lens = np.array([st.n for st in states], dtype=np.int32)
+        self.host_lens = lens.astype(np.int64)
+        self.seq_lens.copy_(torch.from_numpy(lens).to(self.dev))
+        self.anchor.copy_(torch.from_numpy(np.array([st.anchor for st in states], dtype=np.int32)).to(self.dev))
+        for s, st in enumerate(states):
+            for l in range(self.w.target.n_layers):
+                self.write_kv(B.DFLASH_POOL_TARGET, l, s, 0, st.kv.k[l][: st.n], st.kv.v[l][: st.n])
+            for l in range(self.w.draft.n_layers):
+                self.write_kv(B.DFLASH_POOL_DRAFT, l, s, 0, st.ctx.k[l][: st.n], st.ctx.v[l][: st.n])
+        torch.cuda.synchronize(self.dev)
+
+    def expected_slots(self, lens_before: np.ndarray, accept_len: np.ndarray) -> np.ndarray:
+        """page*16 + offset from the page table (the definition of a KV slot id), -1 past the accepted prefix."""
+        out = -np.ones((self.S, self.Bk), dtype=np.int64)
+        for s in range(self.S):
+            for j in range(int(accept_len[s]) + 1):
+                pos = int(lens_before[s]) + j
+                out[s, j] = int(self.table_host[s, pos // 16]) * 16 + pos % 16
+        return out
+
+
+def _with_seqs(w: si.Workload, n: int) -> si.Workload:
+    from dataclasses import replace
+    return replace(w, n_seqs=n)

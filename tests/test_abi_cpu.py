@@ -1,0 +1,79 @@
+"""CPU-side checks of the C ABI: the library loads, exports every symbol the header declares,
+and its size / argument-validation entry points (which launch nothing) behave."""
+import ctypes as C
+import os
+import re
+
+import pytest
+
+from synth import inputs as si
+
+ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
+
+
+@pytest.fixture(scope="module")
+def B():
+    from paper_2602_06036_amd import binding
+    if not os.path.exists(binding.LIB_PATH):
+        from paper_2602_06036_amd import build
+        build.build(verbose=False)
+    return binding
+
+
+def test_every_declared_symbol_is_exported(B):
+    hdr = open(os.path.join(ROOT, "include", "dflash.h")).read()
+    declared = sorted(set(re.findall(r"\b(dflash_[a-z_]+)\s*\(", hdr)))
+    assert set(declared) == set(B.EXPORTS)
+    l = B.lib()
+    for name in declared:
+        assert hasattr(l, name), name
+
+
+def test_struct_sizes_match_the_header(B):
+    assert C.sizeof(B.Dims) == 11 * 4
+    assert C.sizeof(B.LayerWeights) == 11 * 8
+    assert C.sizeof(B.Batch) == 8 + 3 * 8
+    assert C.sizeof(B.Runtime) == 4 * 4 + 4 + 8 * 4 + 4 + 4 * 8   # incl. no padding surprises
+    
+
+def test_sizes_for_the_8b_shape(B):
+    w = si.workload(2)
+    l = B.lib()
+    td, dd = B.make_dims(w.target, "bf16"), B.make_dims(w.draft, "bf16")
+    per_layer = (6144 * 4096 + 4096 * 4096 + 2 * 12288 * 4096 + 4096 * 12288) * 2
+    tb = l.dflash_target_blob_bytes(C.byref(td))
+    assert 36 * per_layer + 2 * 151936 * 4096 * 2 <= tb <= 36 * per_layer + 2 * 151936 * 4096 * 2 + 36 * 40000 + 20000
+    # 147456 bytes of target KV per token (36 layers x 2 x 8 heads x 128 x 2 bytes)
+    assert l.dflash_kv_pool_bytes(C.byref(td), 10) == 10 * 16 * 147456
+    assert l.dflash_kv_pool_bytes(C.byref(dd), 10) == 10 * 16 * 20480
+    db = l.dflash_draft_blob_bytes(C.byref(dd), 5, 4096)
+    assert db >= 5 * per_layer + 4096 * 20480 * 2 + 5 * 2 * 1024 * 4096 * 2
+
+
+def test_bad_shapes_are_rejected_with_a_message(B):
+    from dataclasses import replace
+    w = si.workload(2)
+    l = B.lib()
+    bad = B.make_dims(replace(w.target, d_model=4100), "bf16")
+    assert l.dflash_target_blob_bytes(C.byref(bad)) == 0
+    assert b"multiples of 32" in l.dflash_last_error(None)
+    bad = B.make_dims(replace(w.target, n_q_heads=30), "bf16")
+    assert l.dflash_target_blob_bytes(C.byref(bad)) == 0
+    td, dd = B.make_dims(w.target, "bf16"), B.make_dims(w.draft, "bf16")
+    rt = B.Runtime()
+    rt.block_size, rt.max_seqs, rt.max_pages_per_seq, rt.n_pages, rt.n_taps = 17, 1, 8, 8, 5
+    assert l.dflash_workspace_bytes(C.byref(td), C.byref(dd), C.byref(rt)) == 0
+    assert b"block_size" in l.dflash_last_error(None)
+    rt.block_size = 16
+    for i, t in enumerate((1, 9, 9, 25, 33)):
+        rt.tap_layers[i] = t
+    rt.mask_token_id = 151935
+    assert l.dflash_workspace_bytes(C.byref(td), C.byref(dd), C.byref(rt)) == 0   # taps not ascending
+    for i, t in enumerate((1, 9, 17, 25, 33)):
+        rt.tap_layers[i] = t
+    ws = l.dflash_workspace_bytes(C.byref(td), C.byref(dd), C.byref(rt))
+    # decode-time temporaries stay small: two [16, V] fp32 logit buffers dominate
+    assert 2 * 16 * 151936 * 4 < ws < 64 << 20
+    out = C.c_void_p()
+    assert l.dflash_create(C.byref(td), None, C.byref(dd), None, C.byref(rt), C.byref(out)) == B.DFLASH_EINVAL
+    assert out.value is None

@@ -108,7 +108,7 @@ def test_counter_uniform_is_uniform_and_keyed():
     z = ((z ^ (z >> 30)) * 0xBF58476D1CE4E5B9) & M
     z = ((z ^ (z >> 27)) * 0x94D049BB133111EB) & M
     z = z ^ (z >> 31)
-    assert O.counter_uniform(key, seq, slot, purpose, np.array([i]))[0] == ((z >> 40) + 0.5) / 2 ** 24
+    assert O.counter_uniform(key, seq, slot, purpose, np.array([i]))[0] == ((z >> 41) + 0.5) / 2 ** 23
 
 
 def test_gumbel_argmax_samples_the_softmax():
