@@ -15,9 +15,15 @@ The target is a standard pre-norm decoder (RMSNorm, RoPE, GQA, SwiGLU) of the Qw
 family the paper evaluates (Section 5).  The temperature-1 rule is the standard speculative
 sampling rule of the cited Leviathan et al. work, which the paper uses without restating.
 
-Precision: float64 throughout.  `rnd` is the storage-rounding hook: identity for an fp32 model;
-for a bf16 model it rounds to bf16 exactly the tensors a bf16 model keeps in bf16 (GEMM inputs,
-q/k/v rows, taps, H_t) while residual stream, accumulators, softmax and logits stay wide.
+Precision: float64 throughout.  `rnd` is the storage-rounding hook (class Rounding): the identity
+for an fp32 model.  A bf16 model keeps its weights, its K/V cache rows and the query rows in bf16
+(`rnd.kv`, 8 significand bits) and hands every GEMM input -- normalised activations, attention
+output, SwiGLU product, taps, H_t -- to the matrix units as a pair of bf16 numbers hi + lo
+(`rnd(x)`, about 16 significand bits).  Residual stream, accumulators, softmax and logits stay wide.
+The pair format is this build's choice, not the paper's: with single-bf16 GEMM inputs two correct
+bf16 evaluations of the same model (differing only in summation order) end up 2-3 % of the logit
+standard deviation apart, because one flipped rounding perturbs all later roundings; that is
+above the 2e-2 logit bound at the 8B shape.  tests/test_oracle_model.py measures both variants.
 
 Loop order.  `target_forward_tokens` walks layer by layer and, inside a layer, token by token
 with a growing KV list (token j attends the list as it stands after its own K/V were appended).
@@ -40,14 +46,26 @@ from typing import Callable, Dict, List, Optional, Sequence, Tuple
 
 import numpy as np
 
-Round = Callable[[np.ndarray], np.ndarray]
 
 
 # --------------------------------------------------------------------------------------
 # storage rounding
 # --------------------------------------------------------------------------------------
-def identity(x: np.ndarray) -> np.ndarray:
+def _same(x: np.ndarray) -> np.ndarray:
     return x
+
+
+class Rounding:
+    """rnd(x): rounding of a GEMM input; rnd.kv(x): rounding of stored q / k / v rows."""
+
+    def __init__(self, act: Callable[[np.ndarray], np.ndarray], kv: Callable[[np.ndarray], np.ndarray]):
+        self.act, self.kv = act, kv
+
+    def __call__(self, x: np.ndarray) -> np.ndarray:
+        return self.act(x)
+
+
+identity = Rounding(_same, _same)
 
 
 def round_bf16(x: np.ndarray) -> np.ndarray:
@@ -58,8 +76,20 @@ def round_bf16(x: np.ndarray) -> np.ndarray:
     return u.view(np.float32).astype(np.float64)
 
 
-def rounding_for(dtype: str) -> Round:
-    return round_bf16 if dtype == "bf16" else identity
+def round_bf16_pair(x: np.ndarray) -> np.ndarray:
+    """hi + lo with hi = bf16(x), lo = bf16(x - hi), the subtraction done in single precision."""
+    f = np.asarray(x, dtype=np.float64).astype(np.float32)
+    hi = round_bf16(f).astype(np.float32)
+    lo = round_bf16((f - hi).astype(np.float32))
+    return hi.astype(np.float64) + lo
+
+
+BF16_MODEL = Rounding(round_bf16_pair, round_bf16)
+BF16_SINGLE = Rounding(round_bf16, round_bf16)     # single-bf16 GEMM inputs; used only to measure the noise
+
+
+def rounding_for(dtype: str) -> Rounding:
+    return BF16_MODEL if dtype == "bf16" else identity
 
 
 # --------------------------------------------------------------------------------------
@@ -109,9 +139,9 @@ def _heads(x: np.ndarray, n_heads: int, hd: int) -> np.ndarray:
     return x.reshape(x.shape[0], n_heads, hd)
 
 
-def _qkv(W, m, pre: str, a: np.ndarray, pos: np.ndarray, rnd: Round):
+def _qkv(W, m, pre: str, a: np.ndarray, pos: np.ndarray, rnd: "Rounding"):
     """Projections of normalised rows a [T, D] -> q [T,Hq,hd], k, v [T,Hkv,hd]; optional per-head
-    RMSNorm on q and k, then RoPE at `pos`; each stored rounded."""
+    RMSNorm on q and k, then RoPE at `pos`; each stored with the q/k/v rounding."""
     q = _heads(a @ W(pre + "wq").T, m.n_q_heads, m.head_dim)
     k = _heads(a @ W(pre + "wk").T, m.n_kv_heads, m.head_dim)
     v = _heads(a @ W(pre + "wv").T, m.n_kv_heads, m.head_dim)
@@ -120,7 +150,7 @@ def _qkv(W, m, pre: str, a: np.ndarray, pos: np.ndarray, rnd: Round):
         k = rmsnorm(k, W(pre + "kn"), m.rms_eps)
     q = rope(q, pos, m.rope_theta)
     k = rope(k, pos, m.rope_theta)
-    return rnd(q), rnd(k), rnd(v)
+    return rnd.kv(q), rnd.kv(k), rnd.kv(v)
 
 
 def _attend(m, q: np.ndarray, K: np.ndarray, V: np.ndarray) -> np.ndarray:
@@ -136,7 +166,7 @@ def _attend(m, q: np.ndarray, K: np.ndarray, V: np.ndarray) -> np.ndarray:
     return out
 
 
-def _ffn(W, m, pre: str, h: np.ndarray, rnd: Round) -> np.ndarray:
+def _ffn(W, m, pre: str, h: np.ndarray, rnd: "Rounding") -> np.ndarray:
     a = rnd(rmsnorm(h, W(pre + "g2"), m.rms_eps))
     act = rnd(silu(a @ W(pre + "wg").T) * (a @ W(pre + "wu").T))
     return h + act @ W(pre + "wd").T
@@ -146,7 +176,7 @@ def _ffn(W, m, pre: str, h: np.ndarray, rnd: Round) -> np.ndarray:
 # target model
 # --------------------------------------------------------------------------------------
 def target_forward_tokens(W, m, tokens: Sequence[int], start_pos: int, kv: KVList,
-                          tap_layers: Sequence[int], rnd: Round = identity,
+                          tap_layers: Sequence[int], rnd: "Rounding" = identity,
                           want_logits: bool = True):
     """Run `tokens` (positions start_pos ..) through the target against the cached rows
     kv[:start_pos]; appends their K/V (kv.n becomes start_pos+T).  Token j sees cache rows
@@ -180,7 +210,7 @@ def target_forward_tokens(W, m, tokens: Sequence[int], start_pos: int, kv: KVLis
 
 
 def target_forward_sequence(W, m, tokens: Sequence[int], kv: KVList, tap_layers: Sequence[int],
-                            rnd: Round = identity, logit_rows: Optional[Sequence[int]] = None):
+                            rnd: "Rounding" = identity, logit_rows: Optional[Sequence[int]] = None):
     """Whole-sequence causal forward from an empty cache in matrix form (masked T x T scores):
     the textbook definition of the decoder over a sequence.  Fills kv[0:T].  Returns
     (logits for `logit_rows` (default: all rows), taps [T, n_tap, D])."""
@@ -217,14 +247,14 @@ def target_forward_sequence(W, m, tokens: Sequence[int], kv: KVList, tap_layers:
 # --------------------------------------------------------------------------------------
 # draft model (Appendix A.3)
 # --------------------------------------------------------------------------------------
-def fuse_taps(Wd, md, taps: np.ndarray, rnd: Round = identity) -> np.ndarray:
+def fuse_taps(Wd, md, taps: np.ndarray, rnd: "Rounding" = identity) -> np.ndarray:
     """H_t = RMSNorm(W_c [H^(l1); ...; H^(lk)]) per token; taps [T, n_tap, D_target] are
     concatenated in ascending layer order.  Returns [T, D_draft]."""
     x = rnd(taps).reshape(taps.shape[0], -1)
     return rnd(rmsnorm(x @ Wd("wc").T, Wd("gc"), md.rms_eps))
 
 
-def draft_context_kv(Wd, md, H_t: np.ndarray, pos: np.ndarray, rnd: Round = identity):
+def draft_context_kv(Wd, md, H_t: np.ndarray, pos: np.ndarray, rnd: "Rounding" = identity):
     """Per draft layer i: K = W_K^i H_t (per-head k-norm if enabled, RoPE at the token's own
     position), V = W_V^i H_t.  The features get no per-layer input norm and never pass through
     Q / O / FFN.  Returns [(K [T,Hkv,hd], V [T,Hkv,hd])] per layer."""
@@ -236,12 +266,12 @@ def draft_context_kv(Wd, md, H_t: np.ndarray, pos: np.ndarray, rnd: Round = iden
         if md.qk_norm:
             k = rmsnorm(k, Wd(pre + "kn"), md.rms_eps)
         k = rope(k, pos, md.rope_theta)
-        out.append((rnd(k), rnd(v)))
+        out.append((rnd.kv(k), rnd.kv(v)))
     return out
 
 
 def draft_block_forward(Wd, md, anchor: int, n: int, ctx: KVList, block_size: int, mask_id: int,
-                        rnd: Round = identity) -> np.ndarray:
+                        rnd: "Rounding" = identity) -> np.ndarray:
     """One pass over the block [anchor, mask, ..., mask] placed at positions n .. n+B-1.
     Every block row attends, without any mask, to all n cached context rows of its layer and to
     all B block rows.  Returns logits [B, V]; row j is the prediction for the token of slot j
@@ -341,7 +371,7 @@ class SeqState:
         self.anchor = -1
 
 
-def _append_context(Wd, md, st: SeqState, taps: np.ndarray, start: int, rnd: Round) -> None:
+def _append_context(Wd, md, st: SeqState, taps: np.ndarray, start: int, rnd: "Rounding") -> None:
     H_t = fuse_taps(Wd, md, taps, rnd)
     pos = np.arange(start, start + taps.shape[0])
     for i, (k, v) in enumerate(draft_context_kv(Wd, md, H_t, pos, rnd)):
@@ -351,7 +381,7 @@ def _append_context(Wd, md, st: SeqState, taps: np.ndarray, start: int, rnd: Rou
 
 
 def prefill(Wt, Wd, mt, md, tap_layers, prompt: Sequence[int], st: SeqState,
-            rnd: Round = identity) -> int:
+            rnd: "Rounding" = identity) -> int:
     """Standard prefill (Section 4.1): target over the prompt, taps of every prompt token fused
     and projected into the draft's context K/V; the first generated token becomes the anchor."""
     T = len(prompt)
@@ -363,7 +393,7 @@ def prefill(Wt, Wd, mt, md, tap_layers, prompt: Sequence[int], st: SeqState,
 
 
 def spec_step(Wt, Wd, mt, md, tap_layers, st: SeqState, block_size: int, mask_id: int,
-              rnd: Round = identity, temperature: float = 0.0,
+              rnd: "Rounding" = identity, temperature: float = 0.0,
               uniforms: Optional[Sequence[float]] = None, key: int = 0, seq_id: int = 0,
               proposal: Optional[Sequence[int]] = None) -> Dict:
     """One draft -> verify -> accept -> commit cycle for one sequence.
@@ -413,7 +443,7 @@ def spec_step(Wt, Wd, mt, md, tap_layers, st: SeqState, block_size: int, mask_id
                 taps=taps)
 
 
-def plain_greedy_decode(Wt, mt, prompt: Sequence[int], n_new: int, rnd: Round = identity,
+def plain_greedy_decode(Wt, mt, prompt: Sequence[int], n_new: int, rnd: "Rounding" = identity,
                         capacity: Optional[int] = None) -> List[int]:
     """Token-by-token greedy decoding of the target alone: the definition the speculative
     output must reproduce."""

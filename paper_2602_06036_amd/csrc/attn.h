@@ -96,7 +96,7 @@ __global__ __launch_bounds__(256) void attn_partial_simple_kernel(const T* __res
 
 // ------------------------------------------------------------------------------------------------
 // Merge of the splits in ascending split order; grid (M*Hq), block 128.
-// Output in GEMM operand layout, row length Hq*hd.
+// Output as GEMM activation operand (Act<T>), row length Hq*hd.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
@@ -114,5 +114,5 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict
     L += ml.y * w;
     if (d < hd) o += w * part_o[((size_t)row * n_splits + c) * hd + d];
   }
-  if (d < hd) out[tile_index<T>(m, hq * hd + d, n_q_heads * hd)] = Store<T>::from(L > 0.f ? o / L : 0.f);
+  if (d < hd) Act<T>::store(out, m, hq * hd + d, n_q_heads * hd, L > 0.f ? o / L : 0.f);
 }

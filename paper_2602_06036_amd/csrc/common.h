@@ -51,6 +51,52 @@ template <> __host__ __device__ __forceinline__ size_t tile_index<bf16_t>(int r,
 template <typename T> __host__ __device__ __forceinline__ int tile_rows(int M) { return M; }
 template <> __host__ __device__ __forceinline__ int tile_rows<bf16_t>(int M) { return (M + 15) & ~15; }
 
+// ---- GEMM activation operand ---------------------------------------------------------------------
+// fp32 models: plain row-major fp32.  bf16 models: every activation that feeds a GEMM is kept as a
+// PAIR of bf16 numbers hi + lo (hi = bf16(x), lo = bf16(x - hi)), i.e. ~16 significand bits, and the
+// GEMM issues two MFMAs per weight tile.  Single-bf16 inputs make two correct evaluations of the
+// same model drift apart by percents of the logit spread (one flipped rounding perturbs every later
+// rounding); the pair removes that at no cost while the GEMM is bandwidth-bound.  Layout: the tile
+// layout above with the hi tile (1 KB) immediately followed by the lo tile.
+template <typename T> struct Act;
+template <> struct Act<float> {
+  static constexpr int planes = 1;
+  static __host__ __device__ __forceinline__ size_t elems(int M, int K) { return (size_t)M * K; }
+  static __device__ __forceinline__ void store(float* base, int m, int k, int K, float v) { base[(size_t)m * K + k] = v; }
+  // 4 consecutive k (k % 4 == 0)
+  static __device__ __forceinline__ void store4(float* base, int m, int k, int K, float4 v) {
+    *reinterpret_cast<float4*>(base + (size_t)m * K + k) = v;
+  }
+};
+template <> struct Act<bf16_t> {
+  static constexpr int planes = 2;
+  static __host__ __device__ __forceinline__ size_t elems(int M, int K) { return (size_t)((M + 15) & ~15) * K * 2; }
+  static __host__ __device__ __forceinline__ size_t index(int m, int k, int K) {  // hi element; lo is 512 further
+    return ((size_t)(m >> 4) * (K >> 5) + (k >> 5)) * 1024 + (size_t)(((((k & 31) >> 3) << 4) + (m & 15)) * 8 + (k & 7));
+  }
+  static __device__ __forceinline__ void split(float v, bf16_t& hi, bf16_t& lo) {
+    hi = float_to_bf16_bits(v);
+    lo = float_to_bf16_bits(v - bf16_bits_to_float(hi));
+  }
+  static __device__ __forceinline__ void store(bf16_t* base, int m, int k, int K, float v) {
+    bf16_t hi, lo;
+    split(v, hi, lo);
+    const size_t i = index(m, k, K);
+    base[i] = hi;
+    base[i + 512] = lo;
+  }
+  static __device__ __forceinline__ void store4(bf16_t* base, int m, int k, int K, float4 v) {
+    ushort4 hi, lo;
+    split(v.x, hi.x, lo.x);
+    split(v.y, hi.y, lo.y);
+    split(v.z, hi.z, lo.z);
+    split(v.w, hi.w, lo.w);
+    const size_t i = index(m, k, K);
+    *reinterpret_cast<ushort4*>(base + i) = hi;
+    *reinterpret_cast<ushort4*>(base + i + 512) = lo;
+  }
+};
+
 // ---- KV page layout ----------------------------------------------------------------------------
 // A pool holds, per layer, n_pages pages; a page holds for each kv head 16 keys then 16 values:
 //   pool[layer][page][kv_head][K|V][16*hd]

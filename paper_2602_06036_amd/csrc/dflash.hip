@@ -136,6 +136,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   const size_t es = esize(t.dtype);
   const int M = rt.max_seqs * rt.block_size;
   const size_t Mr = round_rows(t.dtype, M);
+  const size_t planes = t.dtype == DFLASH_BF16 ? 2 : 1;   // bf16 GEMM inputs are hi+lo pairs
   const size_t qd = (size_t)std::max(t.n_q_heads * t.head_dim, d.n_q_heads * d.head_dim);
   const size_t nqkv = std::max((size_t)(t.n_q_heads + 2 * t.n_kv_heads) * t.head_dim, (size_t)(d.n_q_heads + 2 * d.n_kv_heads) * d.head_dim);
   const size_t F = std::max(t.d_ffn, d.d_ffn);
@@ -145,14 +146,14 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   auto take = [&](size_t bytes) { size_t r = off; off += align256(bytes); return r; };
   w.status = take(256);
   w.h = take((size_t)M * D * 4);
-  w.a = take(Mr * D * es);
+  w.a = take(Mr * D * es * planes);
   w.qkv = take((size_t)M * nqkv * 4);
   w.q = take((size_t)M * qd * es);
-  w.o = take(Mr * qd * es);
-  w.act = take(Mr * F * es);
-  w.taps = take(Mr * (size_t)rt.n_taps * D * es);
+  w.o = take(Mr * qd * es * planes);
+  w.act = take(Mr * F * es * planes);
+  w.taps = take(Mr * (size_t)rt.n_taps * D * es * planes);
   w.fuse = take((size_t)M * D * 4);
-  w.ht = take(Mr * D * es);
+  w.ht = take(Mr * D * es * planes);
   w.kvctx = take((size_t)M * d.n_layers * 2 * d.n_kv_heads * d.head_dim * 4);
   w.logits_d = take((size_t)M * t.vocab * 4);
   w.logits_t = take((size_t)M * t.vocab * 4);

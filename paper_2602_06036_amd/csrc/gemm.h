@@ -1,5 +1,6 @@
 // Weight-streaming GEMMs: y[M,N] = a[M,K] * W[N,K]^T with fused epilogues.
-//   bf16: MFMA 16x16x32, operands in the tiled layout of common.h, fp32 accumulation.
+//   bf16: MFMA 16x16x32, weights in the tiled layout of common.h, activations as hi+lo bf16 pairs
+//         (two MFMAs per weight tile), fp32 accumulation.
 //   fp32: one wavefront per output column (tiny models only).
 #pragma once
 #include "common.h"
@@ -42,24 +43,31 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 
   const u32x4* Wp = reinterpret_cast<const u32x4*>(W) + lane;
   const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + lane;
-  // activation bands past the last one alias the last band (their results are never stored)
+  // activation bands past the last one alias the last band (their results are never stored);
+  // a band holds, per k tile, the hi tile then the lo tile (64 lanes x 16 bytes each)
   size_t a_band[MT];
 #pragma unroll
-  for (int j = 0; j < MT; ++j) a_band[j] = (size_t)min(mt0 + j, m_tiles - 1) * KT * 64;
+  for (int j = 0; j < MT; ++j) a_band[j] = (size_t)min(mt0 + j, m_tiles - 1) * KT * 128;
 
 #pragma unroll 4
   for (int kt = kt_begin; kt < kt_end; ++kt) {
-    u32x4 wf[NT], af[MT];
+    u32x4 wf[NT], ah[MT], al[MT];
 #pragma unroll
     for (int i = 0; i < NT; ++i) wf[i] = __builtin_nontemporal_load(Wp + ((size_t)(nt0 + i) * KT + kt) * 64);
 #pragma unroll
-    for (int j = 0; j < MT; ++j) af[j] = Ap[a_band[j] + (size_t)kt * 64];
+    for (int j = 0; j < MT; ++j) {
+      ah[j] = Ap[a_band[j] + (size_t)kt * 128];
+      al[j] = Ap[a_band[j] + (size_t)kt * 128 + 64];
+    }
 #pragma unroll
     for (int i = 0; i < NT; ++i)
 #pragma unroll
-      for (int j = 0; j < MT; ++j)
+      for (int j = 0; j < MT; ++j) {
         acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]),
-                                                            __builtin_bit_cast(bf16x8, af[j]), acc[i][j], 0, 0, 0);
+                                                            __builtin_bit_cast(bf16x8, ah[j]), acc[i][j], 0, 0, 0);
+        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]),
+                                                            __builtin_bit_cast(bf16x8, al[j]), acc[i][j], 0, 0, 0);
+      }
   }
 
   __shared__ float4 red[4][NT * MT][64];
@@ -85,12 +93,8 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       const int m = (mt0 + j) * 16 + mrow;
       if (mt0 + j < m_tiles && m < M) {
         const int col = ((nt0 + 2 * p) >> 1) * 16 + 4 * g;
-        ushort4 o;
-        o.x = float_to_bf16_bits(silu_f(gs.x) * us.x);
-        o.y = float_to_bf16_bits(silu_f(gs.y) * us.y);
-        o.z = float_to_bf16_bits(silu_f(gs.z) * us.z);
-        o.w = float_to_bf16_bits(silu_f(gs.w) * us.w);
-        *reinterpret_cast<ushort4*>(act + tile_index<bf16_t>(m, col, ep.act_K)) = o;
+        Act<bf16_t>::store4(act, m, col, ep.act_K,
+                            make_float4(silu_f(gs.x) * us.x, silu_f(gs.y) * us.y, silu_f(gs.z) * us.z, silu_f(gs.w) * us.w));
       }
     }
   } else {

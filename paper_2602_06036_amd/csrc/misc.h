@@ -26,7 +26,7 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
   for (int d = threadIdx.x; d < D; d += blockDim.x) h[(size_t)m * D + d] = Store<T>::to(src[d]);
 }
 
-// ---- RMSNorm: fp32 rows [M, D] -> storage type in GEMM operand layout ----------------------------
+// ---- RMSNorm: fp32 rows [M, D] -> GEMM activation operand (Act<T>) ----------------------------
 template <typename T>
 __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
                                                       T* __restrict__ out, int D, float eps) {
@@ -46,21 +46,17 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
     const float4 v = *reinterpret_cast<const float4*>(row + d);
     const float4 g = *reinterpret_cast<const float4*>(gain + d);
-    T* dst = out + tile_index<T>(m, d, D);   // 4 consecutive k stay inside one 8-chunk
-    dst[0] = Store<T>::from(v.x * rstd * g.x);
-    dst[1] = Store<T>::from(v.y * rstd * g.y);
-    dst[2] = Store<T>::from(v.z * rstd * g.z);
-    dst[3] = Store<T>::from(v.w * rstd * g.w);
+    Act<T>::store4(out, m, d, D, make_float4(v.x * rstd * g.x, v.y * rstd * g.y, v.z * rstd * g.z, v.w * rstd * g.w));
   }
 }
 
-// ---- tap copy: taps[m, t*D + d] = storage(h[m, d]) in GEMM operand layout (row length n_taps*D) ---
+// ---- tap copy: taps[m, t*D + d] = h[m, d] as GEMM activation operand (row length n_taps*D) ---
 template <typename T>
 __global__ __launch_bounds__(256) void tap_copy_kernel(const float* __restrict__ h, T* __restrict__ taps, int D, int t,
                                                        int K_total) {
   const int m = blockIdx.x;
   for (int d = threadIdx.x; d < D; d += blockDim.x)
-    taps[tile_index<T>(m, t * D + d, K_total)] = Store<T>::from(h[(size_t)m * D + d]);
+    Act<T>::store(taps, m, t * D + d, K_total, h[(size_t)m * D + d]);
 }
 
 // ---- q/k RMSNorm + RoPE + cache write ------------------------------------------------------------

@@ -246,3 +246,26 @@ def test_block_rows_see_each_other_bidirectionally():
 def test_tap_layers_follow_the_paper():
     assert si.tap_layers_for(36, 5) == (1, 9, 17, 25, 33)      # second layer .. third-to-last
     assert si.workload(1).tap_layers == (0,)
+
+
+def test_bf16_pair_inputs_keep_two_evaluations_within_the_logit_bound():
+    """Why GEMM inputs are bf16 pairs: evaluate the same bf16 model twice, the second time with the
+    embedding scaled by (1 + 1e-5) (far below bf16 resolution, standing in for a different summation
+    order).  With single-bf16 GEMM inputs the two logit sets differ by percents of the logit standard
+    deviation; with hi+lo pairs by hundredths of a percent (what is left comes from the bf16 q/k/v rows)."""
+    t = si.ModelDims(6, 256, 4, 1, 64, 768, 2048, 1e6, 1e-6, True)
+    w = si.Workload("noise", "bf16", t, replace(t, n_layers=1), (1,), t.vocab - 1, 16, 1, 48, 48, 0.0, 7)
+    wt, _ = si.make_weights(w, 4)
+    W = W64(wt)
+    toks = si.make_prompts(w)[0]
+
+    def run(rnd, scale):
+        Wp = lambda name: (W(name) * scale if name == "E" else W(name))
+        kv = O.KVList(t.n_layers, t.n_kv_heads, t.head_dim, 64)
+        return O.target_forward_sequence(Wp, t, toks, kv, (), rnd)[0]
+    exact = run(O.identity, 1.0)
+    sigma = exact.std()
+    single = np.abs(run(O.BF16_SINGLE, 1.0) - run(O.BF16_SINGLE, 1.0 + 1e-5)).max() / sigma
+    pair = np.abs(run(O.BF16_MODEL, 1.0) - run(O.BF16_MODEL, 1.0 + 1e-5)).max() / sigma
+    assert single > 0.008          # > 1e-2 in logit units at the 8B shape's sigma of 1.28
+    assert pair < 0.004
