@@ -1,0 +1,246 @@
+#!/usr/bin/env python3
+"""Benchmark of one DFlash speculative-decoding step (draft -> verify -> accept -> commit) on one MI355X.
+
+Default workload: the 8B-shaped bf16 target (36 layers, d=4096, 32/8 heads x 128, FFN 12288, vocab
+151936) with the 5-layer draft, block size 16, batch 1, 2048 cached tokens, greedy.  Weights are
+random N(0, 0.02), the caches hold seeded random rows; everything is resident in HBM before the
+timed region.  Prints ONE JSON line.
+"""
+import argparse
+import json
+import os
+import sys
+import time
+
+ROOT = os.path.dirname(os.path.abspath(__file__))
+if ROOT not in sys.path:
+    sys.path.insert(0, ROOT)
+
+HBM_PEAK_GBS = 8000.0
+
+WORKLOADS = {
+    # name: (synth workload index, n_seqs, context)
+    "cfg2_8b_b1_ctx2048": (2, 1, 2048),
+    "cfg3_8b_b16_ctx2560": (3, 16, 2560),
+    "cfg4_8b_b4_ctx16k": (4, 4, 16384),
+    "cfg5_8b_b32_ctx8k": (5, 32, 8192),
+    "tiny_f32": (1, 1, 128),
+}
+
+
+def build_engine(w, S, ctx, steps_total, dev):
+    """Random-init weights generated on the device tensor by tensor, packed, canonical copy freed."""
+    import torch
+    import paper_2602_06036_amd as dfl
+    from synth import inputs as si
+
+    Bk = w.block_size
+    max_len = ctx + (steps_total + 2) * Bk
+    pps = (max_len + 15) // 16
+    n_pages = S * pps
+    e = dfl.Engine(w.target, w.draft, w.dtype, Bk, S, pps, n_pages, w.tap_layers, w.mask_token_id, str(dev))
+    gen = torch.Generator(device=dev)
+    gen.manual_seed(w.seed)
+    tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
+
+    def mat(shape):
+        return (torch.randn(shape, generator=gen, device=dev, dtype=torch.float32) * 0.02).to(tdt)
+
+    def gain(n):
+        return 1.0 + 0.1 * (2.0 * torch.rand(n, generator=gen, device=dev, dtype=torch.float32) - 1.0)
+
+    def layer(m):
+        shp = si.layer_shapes(m)
+        return {k: (gain(shp[k][0]) if k in si.LAYER_GAINS else mat(shp[k])) for k in shp}
+
+    t, d = w.target, w.draft
+    e.pack_target_head(mat((t.vocab, t.d_model)), mat((t.vocab, t.d_model)), gain(t.d_model))
+    for l in range(t.n_layers):
+        e.pack_target_layer(l, layer(t))
+        torch.cuda.synchronize(dev)
+    e.pack_draft_head(mat((d.d_model, len(w.tap_layers) * t.d_model)), gain(d.d_model), gain(d.d_model))
+    for l in range(d.n_layers):
+        e.pack_draft_layer(l, layer(d))
+        torch.cuda.synchronize(dev)
+    e.create()
+    # caches: seeded random rows standing in for a prefill (unit-scale K after k-norm / RoPE, V likewise)
+    for pool in (e.target_pool, e.draft_pool):
+        v = pool.view(tdt)
+        chunk = 1 << 26
+        for i in range(0, v.numel(), chunk):
+            v[i:i + chunk].normal_(generator=gen)
+    # shuffled (non-contiguous) page assignment
+    perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(w.seed)).to(torch.int32)
+    table = perm.view(S, pps).contiguous().to(dev)
+    torch.cuda.synchronize(dev)
+    return e, table, max_len
+
+
+def cpu_baseline(w, ctx, time_budget_s=25.0):
+    """Times the oracle, as it stands, on a bounded sample of the same step: one target layer and one
+    draft layer of the workload's shape over one 16-token block with `ctx` cached rows, plus the final
+    norm + LM head on a 1/8 vocabulary slice; scaled to the full layer counts and vocabulary."""
+    import numpy as np
+    from dataclasses import replace
+    from oracle import dflash_oracle as O
+    from synth import inputs as si
+
+    t1 = replace(w.target, n_layers=1, vocab=w.target.vocab // 8)
+    d1 = replace(w.draft, n_layers=1, vocab=w.target.vocab // 8)
+    ws = replace(w, target=t1, draft=d1, tap_layers=(0,), mask_token_id=t1.vocab - 1)
+    wt, wd = si.make_weights(ws, min(16, os.cpu_count() or 1))
+    cache = {}
+
+    def getter(weights):
+        def W(name):
+            key = (id(weights), name)
+            if key not in cache:
+                cache[key] = weights.f64(name)
+            return cache[key]
+        return W
+    Wt, Wd = getter(wt), getter(wd)
+    rnd = O.rounding_for(w.dtype)
+    Bk = w.block_size
+    rng = np.random.default_rng(0)
+    st = O.SeqState(t1, d1, ctx + Bk + 1, cache_dtype=np.float32)
+    for lists, m in ((st.kv, t1), (st.ctx, d1)):
+        lists.k[0][:ctx] = O.round_bf16(rng.standard_normal((ctx, m.n_kv_heads, m.head_dim)))
+        lists.v[0][:ctx] = O.round_bf16(rng.standard_normal((ctx, m.n_kv_heads, m.head_dim)))
+        lists.n = ctx
+    st.n, st.anchor = ctx, 7
+    # warm the weight cache (upcast is part of neither leg: the GPU side has its weights resident too)
+    for nm in list(wt.names()):
+        Wt(nm)
+    for nm in list(wd.names()):
+        Wd(nm)
+    t0 = time.perf_counter()
+    O.draft_block_forward(Wd, d1, st.anchor, ctx, st.ctx, Bk, ws.mask_token_id, rnd)
+    t_draft = time.perf_counter() - t0
+    t0 = time.perf_counter()
+    O.target_forward_tokens(Wt, t1, list(range(Bk)), ctx, st.kv, (0,), rnd)
+    t_tgt = time.perf_counter() - t0
+    # each leg = one layer + (norm + LM head on V/8); separate the head by timing it alone
+    h = rng.standard_normal((Bk, t1.d_model))
+    t0 = time.perf_counter()
+    _ = rnd(O.rmsnorm(h, Wt("gf"), t1.rms_eps)) @ Wt("lm").T
+    t_head = time.perf_counter() - t0
+    step = (t_tgt - t_head) * w.target.n_layers + (t_draft - t_head) * w.draft.n_layers + 2 * 8 * t_head
+    return dict(value=Bk / step, unit="tokens/s", cores=min(16, os.cpu_count() or 1), kind="oracle",
+                sample="1 of %d target layers + 1 of %d draft layers over one %d-token block with %d cached rows, "
+                       "LM head on 1/8 of the vocabulary; scaled to the full step (%.1f s/step)" %
+                       (w.target.n_layers, w.draft.n_layers, Bk, ctx, step))
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default="cfg2_8b_b1_ctx2048", choices=sorted(WORKLOADS))
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the step is single-device; see DESIGN.md for how it would shard); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_06036_amd as dfl
+    from paper_2602_06036_amd import binding as B
+    from synth import inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    idx, S, ctx = WORKLOADS[args.workload]
+    w = si.workload(idx)
+    Bk = w.block_size
+    K, Wm = args.steps, args.warmup
+    passes = 1 if args.no_profile else 2
+    e, table, max_len = build_engine(w, S, ctx, Wm + passes * K, dev)
+
+    seq_lens = torch.full((S,), ctx, dtype=torch.int32, device=dev)
+    anchor = torch.full((S,), 11, dtype=torch.int32, device=dev)
+    draft_tokens = torch.zeros((S, Bk), dtype=torch.int32, device=dev)
+    tgt_argmax = torch.zeros_like(draft_tokens)
+    accept_len = torch.zeros(S, dtype=torch.int32, device=dev)
+    out_tokens = torch.zeros_like(draft_tokens)
+    T = float(w.temperature)
+    rng_key = torch.tensor([12345], dtype=torch.int64, device=dev) if T > 0 else None
+    uniforms = torch.rand((S, Bk), device=dev, dtype=torch.float32) if T > 0 else None
+    accepted = torch.zeros(1, dtype=torch.int64, device=dev)
+
+    state = {"upper": ctx}
+
+    def step():
+        b = e.batch(seq_lens, table, anchor, state["upper"])
+        dfl.dflash_draft_block(e, b, draft_tokens, T, rng_key)
+        dfl.dflash_verify(e, b, draft_tokens, tgt_argmax)
+        dfl.dflash_accept(e, b, draft_tokens, tgt_argmax, accept_len, out_tokens, T, uniforms, rng_key)
+        dfl.dflash_kv_commit(e, b, accept_len, out_tokens)
+        state["upper"] += Bk          # host-side bound on the committed length (no device read-back)
+
+    for _ in range(Wm):
+        step()
+    torch.cuda.synchronize(dev)
+    e.device_status()
+    len0 = seq_lens.clone()
+    ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+    torch.cuda.synchronize(dev)
+    ev0.record()
+    for _ in range(K):
+        step()
+    ev1.record()
+    torch.cuda.synchronize(dev)
+    ms_total = ev0.elapsed_time(ev1)
+    e.device_status()
+    committed = int((seq_lens - len0).sum().item())
+    ms_step = ms_total / K
+
+    roof = None
+    extra = {}
+    if not args.no_profile:
+        # the same K steps again with an event pair around every GEMM / attention launch
+        e.profile_enable(True)
+        for _ in range(K):
+            step()
+        prof = e.profile_read()
+        e.profile_enable(False)
+        names = {0: "gemm_store", 1: "gemm_resid", 2: "gemm_swiglu", 3: "attn", 4: "attn_merge", 5: "gemm_lmhead"}
+        per = {}
+        gemm_ms = gemm_bytes = 0.0
+        for k, (ms, cnt, by) in prof.items():
+            per[names[k]] = dict(launches_per_step=cnt / K, avg_us=1e3 * ms / cnt, gbs=(by / cnt) / (ms / cnt) / 1e6 if by else None)
+            if k in (0, 1, 2, 5):
+                gemm_ms += ms
+                gemm_bytes += by
+        extra["kernels"] = per
+        extra["all_gemm"] = dict(ms_per_step=gemm_ms / K, gbs=gemm_bytes / gemm_ms / 1e6)
+        ms, cnt, by = prof[2]        # dominant kernel: gate/up projection with fused SwiGLU
+        ach = (by / cnt) / (ms / cnt) / 1e6
+        roof = dict(bound="hbm", kernel="gemm_bf16_kernel<SWIGLU> (gate/up projection)", achieved=ach, peak=HBM_PEAK_GBS,
+                    unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=None,
+                    bytes_per_launch=by / cnt, avg_launch_us=1e3 * ms / cnt)
+
+    out = {
+        "metric": "draft+verify tokens/sec/GPU (8B-shape, B=16)",
+        "value": S * Bk / (ms_step * 1e-3),
+        "unit": "tokens/s",
+        "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_step,
+        "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
+        "dtype": w.dtype, "data": "synthetic",
+        "config": {"workload": args.workload, "n_seqs": S, "block_size": Bk, "context": ctx,
+                   "temperature": T, "value_counts": "verified positions (S*B per step)"},
+        "committed_tokens_per_s": committed / (ms_total * 1e-3),
+        "mean_tau": committed / (K * S),
+        "roofline": roof,
+    }
+    out.update(extra)
+    if not args.no_cpu_baseline:
+        out["cpu_baseline"] = cpu_baseline(w, ctx)
+    print(json.dumps(out))
+
+
+if __name__ == "__main__":
+    main()

@@ -164,6 +164,24 @@ int dflash_accept(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *dra
 int dflash_kv_commit(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *accept_len,
                      const int32_t *out_tokens, int64_t *kv_slots_out, void *stream);
 
+/* ---- per-launch timing (benchmarks) -------------------------------------------------------------
+ * While enabled, every GEMM and attention launch is bracketed by a pair of HIP events on the caller's
+ * stream (this slows the step down: time whole steps with profiling off).  dflash_profile_read
+ * synchronises the stream, sums elapsed milliseconds, launch counts and algorithmic bytes (GEMM: the
+ * weight matrix once; attention: the K and V rows within the host's max_seq_len hint once) per class
+ * into arrays of DFLASH_PROF_CLASSES entries (host) and forgets the recorded launches. */
+#define DFLASH_PROF_CLASSES 8
+enum {
+  DFLASH_PROF_GEMM_STORE = 0,  /* QKV, W_c and context-K/V projections */
+  DFLASH_PROF_GEMM_RESID = 1,  /* O and down projections (+ residual) */
+  DFLASH_PROF_GEMM_SWIGLU = 2, /* gate/up projection (+ SwiGLU) */
+  DFLASH_PROF_ATTN = 3,        /* split-KV block attention */
+  DFLASH_PROF_ATTN_MERGE = 4,
+  DFLASH_PROF_GEMM_LMHEAD = 5
+};
+int dflash_profile_enable(dflash_ctx *ctx, int32_t enable);
+int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count, double *bytes);
+
 /* ---- cache import / export (state migration, tests) ------------------------------------------ */
 /* Copies rows [start, start+count) of sequence `seq` of one layer between the paged pool and
  * canonical fp32 buffers k, v (device) [count, Hkv, hd].  K rows are stored post-RoPE. */

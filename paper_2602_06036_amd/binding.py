@@ -25,7 +25,7 @@ EXPORTS = [
     "dflash_pack_target_head", "dflash_pack_target_layer", "dflash_pack_draft_head", "dflash_pack_draft_layer",
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
-    "dflash_kv_read", "dflash_kv_write",
+    "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read",
 ]
 
 
@@ -90,6 +90,8 @@ def lib() -> C.CDLL:
         l.dflash_kv_commit.argtypes = [P, C.POINTER(Batch), P, P, P, P]
         l.dflash_kv_read.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
         l.dflash_kv_write.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
+        l.dflash_profile_enable.argtypes = [P, I]
+        l.dflash_profile_read.argtypes = [P, P, C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         for name in EXPORTS:
             if name not in ("dflash_target_blob_bytes", "dflash_draft_blob_bytes", "dflash_kv_pool_bytes",
                             "dflash_workspace_bytes", "dflash_last_error"):
@@ -198,6 +200,16 @@ class Engine:
         assert seq_lens.dtype == torch.int32 and block_table.dtype == torch.int32 and anchor.dtype == torch.int32
         assert block_table.shape == (seq_lens.shape[0], self.max_pages_per_seq)
         return Batch(int(seq_lens.shape[0]), int(max_seq_len), _ptr(seq_lens), _ptr(block_table), _ptr(anchor))
+
+    def profile_enable(self, on: bool):
+        _check(self.l.dflash_profile_enable(self.ctx, int(on)), self.ctx)
+
+    def profile_read(self):
+        """{class index: (ms, launches, algorithmic bytes)} since the last read."""
+        n = 8
+        ms, cnt, by = (C.c_float * n)(), (C.c_int32 * n)(), (C.c_double * n)()
+        _check(self.l.dflash_profile_read(self.ctx, _stream(), ms, cnt, by), self.ctx)
+        return {i: (float(ms[i]), int(cnt[i]), float(by[i])) for i in range(n) if cnt[i]}
 
     def device_status(self):
         _check(self.l.dflash_device_status(self.ctx, _stream()), self.ctx)

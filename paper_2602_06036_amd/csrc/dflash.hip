@@ -10,6 +10,7 @@
 
 #include <algorithm>
 #include <new>
+#include <vector>
 
 #include "attn.h"
 #include "attn_mfma.h"
@@ -205,11 +206,39 @@ struct dflash_ctx {
   const char* dblob;
   char* wsp;
   char err[512];
+  // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
+  bool prof_on = false;
+  std::vector<hipEvent_t> ev;
+  std::vector<int> ev_cls;
+  std::vector<double> ev_bytes;
 };
 
 namespace {
 
 #define CTX_FAIL(ctx, code, ...) fail((ctx)->err, code, __VA_ARGS__)
+
+constexpr size_t kMaxProfLaunches = 16384;
+
+struct ProfScope {
+  dflash_ctx* c;
+  hipStream_t st;
+  hipEvent_t stop = nullptr;
+  ProfScope(dflash_ctx* c_, hipStream_t st_, int cls, double bytes) : c(c_), st(st_) {
+    if (!c->prof_on || c->ev_cls.size() >= kMaxProfLaunches) return;
+    hipEvent_t a, b;
+    if (hipEventCreate(&a) != hipSuccess) return;
+    if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return; }
+    c->ev.push_back(a);
+    c->ev.push_back(b);
+    c->ev_cls.push_back(cls);
+    c->ev_bytes.push_back(bytes);
+    (void)hipEventRecord(a, st);
+    stop = b;
+  }
+  ~ProfScope() {
+    if (stop) (void)hipEventRecord(stop, st);
+  }
+};
 
 template <typename T>
 struct Engine {
@@ -401,8 +430,11 @@ void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N,
   }
 }
 
+inline int gemm_class(int epi, int N, int vocab) { return (epi == EPI_STORE && N == vocab) ? DFLASH_PROF_GEMM_LMHEAD : epi; }
+
 template <>
 void Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep) {
+  ProfScope prof(c, st, gemm_class(epi, N, c->t.vocab), (double)N * K * 2);
   const int nt = N / 16;
   if (M <= 16) {
     if (nt % 4 == 0) launch_bf16<4, 1>(st, W, A, M, N, K, epi, ep);
@@ -417,6 +449,7 @@ void Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int M, int N, int K,
 
 template <>
 void Engine<float>::gemm(const float* W, const float* A, int M, int N, int K, int epi, EpiArgs ep) {
+  ProfScope prof(c, st, gemm_class(epi, N, c->t.vocab), (double)N * K * 4);
   const int cols = epi == EPI_SWIGLU ? N / 2 : N;
   const dim3 grid((cols + 3) / 4), block(256);
   switch (epi) {
@@ -437,13 +470,20 @@ void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const 
   aa.causal = causal ? 1 : 0; aa.chunk = p.chunk; aa.n_splits = p.n_splits; aa.scale = 1.0f / sqrtf((float)m.head_dim);
   float* part_o = ws<float>(c->ws.part_o);
   float2* part_ml = ws<float2>(c->ws.part_ml);
-  if (!attn_mfma_launch<T>(st, ws<T>(c->ws.q), pool, geom(b), aa, S, part_o, part_ml))
-    hipLaunchKernelGGL(attn_partial_simple_kernel<T>, dim3(p.n_splits, m.n_kv_heads, S), dim3(256), 0, st, ws<T>(c->ws.q), pool, geom(b),
-                       aa, part_o, part_ml);
-  check();
-  hipLaunchKernelGGL(attn_merge_kernel<T>, dim3(M * m.n_q_heads), dim3(128), 0, st, part_o, part_ml, ws<T>(c->ws.o), m.n_q_heads,
-                     m.head_dim, p.n_splits);
-  check();
+  {
+    // algorithmic bytes: every cached K and V row of this layer once (upper bound from the host hint)
+    ProfScope prof(c, st, DFLASH_PROF_ATTN, (double)S * max_tokens * 2 * m.n_kv_heads * m.head_dim * sizeof(T));
+    if (!attn_mfma_launch<T>(st, ws<T>(c->ws.q), pool, geom(b), aa, S, part_o, part_ml))
+      hipLaunchKernelGGL(attn_partial_simple_kernel<T>, dim3(p.n_splits, m.n_kv_heads, S), dim3(256), 0, st, ws<T>(c->ws.q), pool,
+                         geom(b), aa, part_o, part_ml);
+    check();
+  }
+  {
+    ProfScope prof(c, st, DFLASH_PROF_ATTN_MERGE, 0.0);
+    hipLaunchKernelGGL(attn_merge_kernel<T>, dim3(M * m.n_q_heads), dim3(128), 0, st, part_o, part_ml, ws<T>(c->ws.o), m.n_q_heads,
+                       m.head_dim, p.n_splits);
+    check();
+  }
 }
 
 // ---- packing helpers -----------------------------------------------------------------------------------
@@ -618,7 +658,32 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
 }
 
 int dflash_destroy(dflash_ctx* ctx) {
+  if (ctx)
+    for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   delete ctx;
+  return DFLASH_OK;
+}
+
+int dflash_profile_enable(dflash_ctx* ctx, int32_t enable) {
+  if (!ctx) return fail(nullptr, DFLASH_EINVAL, "ctx: null");
+  ctx->prof_on = enable != 0;
+  return DFLASH_OK;
+}
+
+int dflash_profile_read(dflash_ctx* ctx, void* stream, float* ms, int32_t* count, double* bytes) {
+  if (!ctx) return fail(nullptr, DFLASH_EINVAL, "ctx: null");
+  if (!ms || !count || !bytes) return CTX_FAIL(ctx, DFLASH_EINVAL, "profile_read: null output");
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "stream synchronise failed");
+  for (int i = 0; i < DFLASH_PROF_CLASSES; ++i) { ms[i] = 0.f; count[i] = 0; bytes[i] = 0.0; }
+  for (size_t i = 0; i < ctx->ev_cls.size(); ++i) {
+    float t = 0.f;
+    if (hipEventElapsedTime(&t, ctx->ev[2 * i], ctx->ev[2 * i + 1]) == hipSuccess) {
+      const int k = ctx->ev_cls[i];
+      ms[k] += t; count[k] += 1; bytes[k] += ctx->ev_bytes[i];
+    }
+  }
+  for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
+  ctx->ev.clear(); ctx->ev_cls.clear(); ctx->ev_bytes.clear();
   return DFLASH_OK;
 }
 
