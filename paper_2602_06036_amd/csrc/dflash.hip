@@ -6,6 +6,7 @@
 #include <math.h>
 #include <stdarg.h>
 #include <stdio.h>
+#include <stdlib.h>
 #include <string.h>
 
 #include <algorithm>
@@ -131,7 +132,7 @@ SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens) {
 
 // ---- workspace ------------------------------------------------------------------------------------
 struct Workspace {
-  size_t status, h, a, qkv, q, o, act, taps, fuse, ht, kvctx, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, total;
+  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, total;
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
   const size_t es = esize(t.dtype);
@@ -148,14 +149,15 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.status = take(256);
   w.h = take((size_t)M * D * 4);
   w.a = take(Mr * D * es * planes);
-  w.qkv = take((size_t)M * nqkv * 4);
   w.q = take((size_t)M * qd * es);
   w.o = take(Mr * qd * es * planes);
   w.act = take(Mr * F * es * planes);
   w.taps = take(Mr * (size_t)rt.n_taps * D * es * planes);
   w.fuse = take((size_t)M * D * 4);
   w.ht = take(Mr * D * es * planes);
-  w.kvctx = take((size_t)M * d.n_layers * 2 * d.n_kv_heads * d.head_dim * 4);
+  // arena: K-range partial results of the QKV / O / down / W_c / context-K/V GEMMs (consumed by the next kernel)
+  const size_t n_max = std::max(std::max(nqkv, D), (size_t)d.n_layers * 2 * d.n_kv_heads * d.head_dim);
+  w.arena = take((size_t)std::max(M, 1024) * n_max * 4);
   w.logits_d = take((size_t)M * t.vocab * 4);
   w.logits_t = take((size_t)M * t.vocab * 4);
   // attention partials: worst case over batch sizes and both models
@@ -267,12 +269,32 @@ struct Engine {
     return g;
   }
 
-  // ---- GEMM dispatch ------------------------------------------------------------------------------
-  void gemm(const T* W, const T* A, int M, int N, int K, int epi, EpiArgs ep);
+  // Result of a GEMM that still has to be summed over its K ranges by the consumer.
+  struct Slab {
+    const float* p = nullptr;
+    int ks = 0;
+    size_t stride = 0;
+  };
+  Slab pending;          // partial sums that the next RMSNorm adds into the residual stream ws.h
+  int pending_tap = -1;  // tap index to be taken from the completed residual stream by the next RMSNorm
 
-  void rmsnorm(const float* x, const float* gain, T* out, int M, int D, float eps) {
-    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(M), dim3(256), 0, st, x, gain, out, D, eps);
+  // ---- GEMM dispatch ------------------------------------------------------------------------------
+  // STORE: partial slabs into ep.out (room for max_ks(M) * M * ld floats).  RESID: y is to be added to
+  // ws.h: the bf16 path writes partial slabs into the arena and returns them as pending, the fp32 path
+  // adds in place and returns nothing.  SWIGLU: complete activations, never split.
+  Slab gemm(const T* W, const T* A, int M, int N, int K, int epi, EpiArgs ep, bool allow_split = true);
+
+  void norm(const float* base, Slab delta, float* h_out, const float* gain, T* out, int M, int D, float eps, int tap = -1) {
+    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(M), dim3(256), 0, st, base, delta.p, delta.ks, delta.stride, h_out, gain, out, D, eps,
+                       tap >= 0 ? ws<T>(c->ws.taps) : (T*)nullptr, tap, c->rt.n_taps * c->t.d_model);
     check();
+  }
+  // RMSNorm of the residual stream, folding in whatever the previous GEMM left pending
+  void norm_h(const float* gain, int M, int D, float eps) {
+    float* h = ws<float>(c->ws.h);
+    norm(h, pending, h, gain, ws<T>(c->ws.a), M, D, eps, pending_tap);
+    pending = Slab{};
+    pending_tap = -1;
   }
 
   void attention(const dflash_dims& m, const T* pool, int layer, const dflash_batch* b, bool causal);
@@ -282,38 +304,33 @@ struct Engine {
     const int S = b->n_seqs, B = c->rt.block_size, M = S * B, D = m.d_model;
     const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, nqkv = qd + 2 * kd;
     float* h = ws<float>(c->ws.h);
+    float* arena = ws<float>(c->ws.arena);
     T* a = ws<T>(c->ws.a);
-    float* qkv = ws<float>(c->ws.qkv);
     T* q = ws<T>(c->ws.q);
     T* o = ws<T>(c->ws.o);
     T* act = ws<T>(c->ws.act);
-    rmsnorm(h, reinterpret_cast<const float*>(lbase + lo.g1), a, M, D, m.rms_eps);
-    EpiArgs e{qkv, nqkv, nullptr, 0};
-    gemm(reinterpret_cast<const T*>(lbase + lo.wqkv), a, M, nqkv, D, EPI_STORE, e);
+    norm_h(reinterpret_cast<const float*>(lbase + lo.g1), M, D, m.rms_eps);
+    const Slab qs = gemm(reinterpret_cast<const T*>(lbase + lo.wqkv), a, M, nqkv, D, EPI_STORE, EpiArgs{arena, nqkv, 0, nullptr, 0});
     RopeArgs ra;
     ra.n_q_heads = m.n_q_heads; ra.n_kv_heads = m.n_kv_heads; ra.head_dim = m.head_dim;
     ra.q_off = 0; ra.k_off = qd; ra.v_off = qd + kd;
     ra.qk_norm = m.qk_norm; ra.eps = m.rms_eps; ra.log_theta = log((double)m.rope_theta); ra.layer = l;
-    hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, m.n_q_heads + 2 * m.n_kv_heads), dim3(64), 0, st, qkv, nqkv,
+    hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, m.n_q_heads + 2 * m.n_kv_heads), dim3(64), 0, st, qs.p, nqkv,
                        reinterpret_cast<const float*>(lbase + lo.qn), reinterpret_cast<const float*>(lbase + lo.kn), q, pool,
-                       geom(b), ra);
+                       geom(b), ra, qs.ks, qs.stride);
     check();
     attention(m, pool, l, b, causal);
-    EpiArgs e2{h, D, nullptr, 0};
-    gemm(reinterpret_cast<const T*>(lbase + lo.wo), o, M, D, qd, EPI_RESID, e2);
-    rmsnorm(h, reinterpret_cast<const float*>(lbase + lo.g2), a, M, D, m.rms_eps);
-    EpiArgs e3{nullptr, 0, act, m.d_ffn};
-    gemm(reinterpret_cast<const T*>(lbase + lo.wgu), a, M, 2 * m.d_ffn, D, EPI_SWIGLU, e3);
-    EpiArgs e4{h, D, nullptr, 0};
-    gemm(reinterpret_cast<const T*>(lbase + lo.wd), act, M, D, m.d_ffn, EPI_RESID, e4);
+    pending = gemm(reinterpret_cast<const T*>(lbase + lo.wo), o, M, D, qd, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
+    norm_h(reinterpret_cast<const float*>(lbase + lo.g2), M, D, m.rms_eps);
+    gemm(reinterpret_cast<const T*>(lbase + lo.wgu), a, M, 2 * m.d_ffn, D, EPI_SWIGLU, EpiArgs{nullptr, 0, 0, act, m.d_ffn});
+    pending = gemm(reinterpret_cast<const T*>(lbase + lo.wd), act, M, D, m.d_ffn, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
   }
 
   void lm_head(const float* final_gain, float eps, int M, float* logits) {
     const dflash_dims& t = c->t;
-    T* a = ws<T>(c->ws.a);
-    rmsnorm(ws<float>(c->ws.h), final_gain, a, M, t.d_model, eps);
-    EpiArgs e{logits, t.vocab, nullptr, 0};
-    gemm(reinterpret_cast<const T*>(c->tblob + c->tl.lm), a, M, t.vocab, t.d_model, EPI_STORE, e);
+    norm_h(final_gain, M, t.d_model, eps);
+    gemm(reinterpret_cast<const T*>(c->tblob + c->tl.lm), ws<T>(c->ws.a), M, t.vocab, t.d_model, EPI_STORE,
+         EpiArgs{logits, t.vocab, 0, nullptr, 0}, false);
   }
 
   int draft_block(const dflash_batch* b, float temperature, const uint64_t* rng_key, int32_t* draft_tokens, float* logits_out) {
@@ -348,12 +365,7 @@ struct Engine {
     int tap = 0;
     for (int l = 0; l < t.n_layers; ++l) {
       layer(t, c->tblob + c->tl.layer0 + c->tl.lo.end * l, c->tl.lo, reinterpret_cast<T*>(c->rt.target_kv_pool), l, b, true);
-      if (tap < c->rt.n_taps && c->rt.tap_layers[tap] == l) {
-        hipLaunchKernelGGL(tap_copy_kernel<T>, dim3(M), dim3(256), 0, st, ws<float>(c->ws.h), ws<T>(c->ws.taps), t.d_model, tap,
-                           c->rt.n_taps * t.d_model);
-        check();
-        ++tap;
-      }
+      if (tap < c->rt.n_taps && c->rt.tap_layers[tap] == l) pending_tap = tap++;   // taken by the next RMSNorm
     }
     float* logits = ws<float>(c->ws.logits_t);
     lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits);
@@ -391,23 +403,21 @@ struct Engine {
     const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
     const dflash_dims& d = c->d;
     const int D = d.d_model, kd = d.n_kv_heads * d.head_dim, nkv = d.n_layers * 2 * kd;
-    float* fuse = ws<float>(c->ws.fuse);
+    float* arena = ws<float>(c->ws.arena);
     T* ht = ws<T>(c->ws.ht);
-    float* kvctx = ws<float>(c->ws.kvctx);
-    EpiArgs e{fuse, D, nullptr, 0};
-    gemm(reinterpret_cast<const T*>(c->dblob + c->dl.wc), ws<T>(c->ws.taps), M, D, c->rt.n_taps * c->t.d_model, EPI_STORE, e);
-    rmsnorm(fuse, reinterpret_cast<const float*>(c->dblob + c->dl.gc), ht, M, D, d.rms_eps);
-    EpiArgs e2{kvctx, nkv, nullptr, 0};
-    gemm(reinterpret_cast<const T*>(c->dblob + c->dl.wkv_all), ht, M, nkv, D, EPI_STORE, e2);
+    const Slab fs = gemm(reinterpret_cast<const T*>(c->dblob + c->dl.wc), ws<T>(c->ws.taps), M, D, c->rt.n_taps * c->t.d_model, EPI_STORE,
+                         EpiArgs{arena, D, 0, nullptr, 0});
+    norm(nullptr, fs, ws<float>(c->ws.fuse), reinterpret_cast<const float*>(c->dblob + c->dl.gc), ht, M, D, d.rms_eps);
+    const Slab kvs = gemm(reinterpret_cast<const T*>(c->dblob + c->dl.wkv_all), ht, M, nkv, D, EPI_STORE, EpiArgs{arena, nkv, 0, nullptr, 0});
     for (int i = 0; i < d.n_layers; ++i) {
       RopeArgs ra;
       ra.n_q_heads = 0; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = d.head_dim;
       ra.q_off = 0; ra.k_off = i * 2 * kd; ra.v_off = i * 2 * kd + kd;
       ra.qk_norm = d.qk_norm; ra.eps = d.rms_eps; ra.log_theta = log((double)d.rope_theta); ra.layer = i;
       const char* lbase = c->dblob + c->dl.layer0 + c->dl.lo.end * i;
-      hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, 2 * d.n_kv_heads), dim3(64), 0, st, kvctx, nkv, (const float*)nullptr,
+      hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, 2 * d.n_kv_heads), dim3(64), 0, st, kvs.p, nkv, (const float*)nullptr,
                          reinterpret_cast<const float*>(lbase + c->dl.lo.kn), (T*)nullptr, reinterpret_cast<T*>(c->rt.draft_kv_pool),
-                         geom(b), ra);
+                         geom(b), ra, kvs.ks, kvs.stride);
       check();
     }
     hipLaunchKernelGGL(commit_update_kernel, dim3((S + 63) / 64), dim3(64), 0, st, geom(b), b->seq_lens, b->anchor, accept_len,
@@ -418,37 +428,83 @@ struct Engine {
 };
 
 // ---- GEMM dispatch ----------------------------------------------------------------------------------
-template <int NT, int MT>
-void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep) {
-  const dim3 grid((N / 16) / NT, ((M + 15) / 16 + MT - 1) / MT), block(256);
-  switch (epi) {
-    case EPI_STORE: hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, ep); break;
-    case EPI_RESID: hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, EPI_RESID>), grid, block, 0, st, W, A, M, N, K, ep); break;
-    default:
-      if constexpr (NT >= 2) hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, ep);
-      break;
+constexpr int kMaxKSplit = 16;
+constexpr int kArenaSplitRows = 1024;   // ks * M never exceeds max(M, this)
+
+template <int NT, int MT, int U>
+void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
+  const dim3 grid((N / 16) / NT, ((M + 15) / 16 + MT - 1) / MT, ks), block(256);
+  if (epi == EPI_SWIGLU) {
+    if constexpr (NT >= 2) hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, U, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, ep);
+  } else {
+    hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, U, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, ep);
   }
 }
 
 inline int gemm_class(int epi, int N, int vocab) { return (epi == EPI_STORE && N == vocab) ? DFLASH_PROF_GEMM_LMHEAD : epi; }
 
-template <>
-void Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep) {
-  ProfScope prof(c, st, gemm_class(epi, N, c->t.vocab), (double)N * K * 2);
-  const int nt = N / 16;
-  if (M <= 16) {
-    if (nt % 4 == 0) launch_bf16<4, 1>(st, W, A, M, N, K, epi, ep);
-    else if (nt % 2 == 0) launch_bf16<2, 1>(st, W, A, M, N, K, epi, ep);
-    else launch_bf16<1, 1>(st, W, A, M, N, K, epi, ep);
-  } else {
-    if (nt % 2 == 0) launch_bf16<2, 4>(st, W, A, M, N, K, epi, ep);
-    else launch_bf16<1, 4>(st, W, A, M, N, K, epi, ep);
-  }
-  check();
+inline int env_int(const char* name, int dflt) {
+  const char* e = getenv(name);
+  const int v = e ? atoi(e) : 0;
+  return v > 0 ? v : dflt;
+}
+
+// K split across workgroups: aim at enough workgroups that every CU keeps several wavefronts streaming,
+// keep at least 2 k-tiles per wavefront, and stay inside the arena.
+inline int pick_ksplit(int n_blocks, int KT, int M) {
+  static const int target = env_int("DFLASH_GEMM_TARGET_WGS", 256);   // tuning knob
+  int ks = 1;
+  while (ks < kMaxKSplit && n_blocks * ks * 2 <= target && KT / (ks * 2 * 4) >= 2 && ks * 2 * M <= kArenaSplitRows) ks *= 2;
+  return ks;
 }
 
 template <>
-void Engine<float>::gemm(const float* W, const float* A, int M, int N, int K, int epi, EpiArgs ep) {
+Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, bool allow_split) {
+  ProfScope prof(c, st, gemm_class(epi, N, c->t.vocab), (double)N * K * 2);
+  static const int U = env_int("DFLASH_GEMM_U", 2);   // tuning knob: k-tiles per prefetch stage
+  const int nt = N / 16, KT = K / 32;
+  int kepi = epi;
+  if (epi == EPI_RESID) {   // partial slabs into the arena; the next RMSNorm adds them to the residual stream
+    ep.out = ws<float>(c->ws.arena);
+    kepi = EPI_STORE;
+  }
+  const bool split = allow_split && epi != EPI_SWIGLU;
+  int ks = 1;
+  if (M <= 16) {
+    if (nt % 4 == 0) {
+      if (split) ks = pick_ksplit(nt / 4, KT, M);
+      ep.slab = (size_t)M * ep.ld;
+      if (U >= 4) launch_bf16<4, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
+      else if (U >= 2) launch_bf16<4, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      else launch_bf16<4, 1, 1>(st, W, A, M, N, K, kepi, ep, ks);
+    } else if (nt % 2 == 0) {
+      if (split) ks = pick_ksplit(nt / 2, KT, M);
+      ep.slab = (size_t)M * ep.ld;
+      launch_bf16<2, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
+    } else {
+      if (split) ks = pick_ksplit(nt, KT, M);
+      ep.slab = (size_t)M * ep.ld;
+      launch_bf16<1, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
+    }
+  } else {
+    const int my = ((M + 15) / 16 + 3) / 4;
+    if (nt % 2 == 0) {
+      if (split && my == 1) ks = pick_ksplit(nt / 2, KT, M);
+      ep.slab = (size_t)M * ep.ld;
+      launch_bf16<2, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
+    } else {
+      if (split && my == 1) ks = pick_ksplit(nt, KT, M);
+      ep.slab = (size_t)M * ep.ld;
+      launch_bf16<1, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
+    }
+  }
+  check();
+  if (epi == EPI_SWIGLU) return Slab{};
+  return Slab{ep.out, ks, ep.slab};
+}
+
+template <>
+Engine<float>::Slab Engine<float>::gemm(const float* W, const float* A, int M, int N, int K, int epi, EpiArgs ep, bool) {
   ProfScope prof(c, st, gemm_class(epi, N, c->t.vocab), (double)N * K * 4);
   const int cols = epi == EPI_SWIGLU ? N / 2 : N;
   const dim3 grid((cols + 3) / 4), block(256);
@@ -458,6 +514,8 @@ void Engine<float>::gemm(const float* W, const float* A, int M, int N, int K, in
     default: hipLaunchKernelGGL(gemm_f32_kernel<EPI_SWIGLU>, grid, block, 0, st, W, A, M, N, K, ep); break;
   }
   check();
+  if (epi == EPI_STORE) return Slab{ep.out, 1, (size_t)M * ep.ld};
+  return Slab{};
 }
 
 template <typename T>

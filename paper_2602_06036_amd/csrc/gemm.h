@@ -8,32 +8,45 @@
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
 
 struct EpiArgs {
-  float* out;   // STORE: out[m*ld + n] = y ; RESID: out[m*ld + n] += y
+  float* out;   // STORE: out[z*slab + m*ld + n] = partial y of K range z ; RESID (fp32 kernel): out[m*ld + n] += y
   int ld;
-  void* act;    // SWIGLU: act (tile layout, row length act_K) [m, j] = silu(gate_j) * up_j
+  size_t slab;  // elements between the partial results of consecutive K ranges (grid.z)
+  void* act;    // SWIGLU: act (GEMM activation operand, row length act_K) [m, j] = silu(gate_j) * up_j
   int act_K;
 };
+
+// Split of K across workgroups (grid.z ranges): the STORE epilogue writes one partial slab per range and
+// the kernel that consumes the result (RMSNorm, q/k-norm + RoPE) adds the slabs in ascending order.
+// The kernel boundary provides the ordering: no atomics, no fences, and a sum that does not depend on
+// which workgroup finished first.
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
 // ------------------------------------------------------------------------------------------------
 // bf16 MFMA kernel.  A workgroup of 4 wavefronts owns NT 16-row bands of W (N tiles) and MT 16-row
-// bands of the activations; each wavefront streams one quarter of K and the four partial sums are
-// added in a fixed order through LDS (deterministic).  The MFMA computes D^T = W_tile * a_tile^T:
-// lane l ends up holding y[m = l%16][n = 4*(l/16) .. +3].
+// bands of the activations for one K range (grid.z ranges); each wavefront streams a quarter of that
+// range, U k-tiles at a time with the next U already in flight, every activation fragment reused for
+// the NT weight tiles.  The four partial sums are added in a fixed order through LDS.  The MFMA
+// computes D^T = W_tile * a_tile^T: lane l ends up holding y[m = l%16][n = 4*(l/16) .. +3].
 // SWIGLU: W rows alternate 16 gate rows / 16 up rows, so tiles (2p, 2p+1) of a workgroup are the
 // gate and up values of the same 16 activation columns.
 // ------------------------------------------------------------------------------------------------
-template <int NT, int MT, int EPI>
+template <int NT, int MT, int U>
+struct GemmBuf {
+  u32x4 w[U][NT], ah[U][MT], al[U][MT];
+};
+
+template <int NT, int MT, int U, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
                                                         int M, int N, int K, EpiArgs ep) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
-  const int nt0 = blockIdx.x * NT, mt0 = blockIdx.y * MT;
+  const int nt0 = blockIdx.x * NT, mt0 = blockIdx.y * MT, kz = blockIdx.z;
   const int KT = K >> 5;
   const int m_tiles = (M + 15) >> 4;
-  const int kt_per = (KT + 3) >> 2;
-  const int kt_begin = wave * kt_per;
-  const int kt_end = min(KT, kt_begin + kt_per);
+  const int ks = gridDim.z;
+  const int per = (KT + ks * 4 - 1) / (ks * 4);
+  const int kb = min(KT, (kz * 4 + wave) * per);
+  const int ke = min(KT, kb + per);
 
   f32x4 acc[NT][MT];
 #pragma unroll
@@ -49,25 +62,47 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
   for (int j = 0; j < MT; ++j) a_band[j] = (size_t)min(mt0 + j, m_tiles - 1) * KT * 128;
 
-#pragma unroll 4
-  for (int kt = kt_begin; kt < kt_end; ++kt) {
-    u32x4 wf[NT], ah[MT], al[MT];
+  auto load = [&](GemmBuf<NT, MT, U>& b, int k0) {
 #pragma unroll
-    for (int i = 0; i < NT; ++i) wf[i] = __builtin_nontemporal_load(Wp + ((size_t)(nt0 + i) * KT + kt) * 64);
+    for (int u = 0; u < U; ++u) {
+      const bool in = k0 + u < ke;
+      const int kt = in ? k0 + u : ke - 1;   // past the range: re-read the last tile, with zeroed activations
 #pragma unroll
-    for (int j = 0; j < MT; ++j) {
-      ah[j] = Ap[a_band[j] + (size_t)kt * 128];
-      al[j] = Ap[a_band[j] + (size_t)kt * 128 + 64];
-    }
-#pragma unroll
-    for (int i = 0; i < NT; ++i)
+      for (int i = 0; i < NT; ++i) b.w[u][i] = __builtin_nontemporal_load(Wp + ((size_t)(nt0 + i) * KT + kt) * 64);
 #pragma unroll
       for (int j = 0; j < MT; ++j) {
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]),
-                                                            __builtin_bit_cast(bf16x8, ah[j]), acc[i][j], 0, 0, 0);
-        acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]),
-                                                            __builtin_bit_cast(bf16x8, al[j]), acc[i][j], 0, 0, 0);
+        const u32x4 h = Ap[a_band[j] + (size_t)kt * 128], l = Ap[a_band[j] + (size_t)kt * 128 + 64];
+        b.ah[u][j] = in ? h : (u32x4){0u, 0u, 0u, 0u};
+        b.al[u][j] = in ? l : (u32x4){0u, 0u, 0u, 0u};
       }
+    }
+  };
+  auto compute = [&](const GemmBuf<NT, MT, U>& b) {
+#pragma unroll
+    for (int u = 0; u < U; ++u)
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < MT; ++j) {
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b.w[u][i]),
+                                                              __builtin_bit_cast(bf16x8, b.ah[u][j]), acc[i][j], 0, 0, 0);
+          acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b.w[u][i]),
+                                                              __builtin_bit_cast(bf16x8, b.al[u][j]), acc[i][j], 0, 0, 0);
+        }
+  };
+
+  if (kb < ke) {
+    GemmBuf<NT, MT, U> b0, b1;
+    load(b0, kb);
+    for (int k0 = kb; k0 < ke; k0 += 2 * U) {
+      const bool more = k0 + U < ke;
+      if (more) load(b1, k0 + U);
+      compute(b0);
+      if (more) {
+        if (k0 + 2 * U < ke) load(b0, k0 + 2 * U);
+        compute(b1);
+      }
+    }
   }
 
   __shared__ float4 red[4][NT * MT][64];
@@ -78,18 +113,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       red[wave][i * MT + j][lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
   __syncthreads();
 
+  auto wg_sum = [&](int t) {   // the four wavefronts' partial sums of tile t, in wavefront order
+    float4 s = red[0][t][lane];
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const float4 a = red[w][t][lane];
+      s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+    return s;
+  };
+
+  auto tile_sum = wg_sum;
+
   const int mrow = lane & 15, g = lane >> 4;
   if (EPI == EPI_SWIGLU) {
     bf16_t* act = reinterpret_cast<bf16_t*>(ep.act);
     for (int t = wave; t < (NT / 2) * MT; t += 4) {
       const int p = t / MT, j = t % MT;
-      float4 gs = red[0][(2 * p) * MT + j][lane], us = red[0][(2 * p + 1) * MT + j][lane];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) {
-        float4 a = red[w][(2 * p) * MT + j][lane], b = red[w][(2 * p + 1) * MT + j][lane];
-        gs.x += a.x; gs.y += a.y; gs.z += a.z; gs.w += a.w;
-        us.x += b.x; us.y += b.y; us.z += b.z; us.w += b.w;
-      }
+      const float4 gs = tile_sum((2 * p) * MT + j), us = tile_sum((2 * p + 1) * MT + j);
       const int m = (mt0 + j) * 16 + mrow;
       if (mt0 + j < m_tiles && m < M) {
         const int col = ((nt0 + 2 * p) >> 1) * 16 + 4 * g;
@@ -100,19 +141,10 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   } else {
     for (int t = wave; t < NT * MT; t += 4) {
       const int i = t / MT, j = t % MT;
-      float4 s = red[0][t][lane];
-#pragma unroll
-      for (int w = 1; w < 4; ++w) {
-        float4 a = red[w][t][lane];
-        s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
-      }
+      const float4 s = tile_sum(t);
       const int m = (mt0 + j) * 16 + mrow;
       if (mt0 + j < m_tiles && m < M) {
-        float4* dst = reinterpret_cast<float4*>(ep.out + (size_t)m * ep.ld + (nt0 + i) * 16 + 4 * g);
-        if (EPI == EPI_RESID) {
-          float4 h = *dst;
-          s.x += h.x; s.y += h.y; s.z += h.z; s.w += h.w;
-        }
+        float4* dst = reinterpret_cast<float4*>(ep.out + (size_t)kz * ep.slab + (size_t)m * ep.ld + (nt0 + i) * 16 + 4 * g);
         *dst = s;
       }
     }

@@ -1,5 +1,5 @@
 // Small memory-bound kernels of the step: embedding gather, RMSNorm, q/k-norm + RoPE + KV page
-// write, tap copy, row argmax / Gumbel-max, acceptance, commit bookkeeping, weight packing and
+// write, row argmax / Gumbel-max, acceptance, commit bookkeeping, weight packing and
 // KV import/export.
 #pragma once
 #include "common.h"
@@ -26,15 +26,27 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
   for (int d = threadIdx.x; d < D; d += blockDim.x) h[(size_t)m * D + d] = Store<T>::to(src[d]);
 }
 
-// ---- RMSNorm: fp32 rows [M, D] -> GEMM activation operand (Act<T>) ----------------------------
+// ---- RMSNorm with pending-sum reduction -----------------------------------------------------------
+// x[m,:] = base[m,:] (if base) + sum_z delta[z*slab + m*D + :] (ascending z: the K-range partial results of
+// the preceding GEMM).  When delta is given the completed row is written to h_out (the residual stream).
+// Optionally the completed row is also stored as tap `tap_idx` (GEMM activation operand, row length tap_K).
+// out[m,:] = x * gain / sqrt(mean(x^2) + eps) as GEMM activation operand (Act<T>).
 template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ x, const float* __restrict__ gain,
-                                                      T* __restrict__ out, int D, float eps) {
+__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const float* __restrict__ delta, int ks,
+                                                      size_t slab, float* h_out, const float* __restrict__ gain,
+                                                      T* __restrict__ out, int D, float eps, T* __restrict__ taps, int tap_idx,
+                                                      int tap_K) {
   const int m = blockIdx.x;
-  const float* row = x + (size_t)m * D;
+  const size_t ro = (size_t)m * D;
   float ss = 0.f;
   for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
-    const float4 v = *reinterpret_cast<const float4*>(row + d);
+    float4 v = base ? *reinterpret_cast<const float4*>(base + ro + d) : make_float4(0.f, 0.f, 0.f, 0.f);
+    for (int z = 0; z < ks; ++z) {
+      const float4 p = *reinterpret_cast<const float4*>(delta + (size_t)z * slab + ro + d);
+      v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
+    }
+    if (ks > 0) *reinterpret_cast<float4*>(h_out + ro + d) = v;
+    if (taps) Act<T>::store4(taps, m, tap_idx * D + d, tap_K, v);
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   __shared__ float part[4];
@@ -43,25 +55,18 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* __restrict__ 
   __syncthreads();
   const float tot = part[0] + part[1] + part[2] + part[3];
   const float rstd = 1.0f / sqrtf(tot / (float)D + eps);
+  const float* src = ks > 0 ? h_out : base;   // each thread re-reads exactly what it wrote
   for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
-    const float4 v = *reinterpret_cast<const float4*>(row + d);
+    const float4 v = *reinterpret_cast<const float4*>(src + ro + d);
     const float4 g = *reinterpret_cast<const float4*>(gain + d);
     Act<T>::store4(out, m, d, D, make_float4(v.x * rstd * g.x, v.y * rstd * g.y, v.z * rstd * g.z, v.w * rstd * g.w));
   }
 }
 
-// ---- tap copy: taps[m, t*D + d] = h[m, d] as GEMM activation operand (row length n_taps*D) ---
-template <typename T>
-__global__ __launch_bounds__(256) void tap_copy_kernel(const float* __restrict__ h, T* __restrict__ taps, int D, int t,
-                                                       int K_total) {
-  const int m = blockIdx.x;
-  for (int d = threadIdx.x; d < D; d += blockDim.x)
-    Act<T>::store(taps, m, t * D + d, K_total, h[(size_t)m * D + d]);
-}
-
 // ---- q/k RMSNorm + RoPE + cache write ------------------------------------------------------------
 // One wavefront per (row m, head); lane i owns the rotate-half pair (i, i + hd/2) [hd <= 128].
-// Input row: fp32 [.. q heads | k heads | v heads ..] starting at in + m*in_ld.
+// Input row: fp32 [.. q heads | k heads | v heads ..] starting at in + m*in_ld, given as `ks` partial
+// slabs (K ranges of the producing GEMM) `slab` elements apart that are added in ascending order.
 // q heads -> q_out [M, Hq, hd] row-major storage type; k/v heads -> page of position seq_len + slot.
 // Angles are formed in double precision (pos * theta^(-2i/hd), reduced by sincos) so that long
 // contexts do not lose phase accuracy.
@@ -77,7 +82,7 @@ struct RopeArgs {
 template <typename T>
 __global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ in, int in_ld, const float* __restrict__ qn,
                                                       const float* __restrict__ kn, T* __restrict__ q_out,
-                                                      T* __restrict__ pool, SeqGeom geo, RopeArgs ra) {
+                                                      T* __restrict__ pool, SeqGeom geo, RopeArgs ra, int ks, size_t slab) {
   const int m = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
   const int hd = ra.head_dim, half = hd >> 1;
   const int s = m / geo.block_size, slot = m % geo.block_size;
@@ -87,7 +92,12 @@ __global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ 
   const int kvh = is_q ? 0 : (is_k ? head - ra.n_q_heads : head - ra.n_q_heads - ra.n_kv_heads);
   const float* src = in + (size_t)m * in_ld + (is_q ? ra.q_off + head * hd : (is_k ? ra.k_off : ra.v_off) + kvh * hd);
   const bool active = lane < half;
-  float x1 = active ? src[lane] : 0.f, x2 = active ? src[lane + half] : 0.f;
+  float x1 = 0.f, x2 = 0.f;
+  if (active)
+    for (int z = 0; z < ks; ++z) {
+      x1 += src[(size_t)z * slab + lane];
+      x2 += src[(size_t)z * slab + lane + half];
+    }
   if (!is_q) {
     const int pidx = pos / DF_PAGE;
     int page = -1;
