@@ -131,7 +131,7 @@ class Engine:
     """Owns the device buffers (torch tensors) that the C library works on, and the context."""
 
     def __init__(self, target, draft, dtype: str, block_size: int, max_seqs: int, max_pages_per_seq: int,
-                 n_pages: int, tap_layers: Sequence[int], mask_token_id: int, device: str = "cuda:0"):
+                 n_pages: int, tap_layers: Sequence[int], mask_token_id: int, device: str = "cuda:0", blobs=None):
         self.l = lib()
         self.device = torch.device(device)
         self.dtype = dtype
@@ -150,8 +150,12 @@ class Engine:
         db = self.l.dflash_draft_blob_bytes(C.byref(self.dd), self.n_taps, target.d_model)
         if tb == 0 or db == 0:
             _check(DFLASH_EINVAL)
-        self.target_blob = torch.empty(tb, dtype=torch.uint8, device=self.device)
-        self.draft_blob = torch.empty(db, dtype=torch.uint8, device=self.device)
+        if blobs is not None:                      # already-packed weights of the same models (shared between engines)
+            self.target_blob, self.draft_blob = blobs
+            assert self.target_blob.numel() == tb and self.draft_blob.numel() == db
+        else:
+            self.target_blob = torch.empty(tb, dtype=torch.uint8, device=self.device)
+            self.draft_blob = torch.empty(db, dtype=torch.uint8, device=self.device)
         self.ctx = None
 
     # ---- weights -------------------------------------------------------------------------------

@@ -95,8 +95,10 @@ __global__ __launch_bounds__(256) void attn_partial_simple_kernel(const T* __res
 }
 
 // ------------------------------------------------------------------------------------------------
-// Merge of the splits in ascending split order; grid (M*Hq), block 128.
-// Output as GEMM activation operand (Act<T>), row length Hq*hd.
+// Merge of the splits in ascending split order; grid (M*Hq), block 128 (one thread per head dim).
+// The (max, sum) pairs are fetched by the first wavefront with one load per split, the partial
+// outputs with independent loads four at a time, so the kernel is not a chain of dependent loads.
+// Output as GEMM activation operand (Act<T>), row length Hq*hd.  n_splits <= 64.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
 __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
@@ -104,15 +106,34 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict
   const int row = blockIdx.x;  // m*Hq + hq
   const int m = row / n_q_heads, hq = row % n_q_heads;
   const int d = threadIdx.x;
-  float mx = -INFINITY;
-  for (int c = 0; c < n_splits; ++c) mx = fmaxf(mx, part_ml[(size_t)row * n_splits + c].x);
-  float L = 0.f, o = 0.f;
-  for (int c = 0; c < n_splits; ++c) {
-    const float2 ml = part_ml[(size_t)row * n_splits + c];
-    if (ml.y <= 0.f) continue;
-    const float w = expf(ml.x - mx);
-    L += ml.y * w;
-    if (d < hd) o += w * part_o[((size_t)row * n_splits + c) * hd + d];
+  __shared__ float wgt[64];
+  __shared__ float s_L;
+  if (threadIdx.x < 64) {
+    const int c = threadIdx.x;
+    float2 ml = make_float2(-INFINITY, 0.f);
+    if (c < n_splits) ml = part_ml[(size_t)row * n_splits + c];
+    const float mx = wave_reduce_max(ml.y > 0.f ? ml.x : -INFINITY);
+    const float w = (ml.y > 0.f) ? expf(ml.x - mx) : 0.f;
+    wgt[c] = w;
+    // sum in ascending split order (fixed order, independent of the wavefront reduction tree)
+    float L = 0.f;
+    for (int i = 0; i < n_splits; ++i) L += __shfl(ml.y * w, i, 64);
+    if (c == 0) s_L = L;
   }
-  if (d < hd) Act<T>::store(out, m, hq * hd + d, n_q_heads * hd, L > 0.f ? o / L : 0.f);
+  __syncthreads();
+  if (d < hd) {
+    const float* po = part_o + (size_t)row * n_splits * hd + d;
+    float o = 0.f;
+    int c = 0;
+    for (; c + 4 <= n_splits; c += 4) {
+      const float a0 = po[(size_t)(c + 0) * hd], a1 = po[(size_t)(c + 1) * hd], a2 = po[(size_t)(c + 2) * hd], a3 = po[(size_t)(c + 3) * hd];
+      o += wgt[c] * a0;
+      o += wgt[c + 1] * a1;
+      o += wgt[c + 2] * a2;
+      o += wgt[c + 3] * a3;
+    }
+    for (; c < n_splits; ++c) o += wgt[c] * po[(size_t)c * hd];
+    const float L = s_L;
+    Act<T>::store(out, m, hq * hd + d, n_q_heads * hd, L > 0.f ? o / L : 0.f);
+  }
 }

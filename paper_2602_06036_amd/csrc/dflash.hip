@@ -117,7 +117,9 @@ struct SplitPlan {
   int bound;  // >= n_splits for this and every smaller max_tokens (sizes the partial buffers)
 };
 SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens) {
-  const int target_wgs = 1024, max_splits = 64;
+  // the attention kernel runs one workgroup per CU (its accumulators fill the register file), so aim at
+  // one round of workgroups on the 256 CUs
+  const int target_wgs = 256, max_splits = 64;
   int splits = (target_wgs + S * n_kv_heads - 1) / (S * n_kv_heads);
   const int by_len = (max_tokens + 63) / 64;
   splits = std::max(1, std::min(splits, std::min(by_len, max_splits)));

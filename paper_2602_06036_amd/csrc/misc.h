@@ -41,7 +41,17 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const f
   float ss = 0.f;
   for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
     float4 v = base ? *reinterpret_cast<const float4*>(base + ro + d) : make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int z = 0; z < ks; ++z) {
+    int z = 0;
+    for (; z + 4 <= ks; z += 4) {   // four independent loads in flight, added in ascending order
+      const float* pz = delta + (size_t)z * slab + ro + d;
+      const float4 p0 = *reinterpret_cast<const float4*>(pz), p1 = *reinterpret_cast<const float4*>(pz + slab);
+      const float4 p2 = *reinterpret_cast<const float4*>(pz + 2 * slab), p3 = *reinterpret_cast<const float4*>(pz + 3 * slab);
+      v.x += p0.x; v.y += p0.y; v.z += p0.z; v.w += p0.w;
+      v.x += p1.x; v.y += p1.y; v.z += p1.z; v.w += p1.w;
+      v.x += p2.x; v.y += p2.y; v.z += p2.z; v.w += p2.w;
+      v.x += p3.x; v.y += p3.y; v.z += p3.z; v.w += p3.w;
+    }
+    for (; z < ks; ++z) {
       const float4 p = *reinterpret_cast<const float4*>(delta + (size_t)z * slab + ro + d);
       v.x += p.x; v.y += p.y; v.z += p.z; v.w += p.w;
     }

@@ -71,6 +71,11 @@ class Workload:
     temperature: float
     seed: int
     n_steps: int = 1
+    weight_seed: Optional[int] = None   # None: weights use `seed`; the 8B configurations share one set
+
+    @property
+    def wseed(self) -> int:
+        return self.seed if self.weight_seed is None else self.weight_seed
 
 
 def tap_layers_for(n_layers: int, n_taps: int) -> Tuple[int, ...]:
@@ -104,11 +109,11 @@ def workload(idx: int) -> Workload:
     if idx == 2:
         return Workload("cfg2_8b_b1_ctx2048", "bf16", t, d, taps, mask, 16, 1, 2048, 2048, 0.0, 2)
     if idx == 3:
-        return Workload("cfg3_8b_b16_ctx1k-4k", "bf16", t, d, taps, mask, 16, 16, 1024, 4096, 0.0, 3)
+        return Workload("cfg3_8b_b16_ctx1k-4k", "bf16", t, d, taps, mask, 16, 16, 1024, 4096, 0.0, 3, weight_seed=2)
     if idx == 4:
-        return Workload("cfg4_8b_b4_ctx16k", "bf16", t, d, taps, mask, 16, 4, 16384, 16384, 0.0, 4)
+        return Workload("cfg4_8b_b4_ctx16k", "bf16", t, d, taps, mask, 16, 4, 16384, 16384, 0.0, 4, weight_seed=2)
     if idx == 5:
-        return Workload("cfg5_8b_b32_ctx8k_T1", "bf16", t, d, taps, mask, 16, 32, 8192, 8192, 1.0, 5)
+        return Workload("cfg5_8b_b32_ctx8k_T1", "bf16", t, d, taps, mask, 16, 32, 8192, 8192, 1.0, 5, weight_seed=2)
     raise ValueError(idx)
 
 
@@ -208,9 +213,9 @@ def make_weights(w: Workload, n_threads: int = 8) -> Tuple[Weights, Weights]:
         dst, prefix, key, shape, gain = job
         full = f"{prefix}.{key}"
         if gain:
-            dst.t[key] = _gain(w.seed, full, shape[0])
+            dst.t[key] = _gain(w.wseed, full, shape[0])
         else:
-            dst.t[key] = _matrix(w.seed, full, shape, w.dtype)
+            dst.t[key] = _matrix(w.wseed, full, shape, w.dtype)
 
     if n_threads > 1:
         with ThreadPoolExecutor(n_threads) as ex:
@@ -256,3 +261,31 @@ def make_accept_plan(w: Workload, step: int = 0) -> np.ndarray:
     """Per-sequence number of correct proposals k_s in [0, block_size-1] for tests that feed
     verification with constructed proposals (true continuation for k_s slots, then a wrong one)."""
     return _rng(w.seed, f"plan{step}").integers(0, w.block_size, size=w.n_seqs).astype(np.int32)
+
+
+# --------------------------------------------------------------------------------------
+# synthetic cache state (stands in for a prefill at sizes the CPU oracle cannot prefill)
+# --------------------------------------------------------------------------------------
+def make_context_lengths(w: Workload) -> np.ndarray:
+    """Committed length n_s of every sequence (the same draw as make_prompts uses)."""
+    r = _rng(w.seed, "prompts")
+    return r.integers(w.ctx_min, w.ctx_max + 1, size=w.n_seqs).astype(np.int64)
+
+
+def make_state_rows(w: Workload, seq: int, pool: str, layer: int, n: int) -> Tuple[np.ndarray, np.ndarray]:
+    """K and V rows [n, Hkv, hd] (fp32 holding bf16-representable values for a bf16 workload) of one layer
+    of one sequence's cache: unit-variance normals, the scale real K rows have after k-norm and RoPE.
+    pool: "target" | "draft"."""
+    m = w.target if pool == "target" else w.draft
+    r = _rng(w.seed, f"state.{w.name}.{seq}.{pool}.{layer}")
+    out = []
+    for _ in range(2):
+        x = r.standard_normal((n, m.n_kv_heads, m.head_dim), dtype=np.float32)
+        if w.dtype == "bf16":
+            x = bf16_bits_to_f32(f32_to_bf16_bits(x)).reshape(x.shape)
+        out.append(x)
+    return out[0], out[1]
+
+
+def make_anchor(w: Workload, seq: int) -> int:
+    return int(_rng(w.seed, f"anchor.{w.name}.{seq}").integers(0, w.target.vocab - 1))

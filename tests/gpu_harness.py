@@ -21,7 +21,7 @@ def to_dev(arr: np.ndarray, dev) -> torch.Tensor:
 
 class GpuModel:
     def __init__(self, w: si.Workload, wt: si.Weights, wd: si.Weights, max_len: int, n_seqs: Optional[int] = None,
-                 shuffle_pages: bool = True, device: str = "cuda:0", max_seqs: Optional[int] = None):
+                 shuffle_pages: bool = True, device: str = "cuda:0", max_seqs: Optional[int] = None, blobs=None):
         self.w = w
         self.dev = torch.device(device)
         self.S = n_seqs or w.n_seqs
@@ -29,7 +29,14 @@ class GpuModel:
         table, n_pages = si.make_block_table(w if self.S == w.n_seqs else _with_seqs(w, self.S), max_len, shuffle_pages)
         self.table_host = table
         self.e = dfl.Engine(w.target, w.draft, w.dtype, w.block_size, max_seqs or self.S, table.shape[1], n_pages,
-                            w.tap_layers, w.mask_token_id, device)
+                            w.tap_layers, w.mask_token_id, device, blobs=blobs)
+        e = self.e
+        if blobs is None:
+            self._pack(w, wt, wd)
+        e.create()
+        self._alloc_io(w, table)
+
+    def _pack(self, w, wt, wd):
         e = self.e
         e.pack_target_head(to_dev(wt.raw("E"), self.dev), to_dev(wt.raw("lm"), self.dev), to_dev(wt.raw("gf"), self.dev))
         for l in range(w.target.n_layers):
@@ -40,7 +47,11 @@ class GpuModel:
             e.pack_draft_layer(l, {k: to_dev(wd.raw(f"L{l}.{k}"), self.dev) for k in si.LAYER_MATS + si.LAYER_GAINS})
             torch.cuda.synchronize(self.dev)
         torch.cuda.synchronize(self.dev)
-        e.create()
+
+    def blobs(self):
+        return (self.e.target_blob, self.e.draft_blob)
+
+    def _alloc_io(self, w, table):
         self.block_table = torch.from_numpy(table).to(self.dev)
         self.seq_lens = torch.zeros(self.S, dtype=torch.int32, device=self.dev)
         self.anchor = torch.zeros(self.S, dtype=torch.int32, device=self.dev)
@@ -85,9 +96,9 @@ class GpuModel:
         rng = torch.tensor([key], dtype=torch.int64, device=self.dev) if temperature > 0 else None
         dfl.dflash_draft_block(self.e, b, self.draft_tokens, temperature, rng, self.logits_d if want_logits else None)
         drafted = self.draft_tokens.cpu().numpy().copy()
-        if proposals is not None:
+        if proposals is not None:                 # entries < 0 keep the GPU's own draft for that slot
             blk = drafted.copy()
-            blk[:, 1:] = proposals
+            blk[:, 1:] = np.where(proposals >= 0, proposals, drafted[:, 1:])
             self.draft_tokens.copy_(torch.from_numpy(blk).to(self.dev))
         dfl.dflash_verify(self.e, b, self.draft_tokens, self.tgt_argmax, self.logits_t if want_logits else None)
         u = torch.from_numpy(np.ascontiguousarray(uniforms, dtype=np.float32)).to(self.dev) if uniforms is not None else None
@@ -131,6 +142,31 @@ class GpuModel:
             for l in range(self.w.draft.n_layers):
                 self.write_kv(B.DFLASH_POOL_DRAFT, l, s, 0, st.ctx.k[l][: st.n], st.ctx.v[l][: st.n])
         torch.cuda.synchronize(self.dev)
+
+    def load_synthetic(self, sampled: Sequence[int]) -> None:
+        """Synthetic cache state (unit normals, bf16-rounded) for every sequence: sequences in `sampled` get the
+        seeded rows of synth.make_state_rows (the oracle's goldens use the same), the others device-generated
+        rows of the same distribution."""
+        w = self.w
+        lens = si.make_context_lengths(w)[: self.S]
+        self.host_lens = lens.astype(np.int64)
+        self.seq_lens.copy_(torch.from_numpy(lens.astype(np.int32)).to(self.dev))
+        self.anchor.copy_(torch.from_numpy(np.array([si.make_anchor(w, s) for s in range(self.S)], dtype=np.int32)).to(self.dev))
+        gen = torch.Generator(device=self.dev)
+        gen.manual_seed(w.seed)
+        for s in range(self.S):
+            n = int(lens[s])
+            for pool, pid, m in (("target", B.DFLASH_POOL_TARGET, w.target), ("draft", B.DFLASH_POOL_DRAFT, w.draft)):
+                for l in range(m.n_layers):
+                    if s in sampled:
+                        k, v = si.make_state_rows(w, s, pool, l, n)
+                        self.write_kv(pid, l, s, 0, k, v)
+                    else:
+                        kv = torch.randn((2, n, m.n_kv_heads, m.head_dim), generator=gen, device=self.dev, dtype=torch.float32)
+                        if w.dtype == "bf16":
+                            kv = kv.to(torch.bfloat16).to(torch.float32)
+                        dfl.dflash_kv_write(self.e, self.batch(), pid, l, s, 0, kv[0].contiguous(), kv[1].contiguous())
+            torch.cuda.synchronize(self.dev)
 
     def expected_slots(self, lens_before: np.ndarray, accept_len: np.ndarray) -> np.ndarray:
         """page*16 + offset from the page table (the definition of a KV slot id), -1 past the accepted prefix."""
