@@ -1,8 +1,9 @@
 // MFMA block attention for bf16 caches (see attn.h for the split / merge contract).
 //
 // One workgroup = one (split, kv head, sequence): the B*group query rows that share the kv head
-// (<= 64, in QG groups of 16) against the chunk's keys.  The four wavefronts take 32-key page pairs
-// round-robin, each with its own online-softmax state, and are merged in a fixed order through LDS.
+// (<= 64) against the chunk's keys.  Wavefront w owns query rows 16w .. 16w+15 for the whole chunk, so
+// the four wavefronts never have to be merged; they read the same K/V tiles (the second to fourth read
+// hit the CU's L1) and the next 32-key page pair is in flight while the current one is processed.
 //
 // Everything streams from the pool in MFMA operand order (page layout in common.h), nothing is
 // transposed:  S^T = K . Q^T   (A = 16 keys x 32 dims of a page, B = Q^T), so a lane ends up with
@@ -13,11 +14,124 @@
 #pragma once
 #include "attn.h"
 
-template <int QG, int HD>
+template <int HD>
+struct KvFrags {
+  u32x4 ka[HD / 32], kb[HD / 32];
+  u32x4 v[HD / 16];   // (4 keys of page A, 4 keys of page B) x one dim per lane: the A operand of P.V
+  int ok_a, ok_b;
+};
+
+struct AttnLane {          // per-lane constants of the kernel below
+  const int32_t* table;
+  int c0, c1, n_tok, last_vis, g, lane, kvh;
+};
+
+template <int HD>
+__device__ __forceinline__ void attn_load_pair(KvFrags<HD>& f, int p, const bf16_t* __restrict__ pool, const SeqGeom& geo,
+                                               const AttnArgs& aa, const AttnLane& L) {
+  const int base = L.c0 + p * 32;           // first key of page A; page B starts at base + 16
+  const int ia = base >> 4;
+  int pa = L.table[ia];
+  f.ok_a = pa >= 0 && pa < geo.n_pages;
+  if (!f.ok_a) pa = 0;
+  const bool has_b = base + 16 < L.c1;
+  int pb = has_b ? L.table[ia + 1] : pa;
+  f.ok_b = has_b && pb >= 0 && pb < geo.n_pages;
+  if (!f.ok_b) pb = pa;
+  const bf16_t* ka = pool + kv_head_base(aa.layer, geo.n_pages, pa, aa.n_kv_heads, L.kvh, HD);
+  const bf16_t* kb = pool + kv_head_base(aa.layer, geo.n_pages, pb, aa.n_kv_heads, L.kvh, HD);
+#pragma unroll
+  for (int kt = 0; kt < HD / 32; ++kt) {
+    f.ka[kt] = reinterpret_cast<const u32x4*>(ka)[kt * 64 + L.lane];
+    f.kb[kt] = reinterpret_cast<const u32x4*>(kb)[kt * 64 + L.lane];
+  }
+#pragma unroll
+  for (int dt = 0; dt < HD / 16; ++dt) {
+    const uint2 a = reinterpret_cast<const uint2*>(ka + DF_PAGE * HD)[dt * 64 + L.lane];
+    const uint2 b = reinterpret_cast<const uint2*>(kb + DF_PAGE * HD)[dt * 64 + L.lane];
+    f.v[dt] = (u32x4){a.x, a.y, b.x, b.y};
+  }
+}
+
+template <int HD>
+__device__ __forceinline__ void attn_process_pair(KvFrags<HD>& f, int p, const u32x4 (&qf)[HD / 32], f32x4 (&acc)[HD / 16],
+                                                  float& m_run, float& l_run, float scale, const AttnLane& L) {
+  constexpr int KT = HD / 32, DT = HD / 16;
+  const int base = L.c0 + p * 32;
+  // rows at or beyond n_tok were never written (and an invalid page is not ours): 0 * garbage must not
+  // become NaN, so clear those V elements.  Only the last pair of a sequence takes this path.
+  if (base + 32 > L.n_tok || !f.ok_a || !f.ok_b) {
+    const int pos_a = base + 4 * L.g, pos_b = base + 16 + 4 * L.g;
+    uint32_t ma0 = 0u, ma1 = 0u, mb0 = 0u, mb1 = 0u;
+    if (f.ok_a && pos_a + 0 < L.n_tok) ma0 |= 0x0000FFFFu;
+    if (f.ok_a && pos_a + 1 < L.n_tok) ma0 |= 0xFFFF0000u;
+    if (f.ok_a && pos_a + 2 < L.n_tok) ma1 |= 0x0000FFFFu;
+    if (f.ok_a && pos_a + 3 < L.n_tok) ma1 |= 0xFFFF0000u;
+    if (f.ok_b && pos_b + 0 < L.n_tok) mb0 |= 0x0000FFFFu;
+    if (f.ok_b && pos_b + 1 < L.n_tok) mb0 |= 0xFFFF0000u;
+    if (f.ok_b && pos_b + 2 < L.n_tok) mb1 |= 0x0000FFFFu;
+    if (f.ok_b && pos_b + 3 < L.n_tok) mb1 |= 0xFFFF0000u;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      f.v[dt] &= (u32x4){ma0, ma1, mb0, mb1};
+    }
+  }
+  f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+#pragma unroll
+  for (int kt = 0; kt < KT; ++kt) {
+    sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.ka[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sa, 0, 0, 0);
+    sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.kb[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sb, 0, 0, 0);
+  }
+  const int pa0 = base + 4 * L.g;
+  float v0, v1, v2, v3, v4, v5, v6, v7;
+#define DF_VIS(ok, pos) ((ok) && (pos) < L.c1 && (pos) <= L.last_vis)
+  v0 = DF_VIS(f.ok_a, pa0 + 0) ? sa[0] * scale : -INFINITY;
+  v1 = DF_VIS(f.ok_a, pa0 + 1) ? sa[1] * scale : -INFINITY;
+  v2 = DF_VIS(f.ok_a, pa0 + 2) ? sa[2] * scale : -INFINITY;
+  v3 = DF_VIS(f.ok_a, pa0 + 3) ? sa[3] * scale : -INFINITY;
+  v4 = DF_VIS(f.ok_b, pa0 + 16) ? sb[0] * scale : -INFINITY;
+  v5 = DF_VIS(f.ok_b, pa0 + 17) ? sb[1] * scale : -INFINITY;
+  v6 = DF_VIS(f.ok_b, pa0 + 18) ? sb[2] * scale : -INFINITY;
+  v7 = DF_VIS(f.ok_b, pa0 + 19) ? sb[3] * scale : -INFINITY;
+#undef DF_VIS
+  float mx = fmaxf(fmaxf(fmaxf(v0, v1), fmaxf(v2, v3)), fmaxf(fmaxf(v4, v5), fmaxf(v6, v7)));
+  mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+  mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+  const float m_new = fmaxf(m_run, mx);
+  // all keys so far masked: exponent base 0 gives exp(-inf) = 0 for every (masked) key and corr 1
+  const float mb = (m_new == -INFINITY) ? 0.f : m_new;
+  const float corr = (m_run == -INFINITY) ? (m_new == -INFINITY ? 1.f : 0.f) : __expf(m_run - m_new);
+  const float p0 = __expf(v0 - mb), p1 = __expf(v1 - mb), p2 = __expf(v2 - mb), p3 = __expf(v3 - mb);
+  const float p4 = __expf(v4 - mb), p5 = __expf(v5 - mb), p6 = __expf(v6 - mb), p7 = __expf(v7 - mb);
+  l_run = l_run * corr + (((p0 + p1) + (p2 + p3)) + ((p4 + p5) + (p6 + p7)));
+  m_run = m_new;
+  u32x4 ph, pl;
+#define DF_PACK(i, a, b)                                                                        \
+  {                                                                                             \
+    const bf16_t h0 = float_to_bf16_bits(a), h1 = float_to_bf16_bits(b);                        \
+    const bf16_t l0 = float_to_bf16_bits((a) - bf16_bits_to_float(h0));                         \
+    const bf16_t l1 = float_to_bf16_bits((b) - bf16_bits_to_float(h1));                         \
+    ph[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);                                                \
+    pl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);                                                \
+  }
+  DF_PACK(0, p0, p1) DF_PACK(1, p2, p3) DF_PACK(2, p4, p5) DF_PACK(3, p6, p7)
+#undef DF_PACK
+#pragma unroll
+  for (int dt = 0; dt < DT; ++dt) {
+    const u32x4 vf = f.v[dt];
+    f32x4 a = acc[dt];
+    a[0] *= corr; a[1] *= corr; a[2] *= corr; a[3] *= corr;
+    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, ph), a, 0, 0, 0);
+    a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pl), a, 0, 0, 0);
+    acc[dt] = a;
+  }
+}
+
+template <int HD>
 __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ pool,
                                                         SeqGeom geo, AttnArgs aa, float* __restrict__ part_o,
                                                         float2* __restrict__ part_ml) {
-  constexpr int KT = HD / 32, DT = HD / 16, LDO = HD + 4;
+  constexpr int KT = HD / 32, DT = HD / 16;
   const int split = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int n = lane & 15, g = lane >> 4;
@@ -26,188 +140,59 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   const int rows = B * group;
   const int n_s = geo.seq_lens[s];
   const int cap = geo.max_pages_per_seq * DF_PAGE;
-  const int n_tok = min(n_s + B, cap);
-  const int c0 = split * aa.chunk;
-  const int c1 = min(n_tok, c0 + aa.chunk);
-  const int32_t* table = geo.block_table + (size_t)s * geo.max_pages_per_seq;
 
-  __shared__ float osum[64 * LDO];
-  __shared__ float sm[4][64];
-  __shared__ float lsum[64];
+  // ---- this lane's query column: row r of the kv head's row set
+  const int r = wave * 16 + n;
+  const bool valid = r < rows;
+  const int slot = valid ? r / group : 0, hq = kvh * group + (valid ? r % group : 0);
+  const size_t pr = ((size_t)(s * B + slot) * aa.n_q_heads + hq) * aa.n_splits + split;
 
-  // ---- query fragments (B operand of S^T): lane (n, g) holds Q[row qg*16+n][kt*32 + g*8 .. +8]
-  u32x4 qf[QG][KT];
-  int last_vis[QG];
-#pragma unroll
-  for (int qg = 0; qg < QG; ++qg) {
-    const int r = qg * 16 + n;
-    const bool valid = r < rows;
-    const int slot = valid ? r / group : 0, hq = kvh * group + (valid ? r % group : 0);
+  AttnLane L;
+  L.table = geo.block_table + (size_t)s * geo.max_pages_per_seq;
+  L.n_tok = min(n_s + B, cap);
+  L.c0 = split * aa.chunk;
+  L.c1 = min(L.n_tok, L.c0 + aa.chunk);
+  L.last_vis = valid ? (aa.causal ? n_s + slot : 0x7FFFFFFF) : -1;
+  L.g = g;
+  L.lane = lane;
+  L.kvh = kvh;
+
+  // query fragments (B operand of S^T): lane (n, g) holds Q[row][kt*32 + g*8 .. +8]
+  u32x4 qf[KT];
+  {
     const u32x4* qp = reinterpret_cast<const u32x4*>(q + ((size_t)(s * B + slot) * aa.n_q_heads + hq) * HD);
 #pragma unroll
-    for (int kt = 0; kt < KT; ++kt) qf[qg][kt] = valid ? qp[kt * 4 + g] : (u32x4){0u, 0u, 0u, 0u};
-    last_vis[qg] = valid ? (aa.causal ? n_s + slot : 0x7FFFFFFF) : -1;
+    for (int kt = 0; kt < KT; ++kt) qf[kt] = valid ? qp[kt * 4 + g] : (u32x4){0u, 0u, 0u, 0u};
   }
 
-  float m_run[QG], l_run[QG];
-  f32x4 acc[DT][QG];
+  float m_run = -INFINITY, l_run = 0.f;   // l_run: this lane's share (its 8 keys per pair) of the row sum
+  f32x4 acc[DT];
 #pragma unroll
-  for (int qg = 0; qg < QG; ++qg) {
-    m_run[qg] = -INFINITY;
-    l_run[qg] = 0.f;
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) acc[dt][qg] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  }
+  for (int dt = 0; dt < DT; ++dt) acc[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
-  const int n_pairs = c1 > c0 ? (c1 - c0 + 31) >> 5 : 0;
-  for (int p = wave; p < n_pairs; p += 4) {
-    const int base = c0 + p * 32;           // first key of page A; page B starts at base + 16
-    const int ia = base >> 4;
-    int pa = table[ia];
-    const bool ok_a = pa >= 0 && pa < geo.n_pages;
-    if (!ok_a) pa = 0;
-    const bool has_b = base + 16 < c1;
-    int pb = has_b ? table[ia + 1] : pa;
-    const bool ok_b = has_b && pb >= 0 && pb < geo.n_pages;
-    if (!ok_b) pb = pa;
-    const bf16_t* ka = pool + kv_head_base(aa.layer, geo.n_pages, pa, aa.n_kv_heads, kvh, HD);
-    const bf16_t* kb = pool + kv_head_base(aa.layer, geo.n_pages, pb, aa.n_kv_heads, kvh, HD);
-    u32x4 kfa[KT], kfb[KT];
-    uint2 vfa[DT], vfb[DT];
-#pragma unroll
-    for (int kt = 0; kt < KT; ++kt) {
-      kfa[kt] = reinterpret_cast<const u32x4*>(ka)[kt * 64 + lane];
-      kfb[kt] = reinterpret_cast<const u32x4*>(kb)[kt * 64 + lane];
-    }
-#pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
-      vfa[dt] = reinterpret_cast<const uint2*>(ka + DF_PAGE * HD)[dt * 64 + lane];
-      vfb[dt] = reinterpret_cast<const uint2*>(kb + DF_PAGE * HD)[dt * 64 + lane];
-    }
-    // rows at or beyond n_tok were never written (and an invalid page is not ours): 0 * garbage must not
-    // become NaN, so clear those V elements.  Only the last pair of a sequence takes this path.
-    if (base + 32 > n_tok || !ok_a || !ok_b) {
-      const int pos_a = base + 4 * g, pos_b = base + 16 + 4 * g;
-      uint32_t ma0 = 0u, ma1 = 0u, mb0 = 0u, mb1 = 0u;
-      if (ok_a && pos_a + 0 < n_tok) ma0 |= 0x0000FFFFu;
-      if (ok_a && pos_a + 1 < n_tok) ma0 |= 0xFFFF0000u;
-      if (ok_a && pos_a + 2 < n_tok) ma1 |= 0x0000FFFFu;
-      if (ok_a && pos_a + 3 < n_tok) ma1 |= 0xFFFF0000u;
-      if (ok_b && pos_b + 0 < n_tok) mb0 |= 0x0000FFFFu;
-      if (ok_b && pos_b + 1 < n_tok) mb0 |= 0xFFFF0000u;
-      if (ok_b && pos_b + 2 < n_tok) mb1 |= 0x0000FFFFu;
-      if (ok_b && pos_b + 3 < n_tok) mb1 |= 0xFFFF0000u;
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        vfa[dt].x &= ma0; vfa[dt].y &= ma1;
-        vfb[dt].x &= mb0; vfb[dt].y &= mb1;
-      }
-    }
-
-#pragma unroll
-    for (int qg = 0; qg < QG; ++qg) {
-      f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int kt = 0; kt < KT; ++kt) {
-        sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kfa[kt]), __builtin_bit_cast(bf16x8, qf[qg][kt]), sa, 0, 0, 0);
-        sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, kfb[kt]), __builtin_bit_cast(bf16x8, qf[qg][kt]), sb, 0, 0, 0);
-      }
-      float v[8];
-      float mx = -INFINITY;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const int pos_a = base + 4 * g + i, pos_b = pos_a + 16;
-        v[i] = (ok_a && pos_a < c1 && pos_a <= last_vis[qg]) ? sa[i] * aa.scale : -INFINITY;
-        v[4 + i] = (ok_b && pos_b < c1 && pos_b <= last_vis[qg]) ? sb[i] * aa.scale : -INFINITY;
-        mx = fmaxf(mx, fmaxf(v[i], v[4 + i]));
-      }
-      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-      const float m_new = fmaxf(m_run[qg], mx);
-      float corr = 1.f, psum = 0.f;
-      float pv[8];
-      if (m_new == -INFINITY) {
-#pragma unroll
-        for (int i = 0; i < 8; ++i) pv[i] = 0.f;
-      } else {
-        corr = (m_run[qg] == -INFINITY) ? 0.f : __expf(m_run[qg] - m_new);
-#pragma unroll
-        for (int i = 0; i < 8; ++i) {
-          pv[i] = __expf(v[i] - m_new);   // exp(-inf) = 0 for masked keys
-          psum += pv[i];
-        }
-      }
-      l_run[qg] = l_run[qg] * corr + psum;
-      m_run[qg] = m_new;
-      u32x4 ph, pl;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        const bf16_t h0 = float_to_bf16_bits(pv[2 * i]), h1 = float_to_bf16_bits(pv[2 * i + 1]);
-        const bf16_t l0 = float_to_bf16_bits(pv[2 * i] - bf16_bits_to_float(h0));
-        const bf16_t l1 = float_to_bf16_bits(pv[2 * i + 1] - bf16_bits_to_float(h1));
-        ph[i] = (uint32_t)h0 | ((uint32_t)h1 << 16);
-        pl[i] = (uint32_t)l0 | ((uint32_t)l1 << 16);
-      }
-#pragma unroll
-      for (int dt = 0; dt < DT; ++dt) {
-        const u32x4 vf = {vfa[dt].x, vfa[dt].y, vfb[dt].x, vfb[dt].y};
-        f32x4 a = acc[dt][qg];
-        a[0] *= corr; a[1] *= corr; a[2] *= corr; a[3] *= corr;
-        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, ph), a, 0, 0, 0);
-        a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, vf), __builtin_bit_cast(bf16x8, pl), a, 0, 0, 0);
-        acc[dt][qg] = a;
+  const int n_pairs = L.c1 > L.c0 ? (L.c1 - L.c0 + 31) >> 5 : 0;
+  if (n_pairs > 0) {
+    KvFrags<HD> f0, f1;
+    attn_load_pair<HD>(f0, 0, pool, geo, aa, L);
+    for (int p = 0; p < n_pairs; p += 2) {
+      if (p + 1 < n_pairs) attn_load_pair<HD>(f1, p + 1, pool, geo, aa, L);
+      attn_process_pair<HD>(f0, p, qf, acc, m_run, l_run, aa.scale, L);
+      if (p + 1 < n_pairs) {
+        if (p + 2 < n_pairs) attn_load_pair<HD>(f0, p + 2, pool, geo, aa, L);
+        attn_process_pair<HD>(f1, p + 1, qf, acc, m_run, l_run, aa.scale, L);
       }
     }
   }
 
-  // ---- merge the four wavefronts in the order 0,1,2,3 -------------------------------------------------
+  // ---- partial result of this split: (max, sum) and the unnormalised output row -------------------------
+  float l = l_run;
+  l += __shfl_xor(l, 16, 64);
+  l += __shfl_xor(l, 32, 64);
+  if (valid) {
+    if (g == 0) part_ml[pr] = make_float2(m_run, l);
 #pragma unroll
-  for (int qg = 0; qg < QG; ++qg)
-    if (g == 0) sm[wave][qg * 16 + n] = m_run[qg];
-  __syncthreads();
-  float sc[QG], lw[QG];
-#pragma unroll
-  for (int qg = 0; qg < QG; ++qg) {
-    const int r = qg * 16 + n;
-    const float mg = fmaxf(fmaxf(sm[0][r], sm[1][r]), fmaxf(sm[2][r], sm[3][r]));
-    sc[qg] = (m_run[qg] == -INFINITY) ? 0.f : __expf(m_run[qg] - mg);
-    float l = l_run[qg];
-    l += __shfl_xor(l, 16, 64);
-    l += __shfl_xor(l, 32, 64);
-    lw[qg] = l * sc[qg];
-  }
-  for (int w = 0; w < 4; ++w) {
-    if (wave == w) {
-#pragma unroll
-      for (int qg = 0; qg < QG; ++qg) {
-        const int r = qg * 16 + n;
-#pragma unroll
-        for (int dt = 0; dt < DT; ++dt) {
-          float4* dst = reinterpret_cast<float4*>(&osum[r * LDO + dt * 16 + 4 * g]);
-          float4 o = make_float4(acc[dt][qg][0] * sc[qg], acc[dt][qg][1] * sc[qg], acc[dt][qg][2] * sc[qg], acc[dt][qg][3] * sc[qg]);
-          if (w > 0) {
-            const float4 prev = *dst;
-            o.x += prev.x; o.y += prev.y; o.z += prev.z; o.w += prev.w;
-          }
-          *dst = o;
-        }
-        if (g == 0) lsum[r] = (w > 0 ? lsum[r] : 0.f) + lw[qg];
-      }
-    }
-    __syncthreads();
-  }
-  for (int idx = threadIdx.x; idx < rows * HD; idx += 256) {
-    const int r = idx / HD, d = idx % HD;
-    const int slot = r / group, hq = kvh * group + r % group;
-    const size_t pr = ((size_t)(s * B + slot) * aa.n_q_heads + hq) * aa.n_splits + split;
-    part_o[pr * HD + d] = osum[r * LDO + d];
-  }
-  if (threadIdx.x < rows) {
-    const int r = threadIdx.x;
-    const int slot = r / group, hq = kvh * group + r % group;
-    const size_t pr = ((size_t)(s * B + slot) * aa.n_q_heads + hq) * aa.n_splits + split;
-    const float mg = fmaxf(fmaxf(sm[0][r], sm[1][r]), fmaxf(sm[2][r], sm[3][r]));
-    part_ml[pr] = make_float2(mg, lsum[r]);
+    for (int dt = 0; dt < DT; ++dt)
+      *reinterpret_cast<float4*>(part_o + pr * HD + dt * 16 + 4 * g) = make_float4(acc[dt][0], acc[dt][1], acc[dt][2], acc[dt][3]);
   }
 }
 
@@ -222,19 +207,10 @@ inline bool attn_mfma_launch<bf16_t>(hipStream_t st, const bf16_t* q, const bf16
                                      float* part_o, float2* part_ml) {
   const int rows = geo.block_size * (aa.n_q_heads / aa.n_kv_heads);
   if (rows > 64 || (aa.head_dim != 128 && aa.head_dim != 64)) return false;
-  const int qg = (rows + 15) / 16;
   const dim3 grid(aa.n_splits, aa.n_kv_heads, S), block(256);
-#define DF_ATTN_CASE(QG_, HD_)                                                                                          \
-  hipLaunchKernelGGL((attn_mfma_kernel<QG_, HD_>), grid, block, 0, st, q, pool, geo, aa, part_o, part_ml)
-  if (aa.head_dim == 128) {
-    if (qg == 1) DF_ATTN_CASE(1, 128);
-    else if (qg == 2) DF_ATTN_CASE(2, 128);
-    else DF_ATTN_CASE(4, 128);
-  } else {
-    if (qg == 1) DF_ATTN_CASE(1, 64);
-    else if (qg == 2) DF_ATTN_CASE(2, 64);
-    else DF_ATTN_CASE(4, 64);
-  }
-#undef DF_ATTN_CASE
+  if (aa.head_dim == 128)
+    hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
+  else
+    hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
   return true;
 }

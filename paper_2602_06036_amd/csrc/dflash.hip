@@ -119,7 +119,12 @@ struct SplitPlan {
 SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens) {
   // the attention kernel runs one workgroup per CU (its accumulators fill the register file), so aim at
   // one round of workgroups on the 256 CUs
-  const int target_wgs = 256, max_splits = 64;
+  static const int target_wgs = [] {
+    const char* e = getenv("DFLASH_ATTN_TARGET_WGS");   // tuning knob
+    const int v = e ? atoi(e) : 0;
+    return v > 0 ? v : 256;
+  }();
+  const int max_splits = 64;
   int splits = (target_wgs + S * n_kv_heads - 1) / (S * n_kv_heads);
   const int by_len = (max_tokens + 63) / 64;
   splits = std::max(1, std::min(splits, std::min(by_len, max_splits)));

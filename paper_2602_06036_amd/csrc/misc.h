@@ -38,11 +38,11 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const f
                                                       int tap_K) {
   const int m = blockIdx.x;
   const size_t ro = (size_t)m * D;
-  float ss = 0.f;
-  for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
+  // completed row chunk d..d+3: base + pending slabs (four independent loads in flight, added in ascending order)
+  auto gather = [&](int d) {
     float4 v = base ? *reinterpret_cast<const float4*>(base + ro + d) : make_float4(0.f, 0.f, 0.f, 0.f);
     int z = 0;
-    for (; z + 4 <= ks; z += 4) {   // four independent loads in flight, added in ascending order
+    for (; z + 4 <= ks; z += 4) {
       const float* pz = delta + (size_t)z * slab + ro + d;
       const float4 p0 = *reinterpret_cast<const float4*>(pz), p1 = *reinterpret_cast<const float4*>(pz + slab);
       const float4 p2 = *reinterpret_cast<const float4*>(pz + 2 * slab), p3 = *reinterpret_cast<const float4*>(pz + 3 * slab);
@@ -57,6 +57,24 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const f
     }
     if (ks > 0) *reinterpret_cast<float4*>(h_out + ro + d) = v;
     if (taps) Act<T>::store4(taps, m, tap_idx * D + d, tap_K, v);
+    return v;
+  };
+  // the first KEEP chunks of a thread stay in registers between the two passes (rows up to 8192 wide);
+  // wider rows re-read the rest from where it was written
+  constexpr int KEEP = 8;
+  float4 keep[KEEP];
+  float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < KEEP; ++c) {
+    const int d = (c * 256 + (int)threadIdx.x) * 4;
+    keep[c] = make_float4(0.f, 0.f, 0.f, 0.f);
+    if (d < D) {
+      keep[c] = gather(d);
+      ss += keep[c].x * keep[c].x + keep[c].y * keep[c].y + keep[c].z * keep[c].z + keep[c].w * keep[c].w;
+    }
+  }
+  for (int d = (KEEP * 256 + (int)threadIdx.x) * 4; d < D; d += 1024) {
+    const float4 v = gather(d);
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
   __shared__ float part[4];
@@ -65,8 +83,17 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const f
   __syncthreads();
   const float tot = part[0] + part[1] + part[2] + part[3];
   const float rstd = 1.0f / sqrtf(tot / (float)D + eps);
+#pragma unroll
+  for (int c = 0; c < KEEP; ++c) {
+    const int d = (c * 256 + (int)threadIdx.x) * 4;
+    if (d < D) {
+      const float4 v = keep[c];
+      const float4 g = *reinterpret_cast<const float4*>(gain + d);
+      Act<T>::store4(out, m, d, D, make_float4(v.x * rstd * g.x, v.y * rstd * g.y, v.z * rstd * g.z, v.w * rstd * g.w));
+    }
+  }
   const float* src = ks > 0 ? h_out : base;   // each thread re-reads exactly what it wrote
-  for (int d = threadIdx.x * 4; d < D; d += blockDim.x * 4) {
+  for (int d = (KEEP * 256 + (int)threadIdx.x) * 4; d < D; d += 1024) {
     const float4 v = *reinterpret_cast<const float4*>(src + ro + d);
     const float4 g = *reinterpret_cast<const float4*>(gain + d);
     Act<T>::store4(out, m, d, D, make_float4(v.x * rstd * g.x, v.y * rstd * g.y, v.z * rstd * g.z, v.w * rstd * g.w));
