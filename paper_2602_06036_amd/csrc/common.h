@@ -35,17 +35,20 @@ template <> struct Store<bf16_t> {
   static __host__ __device__ __forceinline__ float to(bf16_t v) { return bf16_bits_to_float(v); }
 };
 
-// ---- GEMM operand layout -----------------------------------------------------------------------
-// A matrix of `rows` x K (K contiguous in the canonical form).  fp32: plain row-major.  bf16: cut into
+// ---- GEMM weight layout -------------------------------------------------------------------------
+// A matrix of N rows x K (K contiguous in the canonical form).  fp32: plain row-major.  bf16: cut into
 // 16-row x 32-column tiles; a tile is 1 KB holding, for lane = (k%32)/8*16 + r%16 of a 64-wide
-// wavefront, the 8 consecutive k values that lane feeds to v_mfma_f32_16x16x32_bf16.  Tiles of one
-// 16-row band are consecutive along K, so a wavefront streams a band as contiguous 1 KB loads.
-template <typename T> __host__ __device__ __forceinline__ size_t tile_index(int r, int k, int K);
-template <> __host__ __device__ __forceinline__ size_t tile_index<float>(int r, int k, int K) {
+// wavefront, the 8 consecutive k values that lane feeds to v_mfma_f32_16x16x32_bf16.  Tiles are stored
+// k-tile-major: all N/16 tiles of k-tile 0, then all tiles of k-tile 1, ...  A wavefront that owns NT
+// adjacent row bands reads NT KB contiguously per k step and neighbouring workgroups read the neighbouring
+// KBs, so the whole grid sweeps each k slab of the matrix sequentially (DRAM-friendly), instead of
+// thousands of independent 1 KB streams.
+template <typename T> __host__ __device__ __forceinline__ size_t tile_index(int r, int k, int K, int N);
+template <> __host__ __device__ __forceinline__ size_t tile_index<float>(int r, int k, int K, int) {
   return (size_t)r * K + k;
 }
-template <> __host__ __device__ __forceinline__ size_t tile_index<bf16_t>(int r, int k, int K) {
-  return ((size_t)(r >> 4) * (K >> 5) + (k >> 5)) * 512 + (size_t)(((((k & 31) >> 3) << 4) + (r & 15)) * 8 + (k & 7));
+template <> __host__ __device__ __forceinline__ size_t tile_index<bf16_t>(int r, int k, int, int N) {
+  return ((size_t)(k >> 5) * (N >> 4) + (r >> 4)) * 512 + (size_t)(((((k & 31) >> 3) << 4) + (r & 15)) * 8 + (k & 7));
 }
 // rows that a buffer in this layout must provide for M logical rows
 template <typename T> __host__ __device__ __forceinline__ int tile_rows(int M) { return M; }

@@ -478,7 +478,13 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   const bool split = allow_split && epi != EPI_SWIGLU;
   int ks = 1;
   if (M <= 16) {
-    if (nt % 4 == 0) {
+    static const int NT8 = env_int("DFLASH_GEMM_NT8", 1);   // tuning knob: matrices with at least 8*this row bands use 8 weight tiles per activation fragment
+    if (NT8 && nt % 8 == 0 && nt >= 8 * NT8) {
+      if (split) ks = pick_ksplit(nt / 8, KT, M);
+      ep.slab = (size_t)M * ep.ld;
+      if (U >= 2) launch_bf16<8, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      else launch_bf16<8, 1, 1>(st, W, A, M, N, K, kepi, ep, ks);
+    } else if (nt % 4 == 0) {
       if (split) ks = pick_ksplit(nt / 4, KT, M);
       ep.slab = (size_t)M * ep.ld;
       if (U >= 4) launch_bf16<4, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
@@ -553,13 +559,17 @@ void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const 
 
 // ---- packing helpers -----------------------------------------------------------------------------------
 template <typename T>
-int pack_rows(hipStream_t st, PackSrc ps, int K, int total_rows, void* dst) {
+int pack_rows(hipStream_t st, PackSrc ps, int K, int total_rows, void* dst, int dst_row0, int dst_rows) {
   const size_t chunks = (size_t)total_rows * (K / 8);
-  hipLaunchKernelGGL(pack_kernel<T>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, ps, K, total_rows, reinterpret_cast<T*>(dst));
+  hipLaunchKernelGGL(pack_kernel<T>, dim3((unsigned)((chunks + 255) / 256)), dim3(256), 0, st, ps, K, total_rows, reinterpret_cast<T*>(dst),
+                     dst_row0, dst_rows);
   return hipGetLastError() == hipSuccess ? DFLASH_OK : fail(nullptr, DFLASH_EHIP, "pack launch failed");
 }
-int pack_any(int dtype, hipStream_t st, PackSrc ps, int K, int rows, void* dst) {
-  return dtype == DFLASH_BF16 ? pack_rows<bf16_t>(st, ps, K, rows, dst) : pack_rows<float>(st, ps, K, rows, dst);
+// packs `rows` rows into rows dst_row0.. of the dst_rows-row matrix at dst (dst_rows < 0: the matrix is just these rows)
+int pack_any(int dtype, hipStream_t st, PackSrc ps, int K, int rows, void* dst, int dst_row0 = 0, int dst_rows = -1) {
+  if (dst_rows < 0) dst_rows = rows;
+  return dtype == DFLASH_BF16 ? pack_rows<bf16_t>(st, ps, K, rows, dst, dst_row0, dst_rows)
+                              : pack_rows<float>(st, ps, K, rows, dst, dst_row0, dst_rows);
 }
 PackSrc one(const void* p, int rows) {
   PackSrc s{};
@@ -688,8 +698,7 @@ int dflash_pack_draft_layer(const dflash_dims* draft, int32_t n_taps, int32_t d_
   const int kd = draft->n_kv_heads * draft->head_dim;
   PackSrc kv{};
   kv.src[0] = w->wk; kv.src[1] = w->wv; kv.rows[0] = kv.rows[1] = kd; kv.n_src = 2; kv.mode = 0;
-  char* dst = base + dl.wkv_all + (size_t)layer * 2 * kd * draft->d_model * esize(draft->dtype);
-  return pack_any(draft->dtype, st, kv, draft->d_model, 2 * kd, dst);
+  return pack_any(draft->dtype, st, kv, draft->d_model, 2 * kd, base + dl.wkv_all, layer * 2 * kd, draft->n_layers * 2 * kd);
 }
 
 int dflash_create(const dflash_dims* target, const void* target_blob, const dflash_dims* draft, const void* draft_blob,

@@ -41,7 +41,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
                                                         int M, int N, int K, EpiArgs ep) {
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
   const int nt0 = blockIdx.x * NT, mt0 = blockIdx.y * MT, kz = blockIdx.z;
-  const int KT = K >> 5;
+  const int KT = K >> 5, n_tiles = N >> 4;
   const int m_tiles = (M + 15) >> 4;
   const int ks = gridDim.z;
   const int per = (KT + ks * 4 - 1) / (ks * 4);
@@ -68,7 +68,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       const bool in = k0 + u < ke;
       const int kt = in ? k0 + u : ke - 1;   // past the range: re-read the last tile, with zeroed activations
 #pragma unroll
-      for (int i = 0; i < NT; ++i) b.w[u][i] = __builtin_nontemporal_load(Wp + ((size_t)(nt0 + i) * KT + kt) * 64);
+      for (int i = 0; i < NT; ++i) b.w[u][i] = __builtin_nontemporal_load(Wp + ((size_t)kt * n_tiles + nt0 + i) * 64);
 #pragma unroll
       for (int j = 0; j < MT; ++j) {
         const u32x4 h = Ap[a_band[j] + (size_t)kt * 128], l = Ap[a_band[j] + (size_t)kt * 128 + 64];

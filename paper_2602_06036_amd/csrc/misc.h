@@ -369,7 +369,8 @@ struct PackSrc {
   int mode;
 };
 template <typename T>
-__global__ __launch_bounds__(256) void pack_kernel(PackSrc ps, int K, int total_rows, T* __restrict__ dst) {
+__global__ __launch_bounds__(256) void pack_kernel(PackSrc ps, int K, int total_rows, T* __restrict__ dst, int dst_row0,
+                                                   int dst_rows) {
   const size_t chunk = (size_t)blockIdx.x * blockDim.x + threadIdx.x;  // one 8-element chunk
   const int chunks_per_row = K >> 3;
   const size_t n_chunks = (size_t)total_rows * chunks_per_row;
@@ -383,7 +384,7 @@ __global__ __launch_bounds__(256) void pack_kernel(PackSrc ps, int K, int total_
     while (si + 1 < ps.n_src && sr >= ps.rows[si]) { sr -= ps.rows[si]; ++si; }
   }
   const T* s = reinterpret_cast<const T*>(ps.src[si]) + (size_t)sr * K + k;
-  T* d = dst + tile_index<T>(r, k, K);
+  T* d = dst + tile_index<T>(dst_row0 + r, k, K, dst_rows);   // rows land at dst_row0.. of a dst_rows-row matrix
 #pragma unroll
   for (int i = 0; i < 8; ++i) d[i] = s[i];
 }
