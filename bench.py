@@ -17,6 +17,9 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
+# HBM bytes per launch of the dominant kernel (gate/up GEMM at the 8B shape, M = 16) from two rocprofv3 --pmc
+# runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): profiles/cfg2_gateup_gemm_hbm_traffic.md
+MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": 198752 * 1024 + 768 * 1024}
 
 WORKLOADS = {
     # name: (synth workload index, n_seqs, context)
@@ -139,6 +142,9 @@ def main():
     ap.add_argument("--workload", default="cfg2_8b_b1_ctx2048", choices=sorted(WORKLOADS))
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three device copies of exactly 1 GiB (a kernel of known traffic, used to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py: this build runs on ONE GPU (the step is single-device; see DESIGN.md for how it would shard); "
@@ -181,6 +187,13 @@ def main():
         dfl.dflash_kv_commit(e, b, accept_len, out_tokens)
         state["upper"] += Bk          # host-side bound on the committed length (no device read-back)
 
+    if args.copy_probe:
+        src = torch.empty(1 << 30, dtype=torch.uint8, device=dev).view(torch.float32).normal_()
+        dst = torch.empty_like(src)
+        for _ in range(3):
+            dst.copy_(src)
+        torch.cuda.synchronize(dev)
+        del src, dst
     for _ in range(Wm):
         step()
     torch.cuda.synchronize(dev)
@@ -220,7 +233,7 @@ def main():
         ms, cnt, by = prof[2]        # dominant kernel: gate/up projection with fused SwiGLU
         ach = (by / cnt) / (ms / cnt) / 1e6
         roof = dict(bound="hbm", kernel="gemm_bf16_kernel<SWIGLU> (gate/up projection)", achieved=ach, peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=None,
+                    unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
                     bytes_per_launch=by / cnt, avg_launch_us=1e3 * ms / cnt)
 
     out = {

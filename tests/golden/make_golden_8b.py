@@ -73,7 +73,7 @@ def sample_cols(w):
 
 def main():
     out_path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden_8b.json")
-    only = [int(x) for x in sys.argv[1:]] or sorted(CASES)
+    only = [int(x) for x in sys.argv[1:] if x.isdigit()] or sorted(CASES)
     results = {}
     if os.path.exists(out_path):
         results = json.load(open(out_path))
@@ -91,6 +91,8 @@ def main():
         Bk = w.block_size
         for i, seq in enumerate(CASES[cfg]["seqs"]):
             n = int(lens[seq])
+            if f"cfg{cfg}_seq{seq}" in results and "--redo" not in sys.argv:
+                continue                                   # resumable: keep what an earlier run stored
             print(f"[{time.time()-t0:7.1f}s] cfg {cfg} seq {seq} n={n}: state", flush=True)
             st = load_state(w, seq, n)
             rec = dict(config=cfg, seq=seq, n=n, anchor=int(st.anchor), cols=[int(c) for c in cols])
