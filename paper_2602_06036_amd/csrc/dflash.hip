@@ -138,8 +138,10 @@ SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens) {
 }
 
 // ---- workspace ------------------------------------------------------------------------------------
+constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row in the argmax
+
 struct Workspace {
-  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, total;
+  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, total;
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
   const size_t es = esize(t.dtype);
@@ -181,6 +183,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.part_ml = take(part_rows * 8);
   w.stats_p = take((size_t)M * 8);
   w.stats_q = take((size_t)M * 8);
+  w.amax = take((size_t)M * ARGMAX_CHUNKS * 8);
   w.total = off;
   return w;
 }
@@ -292,8 +295,22 @@ struct Engine {
   Slab gemm(const T* W, const T* A, int M, int N, int K, int epi, EpiArgs ep, bool allow_split = true);
 
   void norm(const float* base, Slab delta, float* h_out, const float* gain, T* out, int M, int D, float eps, int tap = -1) {
-    hipLaunchKernelGGL(rmsnorm_kernel<T>, dim3(M), dim3(256), 0, st, base, delta.p, delta.ks, delta.stride, h_out, gain, out, D, eps,
-                       tap >= 0 ? ws<T>(c->ws.taps) : (T*)nullptr, tap, c->rt.n_taps * c->t.d_model);
+    T* taps = tap >= 0 ? ws<T>(c->ws.taps) : (T*)nullptr;
+    const int tap_K = c->rt.n_taps * c->t.d_model;
+    if (D >= 4096)   // one 16-byte chunk per thread: the row's loads are all in flight at once
+      hipLaunchKernelGGL((rmsnorm_kernel<T, 1024>), dim3(M), dim3(1024), 0, st, base, delta.p, delta.ks, delta.stride, h_out, gain, out, D,
+                         eps, taps, tap, tap_K);
+    else
+      hipLaunchKernelGGL((rmsnorm_kernel<T, 256>), dim3(M), dim3(256), 0, st, base, delta.p, delta.ks, delta.stride, h_out, gain, out, D,
+                         eps, taps, tap, tap_K);
+    check();
+  }
+  // row-wise argmax (or Gumbel-perturbed argmax) in two launches: per-chunk winners, then one wavefront per row
+  void argmax(const float* logits, int V, int M, int B, int32_t* out, int skip_slot0, int mode, float inv_T, const uint64_t* key) {
+    float2* part = ws<float2>(c->ws.amax);
+    hipLaunchKernelGGL(argmax_rows_kernel, dim3(ARGMAX_CHUNKS, M), dim3(256), 0, st, logits, V, B, part, mode, inv_T, key);
+    check();
+    hipLaunchKernelGGL(argmax_finish_kernel, dim3(M), dim3(64), 0, st, part, ARGMAX_CHUNKS, B, out, skip_slot0);
     check();
   }
   // RMSNorm of the residual stream, folding in whatever the previous GEMM left pending
@@ -353,9 +370,7 @@ struct Engine {
     float* logits = ws<float>(c->ws.logits_d);
     lm_head(reinterpret_cast<const float*>(c->dblob + c->dl.gf), d.rms_eps, M, logits);
     const int mode = temperature > 0.f ? 1 : 0;
-    hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(1024), 0, st, logits, d.vocab, B, draft_tokens, 1, mode,
-                       mode ? 1.0f / temperature : 1.0f, rng_key);
-    check();
+    argmax(logits, d.vocab, M, B, draft_tokens, 1, mode, mode ? 1.0f / temperature : 1.0f, rng_key);
     if (logits_out) {
       if (hipMemcpyAsync(logits_out, logits, (size_t)M * d.vocab * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
         return CTX_FAIL(c, DFLASH_EHIP, "logits copy failed");
@@ -376,9 +391,7 @@ struct Engine {
     }
     float* logits = ws<float>(c->ws.logits_t);
     lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits);
-    hipLaunchKernelGGL(argmax_rows_kernel, dim3(M), dim3(1024), 0, st, logits, t.vocab, B, tgt_argmax, 0, 0, 1.0f,
-                       (const uint64_t*)nullptr);
-    check();
+    argmax(logits, t.vocab, M, B, tgt_argmax, 0, 0, 1.0f, (const uint64_t*)nullptr);
     if (logits_out) {
       if (hipMemcpyAsync(logits_out, logits, (size_t)M * t.vocab * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
         return CTX_FAIL(c, DFLASH_EHIP, "logits copy failed");

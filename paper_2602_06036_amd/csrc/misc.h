@@ -31,8 +31,8 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
 // the preceding GEMM).  When delta is given the completed row is written to h_out (the residual stream).
 // Optionally the completed row is also stored as tap `tap_idx` (GEMM activation operand, row length tap_K).
 // out[m,:] = x * gain / sqrt(mean(x^2) + eps) as GEMM activation operand (Act<T>).
-template <typename T>
-__global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const float* __restrict__ delta, int ks,
+template <typename T, int NTHR>
+__global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const float* __restrict__ delta, int ks,
                                                       size_t slab, float* h_out, const float* __restrict__ gain,
                                                       T* __restrict__ out, int D, float eps, T* __restrict__ taps, int tap_idx,
                                                       int tap_K) {
@@ -59,33 +59,36 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const f
     if (taps) Act<T>::store4(taps, m, tap_idx * D + d, tap_K, v);
     return v;
   };
-  // the first KEEP chunks of a thread stay in registers between the two passes (rows up to 8192 wide);
+  // NTHR threads per row (1024 for wide rows: one 16-byte chunk per thread keeps every load independent).
+  // The first KEEP chunks of a thread stay in registers between the two passes (rows up to 8192 wide);
   // wider rows re-read the rest from where it was written
-  constexpr int KEEP = 8;
+  constexpr int KEEP = 8192 / (NTHR * 4);
   float4 keep[KEEP];
   float ss = 0.f;
 #pragma unroll
   for (int c = 0; c < KEEP; ++c) {
-    const int d = (c * 256 + (int)threadIdx.x) * 4;
+    const int d = (c * NTHR + (int)threadIdx.x) * 4;
     keep[c] = make_float4(0.f, 0.f, 0.f, 0.f);
     if (d < D) {
       keep[c] = gather(d);
       ss += keep[c].x * keep[c].x + keep[c].y * keep[c].y + keep[c].z * keep[c].z + keep[c].w * keep[c].w;
     }
   }
-  for (int d = (KEEP * 256 + (int)threadIdx.x) * 4; d < D; d += 1024) {
+  for (int d = (KEEP * NTHR + (int)threadIdx.x) * 4; d < D; d += NTHR * 4) {
     const float4 v = gather(d);
     ss += v.x * v.x + v.y * v.y + v.z * v.z + v.w * v.w;
   }
-  __shared__ float part[4];
+  __shared__ float part[NTHR / 64];
   ss = wave_reduce_sum(ss);
   if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
   __syncthreads();
-  const float tot = part[0] + part[1] + part[2] + part[3];
+  float tot = 0.f;
+#pragma unroll
+  for (int w = 0; w < NTHR / 64; ++w) tot += part[w];
   const float rstd = 1.0f / sqrtf(tot / (float)D + eps);
 #pragma unroll
   for (int c = 0; c < KEEP; ++c) {
-    const int d = (c * 256 + (int)threadIdx.x) * 4;
+    const int d = (c * NTHR + (int)threadIdx.x) * 4;
     if (d < D) {
       const float4 v = keep[c];
       const float4 g = *reinterpret_cast<const float4*>(gain + d);
@@ -93,7 +96,7 @@ __global__ __launch_bounds__(256) void rmsnorm_kernel(const float* base, const f
     }
   }
   const float* src = ks > 0 ? h_out : base;   // each thread re-reads exactly what it wrote
-  for (int d = (KEEP * 256 + (int)threadIdx.x) * 4; d < D; d += 1024) {
+  for (int d = (KEEP * NTHR + (int)threadIdx.x) * 4; d < D; d += NTHR * 4) {
     const float4 v = *reinterpret_cast<const float4*>(src + ro + d);
     const float4 g = *reinterpret_cast<const float4*>(gain + d);
     Act<T>::store4(out, m, d, D, make_float4(v.x * rstd * g.x, v.y * rstd * g.y, v.z * rstd * g.z, v.w * rstd * g.w));
@@ -199,7 +202,7 @@ __device__ __forceinline__ void argmax_combine(float& bv, int& bi, float v, int 
   if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
 }
 
-// block-wide (1024 threads) argmax; result valid in thread 0
+// block-wide argmax (up to 1024 threads); result valid in thread 0
 __device__ __forceinline__ void block_argmax(float& bv, int& bi) {
   __shared__ float sv[16];
   __shared__ int si[16];
@@ -218,22 +221,42 @@ __device__ __forceinline__ void block_argmax(float& bv, int& bi) {
 }
 
 // mode 0: greedy.  mode 1: draft sampling, score = logit * inv_T + Gumbel(key, seq, slot, purpose 0).
-// Writes out[m] unless (skip_slot0 && slot == 0).
-__global__ __launch_bounds__(1024) void argmax_rows_kernel(const float* __restrict__ logits, int V, int B, int32_t* __restrict__ out,
-                                                           int skip_slot0, int mode, float inv_T,
-                                                           const uint64_t* __restrict__ rng_key) {
-  const int m = blockIdx.x, slot = m % B, seq = m / B;
-  if (skip_slot0 && slot == 0) return;
+// Stage 1: grid (n_chunks, M): best (score, index) of one chunk of row m -> part[m * n_chunks + chunk].
+// Stage 2 (argmax_finish_kernel): combines the chunks in ascending order (ties -> lowest index) and writes out[m]
+// unless (skip_slot0 && slot == 0).
+__global__ __launch_bounds__(256) void argmax_rows_kernel(const float* __restrict__ logits, int V, int B, float2* __restrict__ part,
+                                                          int mode, float inv_T, const uint64_t* __restrict__ rng_key) {
+  const int chunk = blockIdx.x, n_chunks = gridDim.x, m = blockIdx.y, slot = m % B, seq = m / B;
+  const int per = (V + n_chunks - 1) / n_chunks, i0 = chunk * per, i1 = min(V, i0 + per);
   const float* row = logits + (size_t)m * V;
   float bv = -INFINITY;
   int bi = 0x7FFFFFFF;
   const uint64_t key = mode ? rng_key[0] : 0ull;
-  for (int i = threadIdx.x; i < V; i += blockDim.x) {
+  for (int i = i0 + threadIdx.x; i < i1; i += blockDim.x) {
     float v = row[i];
     if (mode) v = v * inv_T + gumbel(counter_uniform(key, seq, slot, 0, (uint32_t)i));
     argmax_combine(bv, bi, v, i);
   }
   block_argmax(bv, bi);
+  if (threadIdx.x == 0) part[(size_t)m * n_chunks + chunk] = make_float2(bv, __int_as_float(bi));
+}
+
+__global__ __launch_bounds__(64) void argmax_finish_kernel(const float2* __restrict__ part, int n_chunks, int B, int32_t* __restrict__ out,
+                                                           int skip_slot0) {
+  const int m = blockIdx.x;
+  if (skip_slot0 && m % B == 0) return;
+  float bv = -INFINITY;
+  int bi = 0x7FFFFFFF;
+  for (int c = threadIdx.x; c < n_chunks; c += 64) {
+    const float2 p = part[(size_t)m * n_chunks + c];
+    argmax_combine(bv, bi, p.x, __float_as_int(p.y));
+  }
+#pragma unroll
+  for (int o = 32; o > 0; o >>= 1) {
+    const float ov = __shfl_xor(bv, o, 64);
+    const int oi = __shfl_xor(bi, o, 64);
+    argmax_combine(bv, bi, ov, oi);
+  }
   if (threadIdx.x == 0) out[m] = bi;
 }
 
