@@ -512,6 +512,11 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<1, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
     }
+  } else if (M <= 64 && nt % 8 == 0) {
+    // still bandwidth-bound: the same streaming kernel with four activation bands per weight tile
+    if (split) ks = pick_ksplit(nt / 8, KT, M);
+    ep.slab = (size_t)M * ep.ld;
+    launch_bf16<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
   } else {
     const int my = ((M + 15) / 16 + 3) / 4;
     if (nt % 2 == 0) {
