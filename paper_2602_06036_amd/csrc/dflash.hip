@@ -17,6 +17,7 @@
 #include "attn_mfma.h"
 #include "common.h"
 #include "gemm.h"
+#include "gemm_tiled.h"
 #include "misc.h"
 
 namespace {
@@ -138,6 +139,9 @@ SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens) {
 }
 
 // ---- workspace ------------------------------------------------------------------------------------
+// rows of partial results the split-K arena holds for a context of at most max_rows activation rows
+inline int arena_rows(int max_rows) { return std::max(1024, 4 * max_rows); }
+
 constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row in the argmax
 
 struct Workspace {
@@ -166,7 +170,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.ht = take(Mr * D * es * planes);
   // arena: K-range partial results of the QKV / O / down / W_c / context-K/V GEMMs (consumed by the next kernel)
   const size_t n_max = std::max(std::max(nqkv, D), (size_t)d.n_layers * 2 * d.n_kv_heads * d.head_dim);
-  w.arena = take((size_t)std::max(M, 1024) * n_max * 4);
+  w.arena = take((size_t)arena_rows(M) * n_max * 4);
   w.logits_d = take((size_t)M * t.vocab * 4);
   w.logits_t = take((size_t)M * t.vocab * 4);
   // attention partials: worst case over batch sizes and both models
@@ -218,6 +222,7 @@ struct dflash_ctx {
   const char* dblob;
   char* wsp;
   char err[512];
+  int wide_min_wgs = 192;   // tiled GEMM: least number of 256 x 128 tiles for which that tile shape is used (tuning knob)
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
@@ -449,7 +454,6 @@ struct Engine {
 
 // ---- GEMM dispatch ----------------------------------------------------------------------------------
 constexpr int kMaxKSplit = 16;
-constexpr int kArenaSplitRows = 1024;   // ks * M never exceeds max(M, this)
 
 template <int NT, int MT, int U>
 void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
@@ -459,6 +463,16 @@ void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N,
   } else {
     hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, U, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, ep);
   }
+}
+
+template <int WN, int WM>
+void launch_tiled(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
+  const int n_blocks = (N / 16 + 2 * WN - 1) / (2 * WN), m_blocks = ((M + 15) / 16 + 2 * WM - 1) / (2 * WM);
+  const dim3 grid(((n_blocks + 7) / 8) * 8 * m_blocks, ks), block(256);
+  if (epi == EPI_SWIGLU)
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
+  else
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
 }
 
 inline int gemm_class(int epi, int N, int vocab) { return (epi == EPI_STORE && N == vocab) ? DFLASH_PROF_GEMM_LMHEAD : epi; }
@@ -471,10 +485,10 @@ inline int env_int(const char* name, int dflt) {
 
 // K split across workgroups: aim at enough workgroups that every CU keeps several wavefronts streaming,
 // keep at least 2 k-tiles per wavefront, and stay inside the arena.
-inline int pick_ksplit(int n_blocks, int KT, int M) {
+inline int pick_ksplit(int n_blocks, int KT, int M, int arena) {
   static const int target = env_int("DFLASH_GEMM_TARGET_WGS", 256);   // tuning knob
   int ks = 1;
-  while (ks < kMaxKSplit && n_blocks * ks * 2 <= target && KT / (ks * 2 * 4) >= 2 && ks * 2 * M <= kArenaSplitRows) ks *= 2;
+  while (ks < kMaxKSplit && n_blocks * ks * 2 <= target && KT / (ks * 2 * 4) >= 2 && ks * 2 * M <= arena) ks *= 2;
   return ks;
 }
 
@@ -489,42 +503,53 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     kepi = EPI_STORE;
   }
   const bool split = allow_split && epi != EPI_SWIGLU;
+  const int arena = arena_rows(c->rt.max_seqs * c->rt.block_size);
   int ks = 1;
   if (M <= 16) {
     static const int NT8 = env_int("DFLASH_GEMM_NT8", 1);   // tuning knob: matrices with at least 8*this row bands use 8 weight tiles per activation fragment
     if (NT8 && nt % 8 == 0 && nt >= 8 * NT8) {
-      if (split) ks = pick_ksplit(nt / 8, KT, M);
+      if (split) ks = pick_ksplit(nt / 8, KT, M, arena);
       ep.slab = (size_t)M * ep.ld;
       if (U >= 2) launch_bf16<8, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<8, 1, 1>(st, W, A, M, N, K, kepi, ep, ks);
     } else if (nt % 4 == 0) {
-      if (split) ks = pick_ksplit(nt / 4, KT, M);
+      if (split) ks = pick_ksplit(nt / 4, KT, M, arena);
       ep.slab = (size_t)M * ep.ld;
       if (U >= 4) launch_bf16<4, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
       else if (U >= 2) launch_bf16<4, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<4, 1, 1>(st, W, A, M, N, K, kepi, ep, ks);
     } else if (nt % 2 == 0) {
-      if (split) ks = pick_ksplit(nt / 2, KT, M);
+      if (split) ks = pick_ksplit(nt / 2, KT, M, arena);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<2, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
     } else {
-      if (split) ks = pick_ksplit(nt, KT, M);
+      if (split) ks = pick_ksplit(nt, KT, M, arena);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<1, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
     }
   } else if (M <= 64 && nt % 8 == 0) {
     // still bandwidth-bound: the same streaming kernel with four activation bands per weight tile
-    if (split) ks = pick_ksplit(nt / 8, KT, M);
+    if (split) ks = pick_ksplit(nt / 8, KT, M, arena);
     ep.slab = (size_t)M * ep.ld;
     launch_bf16<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
+  } else if (M > 64 && nt % 2 == 0) {
+    // compute-bound: LDS-staged tiles; 256 x 128 outputs per workgroup when that still fills the chip, else 128 x 128
+    const int mt = (M + 15) / 16;
+    const bool wide = ((nt + 15) / 16) * ((mt + 7) / 8) >= c->wide_min_wgs;
+    const int wgs = wide ? ((nt + 15) / 16) * ((mt + 7) / 8) : ((nt + 7) / 8) * ((mt + 7) / 8);
+    if (split)
+      while (ks < kMaxKSplit && wgs * ks * 2 <= 512 && KT / (ks * 2) >= 8 && ks * 2 * M <= arena) ks *= 2;
+    ep.slab = (size_t)M * ep.ld;
+    if (wide) launch_tiled<8, 4>(st, W, A, M, N, K, kepi, ep, ks);
+    else launch_tiled<4, 4>(st, W, A, M, N, K, kepi, ep, ks);
   } else {
     const int my = ((M + 15) / 16 + 3) / 4;
     if (nt % 2 == 0) {
-      if (split && my == 1) ks = pick_ksplit(nt / 2, KT, M);
+      if (split && my == 1) ks = pick_ksplit(nt / 2, KT, M, arena);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<2, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
     } else {
-      if (split && my == 1) ks = pick_ksplit(nt, KT, M);
+      if (split && my == 1) ks = pick_ksplit(nt, KT, M, arena);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<1, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
     }
@@ -741,6 +766,7 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->ws = ws;
   c->tblob = (const char*)target_blob; c->dblob = (const char*)draft_blob; c->wsp = (char*)rt->workspace;
   c->err[0] = 0;
+  c->wide_min_wgs = env_int("DFLASH_GEMM_WIDE_MIN_WGS", 192);
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {
     delete c;
     return fail(nullptr, DFLASH_EHIP, "create: cannot clear the device status word");

@@ -1,0 +1,125 @@
+// Compute-bound GEMM for many activation rows (M > 64): y[M,N] = a[M,K] * W[N,K]^T, bf16 MFMA 16x16x32 with
+// hi+lo activation pairs, fp32 accumulation, the same operand layouts and epilogues as the streaming kernel.
+//
+// A workgroup of 4 wavefronts (2 along N x 2 along M) owns a tile of 2*WN weight row bands x 2*WM activation
+// row bands for one K range (grid.y).  Both operands already sit in HBM in MFMA fragment order (1 KB per
+// 16x32 fragment), so a k step is staged by copying whole fragments: global -> registers -> LDS, one k tile
+// ahead in registers and one more in the second LDS buffer; every wavefront then reads the WN weight and
+// 2*WM activation fragments of its quadrant (each lane its own 16 bytes: conflict-free ds_read_b128) and
+// issues WN*WM*2 MFMAs.  Fragments are shared 2x through LDS, which halves the L2 traffic per flop.
+//
+// Workgroup order: consecutive workgroup ids go to different XCDs (round-robin dispatch), so id = 8*j + x
+// is mapped to weight band block 8*(j / m_blocks) + x and activation block j % m_blocks: the workgroups that
+// re-read one weight block run back to back on one XCD and share its L2.
+#pragma once
+#include "gemm.h"
+
+template <int WN, int WM, int EPI>
+__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
+                                                                 int M, int N, int K, int n_blocks, int m_blocks, EpiArgs ep) {
+  constexpr int BNT = 2 * WN, BMT = 2 * WM;        // fragments of a stage: BNT weight + 2*BMT activation (hi, lo)
+  constexpr int FR = BNT + 2 * BMT, PER = FR / 4;  // fragments copied by each wavefront
+  static_assert(WN % 2 == 0 && FR % 4 == 0, "tile shape");
+  __shared__ u32x4 stage[2][FR][64];
+
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wy = wave >> 1, wx = wave & 1;
+  const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
+  const int nb = (j / m_blocks) * 8 + xcd, mb = j % m_blocks;
+  if (nb >= n_blocks) return;                      // whole workgroup leaves before any barrier
+  const int KT = K >> 5, n_tiles = N >> 4, m_tiles = (M + 15) >> 4;
+  const int ks = gridDim.y, kz = blockIdx.y;
+  const int per = (KT + ks - 1) / ks;
+  const int kb = min(KT, kz * per), ke = min(KT, kb + per);
+  const int nt0 = nb * BNT, mt0 = mb * BMT;
+
+  // the PER fragments this wavefront copies per stage: element offset of k tile 0 and stride per k tile (u32x4 units)
+  size_t g_off[PER];
+  int g_step[PER];
+  const u32x4* g_base[PER];
+#pragma unroll
+  for (int i = 0; i < PER; ++i) {
+    const int f = wave * PER + i;
+    if (f < BNT) {   // weight fragment: bands past the matrix alias the last band (never stored)
+      g_base[i] = reinterpret_cast<const u32x4*>(W);
+      g_off[i] = (size_t)min(nt0 + f, n_tiles - 1) * 64 + lane;
+      g_step[i] = n_tiles * 64;
+    } else {         // activation fragment: band (f - BNT) / 2, plane (f - BNT) % 2
+      const int a = f - BNT;
+      g_base[i] = reinterpret_cast<const u32x4*>(A);
+      g_off[i] = (size_t)min(mt0 + (a >> 1), m_tiles - 1) * KT * 128 + (a & 1) * 64 + lane;
+      g_step[i] = 128;
+    }
+  }
+  auto load_global = [&](u32x4 (&g)[PER], int kt) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) g[i] = g_base[i][g_off[i] + (size_t)kt * g_step[i]];
+  };
+  auto write_lds = [&](int buf, const u32x4 (&g)[PER]) {
+#pragma unroll
+    for (int i = 0; i < PER; ++i) stage[buf][wave * PER + i][lane] = g[i];
+  };
+
+  f32x4 acc[WN][WM];
+#pragma unroll
+  for (int i = 0; i < WN; ++i)
+#pragma unroll
+    for (int jj = 0; jj < WM; ++jj) acc[i][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
+
+  if (kb < ke) {
+    u32x4 g[PER];
+    load_global(g, kb);
+    write_lds(0, g);
+    if (kb + 1 < ke) load_global(g, kb + 1);
+    __syncthreads();
+    for (int kt = kb; kt < ke; ++kt) {
+      const int cur = (kt - kb) & 1;
+      u32x4 wf[WN], ah[WM], al[WM];
+#pragma unroll
+      for (int i = 0; i < WN; ++i) wf[i] = stage[cur][wy * WN + i][lane];
+#pragma unroll
+      for (int jj = 0; jj < WM; ++jj) {
+        ah[jj] = stage[cur][BNT + 2 * (wx * WM + jj)][lane];
+        al[jj] = stage[cur][BNT + 2 * (wx * WM + jj) + 1][lane];
+      }
+#pragma unroll
+      for (int i = 0; i < WN; ++i)
+#pragma unroll
+        for (int jj = 0; jj < WM; ++jj) {
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ah[jj]),
+                                                               acc[i][jj], 0, 0, 0);
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, al[jj]),
+                                                               acc[i][jj], 0, 0, 0);
+        }
+      if (kt + 1 < ke) write_lds(cur ^ 1, g);      // that buffer was last read before the previous barrier
+      if (kt + 2 < ke) load_global(g, kt + 2);
+      __syncthreads();
+    }
+  }
+
+  // lane l holds y[m = band*16 + l%16][n = tile*16 + 4*(l/16) .. +3]
+  const int mrow = lane & 15, gq = lane >> 4;
+#pragma unroll
+  for (int jj = 0; jj < WM; ++jj) {
+    const int mt = mt0 + wx * WM + jj, m = mt * 16 + mrow;
+    if (mt >= m_tiles || m >= M) continue;
+    if (EPI == EPI_SWIGLU) {
+      bf16_t* act = reinterpret_cast<bf16_t*>(ep.act);
+#pragma unroll
+      for (int p = 0; p < WN / 2; ++p) {
+        const int nt = nt0 + wy * WN + 2 * p;      // gate tile; the up tile follows it
+        if (nt + 1 >= n_tiles) continue;
+        const f32x4 gs = acc[2 * p][jj], us = acc[2 * p + 1][jj];
+        Act<bf16_t>::store4(act, m, (nt >> 1) * 16 + 4 * gq, ep.act_K,
+                            make_float4(silu_f(gs[0]) * us[0], silu_f(gs[1]) * us[1], silu_f(gs[2]) * us[2], silu_f(gs[3]) * us[3]));
+      }
+    } else {
+#pragma unroll
+      for (int i = 0; i < WN; ++i) {
+        const int nt = nt0 + wy * WN + i;
+        if (nt >= n_tiles) continue;
+        const f32x4 s = acc[i][jj];
+        *reinterpret_cast<float4*>(ep.out + (size_t)kz * ep.slab + (size_t)m * ep.ld + nt * 16 + 4 * gq) = make_float4(s[0], s[1], s[2], s[3]);
+      }
+    }
+  }
+}

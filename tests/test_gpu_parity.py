@@ -218,6 +218,27 @@ def test_small_bf16_model_steps_and_cache():
     assert ls.stats["reseeds"] <= 1
 
 
+@pytest.mark.parametrize("wide_min_wgs", ["192", "1"])
+def test_small_bf16_many_rows_tiled_gemm(wide_min_wgs, monkeypatch):
+    """The same small bf16 model with 10 sequences: 160 activation rows per step go through the LDS-staged
+    GEMM for many rows (two activation blocks, the second with a ragged tail); the prefill chunks with 6
+    sequences still alive exercise one partly filled block.  Run once with the tile shape the dispatcher
+    picks at this size (128 x 128) and once forced to 256 x 128, the shape of the large matrices."""
+    monkeypatch.setenv("DFLASH_GEMM_WIDE_MIN_WGS", wide_min_wgs)
+    w = si.small_bf16_workload(n_seqs=10, ctx_min=17, ctx_max=90, seed=23)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=90 + 4 * 16)
+    ls.prefill()
+    ls.check_cache([0, 7], [0, 1])
+    plans = [None, [15, 0, 9, 1, 2, 3, 4, 5, 15, 7], None]
+    for i, plan in enumerate(plans):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([3], [1])
+    print("small bf16 (160 rows) stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
 def test_temperature1_sampling_matches_oracle_decisions():
     """Speculative sampling at T=1 on the tiny fp32 model: drafted tokens (Gumbel-max with the shared
     counter-based generator), accept lengths and replacement / bonus tokens agree with the oracle."""
