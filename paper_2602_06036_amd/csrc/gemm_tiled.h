@@ -3,10 +3,16 @@
 //
 // A workgroup of 4 wavefronts (2 along N x 2 along M) owns a tile of 2*WN weight row bands x 2*WM activation
 // row bands for one K range (grid.y).  Both operands already sit in HBM in MFMA fragment order (1 KB per
-// 16x32 fragment), so a k step is staged by copying whole fragments: global -> registers -> LDS, one k tile
-// ahead in registers and one more in the second LDS buffer; every wavefront then reads the WN weight and
-// 2*WM activation fragments of its quadrant (each lane its own 16 bytes: conflict-free ds_read_b128) and
-// issues WN*WM*2 MFMAs.  Fragments are shared 2x through LDS, which halves the L2 traffic per flop.
+// 16x32 fragment), so a k tile is staged by copying whole fragments: global -> registers (one k tile ahead)
+// -> one of two LDS slots; every wavefront reads the WN weight and 2*WM activation fragments of its quadrant
+// (each lane its own 16 bytes: conflict-free ds_read_b128) and issues WN*WM*2 MFMAs per k tile.
+//
+// Register schedule of a k tile: the WN weight fragments stay resident, the activation (hi, lo) pair of one
+// row band rotates through a double buffer, read one step (2*WN MFMAs) ahead.  In the last step every weight
+// fragment is re-read for the next k tile right after its last MFMA, so the LDS latency hides behind the
+// remaining MFMAs and a wavefront that is alone on its SIMD does not idle on it.  One barrier per k tile,
+// before that last step: by then every wavefront has issued all its reads of the current slot (so it can be
+// refilled with k tile t+2) and has finished writing the other slot (k tile t+1, which the last step reads).
 //
 // Workgroup order: consecutive workgroup ids go to different XCDs (round-robin dispatch), so id = 8*j + x
 // is mapped to weight band block 8*(j / m_blocks) + x and activation block j % m_blocks: the workgroups that
@@ -15,11 +21,12 @@
 #include "gemm.h"
 
 template <int WN, int WM, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
-                                                                 int M, int N, int K, int n_blocks, int m_blocks, EpiArgs ep) {
+__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W,
+                                                                                const bf16_t* __restrict__ A, int M, int N, int K,
+                                                                                int n_blocks, int m_blocks, EpiArgs ep) {
   constexpr int BNT = 2 * WN, BMT = 2 * WM;        // fragments of a stage: BNT weight + 2*BMT activation (hi, lo)
   constexpr int FR = BNT + 2 * BMT, PER = FR / 4;  // fragments copied by each wavefront
-  static_assert(WN % 2 == 0 && FR % 4 == 0, "tile shape");
+  static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % 4 == 0, "tile shape");
   __shared__ u32x4 stage[2][FR][64];
 
   const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wy = wave >> 1, wx = wave & 1;
@@ -32,7 +39,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
   const int kb = min(KT, kz * per), ke = min(KT, kb + per);
   const int nt0 = nb * BNT, mt0 = mb * BMT;
 
-  // the PER fragments this wavefront copies per stage: element offset of k tile 0 and stride per k tile (u32x4 units)
+  // the PER fragments this wavefront copies per stage: offset at k tile 0 and stride per k tile (u32x4 units)
   size_t g_off[PER];
   int g_step[PER];
   const u32x4* g_base[PER];
@@ -54,9 +61,9 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
 #pragma unroll
     for (int i = 0; i < PER; ++i) g[i] = g_base[i][g_off[i] + (size_t)kt * g_step[i]];
   };
-  auto write_lds = [&](int buf, const u32x4 (&g)[PER]) {
+  auto write_lds = [&](int slot, const u32x4 (&g)[PER]) {
 #pragma unroll
-    for (int i = 0; i < PER; ++i) stage[buf][wave * PER + i][lane] = g[i];
+    for (int i = 0; i < PER; ++i) stage[slot][wave * PER + i][lane] = g[i];
   };
 
   f32x4 acc[WN][WM];
@@ -69,30 +76,42 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
     u32x4 g[PER];
     load_global(g, kb);
     write_lds(0, g);
-    if (kb + 1 < ke) load_global(g, kb + 1);
+    load_global(g, min(kb + 1, ke - 1));
+    write_lds(1, g);
+    load_global(g, min(kb + 2, ke - 1));
     __syncthreads();
-    for (int kt = kb; kt < ke; ++kt) {
-      const int cur = (kt - kb) & 1;
-      u32x4 wf[WN], ah[WM], al[WM];
+
+    u32x4 wf[WN];      // weight fragments of the current k tile
+    u32x4 ap[2][2];    // activation (hi, lo) pair of row band jj in set jj & 1
 #pragma unroll
-      for (int i = 0; i < WN; ++i) wf[i] = stage[cur][wy * WN + i][lane];
+    for (int i = 0; i < WN; ++i) wf[i] = stage[0][wy * WN + i][lane];
+    ap[0][0] = stage[0][BNT + 2 * wx * WM][lane];
+    ap[0][1] = stage[0][BNT + 2 * wx * WM + 1][lane];
+
+    // Straight-line body: past the end of the K range the prefetches read a stale slot, the refill rewrites a
+    // slot nobody reads any more and the global loads repeat the last k tile, so no branch splits the MFMA stream.
+    for (int kt = kb; kt < ke; ++kt) {
+      const int s0 = (kt - kb) & 1, s1 = s0 ^ 1;
 #pragma unroll
       for (int jj = 0; jj < WM; ++jj) {
-        ah[jj] = stage[cur][BNT + 2 * (wx * WM + jj)][lane];
-        al[jj] = stage[cur][BNT + 2 * (wx * WM + jj) + 1][lane];
-      }
+        constexpr int last = WM - 1;
+        if (jj == last) __syncthreads();
+        const int slot = jj == last ? s1 : s0, band = jj == last ? 0 : jj + 1;
+        ap[(jj + 1) & 1][0] = stage[slot][BNT + 2 * (wx * WM + band)][lane];
+        ap[(jj + 1) & 1][1] = stage[slot][BNT + 2 * (wx * WM + band) + 1][lane];
 #pragma unroll
-      for (int i = 0; i < WN; ++i)
+        for (int i = 0; i < WN; ++i)
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj & 1][0]),
+                                                               acc[i][jj], 0, 0, 0);
 #pragma unroll
-        for (int jj = 0; jj < WM; ++jj) {
-          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ah[jj]),
+        for (int i = 0; i < WN; ++i) {
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj & 1][1]),
                                                                acc[i][jj], 0, 0, 0);
-          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, al[jj]),
-                                                               acc[i][jj], 0, 0, 0);
+          if (jj == last) wf[i] = stage[s1][wy * WN + i][lane];
         }
-      if (kt + 1 < ke) write_lds(cur ^ 1, g);      // that buffer was last read before the previous barrier
-      if (kt + 2 < ke) load_global(g, kt + 2);
-      __syncthreads();
+      }
+      write_lds(s0, g);
+      load_global(g, min(kt + 3, ke - 1));
     }
   }
 
