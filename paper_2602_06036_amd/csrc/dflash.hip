@@ -223,7 +223,7 @@ struct dflash_ctx {
   const char* dblob;
   char* wsp;
   char err[512];
-  int wide_min_wgs = 192;   // tiled GEMM: least number of 256 x 128 tiles for which that tile shape is used (tuning knob)
+  int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
@@ -534,14 +534,30 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     ep.slab = (size_t)M * ep.ld;
     launch_bf16<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
   } else if (M > 64 && nt % 2 == 0) {
-    // compute-bound: LDS-staged tiles; 256 x 128 outputs per workgroup when that still fills the chip, else 128 x 128
-    const int mt = (M + 15) / 16;
-    const bool wide = ((nt + 15) / 16) * ((mt + 7) / 8) >= c->wide_min_wgs;
-    const int wgs = wide ? ((nt + 15) / 16) * ((mt + 7) / 8) : ((nt + 7) / 8) * ((mt + 7) / 8);
-    if (split)
-      while (ks < kMaxKSplit && wgs * ks * 2 <= 512 && KT / (ks * 2) >= 8 && ks * 2 * M <= arena) ks *= 2;
+    // compute-bound: LDS-staged tiles of 256, 192 or 128 weight rows x 128 activation rows.  Pick the shape and
+    // K split with the least estimated time: workgroups on the busiest CU x MFMA time of one workgroup (larger
+    // tiles move fewer operand bytes per flop, hence the efficiency factors; a workgroup alone on its CU has
+    // nobody to hide its barriers and LDS latency behind), plus the traffic of the partial slabs.
+    struct Cand { int wn; double eff; };
+    static const Cand cands[3] = {{8, 1.0}, {6, 0.95}, {4, 0.85}};
+    const int mb = ((M + 15) / 16 + 7) / 8;
+    int best_wn = 4;
+    double best = 1e30;
+    for (const Cand& cd : cands) {
+      if (c->tile_force && cd.wn != c->tile_force) continue;
+      const int wgs = ((nt + 2 * cd.wn - 1) / (2 * cd.wn)) * mb;
+      for (int k = 1; k <= kMaxKSplit; k *= 2) {
+        if (k > 1 && (!split || KT / k < 8 || k * M > arena)) break;
+        const int per_cu = (wgs * k + 255) / 256;
+        const double mfma_us = 32.0 * cd.wn * 4 * ((KT + k - 1) / k) / 2400.0;   // MFMA issue time of one workgroup
+        const double slab_us = k > 1 ? (double)k * M * N * 8 / 4e6 : 0.0;
+        const double t = per_cu * mfma_us / cd.eff * (per_cu == 1 ? 1.4 : 1.0) + slab_us;
+        if (t < best) { best = t; best_wn = cd.wn; ks = k; }
+      }
+    }
     ep.slab = (size_t)M * ep.ld;
-    if (wide) launch_tiled<8, 4>(st, W, A, M, N, K, kepi, ep, ks);
+    if (best_wn == 8) launch_tiled<8, 4>(st, W, A, M, N, K, kepi, ep, ks);
+    else if (best_wn == 6) launch_tiled<6, 4>(st, W, A, M, N, K, kepi, ep, ks);
     else launch_tiled<4, 4>(st, W, A, M, N, K, kepi, ep, ks);
   } else {
     const int my = ((M + 15) / 16 + 3) / 4;
@@ -767,7 +783,7 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->ws = ws;
   c->tblob = (const char*)target_blob; c->dblob = (const char*)draft_blob; c->wsp = (char*)rt->workspace;
   c->err[0] = 0;
-  c->wide_min_wgs = env_int("DFLASH_GEMM_WIDE_MIN_WGS", 192);
+  c->tile_force = env_int("DFLASH_GEMM_TILE", 0);
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {
     delete c;
     return fail(nullptr, DFLASH_EHIP, "create: cannot clear the device status word");

@@ -218,13 +218,13 @@ def test_small_bf16_model_steps_and_cache():
     assert ls.stats["reseeds"] <= 1
 
 
-@pytest.mark.parametrize("wide_min_wgs", ["192", "1"])
-def test_small_bf16_many_rows_tiled_gemm(wide_min_wgs, monkeypatch):
+@pytest.mark.parametrize("tile", ["0", "8", "6"])
+def test_small_bf16_many_rows_tiled_gemm(tile, monkeypatch):
     """The same small bf16 model with 10 sequences: 160 activation rows per step go through the LDS-staged
     GEMM for many rows (two activation blocks, the second with a ragged tail); the prefill chunks with 6
-    sequences still alive exercise one partly filled block.  Run once with the tile shape the dispatcher
-    picks at this size (128 x 128) and once forced to 256 x 128, the shape of the large matrices."""
-    monkeypatch.setenv("DFLASH_GEMM_WIDE_MIN_WGS", wide_min_wgs)
+    sequences still alive exercise one partly filled block.  Run with the tile shapes the dispatcher picks at
+    this size and forced to 256 x 128 and 192 x 128, the shapes of the large matrices."""
+    monkeypatch.setenv("DFLASH_GEMM_TILE", tile)
     w = si.small_bf16_workload(n_seqs=10, ctx_min=17, ctx_max=90, seed=23)
     prompts = si.make_prompts(w)
     ls = Lockstep(w, prompts, max_len=90 + 4 * 16)
