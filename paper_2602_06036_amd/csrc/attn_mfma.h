@@ -196,19 +196,234 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   }
 }
 
+// ------------------------------------------------------------------------------------------------
+// Long-chunk variant (hundreds of keys or more per workgroup).  The kernel above keeps only one page pair
+// of unique bytes in flight per CU (its four wavefronts read the same keys), which is latency-bound once a
+// chunk is long.  Here the four wavefronts split the KEYS instead: wavefront w takes page pairs w, w+4, ...
+// of the chunk for all RB = 4 blocks of 16 query rows, each with its own pair in flight (4x the bytes in
+// flight, K/V fragments read from HBM exactly once per workgroup), and the four partial (max, sum, O) sets
+// are merged through LDS at the end with the same log-sum-exp rule as the cross-split merge.
+// ------------------------------------------------------------------------------------------------
+__device__ __forceinline__ uint32_t pack_bf16_pair(float a, float b) {   // RNE, a in the low half
+  typedef __bf16 bf16x2_t __attribute__((ext_vector_type(2)));
+  typedef float f32x2_t __attribute__((ext_vector_type(2)));
+  const bf16x2_t r = __builtin_convertvector((f32x2_t){a, b}, bf16x2_t);
+  return __builtin_bit_cast(uint32_t, r);
+}
+
+template <int HD, int RB>
+__device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base, const u32x4* __restrict__ q_lds,
+                                                       f32x4 (&acc)[RB][HD / 16], float (&m_run)[RB], float (&l_run)[RB],
+                                                       const int (&last_vis)[RB], int n_all_vis, float scale, const AttnLane& L) {
+  constexpr int KT = HD / 32, DT = HD / 16;
+  if (base + 32 > L.n_tok || !f.ok_a || !f.ok_b) {   // never-written rows / foreign pages: clear V (0 * garbage != NaN)
+    const int pos_a = base + 4 * L.g, pos_b = base + 16 + 4 * L.g;
+    uint32_t ma0 = 0u, ma1 = 0u, mb0 = 0u, mb1 = 0u;
+    if (f.ok_a && pos_a + 0 < L.n_tok) ma0 |= 0x0000FFFFu;
+    if (f.ok_a && pos_a + 1 < L.n_tok) ma0 |= 0xFFFF0000u;
+    if (f.ok_a && pos_a + 2 < L.n_tok) ma1 |= 0x0000FFFFu;
+    if (f.ok_a && pos_a + 3 < L.n_tok) ma1 |= 0xFFFF0000u;
+    if (f.ok_b && pos_b + 0 < L.n_tok) mb0 |= 0x0000FFFFu;
+    if (f.ok_b && pos_b + 1 < L.n_tok) mb0 |= 0xFFFF0000u;
+    if (f.ok_b && pos_b + 2 < L.n_tok) mb1 |= 0x0000FFFFu;
+    if (f.ok_b && pos_b + 3 < L.n_tok) mb1 |= 0xFFFF0000u;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) f.v[dt] &= (u32x4){ma0, ma1, mb0, mb1};
+  }
+  // every key of the pair visible to every row (the bulk of a long context): no per-element masking
+  const bool all_vis = f.ok_a && f.ok_b && base + 32 <= n_all_vis;
+  const int pa0 = base + 4 * L.g;
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    f32x4 sa = {0.f, 0.f, 0.f, 0.f}, sb = {0.f, 0.f, 0.f, 0.f};
+    u32x4 qf[KT];   // query fragments of this row block, kept in LDS between uses
+    asm volatile("" ::: "memory");   // keep these reads inside the loop: hoisted, they would cost 64 registers
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) qf[kt] = q_lds[(rb * KT + kt) * 64 + L.lane];
+#pragma unroll
+    for (int kt = 0; kt < KT; ++kt) {
+      sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.ka[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sa, 0, 0, 0);
+      sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.kb[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sb, 0, 0, 0);
+    }
+    float v[8];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      v[i] = sa[i] * scale;
+      v[4 + i] = sb[i] * scale;
+    }
+    if (!all_vis) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        if (!(f.ok_a && pa0 + i < L.c1 && pa0 + i <= last_vis[rb])) v[i] = -INFINITY;
+        if (!(f.ok_b && pa0 + 16 + i < L.c1 && pa0 + 16 + i <= last_vis[rb])) v[4 + i] = -INFINITY;
+      }
+    }
+    float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
+    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    const float m_old = m_run[rb];
+    const float m_new = fmaxf(m_old, mx);
+    const float mb = (m_new == -INFINITY) ? 0.f : m_new;
+    const float corr = (m_old == -INFINITY) ? (m_new == -INFINITY ? 1.f : 0.f) : __expf(m_old - m_new);
+    float pe[8];
+#pragma unroll
+    for (int i = 0; i < 8; ++i) pe[i] = __expf(v[i] - mb);
+    l_run[rb] = l_run[rb] * corr + (((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7])));
+    m_run[rb] = m_new;
+    u32x4 ph, pl;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const uint32_t h = pack_bf16_pair(pe[2 * i], pe[2 * i + 1]);
+      ph[i] = h;
+      pl[i] = pack_bf16_pair(pe[2 * i] - __uint_as_float(h << 16), pe[2 * i + 1] - __uint_as_float(h & 0xFFFF0000u));
+    }
+    // the running maximum rarely moves after the first pairs: skip the rescale when no lane needs it
+    const bool rescale = __any(corr != 1.f);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) {
+      f32x4 a = acc[rb][dt];
+      if (rescale) { a[0] *= corr; a[1] *= corr; a[2] *= corr; a[3] *= corr; }
+      a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, ph), a, 0, 0, 0);
+      a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, pl), a, 0, 0, 0);
+      acc[rb][dt] = a;
+    }
+  }
+}
+
+template <int HD>
+__global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __restrict__ q, const bf16_t* __restrict__ pool,
+                                                                SeqGeom geo, AttnArgs aa, float* __restrict__ part_o,
+                                                                float2* __restrict__ part_ml) {
+  constexpr int KT = HD / 32, DT = HD / 16, RB = 4, LD = HD + 4;
+  __shared__ float2 s_ml[4][64];
+  __shared__ __attribute__((aligned(16))) float s_raw[4 * 64 * LD];   // query fragments during the sweep, outputs in the merge
+  float (*s_o)[64][LD] = reinterpret_cast<float (*)[64][LD]>(s_raw);
+  u32x4* q_lds = reinterpret_cast<u32x4*>(s_raw);                      // [rb][kt][lane]
+  const int split = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
+  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int n = lane & 15, g = lane >> 4;
+  const int B = geo.block_size;
+  const int group = aa.n_q_heads / aa.n_kv_heads;
+  const int rows = B * group;
+  const int n_s = geo.seq_lens[s];
+  const int cap = geo.max_pages_per_seq * DF_PAGE;
+
+  AttnLane L;
+  L.table = geo.block_table + (size_t)s * geo.max_pages_per_seq;
+  L.n_tok = min(n_s + B, cap);
+  L.c0 = split * aa.chunk;
+  L.c1 = min(L.n_tok, L.c0 + aa.chunk);
+  L.last_vis = 0;
+  L.g = g;
+  L.lane = lane;
+  L.kvh = kvh;
+  const int n_all_vis = min(L.c1, aa.causal ? n_s : L.n_tok);   // keys below this are visible to every row
+
+  // query fragments of the RB row blocks: lane (n, g) holds Q[row rb*16 + n][kt*32 + g*8 .. +8]; wavefront w
+  // stages row block w in LDS for everybody
+  int last_vis[RB];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int r = rb * 16 + n;
+    const bool valid = r < rows;
+    const int slot = valid ? r / group : 0, hq = kvh * group + (valid ? r % group : 0);
+    last_vis[rb] = valid ? (aa.causal ? n_s + slot : 0x7FFFFFFF) : -1;
+    if (rb == wave) {
+      const u32x4* qp = reinterpret_cast<const u32x4*>(q + ((size_t)(s * B + slot) * aa.n_q_heads + hq) * HD);
+#pragma unroll
+      for (int kt = 0; kt < KT; ++kt) q_lds[(rb * KT + kt) * 64 + lane] = valid ? qp[kt * 4 + g] : (u32x4){0u, 0u, 0u, 0u};
+    }
+  }
+  __syncthreads();
+
+  float m_run[RB], l_run[RB];
+  f32x4 acc[RB][DT];
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    m_run[rb] = -INFINITY;
+    l_run[rb] = 0.f;
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt) acc[rb][dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  }
+
+  const int n_pairs = L.c1 > L.c0 ? (L.c1 - L.c0 + 31) >> 5 : 0;
+  if (wave < n_pairs) {
+    KvFrags<HD> f0, f1;
+    attn_load_pair<HD>(f0, wave, pool, geo, aa, L);
+    for (int p = wave; p < n_pairs; p += 8) {
+      if (p + 4 < n_pairs) attn_load_pair<HD>(f1, p + 4, pool, geo, aa, L);
+      attn_process_pair_wide<HD, RB>(f0, L.c0 + p * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, aa.scale, L);
+      if (p + 4 < n_pairs) {
+        if (p + 8 < n_pairs) attn_load_pair<HD>(f0, p + 8, pool, geo, aa, L);
+        attn_process_pair_wide<HD, RB>(f1, L.c0 + (p + 4) * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, aa.scale, L);
+      }
+    }
+  }
+
+  // ---- merge the four wavefronts' partial results (each over its own keys) --------------------------------
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    float l = l_run[rb];
+    l += __shfl_xor(l, 16, 64);
+    l += __shfl_xor(l, 32, 64);
+    if (g == 0) s_ml[wave][rb * 16 + n] = make_float2(m_run[rb], l);
+  }
+  __syncthreads();   // also: every wavefront is done with the query fragments that s_o overlays
+#pragma unroll
+  for (int rb = 0; rb < RB; ++rb) {
+    const int r = rb * 16 + n;
+    float m_all = -INFINITY;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) m_all = fmaxf(m_all, s_ml[w][r].x);
+    const float mine = (m_run[rb] == -INFINITY) ? 0.f : __expf(m_run[rb] - m_all);   // m_all is finite whenever m_run is
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
+      *reinterpret_cast<float4*>(&s_o[wave][r][dt * 16 + 4 * g]) =
+          make_float4(acc[rb][dt][0] * mine, acc[rb][dt][1] * mine, acc[rb][dt][2] * mine, acc[rb][dt][3] * mine);
+  }
+  __syncthreads();
+  for (int idx = threadIdx.x; idx < 64 * (HD / 4); idx += 256) {
+    const int r = idx / (HD / 4), d4 = idx % (HD / 4);
+    if (r >= rows) continue;
+    const int slot = r / group, hq = kvh * group + r % group;
+    const size_t pr = ((size_t)(s * B + slot) * aa.n_q_heads + hq) * aa.n_splits + split;
+    float4 o = *reinterpret_cast<const float4*>(&s_o[0][r][d4 * 4]);
+#pragma unroll
+    for (int w = 1; w < 4; ++w) {
+      const float4 a = *reinterpret_cast<const float4*>(&s_o[w][r][d4 * 4]);
+      o.x += a.x; o.y += a.y; o.z += a.z; o.w += a.w;
+    }
+    *reinterpret_cast<float4*>(part_o + pr * HD + d4 * 4) = o;
+    if (d4 == 0) {
+      float m_all = -INFINITY;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) m_all = fmaxf(m_all, s_ml[w][r].x);
+      float l = 0.f;
+#pragma unroll
+      for (int w = 0; w < 4; ++w) {
+        const float2 ml = s_ml[w][r];
+        l += (ml.x == -INFINITY) ? 0.f : ml.y * __expf(ml.x - m_all);
+      }
+      part_ml[pr] = make_float2(m_all, l);
+    }
+  }
+}
+
 // Returns true when it launched a kernel for this configuration; false -> caller uses the generic kernel.
 template <typename T>
-inline bool attn_mfma_launch(hipStream_t, const T*, const T*, SeqGeom, AttnArgs, int, float*, float2*) {
+inline bool attn_mfma_launch(hipStream_t, const T*, const T*, SeqGeom, AttnArgs, int, float*, float2*, int) {
   return false;
 }
 
 template <>
 inline bool attn_mfma_launch<bf16_t>(hipStream_t st, const bf16_t* q, const bf16_t* pool, SeqGeom geo, AttnArgs aa, int S,
-                                     float* part_o, float2* part_ml) {
+                                     float* part_o, float2* part_ml, int wide_min_chunk) {
   const int rows = geo.block_size * (aa.n_q_heads / aa.n_kv_heads);
   if (rows > 64 || (aa.head_dim != 128 && aa.head_dim != 64)) return false;
   const dim3 grid(aa.n_splits, aa.n_kv_heads, S), block(256);
-  if (aa.head_dim == 128)
+  if (aa.head_dim == 128 && aa.chunk >= wide_min_chunk)   // long chunks: wavefronts split the keys
+    hipLaunchKernelGGL(attn_mfma_wide_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
+  else if (aa.head_dim == 128)
     hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
   else
     hipLaunchKernelGGL(attn_mfma_kernel<64>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);

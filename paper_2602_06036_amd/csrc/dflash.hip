@@ -223,6 +223,7 @@ struct dflash_ctx {
   const char* dblob;
   char* wsp;
   char err[512];
+  int attn_wide_min_chunk = 512;   // keys per workgroup from which the key-split attention kernel is used (tuning knob)
   int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
@@ -604,7 +605,7 @@ void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const 
   {
     // algorithmic bytes: every cached K and V row of this layer once (upper bound from the host hint)
     ProfScope prof(c, st, DFLASH_PROF_ATTN, (double)S * max_tokens * 2 * m.n_kv_heads * m.head_dim * sizeof(T));
-    if (!attn_mfma_launch<T>(st, ws<T>(c->ws.q), pool, geom(b), aa, S, part_o, part_ml))
+    if (!attn_mfma_launch<T>(st, ws<T>(c->ws.q), pool, geom(b), aa, S, part_o, part_ml, c->attn_wide_min_chunk))
       hipLaunchKernelGGL(attn_partial_simple_kernel<T>, dim3(p.n_splits, m.n_kv_heads, S), dim3(256), 0, st, ws<T>(c->ws.q), pool,
                          geom(b), aa, part_o, part_ml);
     check();
@@ -784,6 +785,7 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->tblob = (const char*)target_blob; c->dblob = (const char*)draft_blob; c->wsp = (char*)rt->workspace;
   c->err[0] = 0;
   c->tile_force = env_int("DFLASH_GEMM_TILE", 0);
+  c->attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {
     delete c;
     return fail(nullptr, DFLASH_EHIP, "create: cannot clear the device status word");

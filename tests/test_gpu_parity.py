@@ -239,6 +239,25 @@ def test_small_bf16_many_rows_tiled_gemm(tile, monkeypatch):
     assert ls.stats["reseeds"] <= 1
 
 
+def test_small_bf16_key_split_attention(monkeypatch):
+    """The attention kernel for long chunks (wavefronts split the keys of a chunk, merged through LDS) forced on
+    at small context lengths: chunks of 1 to 5 page pairs, so some wavefronts get no keys at all, the ragged
+    last pair and the causal block rows all go through it."""
+    monkeypatch.setenv("DFLASH_ATTN_WIDE_MIN_CHUNK", "64")
+    w = si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=150, seed=11)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=150 + 8 * 16)
+    ls.prefill()
+    ls.check_cache([0, 3, 7], [0, 1])
+    plans = [None, [15, 0, 9], [3, 15, 15], None]
+    for i, plan in enumerate(plans):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([0, 7], [0, 1])
+    print("small bf16 (key-split attention) stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
 def test_temperature1_sampling_matches_oracle_decisions():
     """Speculative sampling at T=1 on the tiny fp32 model: drafted tokens (Gumbel-max with the shared
     counter-based generator), accept lengths and replacement / bonus tokens agree with the oracle."""
