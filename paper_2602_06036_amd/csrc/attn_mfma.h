@@ -26,16 +26,12 @@ struct AttnLane {          // per-lane constants of the kernel below
   int c0, c1, n_tok, last_vis, g, lane, kvh;
 };
 
+// issues the loads of page pair (pa, pb); pb < 0 means the chunk ends after page A
 template <int HD>
-__device__ __forceinline__ void attn_load_pair(KvFrags<HD>& f, int p, const bf16_t* __restrict__ pool, const SeqGeom& geo,
-                                               const AttnArgs& aa, const AttnLane& L) {
-  const int base = L.c0 + p * 32;           // first key of page A; page B starts at base + 16
-  const int ia = base >> 4;
-  int pa = L.table[ia];
+__device__ __forceinline__ void attn_load_pages(KvFrags<HD>& f, int pa, int pb, bool has_b, const bf16_t* __restrict__ pool,
+                                                const SeqGeom& geo, const AttnArgs& aa, const AttnLane& L) {
   f.ok_a = pa >= 0 && pa < geo.n_pages;
   if (!f.ok_a) pa = 0;
-  const bool has_b = base + 16 < L.c1;
-  int pb = has_b ? L.table[ia + 1] : pa;
   f.ok_b = has_b && pb >= 0 && pb < geo.n_pages;
   if (!f.ok_b) pb = pa;
   const bf16_t* ka = pool + kv_head_base(aa.layer, geo.n_pages, pa, aa.n_kv_heads, L.kvh, HD);
@@ -51,6 +47,17 @@ __device__ __forceinline__ void attn_load_pair(KvFrags<HD>& f, int p, const bf16
     const uint2 b = reinterpret_cast<const uint2*>(kb + DF_PAGE * HD)[dt * 64 + L.lane];
     f.v[dt] = (u32x4){a.x, a.y, b.x, b.y};
   }
+}
+
+template <int HD>
+__device__ __forceinline__ void attn_load_pair(KvFrags<HD>& f, int p, const bf16_t* __restrict__ pool, const SeqGeom& geo,
+                                               const AttnArgs& aa, const AttnLane& L) {
+  const int base = L.c0 + p * 32;           // first key of page A; page B starts at base + 16
+  const int ia = base >> 4;
+  const bool has_b = base + 16 < L.c1;
+  const int pa = L.table[ia];
+  const int pb = has_b ? L.table[ia + 1] : pa;
+  attn_load_pages<HD>(f, pa, pb, has_b, pool, geo, aa, L);
 }
 
 template <int HD>
@@ -133,7 +140,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
                                                         float2* __restrict__ part_ml) {
   constexpr int KT = HD / 32, DT = HD / 16;
   const int split = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int B = geo.block_size;
   const int group = aa.n_q_heads / aa.n_kv_heads;
@@ -214,7 +221,7 @@ __device__ __forceinline__ uint32_t pack_bf16_pair(float a, float b) {   // RNE,
 template <int HD, int RB>
 __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base, const u32x4* __restrict__ q_lds,
                                                        f32x4 (&acc)[RB][HD / 16], float (&m_run)[RB], float (&l_run)[RB],
-                                                       const int (&last_vis)[RB], int n_all_vis, float scale, const AttnLane& L) {
+                                                       const int (&last_vis)[RB], int n_all_vis, float scale2, const AttnLane& L) {
   constexpr int KT = HD / 32, DT = HD / 16;
   if (base + 32 > L.n_tok || !f.ok_a || !f.ok_b) {   // never-written rows / foreign pages: clear V (0 * garbage != NaN)
     const int pos_a = base + 4 * L.g, pos_b = base + 16 + 4 * L.g;
@@ -245,11 +252,11 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
       sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.ka[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sa, 0, 0, 0);
       sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.kb[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sb, 0, 0, 0);
     }
-    float v[8];
+    float v[8];   // scores in the base-2 exponent domain: scale2 = log2(e) / sqrt(head_dim)
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      v[i] = sa[i] * scale;
-      v[4 + i] = sb[i] * scale;
+      v[i] = sa[i] * scale2;
+      v[4 + i] = sb[i] * scale2;
     }
     if (!all_vis) {
 #pragma unroll
@@ -261,15 +268,25 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
     float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    // Lazy reference maximum: m_run only moves when the true maximum has grown by more than 8 (a factor 256),
+    // so the accumulators (which live in the MFMA accumulation registers, out of reach of plain ALU ops) are
+    // rescaled once or twice per sweep instead of after every pair.  exp2(v - m_run) <= 256 meanwhile.
     const float m_old = m_run[rb];
-    const float m_new = fmaxf(m_old, mx);
-    const float mb = (m_new == -INFINITY) ? 0.f : m_new;
-    const float corr = (m_old == -INFINITY) ? (m_new == -INFINITY ? 1.f : 0.f) : __expf(m_old - m_new);
+    const bool grow = mx > m_old + 8.f;
+    if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+      const float corr = grow ? (m_old == -INFINITY ? 0.f : exp2f(m_old - mx)) : 1.f;
+      l_run[rb] *= corr;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) {
+        acc[rb][dt][0] *= corr; acc[rb][dt][1] *= corr; acc[rb][dt][2] *= corr; acc[rb][dt][3] *= corr;
+      }
+      if (grow) m_run[rb] = mx;
+    }
+    const float mb = (m_run[rb] == -INFINITY) ? 0.f : m_run[rb];   // nothing visible yet: exp2(-inf - 0) = 0
     float pe[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) pe[i] = __expf(v[i] - mb);
-    l_run[rb] = l_run[rb] * corr + (((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7])));
-    m_run[rb] = m_new;
+    for (int i = 0; i < 8; ++i) pe[i] = __builtin_amdgcn_exp2f(v[i] - mb);
+    l_run[rb] += ((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7]));
     u32x4 ph, pl;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
@@ -277,15 +294,10 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
       ph[i] = h;
       pl[i] = pack_bf16_pair(pe[2 * i] - __uint_as_float(h << 16), pe[2 * i + 1] - __uint_as_float(h & 0xFFFF0000u));
     }
-    // the running maximum rarely moves after the first pairs: skip the rescale when no lane needs it
-    const bool rescale = __any(corr != 1.f);
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt) {
-      f32x4 a = acc[rb][dt];
-      if (rescale) { a[0] *= corr; a[1] *= corr; a[2] *= corr; a[3] *= corr; }
-      a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, ph), a, 0, 0, 0);
-      a = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, pl), a, 0, 0, 0);
-      acc[rb][dt] = a;
+      acc[rb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, ph), acc[rb][dt], 0, 0, 0);
+      acc[rb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, pl), acc[rb][dt], 0, 0, 0);
     }
   }
 }
@@ -299,8 +311,9 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
   __shared__ __attribute__((aligned(16))) float s_raw[4 * 64 * LD];   // query fragments during the sweep, outputs in the merge
   float (*s_o)[64][LD] = reinterpret_cast<float (*)[64][LD]>(s_raw);
   u32x4* q_lds = reinterpret_cast<u32x4*>(s_raw);                      // [rb][kt][lane]
+  int32_t* s_pages = reinterpret_cast<int32_t*>(s_raw) + RB * KT * 64 * 4;   // page ids of this chunk (behind the queries)
   const int split = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int B = geo.block_size;
   const int group = aa.n_q_heads / aa.n_kv_heads;
@@ -334,6 +347,11 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
       for (int kt = 0; kt < KT; ++kt) q_lds[(rb * KT + kt) * 64 + lane] = valid ? qp[kt * 4 + g] : (u32x4){0u, 0u, 0u, 0u};
     }
   }
+  // the chunk's slice of the page table: the sweep then never waits on a dependent table load from memory
+  {
+    const int first = L.c0 >> 4, count = L.c1 > L.c0 ? ((L.c1 - L.c0 + 15) >> 4) : 0;
+    for (int i = threadIdx.x; i < count; i += 256) s_pages[i] = L.table[first + i];
+  }
   __syncthreads();
 
   float m_run[RB], l_run[RB];
@@ -347,15 +365,23 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
   }
 
   const int n_pairs = L.c1 > L.c0 ? (L.c1 - L.c0 + 31) >> 5 : 0;
+  const float scale2 = aa.scale * 1.44269504088896341f;   // scores and running maxima in the base-2 exponent domain
+  auto load = [&](KvFrags<HD>& f, int p) {
+    const bool has_b = L.c0 + p * 32 + 16 < L.c1;
+    // the same for every lane: tell the compiler, so addresses and validity branches stay scalar
+    const int pa = __builtin_amdgcn_readfirstlane(s_pages[2 * p]);
+    const int pb = has_b ? __builtin_amdgcn_readfirstlane(s_pages[2 * p + 1]) : pa;
+    attn_load_pages<HD>(f, pa, pb, has_b, pool, geo, aa, L);
+  };
   if (wave < n_pairs) {
     KvFrags<HD> f0, f1;
-    attn_load_pair<HD>(f0, wave, pool, geo, aa, L);
+    load(f0, wave);
     for (int p = wave; p < n_pairs; p += 8) {
-      if (p + 4 < n_pairs) attn_load_pair<HD>(f1, p + 4, pool, geo, aa, L);
-      attn_process_pair_wide<HD, RB>(f0, L.c0 + p * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, aa.scale, L);
+      if (p + 4 < n_pairs) load(f1, p + 4);
+      attn_process_pair_wide<HD, RB>(f0, L.c0 + p * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, scale2, L);
       if (p + 4 < n_pairs) {
-        if (p + 8 < n_pairs) attn_load_pair<HD>(f0, p + 8, pool, geo, aa, L);
-        attn_process_pair_wide<HD, RB>(f1, L.c0 + (p + 4) * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, aa.scale, L);
+        if (p + 8 < n_pairs) load(f0, p + 8);
+        attn_process_pair_wide<HD, RB>(f1, L.c0 + (p + 4) * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, scale2, L);
       }
     }
   }
@@ -375,7 +401,7 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
     float m_all = -INFINITY;
 #pragma unroll
     for (int w = 0; w < 4; ++w) m_all = fmaxf(m_all, s_ml[w][r].x);
-    const float mine = (m_run[rb] == -INFINITY) ? 0.f : __expf(m_run[rb] - m_all);   // m_all is finite whenever m_run is
+    const float mine = (m_run[rb] == -INFINITY) ? 0.f : exp2f(m_run[rb] - m_all);   // m_all is finite whenever m_run is
 #pragma unroll
     for (int dt = 0; dt < DT; ++dt)
       *reinterpret_cast<float4*>(&s_o[wave][r][dt * 16 + 4 * g]) =
@@ -402,9 +428,9 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
 #pragma unroll
       for (int w = 0; w < 4; ++w) {
         const float2 ml = s_ml[w][r];
-        l += (ml.x == -INFINITY) ? 0.f : ml.y * __expf(ml.x - m_all);
+        l += (ml.x == -INFINITY) ? 0.f : ml.y * exp2f(ml.x - m_all);
       }
-      part_ml[pr] = make_float2(m_all, l);
+      part_ml[pr] = make_float2(m_all * 0.69314718055994531f, l);   // the cross-split merge works with natural exponents
     }
   }
 }
@@ -421,7 +447,8 @@ inline bool attn_mfma_launch<bf16_t>(hipStream_t st, const bf16_t* q, const bf16
   const int rows = geo.block_size * (aa.n_q_heads / aa.n_kv_heads);
   if (rows > 64 || (aa.head_dim != 128 && aa.head_dim != 64)) return false;
   const dim3 grid(aa.n_splits, aa.n_kv_heads, S), block(256);
-  if (aa.head_dim == 128 && aa.chunk >= wide_min_chunk)   // long chunks: wavefronts split the keys
+  // long chunks: wavefronts split the keys (the chunk's page ids must fit the kernel's LDS slice)
+  if (aa.head_dim == 128 && aa.chunk >= wide_min_chunk && aa.chunk / DF_PAGE + 2 <= 29000)
     hipLaunchKernelGGL(attn_mfma_wide_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
   else if (aa.head_dim == 128)
     hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);

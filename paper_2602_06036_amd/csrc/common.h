@@ -8,6 +8,9 @@ typedef __bf16 bf16x8 __attribute__((ext_vector_type(8)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 
+// Wavefront index inside a workgroup: kernels compute it as readfirstlane(threadIdx.x >> 6) so that the compiler
+// knows it is the same for all 64 lanes; loop bounds, slot numbers and base addresses derived from it then stay
+// in scalar registers and the branches on them are plain scalar branches.
 #define DF_WAVE 64
 #define DF_PAGE 16
 

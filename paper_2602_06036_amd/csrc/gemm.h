@@ -39,7 +39,7 @@ struct GemmBuf {
 template <int NT, int MT, int U, int EPI>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
                                                         int M, int N, int K, EpiArgs ep) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int nt0 = blockIdx.x * NT, mt0 = blockIdx.y * MT, kz = blockIdx.z;
   const int KT = K >> 5, n_tiles = N >> 4;
   const int m_tiles = (M + 15) >> 4;
@@ -158,7 +158,7 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 template <int EPI>
 __global__ __launch_bounds__(256) void gemm_f32_kernel(const float* __restrict__ W, const float* __restrict__ A, int M,
                                                        int N, int K, EpiArgs ep) {
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int col = blockIdx.x * 4 + wave;
   const int n_cols = (EPI == EPI_SWIGLU) ? N / 2 : N;
   if (col >= n_cols) return;

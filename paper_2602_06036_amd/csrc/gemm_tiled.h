@@ -29,7 +29,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
   static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % 4 == 0, "tile shape");
   __shared__ u32x4 stage[2][FR][64];
 
-  const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, wy = wave >> 1, wx = wave & 1;
+  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wy = wave >> 1, wx = wave & 1;
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
   const int nb = (j / m_blocks) * 8 + xcd, mb = j % m_blocks;
   if (nb >= n_blocks) return;                      // whole workgroup leaves before any barrier
