@@ -224,6 +224,7 @@ struct dflash_ctx {
   char* wsp;
   char err[512];
   int attn_wide_min_chunk = 512;   // keys per workgroup from which the key-split attention kernel is used (tuning knob)
+  int ks_force = 0;     // tiled GEMM: forces the K split where a split is allowed (tuning knob)
   int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
@@ -467,14 +468,14 @@ void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N,
   }
 }
 
-template <int WN, int WM>
+template <int WN, int WM, int PD>
 void launch_tiled(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
   const int n_blocks = (N / 16 + 2 * WN - 1) / (2 * WN), m_blocks = ((M + 15) / 16 + 2 * WM - 1) / (2 * WM);
   const dim3 grid(((n_blocks + 7) / 8) * 8 * m_blocks, ks), block(256);
   if (epi == EPI_SWIGLU)
-    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
   else
-    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
 }
 
 inline int gemm_class(int epi, int N, int vocab) { return (epi == EPI_STORE && N == vocab) ? DFLASH_PROF_GEMM_LMHEAD : epi; }
@@ -549,6 +550,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
       const int wgs = ((nt + 2 * cd.wn - 1) / (2 * cd.wn)) * mb;
       for (int k = 1; k <= kMaxKSplit; k *= 2) {
         if (k > 1 && (!split || KT / k < 8 || k * M > arena)) break;
+        if (c->ks_force && split && k != c->ks_force && c->ks_force * M <= arena && KT / c->ks_force >= 8) continue;
         const int per_cu = (wgs * k + 255) / 256;
         const double mfma_us = 32.0 * cd.wn * 4 * ((KT + k - 1) / k) / 2400.0;   // MFMA issue time of one workgroup
         const double slab_us = k > 1 ? (double)k * M * N * 8 / 4e6 : 0.0;
@@ -557,9 +559,12 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
       }
     }
     ep.slab = (size_t)M * ep.ld;
-    if (best_wn == 8) launch_tiled<8, 4>(st, W, A, M, N, K, kepi, ep, ks);
-    else if (best_wn == 6) launch_tiled<6, 4>(st, W, A, M, N, K, kepi, ep, ks);
-    else launch_tiled<4, 4>(st, W, A, M, N, K, kepi, ep, ks);
+    static const int PD = env_int("DFLASH_GEMM_PD", 2);   // tuning knob: k tiles in flight from global memory (192/128-row tiles)
+    if (best_wn == 8) launch_tiled<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);   // no registers left for a second set
+    else if (best_wn == 6 && PD == 2) launch_tiled<6, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
+    else if (best_wn == 6) launch_tiled<6, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
+    else if (PD == 2) launch_tiled<4, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
+    else launch_tiled<4, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
   } else {
     const int my = ((M + 15) / 16 + 3) / 4;
     if (nt % 2 == 0) {
@@ -785,6 +790,7 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->tblob = (const char*)target_blob; c->dblob = (const char*)draft_blob; c->wsp = (char*)rt->workspace;
   c->err[0] = 0;
   c->tile_force = env_int("DFLASH_GEMM_TILE", 0);
+  c->ks_force = env_int("DFLASH_GEMM_KS", 0);
   c->attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {
     delete c;

@@ -3,7 +3,7 @@
 //
 // A workgroup of 4 wavefronts (2 along N x 2 along M) owns a tile of 2*WN weight row bands x 2*WM activation
 // row bands for one K range (grid.y).  Both operands already sit in HBM in MFMA fragment order (1 KB per
-// 16x32 fragment), so a k tile is staged by copying whole fragments: global -> registers (one k tile ahead)
+// 16x32 fragment), so a k tile is staged by copying whole fragments: global -> registers (PD k tiles in flight)
 // -> one of two LDS slots; every wavefront reads the WN weight and 2*WM activation fragments of its quadrant
 // (each lane its own 16 bytes: conflict-free ds_read_b128) and issues WN*WM*2 MFMAs per k tile.
 //
@@ -20,13 +20,13 @@
 #pragma once
 #include "gemm.h"
 
-template <int WN, int WM, int EPI>
+template <int WN, int WM, int PD, int EPI>
 __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W,
                                                                                 const bf16_t* __restrict__ A, int M, int N, int K,
                                                                                 int n_blocks, int m_blocks, EpiArgs ep) {
   constexpr int BNT = 2 * WN, BMT = 2 * WM;        // fragments of a stage: BNT weight + 2*BMT activation (hi, lo)
   constexpr int FR = BNT + 2 * BMT, PER = FR / 4;  // fragments copied by each wavefront
-  static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % 4 == 0, "tile shape");
+  static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % 4 == 0 && (PD == 1 || PD == 2), "tile shape");
   __shared__ u32x4 stage[2][FR][64];
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wy = wave >> 1, wx = wave & 1;
@@ -73,12 +73,13 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
     for (int jj = 0; jj < WM; ++jj) acc[i][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   if (kb < ke) {
-    u32x4 g[PER];
-    load_global(g, kb);
-    write_lds(0, g);
-    load_global(g, min(kb + 1, ke - 1));
-    write_lds(1, g);
-    load_global(g, min(kb + 2, ke - 1));
+    u32x4 g[PD][PER];   // k tiles t+2 .. t+1+PD on their way from global memory while k tile t is multiplied
+    load_global(g[0], kb);
+    write_lds(0, g[0]);
+    load_global(g[0], min(kb + 1, ke - 1));
+    write_lds(1, g[0]);
+#pragma unroll
+    for (int d = 0; d < PD; ++d) load_global(g[d], min(kb + 2 + d, ke - 1));
     __syncthreads();
 
     u32x4 wf[WN];      // weight fragments of the current k tile
@@ -88,10 +89,11 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
     ap[0][0] = stage[0][BNT + 2 * wx * WM][lane];
     ap[0][1] = stage[0][BNT + 2 * wx * WM + 1][lane];
 
-    // Straight-line body: past the end of the K range the prefetches read a stale slot, the refill rewrites a
-    // slot nobody reads any more and the global loads repeat the last k tile, so no branch splits the MFMA stream.
-    for (int kt = kb; kt < ke; ++kt) {
-      const int s0 = (kt - kb) & 1, s1 = s0 ^ 1;
+    // One k tile out of LDS slot S0, refilled afterwards from register set G.  Straight-line body: past the end
+    // of the K range the prefetches read a stale slot, the refill rewrites a slot nobody reads any more and the
+    // global loads repeat the last k tile, so no branch splits the MFMA stream.
+    auto k_tile = [&](auto s0_c, auto g_c, int kt) {
+      constexpr int s0 = decltype(s0_c)::value, s1 = s0 ^ 1, G = decltype(g_c)::value;
 #pragma unroll
       for (int jj = 0; jj < WM; ++jj) {
         constexpr int last = WM - 1;
@@ -110,9 +112,18 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
           if (jj == last) wf[i] = stage[s1][wy * WN + i][lane];
         }
       }
-      write_lds(s0, g);
-      load_global(g, min(kt + 3, ke - 1));
+      write_lds(s0, g[G]);
+      load_global(g[G], min(kt + 2 + PD, ke - 1));
+    };
+    using I0 = std::integral_constant<int, 0>;
+    using I1 = std::integral_constant<int, 1>;
+    using IG = std::integral_constant<int, PD - 1>;
+    int kt = kb;
+    for (; kt + 1 < ke; kt += 2) {
+      k_tile(I0{}, I0{}, kt);
+      k_tile(I1{}, IG{}, kt + 1);
     }
+    if (kt < ke) k_tile(I0{}, I0{}, kt);
   }
 
   // lane l holds y[m = band*16 + l%16][n = tile*16 + 4*(l/16) .. +3]
