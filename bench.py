@@ -31,7 +31,7 @@ WORKLOADS = {
 }
 
 
-def build_engine(w, S, ctx, steps_total, dev):
+def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
     """Random-init weights generated on the device tensor by tensor, packed, canonical copy freed."""
     import torch
     import paper_2602_06036_amd as dfl
@@ -72,8 +72,11 @@ def build_engine(w, S, ctx, steps_total, dev):
         chunk = 1 << 26
         for i in range(0, v.numel(), chunk):
             v[i:i + chunk].normal_(generator=gen)
-    # shuffled (non-contiguous) page assignment
-    perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(w.seed)).to(torch.int32)
+    # shuffled (non-contiguous) page assignment unless asked otherwise
+    if page_order == "contiguous":
+        perm = torch.arange(n_pages, dtype=torch.int32)
+    else:
+        perm = torch.randperm(n_pages, generator=torch.Generator().manual_seed(w.seed)).to(torch.int32)
     table = perm.view(S, pps).contiguous().to(dev)
     torch.cuda.synchronize(dev)
     return e, table, max_len
@@ -140,6 +143,8 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_8b_b1_ctx2048", choices=sorted(WORKLOADS))
+    ap.add_argument("--page-order", default="shuffled", choices=["shuffled", "contiguous"],
+                    help="how cache pages are assigned to sequences (shuffled = scattered 16-token pages, the harder case)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -164,7 +169,7 @@ def main():
     Bk = w.block_size
     K, Wm = args.steps, args.warmup
     passes = 1 if args.no_profile else 2
-    e, table, max_len = build_engine(w, S, ctx, Wm + passes * K, dev)
+    e, table, max_len = build_engine(w, S, ctx, Wm + passes * K, dev, args.page_order)
 
     seq_lens = torch.full((S,), ctx, dtype=torch.int32, device=dev)
     anchor = torch.full((S,), 11, dtype=torch.int32, device=dev)

@@ -178,16 +178,25 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   for (int dt = 0; dt < DT; ++dt) acc[dt] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const int n_pairs = L.c1 > L.c0 ? (L.c1 - L.c0 + 31) >> 5 : 0;
+  // Two fragment sets, one multiplied while the other is on its way.  Inside the loop no load is conditional (a
+  // load skipped on some path would force every wait to drain all loads in flight); the last one or two pairs
+  // are peeled off.
   if (n_pairs > 0) {
     KvFrags<HD> f0, f1;
     attn_load_pair<HD>(f0, 0, pool, geo, aa, L);
-    for (int p = 0; p < n_pairs; p += 2) {
-      if (p + 1 < n_pairs) attn_load_pair<HD>(f1, p + 1, pool, geo, aa, L);
+    int p = 0;
+    for (; p + 2 < n_pairs; p += 2) {
+      attn_load_pair<HD>(f1, p + 1, pool, geo, aa, L);
       attn_process_pair<HD>(f0, p, qf, acc, m_run, l_run, aa.scale, L);
-      if (p + 1 < n_pairs) {
-        if (p + 2 < n_pairs) attn_load_pair<HD>(f0, p + 2, pool, geo, aa, L);
-        attn_process_pair<HD>(f1, p + 1, qf, acc, m_run, l_run, aa.scale, L);
-      }
+      attn_load_pair<HD>(f0, p + 2, pool, geo, aa, L);
+      attn_process_pair<HD>(f1, p + 1, qf, acc, m_run, l_run, aa.scale, L);
+    }
+    if (p + 1 < n_pairs) {
+      attn_load_pair<HD>(f1, p + 1, pool, geo, aa, L);
+      attn_process_pair<HD>(f0, p, qf, acc, m_run, l_run, aa.scale, L);
+      attn_process_pair<HD>(f1, p + 1, qf, acc, m_run, l_run, aa.scale, L);
+    } else {
+      attn_process_pair<HD>(f0, p, qf, acc, m_run, l_run, aa.scale, L);
     }
   }
 
@@ -373,16 +382,26 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
     const int pb = has_b ? __builtin_amdgcn_readfirstlane(s_pages[2 * p + 1]) : pa;
     attn_load_pages<HD>(f, pa, pb, has_b, pool, geo, aa, L);
   };
+  // Two fragment sets per wavefront; no conditional load inside the loop (see the kernel above), tail peeled off.
   if (wave < n_pairs) {
     KvFrags<HD> f0, f1;
+    auto process = [&](KvFrags<HD>& f, int p) {
+      attn_process_pair_wide<HD, RB>(f, L.c0 + p * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, scale2, L);
+    };
     load(f0, wave);
-    for (int p = wave; p < n_pairs; p += 8) {
-      if (p + 4 < n_pairs) load(f1, p + 4);
-      attn_process_pair_wide<HD, RB>(f0, L.c0 + p * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, scale2, L);
-      if (p + 4 < n_pairs) {
-        if (p + 8 < n_pairs) load(f0, p + 8);
-        attn_process_pair_wide<HD, RB>(f1, L.c0 + (p + 4) * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, scale2, L);
-      }
+    int p = wave;
+    for (; p + 8 < n_pairs; p += 8) {
+      load(f1, p + 4);
+      process(f0, p);
+      load(f0, p + 8);
+      process(f1, p + 4);
+    }
+    if (p + 4 < n_pairs) {
+      load(f1, p + 4);
+      process(f0, p);
+      process(f1, p + 4);
+    } else {
+      process(f0, p);
     }
   }
 

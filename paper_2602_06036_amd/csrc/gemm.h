@@ -91,18 +91,24 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
         }
   };
 
+  // Two register buffers, one being multiplied while the other is on its way.  No load inside the loop is
+  // conditional: a load that is skipped on some path would make the number of loads in flight unknown at compile
+  // time, and the wait for the older buffer would then have to drain the newer one as well.  The last one or two
+  // stages are peeled off; if the range has an odd number of stages the final load re-reads the last tile
+  // (still in cache) and meets zeroed activations.
   if (kb < ke) {
     GemmBuf<NT, MT, U> b0, b1;
     load(b0, kb);
-    for (int k0 = kb; k0 < ke; k0 += 2 * U) {
-      const bool more = k0 + U < ke;
-      if (more) load(b1, k0 + U);
+    int k0 = kb;
+    for (; k0 + 2 * U < ke; k0 += 2 * U) {
+      load(b1, k0 + U);
       compute(b0);
-      if (more) {
-        if (k0 + 2 * U < ke) load(b0, k0 + 2 * U);
-        compute(b1);
-      }
+      load(b0, k0 + 2 * U);
+      compute(b1);
     }
+    load(b1, k0 + U);
+    compute(b0);
+    compute(b1);
   }
 
   __shared__ float4 red[4][NT * MT][64];
