@@ -28,6 +28,8 @@ WORKLOADS = {
     "cfg4_8b_b4_ctx16k": (4, 4, 16384),
     "cfg5_8b_b32_ctx8k": (5, 32, 8192),
     "tiny_f32": (1, 1, 128),
+    # block-size variant: LLaMA-3.1-8B shape, B = 10 (synth.inputs.llama31_8b_workload)
+    "llama31_8b_b1_ctx2048_B10": ("llama31", 1, 2048),
 }
 
 
@@ -165,7 +167,7 @@ def main():
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
     idx, S, ctx = WORKLOADS[args.workload]
-    w = si.workload(idx)
+    w = si.llama31_8b_workload(S, ctx) if idx == "llama31" else si.workload(idx)
     Bk = w.block_size
     K, Wm = args.steps, args.warmup
     passes = 1 if args.no_profile else 2

@@ -117,6 +117,14 @@ def workload(idx: int) -> Workload:
     raise ValueError(idx)
 
 
+def llama31_8b_workload(n_seqs: int = 1, ctx: int = 2048) -> Workload:
+    """The second target shape of Section 5 ('Implementation', Table 5): LLaMA-3.1-8B (32 layers, FFN 14336,
+    vocabulary 128256, rope base 5e5, no q/k norm) with a 5-layer drafter and block size 10."""
+    t = ModelDims(32, 4096, 32, 8, 128, 14336, 128256, 5e5, 1e-5, False)
+    d = replace(t, n_layers=5)
+    return Workload("llama31_8b_b10", "bf16", t, d, tap_layers_for(32, 5), t.vocab - 1, 10, n_seqs, ctx, ctx, 0.0, 6)
+
+
 def small_bf16_workload(n_seqs: int = 3, ctx_min: int = 20, ctx_max: int = 150, seed: int = 11,
                         block_size: int = 16, temperature: float = 0.0) -> Workload:
     """A scaled-down bf16 model with the 8B model's structure (GQA 4:1, head_dim 128, QK-norm,

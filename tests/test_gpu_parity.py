@@ -239,6 +239,26 @@ def test_small_bf16_many_rows_tiled_gemm(tile, monkeypatch):
     assert ls.stats["reseeds"] <= 1
 
 
+@pytest.mark.parametrize("block", [8, 10])
+def test_small_bf16_other_block_sizes(block):
+    """Block sizes other than 16 (Section 5, Implementation: B = 10 for the LLaMA-3.1 drafter; the block-size ablation of Section 5.5 uses B = 8):
+    30 or 24 activation rows per step (not a multiple of the 16-row MFMA band), 40 or 32 query rows per kv head,
+    blocks that straddle page boundaries at every offset."""
+    w = si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=150, seed=31, block_size=block)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=150 + 8 * block)
+    ls.prefill()
+    ls.check_cache([0, 7], [0, 1])
+    k = block - 1
+    plans = [None, [k, 0, 5], [3, k, k], None, [k, k, k]]
+    for i, plan in enumerate(plans):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([0, 7], [0, 1])
+    print(f"small bf16 (B={block}) stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
 def test_small_bf16_key_split_attention(monkeypatch):
     """The attention kernel for long chunks (wavefronts split the keys of a chunk, merged through LDS) forced on
     at small context lengths: chunks of 1 to 5 page pairs, so some wavefronts get no keys at all, the ragged
