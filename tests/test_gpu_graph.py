@@ -1,0 +1,109 @@
+"""The whole speculative step (draft -> verify -> accept -> commit) captured once into a HIP graph and replayed:
+every call only enqueues kernels and device-to-device copies on the caller's stream, reads nothing back and
+allocates nothing, and the per-sequence state (lengths, anchors, caches) lives on the device, so one captured
+step replayed N times is N decoding steps.  Each replay is checked bit for bit against the same step run
+eagerly from the same state, with eager work and synchronisations between the replays."""
+from dataclasses import replace
+
+import numpy as np
+import pytest
+
+from synth import inputs as si
+from tests.helpers import tiny_workload
+
+pytestmark = pytest.mark.gpu
+
+N_STEPS = 5
+
+
+def _snapshot(g):
+    return dict(target=g.e.target_pool.clone(), draft=g.e.draft_pool.clone(), lens=g.seq_lens.clone(), anchor=g.anchor.clone(),
+                host_lens=g.host_lens.copy())
+
+
+def _restore(g, snap):
+    g.e.target_pool.copy_(snap["target"])
+    g.e.draft_pool.copy_(snap["draft"])
+    g.seq_lens.copy_(snap["lens"])
+    g.anchor.copy_(snap["anchor"])
+    g.host_lens = snap["host_lens"].copy()
+
+
+def _outputs(g):
+    import torch
+    torch.cuda.synchronize(g.dev)
+    return dict(draft=g.draft_tokens.cpu().numpy().copy(), tgt=g.tgt_argmax.cpu().numpy().copy(),
+                accept=g.accept_len.cpu().numpy().copy(), out=g.out_tokens.cpu().numpy().copy(),
+                slots=g.kv_slots.cpu().numpy().copy(), lens=g.seq_lens.cpu().numpy().copy(),
+                anchor=g.anchor.cpu().numpy().copy(), logits=g.logits_t.cpu().numpy().copy())
+
+
+def _enqueue_step(g, batch, temperature, rng, uniforms):
+    import paper_2602_06036_amd as dfl
+    dfl.dflash_draft_block(g.e, batch, g.draft_tokens, temperature, rng, g.logits_d)
+    dfl.dflash_verify(g.e, batch, g.draft_tokens, g.tgt_argmax, g.logits_t)
+    dfl.dflash_accept(g.e, batch, g.draft_tokens, g.tgt_argmax, g.accept_len, g.out_tokens, temperature, uniforms, rng)
+    dfl.dflash_kv_commit(g.e, batch, g.accept_len, g.out_tokens, g.kv_slots)
+
+
+def _run(w, prompts, temperature):
+    import torch
+    from tests.gpu_harness import GpuModel
+    wt, wd = si.make_weights(w, 8)
+    Bk = w.block_size
+    max_len = max(len(p) for p in prompts) + (N_STEPS + 1) * Bk
+    g = GpuModel(w, wt, wd, max_len, n_seqs=len(prompts))
+    g.prefill(prompts)
+    snap = _snapshot(g)
+    rng = torch.tensor([77], dtype=torch.int64, device=g.dev) if temperature > 0 else None
+    uniforms = torch.from_numpy(si.make_uniforms(replace(w, n_seqs=len(prompts)), 0).astype(np.float32)).to(g.dev) \
+        if temperature > 0 else None
+    # the launch shapes (attention splits) are planned on the host from an upper bound of the lengths: give the
+    # bound that holds for every replayed step
+    bound = int(g.host_lens.max()) + N_STEPS * Bk
+    batch = g.e.batch(g.seq_lens, g.block_table, g.anchor, bound)
+
+    eager = []
+    for _ in range(N_STEPS):
+        _enqueue_step(g, batch, temperature, rng, uniforms)
+        eager.append(_outputs(g))
+    g.e.device_status()
+
+    _restore(g, snap)
+    torch.cuda.synchronize(g.dev)
+    graph = torch.cuda.CUDAGraph()
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        _enqueue_step(g, batch, temperature, rng, uniforms)      # warm-up on the capture stream, then undo it
+    torch.cuda.synchronize(g.dev)
+    _restore(g, snap)
+    torch.cuda.synchronize(g.dev)
+    with torch.cuda.graph(graph, stream=side):
+        _enqueue_step(g, batch, temperature, rng, uniforms)
+    torch.cuda.synchronize(g.dev)
+    _restore(g, snap)                                            # capture does not execute, but be explicit
+    for i in range(N_STEPS):
+        graph.replay()
+        got = _outputs(g)
+        for k, v in eager[i].items():
+            assert np.array_equal(got[k], v), f"replay {i}: {k} differs from the eager step"
+        # eager work between replays: a read through the library and a synchronisation
+        g.host_lens = got["lens"].astype(np.int64)
+        g.read_kv(0, 0, 0, 0, int(got["lens"][0]))
+    g.e.device_status()
+    assert (eager[-1]["lens"] > snap["lens"].cpu().numpy()).all()
+    g.e.close()
+
+
+def test_graph_replay_tiny_fp32_greedy():
+    w = tiny_workload(seed=5, n_layers=2, draft_layers=1, vocab=512, block=8, n_seqs=2, taps=(0,))
+    prompts = [p[:n] for p, n in zip(si.make_prompts(replace(w, ctx_min=40, ctx_max=40)), (40, 27))]
+    _run(w, prompts, 0.0)
+
+
+def test_graph_replay_small_bf16_greedy_and_sampling():
+    w = si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=90, seed=13)
+    prompts = si.make_prompts(w)
+    _run(w, prompts, 0.0)
+    _run(replace(w, temperature=1.0), prompts, 1.0)
