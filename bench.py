@@ -147,6 +147,9 @@ def main():
     ap.add_argument("--workload", default="cfg2_8b_b1_ctx2048", choices=sorted(WORKLOADS))
     ap.add_argument("--page-order", default="shuffled", choices=["shuffled", "contiguous"],
                     help="how cache pages are assigned to sequences (shuffled = scattered 16-token pages, the harder case)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph (attention splits planned for the longest length the run "
+                         "reaches) and time K replays instead of K eager steps")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -205,12 +208,23 @@ def main():
         step()
     torch.cuda.synchronize(dev)
     e.device_status()
+    timed_step = step
+    if args.graph:
+        # one captured step; lengths, anchors and caches live on the device, so each replay is the next step
+        state["upper"] = max_len - Bk          # the longest committed length the block table still covers with a block on top
+        graph = torch.cuda.CUDAGraph()
+        side = torch.cuda.Stream()
+        side.wait_stream(torch.cuda.current_stream())
+        with torch.cuda.graph(graph, stream=side):
+            step()
+        torch.cuda.synchronize(dev)
+        timed_step = graph.replay
     len0 = seq_lens.clone()
     ev0, ev1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     torch.cuda.synchronize(dev)
     ev0.record()
     for _ in range(K):
-        step()
+        timed_step()
     ev1.record()
     torch.cuda.synchronize(dev)
     ms_total = ev0.elapsed_time(ev1)
@@ -251,7 +265,8 @@ def main():
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
         "config": {"workload": args.workload, "n_seqs": S, "block_size": Bk, "context": ctx,
-                   "temperature": T, "value_counts": "verified positions (S*B per step)"},
+                   "temperature": T, "value_counts": "verified positions (S*B per step)",
+                   "launch": "hip graph replay" if args.graph else "eager", "page_order": args.page_order},
         "committed_tokens_per_s": committed / (ms_total * 1e-3),
         "mean_tau": committed / (K * S),
         "roofline": roof,
