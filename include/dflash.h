@@ -78,7 +78,8 @@ typedef struct {
 
 /* Per-call batch description. */
 typedef struct {
-  int32_t n_seqs;             /* S */
+  int32_t n_seqs;             /* S in [0, max_seqs]; with S = 0 the four step calls return DFLASH_OK and enqueue nothing
+                                 (the pointers below are then not looked at) */
   int32_t max_seq_len;        /* (host) upper bound on seq_lens[s] over the batch; sizes launch grids only */
   int32_t *seq_lens;          /* (device) [S] committed length n_s; updated by dflash_kv_commit */
   const int32_t *block_table; /* (device) [S, max_pages_per_seq] page ids; pages covering n_s + B tokens must be valid */
@@ -184,7 +185,8 @@ int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count
 
 /* ---- cache import / export (state migration, tests) ------------------------------------------ */
 /* Copies rows [start, start+count) of sequence `seq` of one layer between the paged pool and
- * canonical fp32 buffers k, v (device) [count, Hkv, hd].  K rows are stored post-RoPE. */
+ * canonical fp32 buffers k, v (device) [count, Hkv, hd].  K rows are stored post-RoPE.
+ * count = 0 is valid (nothing is copied; k and v may then be null). */
 int dflash_kv_read(dflash_ctx *ctx, const dflash_batch *batch, int32_t pool, int32_t layer, int32_t seq,
                    int32_t start, int32_t count, float *k, float *v, void *stream);
 int dflash_kv_write(dflash_ctx *ctx, const dflash_batch *batch, int32_t pool, int32_t layer, int32_t seq,

@@ -684,8 +684,10 @@ int run_kv_copy(dflash_ctx* ctx, const dflash_batch* b, int pool, int layer, int
 
 int check_batch(dflash_ctx* ctx, const dflash_batch* b) {
   if (!ctx) return fail(nullptr, DFLASH_EINVAL, "ctx: null");
-  if (!b || !b->seq_lens || !b->block_table || !b->anchor) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: null pointer");
-  if (b->n_seqs < 1 || b->n_seqs > ctx->rt.max_seqs) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: n_seqs %d outside [1,%d]", b->n_seqs, ctx->rt.max_seqs);
+  if (!b) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: null pointer");
+  if (b->n_seqs == 0) return DFLASH_OK;   // an empty batch is valid: the step calls enqueue nothing
+  if (!b->seq_lens || !b->block_table || !b->anchor) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: null pointer");
+  if (b->n_seqs < 0 || b->n_seqs > ctx->rt.max_seqs) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: n_seqs %d outside [0,%d]", b->n_seqs, ctx->rt.max_seqs);
   if (b->max_seq_len < 0) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: negative max_seq_len");
   if ((int64_t)b->max_seq_len + ctx->rt.block_size > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE)
     return CTX_FAIL(ctx, DFLASH_ECAPACITY, "batch: max_seq_len %d + block %d exceeds the %d tokens a block-table row covers", b->max_seq_len,
@@ -852,6 +854,7 @@ int dflash_draft_block(dflash_ctx* ctx, const dflash_batch* batch, float tempera
                        float* logits_out, void* stream) {
   int rc;
   if ((rc = check_batch(ctx, batch))) return rc;
+  if (batch->n_seqs == 0) return DFLASH_OK;
   if (!draft_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "draft_block: draft_tokens is null");
   if (!(temperature >= 0.f)) return CTX_FAIL(ctx, DFLASH_EINVAL, "draft_block: negative temperature");
   if (temperature > 0.f && !rng_key) return CTX_FAIL(ctx, DFLASH_EINVAL, "draft_block: sampling needs rng_key");
@@ -861,6 +864,7 @@ int dflash_draft_block(dflash_ctx* ctx, const dflash_batch* batch, float tempera
 int dflash_verify(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* tokens, int32_t* tgt_argmax, float* logits_out, void* stream) {
   int rc;
   if ((rc = check_batch(ctx, batch))) return rc;
+  if (batch->n_seqs == 0) return DFLASH_OK;
   if (!tokens || !tgt_argmax) return CTX_FAIL(ctx, DFLASH_EINVAL, "verify: null tokens or tgt_argmax");
   return DISPATCH(ctx, verify(batch, tokens, tgt_argmax, logits_out));
 }
@@ -869,6 +873,7 @@ int dflash_accept(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* dra
                   const float* uniforms, const uint64_t* rng_key, int32_t* accept_len, int32_t* out_tokens, void* stream) {
   int rc;
   if ((rc = check_batch(ctx, batch))) return rc;
+  if (batch->n_seqs == 0) return DFLASH_OK;
   if (!draft_tokens || !tgt_argmax || !accept_len || !out_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: null pointer");
   if (!(temperature >= 0.f)) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: negative temperature");
   if (temperature > 0.f && (!uniforms || !rng_key)) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: sampling needs uniforms and rng_key");
@@ -879,6 +884,7 @@ int dflash_kv_commit(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* 
                      void* stream) {
   int rc;
   if ((rc = check_batch(ctx, batch))) return rc;
+  if (batch->n_seqs == 0) return DFLASH_OK;
   if (!accept_len || !out_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "kv_commit: null pointer");
   return DISPATCH(ctx, commit(batch, accept_len, out_tokens, kv_slots_out));
 }
@@ -889,7 +895,7 @@ static int kv_copy_checked(dflash_ctx* ctx, const dflash_batch* batch, int32_t p
   if ((rc = check_batch(ctx, batch))) return rc;
   if (pool != DFLASH_POOL_TARGET && pool != DFLASH_POOL_DRAFT) return CTX_FAIL(ctx, DFLASH_EINVAL, "kv copy: bad pool");
   const dflash_dims& m = pool == DFLASH_POOL_TARGET ? ctx->t : ctx->d;
-  if (layer < 0 || layer >= m.n_layers || seq < 0 || seq >= batch->n_seqs || start < 0 || count < 0 || !k || !v)
+  if (layer < 0 || layer >= m.n_layers || seq < 0 || seq >= batch->n_seqs || start < 0 || count < 0 || (count > 0 && (!k || !v)))
     return CTX_FAIL(ctx, DFLASH_EINVAL, "kv copy: bad layer, seq, range or pointer");
   if ((int64_t)start + count > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE) return CTX_FAIL(ctx, DFLASH_ECAPACITY, "kv copy: range beyond the block table");
   if (count == 0) return DFLASH_OK;

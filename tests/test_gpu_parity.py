@@ -29,7 +29,7 @@ def _gpu():
 class Lockstep:
     """Runs oracle and GPU side by side."""
 
-    def __init__(self, w, prompts, max_len, n_threads=8):
+    def __init__(self, w, prompts, max_len, n_threads=8, max_seqs=None):
         GpuModel = _gpu()
         self.w = w
         self.wt, self.wd = si.make_weights(w, n_threads)
@@ -38,7 +38,7 @@ class Lockstep:
         self.tol = TOL[w.dtype]
         self.prompts = prompts
         self.S = len(prompts)
-        self.g = GpuModel(w, self.wt, self.wd, max_len, n_seqs=self.S)
+        self.g = GpuModel(w, self.wt, self.wd, max_len, n_seqs=self.S, max_seqs=max_seqs)
         self.states = [O.SeqState(w.target, w.draft, max_len + 1) for _ in prompts]
         self.stats = dict(rows=0, low_margin_flips=0, reseeds=0, max_err_t=0.0, max_err_d=0.0)
         self.emitted = [[] for _ in prompts]
@@ -292,6 +292,44 @@ def test_temperature1_sampling_matches_oracle_decisions():
         accepts += list(out["accept_len"])
     print("sampling stats", ls.stats, accepts)
     assert ls.stats["reseeds"] <= 1
+
+
+def test_empty_context_exact_fit_partial_and_empty_batch():
+    """Degenerate and limit cases in one run: sequences that start with NO cached context (the draft block then
+    attends to its own rows only, the verify block to nothing before it), a batch smaller than the context's
+    max_seqs, every proposal accepted until the block table is filled to the last token (n_s + B equals its
+    capacity exactly), one more step refused on the host, and an empty batch (S = 0) that must be a no-op."""
+    import paper_2602_06036_amd as dfl
+    from paper_2602_06036_amd import binding as B
+    w = tiny_workload(seed=9, n_layers=2, draft_layers=1, vocab=256, block=8, n_seqs=2, taps=(0,))
+    Bk, cap = 8, 32
+    ls = Lockstep(w, [np.zeros(0, dtype=np.int32)] * 2, max_len=cap, max_seqs=5)
+    for s, st in enumerate(ls.states):         # nothing prefetched: length 0, anchor = some clean token
+        st.n, st.anchor = 0, 17 + s
+    ls.g.load_state(ls.states)
+    for i in range(cap // Bk):                 # 0 -> 8 -> 16 -> 24, the last block ends at token 31 of 32
+        out, res = ls.step(plan=[Bk - 1, Bk - 1], step_idx=i)
+        assert list(out["lens_before"]) == [i * Bk] * 2
+        if not ls.stats["reseeds"]:
+            assert list(out["accept_len"]) == [Bk - 1] * 2
+    assert ls.stats["reseeds"] <= 1
+    g = ls.g
+    with pytest.raises(B.DFlashError) as ei:   # lengths are 32 now: no room for another block
+        g.step()
+    assert ei.value.code == B.DFLASH_ECAPACITY
+    # S = 0: valid, nothing enqueued, nothing touched
+    before = (g.seq_lens.clone(), g.anchor.clone(), g.draft_tokens.clone(), g.accept_len.clone())
+    b0 = g.e.batch(g.seq_lens[:0], g.block_table[:0], g.anchor[:0], 0)
+    dfl.dflash_draft_block(g.e, b0, g.draft_tokens[:0], 0.0, None, None)
+    dfl.dflash_verify(g.e, b0, g.draft_tokens[:0], g.tgt_argmax[:0], None)
+    dfl.dflash_accept(g.e, b0, g.draft_tokens[:0], g.tgt_argmax[:0], g.accept_len[:0], g.out_tokens[:0], 0.0, None, None)
+    dfl.dflash_kv_commit(g.e, b0, g.accept_len[:0], g.out_tokens[:0], None)
+    import torch
+    torch.cuda.synchronize(g.dev)
+    g.e.device_status()
+    for a, b in zip(before, (g.seq_lens, g.anchor, g.draft_tokens, g.accept_len)):
+        assert torch.equal(a, b)
+    print("empty-context / exact-fit stats", ls.stats)
 
 
 def test_device_status_reports_a_sequence_that_outgrew_its_pages():
