@@ -89,6 +89,42 @@ class GpuModel:
         assert np.array_equal(self.seq_lens.cpu().numpy(), self.host_lens)
         return self.anchor.cpu().numpy().copy()
 
+    def prefill_one_pass(self, prompts: Sequence[np.ndarray]) -> np.ndarray:
+        """The same prefill as ONE verify + commit with many rows: every B-token chunk of every prompt becomes a
+        pseudo-sequence whose committed length is the chunk's offset and whose block-table row is its prompt's.
+        Inside a layer all K/V rows are written to the pages before attention runs, so chunk i sees chunks
+        0..i-1 of its prompt exactly as a causal prefill does; the forced commit then projects the taps of all
+        prompt rows into the draft's context cache.  Needs a context created with max_seqs >= number of chunks."""
+        S, Bk = self.S, self.Bk
+        lens = np.array([len(p) for p in prompts])
+        owner, offset, rows = [], [], []
+        for s in range(S):
+            for c in range(int((lens[s] + Bk - 1) // Bk)):
+                owner.append(s); offset.append(c * Bk); rows.append(min(Bk, lens[s] - c * Bk))
+        n = len(owner)
+        toks = np.zeros((n, Bk), dtype=np.int32)
+        for i in range(n):
+            toks[i, : rows[i]] = prompts[owner[i]][offset[i]: offset[i] + rows[i]]
+        dev = self.dev
+        p_lens = torch.from_numpy(np.array(offset, dtype=np.int32)).to(dev)
+        p_table = self.block_table[torch.from_numpy(np.array(owner, dtype=np.int64)).to(dev)].contiguous()
+        p_anchor = torch.zeros(n, dtype=torch.int32, device=dev)
+        tokens = torch.from_numpy(toks).to(dev)
+        argmax = torch.zeros((n, Bk), dtype=torch.int32, device=dev)
+        acc = torch.from_numpy(np.array(rows, dtype=np.int32) - 1).to(dev)
+        b = self.e.batch(p_lens, p_table, p_anchor, int(max(offset)))
+        dfl.dflash_verify(self.e, b, tokens, argmax)
+        dfl.dflash_kv_commit(self.e, b, acc, argmax)
+        torch.cuda.synchronize(dev)
+        self.e.device_status()
+        last = [max(i for i in range(n) if owner[i] == s) for s in range(S)]
+        first_tokens = p_anchor.cpu().numpy()[last].astype(np.int32)
+        assert np.array_equal(p_lens.cpu().numpy()[last], lens)
+        self.host_lens = lens.astype(np.int64)
+        self.seq_lens.copy_(torch.from_numpy(lens.astype(np.int32)).to(dev))
+        self.anchor.copy_(torch.from_numpy(first_tokens).to(dev))
+        return first_tokens.copy()
+
     # ---- one speculative step --------------------------------------------------------------------------
     def step(self, proposals: Optional[np.ndarray] = None, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None,
              key: int = 0, want_logits: bool = True) -> Dict[str, np.ndarray]:

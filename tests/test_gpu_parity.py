@@ -43,11 +43,11 @@ class Lockstep:
         self.stats = dict(rows=0, low_margin_flips=0, reseeds=0, max_err_t=0.0, max_err_d=0.0)
         self.emitted = [[] for _ in prompts]
 
-    def prefill(self):
+    def prefill(self, one_pass=False):
         w = self.w
         first = [O.prefill(self.Wt, self.Wd, w.target, w.draft, w.tap_layers, p, st, self.rnd)
                  for p, st in zip(self.prompts, self.states)]
-        got = self.g.prefill(self.prompts)
+        got = self.g.prefill_one_pass(self.prompts) if one_pass else self.g.prefill(self.prompts)
         for s in range(self.S):
             self.emitted[s].append(first[s])
         mism = [s for s in range(self.S) if got[s] != first[s]]
@@ -256,6 +256,24 @@ def test_small_bf16_other_block_sizes(block):
     ls.check_cache([0, 7], [0, 1])
     print(f"small bf16 (B={block}) stats", ls.stats)
     assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
+def test_prefill_as_one_many_row_pass():
+    """Prefill (Section 4.1) run as a single verify + forced commit over all prompt chunks at once (here 21 chunks,
+    336 rows through the tiled GEMM) instead of chunk after chunk: caches, first tokens and the following
+    speculative steps against the oracle's prefill."""
+    w = si.small_bf16_workload(n_seqs=3, ctx_min=70, ctx_max=150, seed=17)
+    prompts = si.make_prompts(w)
+    n_chunks = sum((len(p) + 15) // 16 for p in prompts)
+    ls = Lockstep(w, prompts, max_len=150 + 4 * 16, max_seqs=n_chunks)
+    first, got, mism = ls.prefill(one_pass=True)
+    assert len(mism) <= 1
+    ls.check_cache([0, 3, 7], [0, 1])
+    for i, plan in enumerate([None, [15, 0, 9]]):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([7], [1])
+    print("one-pass prefill stats", ls.stats, "chunks", n_chunks)
     assert ls.stats["reseeds"] <= 1
 
 
