@@ -19,7 +19,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel (gate/up GEMM at the 8B shape, M = 16) from two rocprofv3 --pmc
 # runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): profiles/cfg2_gateup_gemm_hbm_traffic.md
-MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": 198752 * 1024 + 768 * 1024}
+MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": 198764 * 1024 + 768 * 1024}
 
 WORKLOADS = {
     # name: (synth workload index, n_seqs, context)
