@@ -157,7 +157,7 @@ def main():
                          "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
     args = ap.parse_args()
     if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the step is single-device; see DESIGN.md for how it would shard); "
+        print("bench.py: this build runs on ONE GPU (the step is single-device: sequences are independent, so more GPUs would each take a share of the batch); "
               "use --gpus 1", file=sys.stderr)
         sys.exit(2)
 
