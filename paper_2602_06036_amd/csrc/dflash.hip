@@ -534,7 +534,14 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     // still bandwidth-bound: the same streaming kernel with four activation bands per weight tile
     if (split) ks = pick_ksplit(nt / 8, KT, M, arena);
     ep.slab = (size_t)M * ep.ld;
-    launch_bf16<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
+    static const int U4 = env_int("DFLASH_GEMM_U4", 1);   // tuning knob: k-tiles per prefetch stage for 16 < M <= 64 (2 measured slower)
+    if (M <= 32) {
+      if (U4 >= 2) launch_bf16<8, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      else launch_bf16<8, 2, 1>(st, W, A, M, N, K, kepi, ep, ks);
+    } else {
+      if (U4 >= 2) launch_bf16<8, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      else launch_bf16<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
+    }
   } else if (M > 64 && nt % 2 == 0) {
     // compute-bound: LDS-staged tiles of 256, 192 or 128 weight rows x 128 activation rows.  Pick the shape and
     // K split with the least estimated time: workgroups on the busiest CU x MFMA time of one workgroup (larger
