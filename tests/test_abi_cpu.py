@@ -77,3 +77,43 @@ def test_bad_shapes_are_rejected_with_a_message(B):
     out = C.c_void_p()
     assert l.dflash_create(C.byref(td), None, C.byref(dd), None, C.byref(rt), C.byref(out)) == B.DFLASH_EINVAL
     assert out.value is None
+
+
+def _runtime(B, max_seqs, pages_per_seq, block=16):
+    rt = B.Runtime()
+    rt.block_size, rt.max_seqs, rt.max_pages_per_seq, rt.n_pages, rt.n_taps = block, max_seqs, pages_per_seq, max_seqs * pages_per_seq, 5
+    for i, t in enumerate((1, 9, 17, 25, 33)):
+        rt.tap_layers[i] = t
+    rt.mask_token_id = 151935
+    return rt
+
+
+def test_workspace_grows_monotonically_with_batch_and_context(B):
+    """Host-side sizing: a context created for more sequences or longer block tables never needs less
+    workspace (callers size once for their largest batch), and configuration 5 stays far below the HBM size."""
+    w = si.workload(2)
+    l = B.lib()
+    td, dd = B.make_dims(w.target, "bf16"), B.make_dims(w.draft, "bf16")
+    prev = 0
+    for s in (1, 2, 3, 4, 7, 8, 16, 31, 32, 33, 64):
+        ws = l.dflash_workspace_bytes(C.byref(td), C.byref(dd), C.byref(_runtime(B, s, 160)))
+        assert ws >= prev > -1, (s, ws, prev)
+        prev = ws
+    prev = 0
+    for pages in (1, 2, 8, 64, 129, 512, 1030, 4096, 8192):
+        ws = l.dflash_workspace_bytes(C.byref(td), C.byref(dd), C.byref(_runtime(B, 4, pages)))
+        assert ws >= prev, (pages, ws, prev)
+        prev = ws
+    ws5 = l.dflash_workspace_bytes(C.byref(td), C.byref(dd), C.byref(_runtime(B, 32, 8192 // 16 + 2)))
+    assert 2 * 512 * 151936 * 4 < ws5 < 3 << 30
+
+
+def test_step_calls_reject_null_handles_before_touching_the_device(B):
+    l = B.lib()
+    batch = B.Batch(1, 0, None, None, None)
+    assert l.dflash_draft_block(None, C.byref(batch), C.c_float(0.0), None, None, None, None) == B.DFLASH_EINVAL
+    assert l.dflash_verify(None, C.byref(batch), None, None, None, None) == B.DFLASH_EINVAL
+    assert l.dflash_accept(None, C.byref(batch), None, None, C.c_float(0.0), None, None, None, None, None) == B.DFLASH_EINVAL
+    assert l.dflash_kv_commit(None, C.byref(batch), None, None, None, None) == B.DFLASH_EINVAL
+    assert b"ctx" in l.dflash_last_error(None)
+    assert l.dflash_destroy(None) in (B.DFLASH_OK, B.DFLASH_EINVAL)
