@@ -19,6 +19,7 @@ if ROOT not in sys.path:
 HBM_PEAK_GBS = 8000.0
 # HBM bytes per launch of the dominant kernel (gate/up GEMM at the 8B shape, M = 16) from two rocprofv3 --pmc
 # runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): profiles/cfg2_gateup_gemm_hbm_traffic.md
+MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": 198764 * 1024 + 768 * 1024}
 
 WORKLOADS = {
@@ -27,6 +28,8 @@ WORKLOADS = {
     "cfg3_8b_b16_ctx2560": (3, 16, 2560),
     "cfg4_8b_b4_ctx16k": (4, 4, 16384),
     "cfg5_8b_b32_ctx8k": (5, 32, 8192),
+    # GEMM-dominated supplement to configuration 5: the same batch at a short context
+    "cfg5_8b_b32_ctx512": (5, 32, 512),
     "tiny_f32": (1, 1, 128),
     # block-size variant: LLaMA-3.1-8B shape, B = 10 (synth.inputs.llama31_8b_workload)
     "llama31_8b_b1_ctx2048_B10": ("llama31", 1, 2048),
@@ -252,10 +255,20 @@ def main():
         extra["kernels"] = per
         extra["all_gemm"] = dict(ms_per_step=gemm_ms / K, gbs=gemm_bytes / gemm_ms / 1e6)
         ms, cnt, by = prof[2]        # dominant kernel: gate/up projection with fused SwiGLU
-        ach = (by / cnt) / (ms / cnt) / 1e6
-        roof = dict(bound="hbm", kernel="gemm_bf16_kernel<SWIGLU> (gate/up projection)", achieved=ach, peak=HBM_PEAK_GBS,
-                    unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
-                    bytes_per_launch=by / cnt, avg_launch_us=1e3 * ms / cnt)
+        M_rows = S * Bk
+        if M_rows * 2 > 620:         # above the ridge (2.5 PFLOP/s / 8 TB/s = 310 flop per weight byte = M rows): MFMA-bound
+            # algorithmic flops: 2 * M * N * K = M flops per weight byte (bf16); the hi+lo activation pair doubles the
+            # MFMA instructions that are issued, which is not counted here
+            ach = (by / cnt) * M_rows / (ms / cnt) / 1e9
+            roof = dict(bound="mfma", kernel="gemm_bf16_tiled_kernel<SWIGLU> (gate/up projection)", achieved=ach,
+                        peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                        flops_per_launch=(by / cnt) * M_rows, issued_mfma_flops_per_launch=2 * (by / cnt) * M_rows,
+                        avg_launch_us=1e3 * ms / cnt)
+        else:
+            ach = (by / cnt) / (ms / cnt) / 1e6
+            roof = dict(bound="hbm", kernel="gemm_bf16_kernel<SWIGLU> (gate/up projection)", achieved=ach, peak=HBM_PEAK_GBS,
+                        unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
+                        bytes_per_launch=by / cnt, avg_launch_us=1e3 * ms / cnt)
 
     out = {
         "metric": "draft+verify tokens/sec/GPU (8B-shape, B=16)",
