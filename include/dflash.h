@@ -128,7 +128,10 @@ int dflash_device_status(dflash_ctx *ctx, void *stream);
  * temperature == 0: draft_tokens[s,j] = argmax of slot j's logits (ties -> lowest id);
  * temperature  > 0: a draw from softmax(logits/temperature) by Gumbel-max with the counter-based
  * generator keyed by *rng_key.  draft_tokens (device) [S,B] out, slot 0 = anchor.
- * logits_out (device, nullable) [S,B,V] fp32 receives the draft logits (row j = slot j). */
+ * logits_out (device, nullable) [S,B,V] fp32 receives the draft logits (row j = slot j).
+ * The token choice is fused into the LM-head GEMM (per-workgroup row maxima, combined by a small
+ * second kernel); the [S,B,V] logits are materialised only if logits_out is given or temperature > 0
+ * (dflash_accept then needs the proposal distribution). */
 int dflash_draft_block(dflash_ctx *ctx, const dflash_batch *batch, float temperature,
                        const uint64_t *rng_key /*(device) [1], nullable when temperature == 0*/,
                        int32_t *draft_tokens, float *logits_out, void *stream);
@@ -138,7 +141,8 @@ int dflash_draft_block(dflash_ctx *ctx, const dflash_batch *batch, float tempera
  * Writes the B new K/V rows of every layer into the target pool (speculatively: they become
  * visible only when dflash_kv_commit advances seq_lens) and the tapped hidden states into the
  * workspace.  tgt_argmax (device) [S,B]: greedy token after row j.  logits_out (device, nullable)
- * [S,B,V] fp32. */
+ * [S,B,V] fp32.  The logits are materialised only if logits_out is given or the last
+ * dflash_draft_block call on this context sampled (temperature > 0), i.e. dflash_accept will need them. */
 int dflash_verify(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *tokens /*(device) [S,B]*/,
                   int32_t *tgt_argmax, float *logits_out, void *stream);
 
@@ -148,7 +152,8 @@ int dflash_verify(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *tok
  * temperature  > 0: speculative sampling on the logits the preceding dflash_draft_block and
  * dflash_verify calls left in the workspace: slot j accepted iff u[s,j] * q_j(d_j) < p_{j-1}(d_j);
  * first rejected slot is replaced by a draw from normalise(max(p - q, 0)); all accepted -> bonus
- * draw from the last row.  uniforms (device) [S,B] fp32 in [0,1). */
+ * draw from the last row.  uniforms (device) [S,B] fp32 in [0,1).  DFLASH_EINVAL if this step's
+ * dflash_draft_block did not run with temperature > 0 (the workspace then holds no logits). */
 int dflash_accept(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *draft_tokens,
                   const int32_t *tgt_argmax, float temperature, const float *uniforms /*nullable when greedy*/,
                   const uint64_t *rng_key /*(device) [1], nullable when greedy*/,

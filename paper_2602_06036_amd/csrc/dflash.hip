@@ -188,7 +188,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.part_ml = take(part_rows * 8);
   w.stats_p = take((size_t)M * 8);
   w.stats_q = take((size_t)M * 8);
-  w.amax = take((size_t)M * ARGMAX_CHUNKS * 8);
+  w.amax = take((size_t)M * std::max(ARGMAX_CHUNKS, t.vocab / 16 + 1) * 8);   // one partial per weight row band at most
   w.total = off;
   return w;
 }
@@ -224,6 +224,8 @@ struct dflash_ctx {
   char* wsp;
   char err[512];
   int attn_wide_min_chunk = 512;   // keys per workgroup from which the key-split attention kernel is used (tuning knob)
+  bool have_logits_d = false, have_logits_t = false;   // the workspace holds this step's draft / target logits
+  float draft_temperature = 0.f;                       // of the last dflash_draft_block call
   int ks_force = 0;     // tiled GEMM: forces the K split where a split is allowed (tuning knob)
   int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
@@ -294,6 +296,8 @@ struct Engine {
     size_t stride = 0;
   };
   Slab pending;          // partial sums that the next RMSNorm adds into the residual stream ws.h
+  int amax_parts = 0;    // > 0: the last LM-head GEMM left that many per-row argmax partials in ws.amax (fused epilogue)
+  bool lm_skip_store = false;   // the LM-head GEMM may drop its logits when its argmax is fused (nobody will read them)
   int pending_tap = -1;  // tap index to be taken from the completed residual stream by the next RMSNorm
 
   // ---- GEMM dispatch ------------------------------------------------------------------------------
@@ -316,10 +320,15 @@ struct Engine {
   // row-wise argmax (or Gumbel-perturbed argmax) in two launches: per-chunk winners, then one wavefront per row
   void argmax(const float* logits, int V, int M, int B, int32_t* out, int skip_slot0, int mode, float inv_T, const uint64_t* key) {
     float2* part = ws<float2>(c->ws.amax);
-    hipLaunchKernelGGL(argmax_rows_kernel, dim3(ARGMAX_CHUNKS, M), dim3(256), 0, st, logits, V, B, part, mode, inv_T, key);
+    int parts = amax_parts;
+    if (parts == 0) {   // not fused into the LM head (fp32 models): partials from the stored logits
+      parts = ARGMAX_CHUNKS;
+      hipLaunchKernelGGL(argmax_rows_kernel, dim3(ARGMAX_CHUNKS, M), dim3(256), 0, st, logits, V, B, part, mode, inv_T, key);
+      check();
+    }
+    hipLaunchKernelGGL(argmax_finish_kernel, dim3(M), dim3(64), 0, st, part, parts, B, out, skip_slot0);
     check();
-    hipLaunchKernelGGL(argmax_finish_kernel, dim3(M), dim3(64), 0, st, part, ARGMAX_CHUNKS, B, out, skip_slot0);
-    check();
+    amax_parts = 0;
   }
   // RMSNorm of the residual stream, folding in whatever the previous GEMM left pending
   void norm_h(const float* gain, int M, int D, float eps) {
@@ -358,11 +367,22 @@ struct Engine {
     pending = gemm(reinterpret_cast<const T*>(lbase + lo.wd), act, M, D, m.d_ffn, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
   }
 
-  void lm_head(const float* final_gain, float eps, int M, float* logits) {
+  // final norm + LM head with the row argmax fused into the GEMM epilogue where the kernel supports it (then
+  // amax_parts > 0 and, unless want_logits, the [M, V] logits are never written); argmax() finishes the job
+  void lm_head(const float* final_gain, float eps, int M, float* logits, bool want_logits, int B, int mode, float inv_T,
+               const uint64_t* key) {
     const dflash_dims& t = c->t;
     norm_h(final_gain, M, t.d_model, eps);
-    gemm(reinterpret_cast<const T*>(c->tblob + c->tl.lm), ws<T>(c->ws.a), M, t.vocab, t.d_model, EPI_STORE,
-         EpiArgs{logits, t.vocab, 0, nullptr, 0}, false);
+    EpiArgs ep{logits, t.vocab, 0, nullptr, 0};
+    ep.amax = ws<float2>(c->ws.amax);
+    ep.amax_mode = mode;
+    ep.amax_inv_T = inv_T;
+    ep.amax_key = key;
+    ep.amax_B = B;
+    lm_skip_store = !want_logits;
+    amax_parts = 0;
+    gemm(reinterpret_cast<const T*>(c->tblob + c->tl.lm), ws<T>(c->ws.a), M, t.vocab, t.d_model, EPI_STORE, ep, false);
+    lm_skip_store = false;
   }
 
   int draft_block(const dflash_batch* b, float temperature, const uint64_t* rng_key, int32_t* draft_tokens, float* logits_out) {
@@ -376,9 +396,13 @@ struct Engine {
     for (int i = 0; i < d.n_layers; ++i)
       layer(d, c->dblob + c->dl.layer0 + c->dl.lo.end * i, c->dl.lo, reinterpret_cast<T*>(c->rt.draft_kv_pool), i, b, false);
     float* logits = ws<float>(c->ws.logits_d);
-    lm_head(reinterpret_cast<const float*>(c->dblob + c->dl.gf), d.rms_eps, M, logits);
     const int mode = temperature > 0.f ? 1 : 0;
-    argmax(logits, d.vocab, M, B, draft_tokens, 1, mode, mode ? 1.0f / temperature : 1.0f, rng_key);
+    const float inv_T = mode ? 1.0f / temperature : 1.0f;
+    const bool want_logits = logits_out || mode;        // sampling: dflash_accept needs the proposal distribution
+    lm_head(reinterpret_cast<const float*>(c->dblob + c->dl.gf), d.rms_eps, M, logits, want_logits, B, mode, inv_T, rng_key);
+    c->have_logits_d = want_logits || amax_parts == 0;
+    c->draft_temperature = temperature;
+    argmax(logits, d.vocab, M, B, draft_tokens, 1, mode, inv_T, rng_key);
     if (logits_out) {
       if (hipMemcpyAsync(logits_out, logits, (size_t)M * d.vocab * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
         return CTX_FAIL(c, DFLASH_EHIP, "logits copy failed");
@@ -398,7 +422,9 @@ struct Engine {
       if (tap < c->rt.n_taps && c->rt.tap_layers[tap] == l) pending_tap = tap++;   // taken by the next RMSNorm
     }
     float* logits = ws<float>(c->ws.logits_t);
-    lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits);
+    const bool want_logits = logits_out || c->draft_temperature > 0.f;   // sampling: dflash_accept needs the target distribution
+    lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits, want_logits, B, 0, 1.0f, nullptr);
+    c->have_logits_t = want_logits || amax_parts == 0;
     argmax(logits, t.vocab, M, B, tgt_argmax, 0, 0, 1.0f, (const uint64_t*)nullptr);
     if (logits_out) {
       if (hipMemcpyAsync(logits_out, logits, (size_t)M * t.vocab * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
@@ -458,9 +484,12 @@ struct Engine {
 // ---- GEMM dispatch ----------------------------------------------------------------------------------
 constexpr int kMaxKSplit = 16;
 
+thread_local int g_launch_parts = 0;   // column blocks of the last bf16 GEMM launch (= fused-argmax partials per row)
+
 template <int NT, int MT, int U>
 void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
   const dim3 grid((N / 16) / NT, ((M + 15) / 16 + MT - 1) / MT, ks), block(256);
+  g_launch_parts = (int)grid.x;
   if (epi == EPI_SWIGLU) {
     if constexpr (NT >= 2) hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, U, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, ep);
   } else {
@@ -472,6 +501,7 @@ template <int WN, int WM, int PD>
 void launch_tiled(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
   const int n_blocks = (N / 16 + 2 * WN - 1) / (2 * WN), m_blocks = ((M + 15) / 16 + 2 * WM - 1) / (2 * WM);
   const dim3 grid(((n_blocks + 7) / 8) * 8 * m_blocks, ks), block(256);
+  g_launch_parts = n_blocks;
   if (epi == EPI_SWIGLU)
     hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
   else
@@ -508,6 +538,8 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   const bool split = allow_split && epi != EPI_SWIGLU;
   const int arena = arena_rows(c->rt.max_seqs * c->rt.block_size);
   int ks = 1;
+  if (ep.amax && (split || epi != EPI_STORE)) ep.amax = nullptr;   // the fused argmax needs complete sums
+  if (ep.amax && lm_skip_store) ep.out = nullptr;
   if (M <= 16) {
     static const int NT8 = env_int("DFLASH_GEMM_NT8", 1);   // tuning knob: matrices with at least 8*this row bands use 8 weight tiles per activation fragment
     if (NT8 && nt % 8 == 0 && nt >= 8 * NT8) {
@@ -585,6 +617,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     }
   }
   check();
+  if (ep.amax) amax_parts = g_launch_parts;
   if (epi == EPI_SWIGLU) return Slab{};
   return Slab{ep.out, ks, ep.slab};
 }
@@ -884,6 +917,8 @@ int dflash_accept(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* dra
   if (!draft_tokens || !tgt_argmax || !accept_len || !out_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: null pointer");
   if (!(temperature >= 0.f)) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: negative temperature");
   if (temperature > 0.f && (!uniforms || !rng_key)) return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: sampling needs uniforms and rng_key");
+  if (temperature > 0.f && !(ctx->have_logits_d && ctx->have_logits_t))
+    return CTX_FAIL(ctx, DFLASH_EINVAL, "accept: sampling needs the logits of this step: run dflash_draft_block with temperature > 0 and then dflash_verify first");
   return DISPATCH(ctx, accept(batch, draft_tokens, tgt_argmax, temperature, uniforms, rng_key, accept_len, out_tokens));
 }
 

@@ -13,7 +13,21 @@ struct EpiArgs {
   size_t slab;  // elements between the partial results of consecutive K ranges (grid.z)
   void* act;    // SWIGLU: act (GEMM activation operand, row length act_K) [m, j] = silu(gate_j) * up_j
   int act_K;
+  // STORE with a single K range, LM head only: fused row argmax.  Every workgroup also writes the best
+  // (score, column) of its columns for each of its rows to amax[m * gridDim.x-many parts + part]; score = y
+  // (mode 0) or y * inv_T + Gumbel(key, m / B, m % B, purpose 0, column) (mode 1).  out may then be null
+  // (logits not wanted).  A second, tiny kernel combines the parts (ties -> lowest column).
+  float2* amax = nullptr;
+  int amax_mode = 0;
+  float amax_inv_T = 1.f;
+  const uint64_t* amax_key = nullptr;
+  int amax_B = 1;
 };
+
+// score of logit y at (row m, column col) for the fused argmax
+__device__ __forceinline__ float amax_score(const EpiArgs& ep, uint64_t key, float y, int m, int col) {
+  return ep.amax_mode ? y * ep.amax_inv_T + gumbel(counter_uniform(key, m / ep.amax_B, m % ep.amax_B, 0, (uint32_t)col)) : y;
+}
 
 // Split of K across workgroups (grid.z ranges): the STORE epilogue writes one partial slab per range and
 // the kernel that consumes the result (RMSNorm, q/k-norm + RoPE) adds the slabs in ascending order.
@@ -145,13 +159,50 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
       }
     }
   } else {
-    for (int t = wave; t < NT * MT; t += 4) {
-      const int i = t / MT, j = t % MT;
-      const float4 s = tile_sum(t);
-      const int m = (mt0 + j) * 16 + mrow;
-      if (mt0 + j < m_tiles && m < M) {
-        float4* dst = reinterpret_cast<float4*>(ep.out + (size_t)kz * ep.slab + (size_t)m * ep.ld + (nt0 + i) * 16 + 4 * g);
-        *dst = s;
+    if (ep.out) {
+      for (int t = wave; t < NT * MT; t += 4) {
+        const int i = t / MT, j = t % MT;
+        const float4 s = tile_sum(t);
+        const int m = (mt0 + j) * 16 + mrow;
+        if (mt0 + j < m_tiles && m < M) {
+          float4* dst = reinterpret_cast<float4*>(ep.out + (size_t)kz * ep.slab + (size_t)m * ep.ld + (nt0 + i) * 16 + 4 * g);
+          *dst = s;
+        }
+      }
+    }
+    if (ep.amax) {   // fused argmax over this workgroup's NT*16 columns (host guarantees a single K range)
+      __shared__ float2 wbest[4][MT * 16];
+      const uint64_t key = ep.amax_mode ? ep.amax_key[0] : 0ull;
+#pragma unroll
+      for (int j = 0; j < MT; ++j) {
+        const int m = (mt0 + j) * 16 + mrow;
+        float bv = -INFINITY;
+        int bi = 0x7FFFFFFF;
+        for (int i = wave; i < NT; i += 4) {
+          const float4 s = tile_sum(i * MT + j);
+          const int col = (nt0 + i) * 16 + 4 * g;
+          argmax_combine(bv, bi, amax_score(ep, key, s.x, m, col), col);
+          argmax_combine(bv, bi, amax_score(ep, key, s.y, m, col + 1), col + 1);
+          argmax_combine(bv, bi, amax_score(ep, key, s.z, m, col + 2), col + 2);
+          argmax_combine(bv, bi, amax_score(ep, key, s.w, m, col + 3), col + 3);
+        }
+#pragma unroll
+        for (int o = 16; o <= 32; o <<= 1) {
+          const float ov = __shfl_xor(bv, o, 64);
+          const int oi = __shfl_xor(bi, o, 64);
+          argmax_combine(bv, bi, ov, oi);
+        }
+        if (g == 0) wbest[wave][j * 16 + mrow] = make_float2(bv, __int_as_float(bi));
+      }
+      __syncthreads();
+      for (int r = threadIdx.x; r < MT * 16; r += 256) {
+        const int m = mt0 * 16 + r;
+        if (m >= M) continue;
+        float bv = wbest[0][r].x;
+        int bi = __float_as_int(wbest[0][r].y);
+#pragma unroll
+        for (int w = 1; w < 4; ++w) argmax_combine(bv, bi, wbest[w][r].x, __float_as_int(wbest[w][r].y));
+        ep.amax[(size_t)m * gridDim.x + blockIdx.x] = make_float2(bv, __int_as_float(bi));
       }
     }
   }

@@ -146,10 +146,45 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
 #pragma unroll
       for (int i = 0; i < WN; ++i) {
         const int nt = nt0 + wy * WN + i;
-        if (nt >= n_tiles) continue;
+        if (nt >= n_tiles || !ep.out) continue;
         const f32x4 s = acc[i][jj];
         *reinterpret_cast<float4*>(ep.out + (size_t)kz * ep.slab + (size_t)m * ep.ld + nt * 16 + 4 * gq) = make_float4(s[0], s[1], s[2], s[3]);
       }
+    }
+  }
+  if (EPI == EPI_STORE && ep.amax) {   // fused argmax over this workgroup's columns (host guarantees a single K range)
+    __syncthreads();                   // the staging slots are free now: reuse them for the two N halves' bests
+    float2* wbest = reinterpret_cast<float2*>(&stage[0][0][0]);   // [wy][BMT * 16 rows]
+    const uint64_t key = ep.amax_mode ? ep.amax_key[0] : 0ull;
+#pragma unroll
+    for (int jj = 0; jj < WM; ++jj) {
+      const int mt = mt0 + wx * WM + jj, m = mt * 16 + mrow;
+      float bv = -INFINITY;
+      int bi = 0x7FFFFFFF;
+#pragma unroll
+      for (int i = 0; i < WN; ++i) {
+        const int nt = nt0 + wy * WN + i;
+        if (nt >= n_tiles) continue;
+        const int col = nt * 16 + 4 * gq;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) argmax_combine(bv, bi, amax_score(ep, key, acc[i][jj][e], m, col + e), col + e);
+      }
+#pragma unroll
+      for (int o = 16; o <= 32; o <<= 1) {
+        const float ov = __shfl_xor(bv, o, 64);
+        const int oi = __shfl_xor(bi, o, 64);
+        argmax_combine(bv, bi, ov, oi);
+      }
+      if (gq == 0) wbest[wy * (BMT * 16) + (wx * WM + jj) * 16 + mrow] = make_float2(bv, __int_as_float(bi));
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < BMT * 16; r += 256) {
+      const int m = mt0 * 16 + r;
+      if (m >= M) continue;
+      float bv = wbest[r].x;
+      int bi = __float_as_int(wbest[r].y);
+      argmax_combine(bv, bi, wbest[BMT * 16 + r].x, __float_as_int(wbest[BMT * 16 + r].y));
+      ep.amax[(size_t)m * n_blocks + nb] = make_float2(bv, __int_as_float(bi));
     }
   }
 }

@@ -185,23 +185,6 @@ __global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ 
 }
 
 // ---- row argmax (ties -> lowest index), optionally of logit/T + Gumbel noise ---------------------
-__device__ __forceinline__ uint64_t mix64(uint64_t z) {
-  z = (z ^ (z >> 30)) * 0xBF58476D1CE4E5B9ull;
-  z = (z ^ (z >> 27)) * 0x94D049BB133111EBull;
-  return z ^ (z >> 31);
-}
-// u in (0,1), 23 bits (so that x + 0.5 is exact in fp32): counter c = (((seq*64 + slot)*4 + purpose) << 32) | idx
-__device__ __forceinline__ float counter_uniform(uint64_t key, int seq, int slot, int purpose, uint32_t idx) {
-  const uint64_t c = ((uint64_t)(((uint32_t)seq * 64u + (uint32_t)slot) * 4u + (uint32_t)purpose) << 32) | idx;
-  const uint64_t z = mix64(key + 0x9E3779B97F4A7C15ull * (c + 1ull));
-  return ((float)(z >> 41) + 0.5f) * 1.1920928955078125e-7f;  // 2^-23
-}
-__device__ __forceinline__ float gumbel(float u) { return -logf(-logf(u)); }
-
-__device__ __forceinline__ void argmax_combine(float& bv, int& bi, float v, int i) {
-  if (v > bv || (v == bv && i < bi)) { bv = v; bi = i; }
-}
-
 // block-wide argmax (up to 1024 threads); result valid in thread 0
 __device__ __forceinline__ void block_argmax(float& bv, int& bi) {
   __shared__ float sv[16];

@@ -107,3 +107,32 @@ def test_graph_replay_small_bf16_greedy_and_sampling():
     prompts = si.make_prompts(w)
     _run(w, prompts, 0.0)
     _run(replace(w, temperature=1.0), prompts, 1.0)
+
+
+def test_step_without_materialised_logits_gives_the_same_tokens():
+    """Greedy steps that ask for no logits (the LM-head GEMMs then only leave their fused per-row argmax partials
+    and never write the [S, B, V] logits) choose exactly the tokens of steps that do; a sampling accept after a
+    greedy draft is refused because the workspace holds no distributions."""
+    import torch
+    import paper_2602_06036_amd as dfl
+    from paper_2602_06036_amd import binding as B
+    from tests.gpu_harness import GpuModel
+    for w in (si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=90, seed=19),
+              si.small_bf16_workload(n_seqs=9, ctx_min=17, ctx_max=40, seed=29)):     # 48 and 144 rows per step
+        prompts = si.make_prompts(w)
+        wt, wd = si.make_weights(w, 8)
+        g = GpuModel(w, wt, wd, max(len(p) for p in prompts) + 4 * w.block_size, n_seqs=len(prompts))
+        g.prefill(prompts)
+        snap = _snapshot(g)
+        ref = [g.step(want_logits=True) for _ in range(2)]
+        _restore(g, snap)
+        for r in ref:
+            out = g.step(want_logits=False)
+            for k in ("drafted", "tgt_argmax", "accept_len", "out_tokens", "kv_slots", "anchor"):
+                assert np.array_equal(out[k], r[k]), k
+        u = torch.rand((g.S, g.Bk), device=g.dev)
+        key = torch.tensor([5], dtype=torch.int64, device=g.dev)
+        with pytest.raises(B.DFlashError) as ei:
+            dfl.dflash_accept(g.e, g.batch(), g.draft_tokens, g.tgt_argmax, g.accept_len, g.out_tokens, 1.0, u, key)
+        assert ei.value.code == B.DFLASH_EINVAL
+        g.e.close()
