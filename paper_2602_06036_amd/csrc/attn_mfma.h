@@ -230,7 +230,7 @@ __device__ __forceinline__ uint32_t pack_bf16_pair(float a, float b) {   // RNE,
 template <int HD, int RB>
 __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base, const u32x4* __restrict__ q_lds,
                                                        f32x4 (&acc)[RB][HD / 16], float (&m_run)[RB], float (&l_run)[RB],
-                                                       const int (&last_vis)[RB], int n_all_vis, float scale2, const AttnLane& L) {
+                                                       const int (&last_vis)[RB], int n_all_vis, float scale2, const AttnLane& L, f32x4* rescale_lds) {
   constexpr int KT = HD / 32, DT = HD / 16;
   if (base + 32 > L.n_tok || !f.ok_a || !f.ok_b) {   // never-written rows / foreign pages: clear V (0 * garbage != NaN)
     const int pos_a = base + 4 * L.g, pos_b = base + 16 + 4 * L.g;
@@ -285,10 +285,21 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
     if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
       const float corr = grow ? (m_old == -INFINITY ? 0.f : exp2f(m_old - mx)) : 1.f;
       l_run[rb] *= corr;
+      // through LDS: the accumulators can be stored from and loaded into the accumulation registers directly, so
+      // the common path never has to shuttle them to ordinary registers on behalf of this rare one
+      f32x4* scr = rescale_lds + L.lane;
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) scr[dt * 64] = acc[rb][dt];
+      asm volatile("" ::: "memory");
 #pragma unroll
       for (int dt = 0; dt < DT; ++dt) {
-        acc[rb][dt][0] *= corr; acc[rb][dt][1] *= corr; acc[rb][dt][2] *= corr; acc[rb][dt][3] *= corr;
+        f32x4 a = scr[dt * 64];
+        a[0] *= corr; a[1] *= corr; a[2] *= corr; a[3] *= corr;
+        scr[dt * 64] = a;
       }
+      asm volatile("" ::: "memory");
+#pragma unroll
+      for (int dt = 0; dt < DT; ++dt) acc[rb][dt] = scr[dt * 64];
       if (grow) m_run[rb] = mx;
     }
     const float mb = (m_run[rb] == -INFINITY) ? 0.f : m_run[rb];   // nothing visible yet: exp2(-inf - 0) = 0
@@ -329,6 +340,8 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
   const int rows = B * group;
   const int n_s = geo.seq_lens[s];
   const int cap = geo.max_pages_per_seq * DF_PAGE;
+  // per-wavefront staging for the rare accumulator rescale (behind room for 16384 page ids)
+  f32x4* rescale_lds = reinterpret_cast<f32x4*>(s_raw + RB * KT * 64 * 4 + 16384) + wave * (DT * 64);
 
   AttnLane L;
   L.table = geo.block_table + (size_t)s * geo.max_pages_per_seq;
@@ -386,7 +399,7 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
   if (wave < n_pairs) {
     KvFrags<HD> f0, f1;
     auto process = [&](KvFrags<HD>& f, int p) {
-      attn_process_pair_wide<HD, RB>(f, L.c0 + p * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, scale2, L);
+      attn_process_pair_wide<HD, RB>(f, L.c0 + p * 32, q_lds, acc, m_run, l_run, last_vis, n_all_vis, scale2, L, rescale_lds);
     };
     load(f0, wave);
     int p = wave;
@@ -467,7 +480,7 @@ inline bool attn_mfma_launch<bf16_t>(hipStream_t st, const bf16_t* q, const bf16
   if (rows > 64 || (aa.head_dim != 128 && aa.head_dim != 64)) return false;
   const dim3 grid(aa.n_splits, aa.n_kv_heads, S), block(256);
   // long chunks: wavefronts split the keys (the chunk's page ids must fit the kernel's LDS slice)
-  if (aa.head_dim == 128 && aa.chunk >= wide_min_chunk && aa.chunk / DF_PAGE + 2 <= 29000)
+  if (aa.head_dim == 128 && aa.chunk >= wide_min_chunk && aa.chunk / DF_PAGE + 2 <= 16384)
     hipLaunchKernelGGL(attn_mfma_wide_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
   else if (aa.head_dim == 128)
     hipLaunchKernelGGL(attn_mfma_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
