@@ -261,11 +261,11 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
       sa = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.ka[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sa, 0, 0, 0);
       sb = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.kb[kt]), __builtin_bit_cast(bf16x8, qf[kt]), sb, 0, 0, 0);
     }
-    float v[8];   // scores in the base-2 exponent domain: scale2 = log2(e) / sqrt(head_dim)
+    float v[8];   // raw scores q.k; the base-2 exponent domain value is v * scale2, scale2 = log2(e) / sqrt(head_dim) > 0
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
-      v[i] = sa[i] * scale2;
-      v[4 + i] = sb[i] * scale2;
+      v[i] = sa[i];
+      v[4 + i] = sb[i];
     }
     if (!all_vis) {
 #pragma unroll
@@ -277,6 +277,7 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
     float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
     mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
     mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+    mx *= scale2;   // the maximum commutes with the positive scale
     // Lazy reference maximum: m_run only moves when the true maximum has grown by more than 8 (a factor 256),
     // so the accumulators (which live in the MFMA accumulation registers, out of reach of plain ALU ops) are
     // rescaled once or twice per sweep instead of after every pair.  exp2(v - m_run) <= 256 meanwhile.
@@ -305,7 +306,7 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
     const float mb = (m_run[rb] == -INFINITY) ? 0.f : m_run[rb];   // nothing visible yet: exp2(-inf - 0) = 0
     float pe[8];
 #pragma unroll
-    for (int i = 0; i < 8; ++i) pe[i] = __builtin_amdgcn_exp2f(v[i] - mb);
+    for (int i = 0; i < 8; ++i) pe[i] = __builtin_amdgcn_exp2f(fmaf(v[i], scale2, -mb));   // -inf stays -inf -> 0
     l_run[rb] += ((pe[0] + pe[1]) + (pe[2] + pe[3])) + ((pe[4] + pe[5]) + (pe[6] + pe[7]));
     u32x4 ph, pl;
 #pragma unroll
@@ -314,11 +315,13 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
       ph[i] = h;
       pl[i] = pack_bf16_pair(pe[2 * i] - __uint_as_float(h << 16), pe[2 * i + 1] - __uint_as_float(h & 0xFFFF0000u));
     }
+    // all hi products, then all lo products: two MFMAs on the same accumulator are never back to back
 #pragma unroll
-    for (int dt = 0; dt < DT; ++dt) {
+    for (int dt = 0; dt < DT; ++dt)
       acc[rb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, ph), acc[rb][dt], 0, 0, 0);
+#pragma unroll
+    for (int dt = 0; dt < DT; ++dt)
       acc[rb][dt] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, f.v[dt]), __builtin_bit_cast(bf16x8, pl), acc[rb][dt], 0, 0, 0);
-    }
   }
 }
 
