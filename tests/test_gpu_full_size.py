@@ -52,7 +52,24 @@ def _run_config(shared, cfg):
     for v in golden.values():
         proposals[v["seq"]] = v["block"][1:]
     uniforms = si.make_uniforms(w, 0) if w.temperature > 0 else None
+    # the launch configuration bench.py times asks for no logits (row argmax fused into the LM-head GEMMs, logits
+    # never written): run draft and verify that way first -- both leave the committed state untouched -- and
+    # require the same tokens from the step below, whose logits are compared with the oracle's
+    import torch
+    import paper_2602_06036_amd as dfl
+    rng = torch.tensor([RNG_KEY], dtype=torch.int64, device=g.dev) if w.temperature > 0 else None
+    b = g.batch()
+    dfl.dflash_draft_block(g.e, b, g.draft_tokens, w.temperature, rng, None)
+    blk0 = g.draft_tokens.cpu().numpy().copy()
+    blk0[:, 1:] = np.where(proposals >= 0, proposals, blk0[:, 1:])
+    g.draft_tokens.copy_(torch.from_numpy(blk0).to(g.dev))
+    dfl.dflash_verify(g.e, b, g.draft_tokens, g.tgt_argmax, None)
+    tgt0 = g.tgt_argmax.cpu().numpy().copy()
     out = g.step(proposals, w.temperature, uniforms, RNG_KEY)
+    assert np.array_equal(out["block"], blk0), "draft tokens differ between the runs with and without logits"
+    assert np.array_equal(out["tgt_argmax"], tgt0), "target argmax differs between the runs with and without logits"
+    lt = torch.from_numpy(out["logits_t"])
+    assert np.array_equal(out["tgt_argmax"], lt.argmax(-1).numpy()), "fused argmax is not the argmax of the stored logits"
     stats = dict(max_err_d=0.0, max_err_t=0.0, flips=0, rows=0)
     for name, v in golden.items():
         s, n, a = v["seq"], v["n"], v["accept_len"]
