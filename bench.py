@@ -87,6 +87,28 @@ def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
     return e, table, max_len
 
 
+def measure_peaks(dev):
+    """Machine probes through the library: back-to-back read-only launches over fresh memory (sizes of the O, QKV,
+    down, gate/up projections and the LM head) and a bf16 MFMA loop at 1, 2 and 4 wavefronts per SIMD."""
+    import torch
+    from paper_2602_06036_amd import binding as B
+    buf = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
+    buf.zero_()
+    torch.cuda.synchronize(dev)
+    out = {"hbm_read": {}, "mfma_bf16": {}, "peaks_quoted": {"hbm_GBps": HBM_PEAK_GBS, "mfma_bf16_TFLOPs": MFMA_BF16_PEAK_TFLOPS}}
+    for name, nbytes in (("o_proj_33MB", 33554432), ("qkv_50MB", 50331648), ("down_101MB", 100663296),
+                         ("gate_up_201MB", 201326592), ("lm_head_1245MB", 1244659712)):
+        n = max(1, min(24, (6 << 30) // nbytes))
+        B.dflash_probe_hbm_read(buf, nbytes, n)                       # warm-up (code, clocks)
+        ms = B.dflash_probe_hbm_read(buf, nbytes, n)
+        out["hbm_read"][name] = {"us_per_launch": 1e3 * ms / n, "GBps": nbytes * n / ms / 1e6}
+    for wgs in (256, 512, 1024):
+        B.dflash_probe_mfma(wgs, 2000)
+        ms, fl = B.dflash_probe_mfma(wgs, 20000)
+        out["mfma_bf16"][f"{wgs // 256}_waves_per_simd"] = {"ms": ms, "TFLOPs": fl / ms / 1e9}
+    return out
+
+
 def cpu_baseline(w, ctx, time_budget_s=25.0):
     """Times the oracle, as it stands, on a bounded sample of the same step: one target layer and one
     draft layer of the workload's shape over one 16-token block with `ctx` cached rows, plus the final
@@ -153,6 +175,9 @@ def main():
     ap.add_argument("--graph", action="store_true",
                     help="capture one step into a HIP graph (attention splits planned for the longest length the run "
                          "reaches) and time K replays instead of K eager steps")
+    ap.add_argument("--peaks", action="store_true",
+                    help="instead of the step: what single launches reach on this GPU (read-only HBM streaming of the "
+                         "sizes of the weight matrices, register-resident bf16 MFMA loop), one JSON line")
     ap.add_argument("--no-cpu-baseline", action="store_true")
     ap.add_argument("--no-profile", action="store_true")
     ap.add_argument("--copy-probe", action="store_true",
@@ -172,6 +197,9 @@ def main():
     assert torch.cuda.is_available(), "bench.py needs a GPU"
     dev = torch.device("cuda:0")
     torch.cuda.set_device(dev)
+    if args.peaks:
+        print(json.dumps(measure_peaks(dev)))
+        return
     idx, S, ctx = WORKLOADS[args.workload]
     w = si.llama31_8b_workload(S, ctx) if idx == "llama31" else si.workload(idx)
     Bk = w.block_size

@@ -188,6 +188,18 @@ enum {
 int dflash_profile_enable(dflash_ctx *ctx, int32_t enable);
 int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count, double *bytes);
 
+/* ---- machine probes (benchmarks; not part of the method) -----------------------------------------
+ * What one launch can reach on this GPU, to put the kernels' figures beside: neither needs a context.
+ * dflash_probe_hbm_read: `launches` back-to-back kernels (256 workgroups of 256 threads, 8 non-temporal 1 KB
+ * loads in flight per wavefront), launch i reading bytes_per_launch bytes at buf + i * bytes_per_launch
+ * (device memory, at least launches * bytes_per_launch bytes, a multiple of 1024; use more than the 256 MB
+ * memory-side cache in total so that every launch reads HBM).  *ms_total (host) = time of all launches.
+ * dflash_probe_mfma: one kernel of `workgroups` x 4 wavefronts, each issuing iters x 16 independent
+ * v_mfma_f32_16x16x32_bf16 on register operands.  *ms (host) = its time, *flops (host) = 2*16*16*32 per MFMA.
+ * Both synchronise the stream.  DFLASH_EINVAL on bad arguments, DFLASH_EHIP if the device reports an error. */
+int dflash_probe_hbm_read(const void *buf, size_t bytes_per_launch, int32_t launches, float *ms_total, void *stream);
+int dflash_probe_mfma(int32_t workgroups, int32_t iters, float *ms, double *flops, void *stream);
+
 /* ---- cache import / export (state migration, tests) ------------------------------------------ */
 /* Copies rows [start, start+count) of sequence `seq` of one layer between the paged pool and
  * canonical fp32 buffers k, v (device) [count, Hkv, hd].  K rows are stored post-RoPE.

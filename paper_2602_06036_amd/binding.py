@@ -26,6 +26,7 @@ EXPORTS = [
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
     "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read",
+    "dflash_probe_hbm_read", "dflash_probe_mfma",
 ]
 
 
@@ -254,3 +255,19 @@ def dflash_kv_read(e: Engine, batch: Batch, pool: int, layer: int, seq: int, sta
 def dflash_kv_write(e: Engine, batch: Batch, pool: int, layer: int, seq: int, start: int, k: torch.Tensor, v: torch.Tensor):
     assert k.dtype == torch.float32 and v.dtype == torch.float32 and k.shape == v.shape
     _check(e.l.dflash_kv_write(e.ctx, C.byref(batch), pool, layer, seq, start, int(k.shape[0]), _ptr(k), _ptr(v), _stream()), e.ctx)
+
+
+# ---- machine probes (same names as the C ABI) -----------------------------------------------------------
+def dflash_probe_hbm_read(buf: torch.Tensor, bytes_per_launch: int, launches: int) -> float:
+    """Milliseconds for `launches` read-only streaming kernels over consecutive pieces of `buf`."""
+    assert buf.is_cuda and buf.is_contiguous() and buf.numel() * buf.element_size() >= bytes_per_launch * launches
+    ms = C.c_float()
+    _check(lib().dflash_probe_hbm_read(C.c_void_p(buf.data_ptr()), C.c_size_t(bytes_per_launch), launches, C.byref(ms), _stream()))
+    return float(ms.value)
+
+
+def dflash_probe_mfma(workgroups: int, iters: int):
+    """(milliseconds, flops) of one kernel of register-resident bf16 MFMAs."""
+    ms, fl = C.c_float(), C.c_double()
+    _check(lib().dflash_probe_mfma(workgroups, iters, C.byref(ms), C.byref(fl), _stream()))
+    return float(ms.value), float(fl.value)

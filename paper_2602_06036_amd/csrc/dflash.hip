@@ -737,6 +737,25 @@ int check_batch(dflash_ctx* ctx, const dflash_batch* b) {
 
 }  // namespace
 
+namespace {
+// times `enqueue` on `st` with a pair of events; synchronises
+template <typename F>
+int timed(hipStream_t st, float* ms, F&& enqueue) {
+  hipEvent_t a, b;
+  if (hipEventCreate(&a) != hipSuccess) return fail(nullptr, DFLASH_EHIP, "probe: event creation failed");
+  if (hipEventCreate(&b) != hipSuccess) { (void)hipEventDestroy(a); return fail(nullptr, DFLASH_EHIP, "probe: event creation failed"); }
+  int rc = DFLASH_OK;
+  if (hipEventRecord(a, st) != hipSuccess) rc = DFLASH_EHIP;
+  enqueue();
+  if (hipEventRecord(b, st) != hipSuccess || hipEventSynchronize(b) != hipSuccess || hipEventElapsedTime(ms, a, b) != hipSuccess ||
+      hipGetLastError() != hipSuccess)
+    rc = DFLASH_EHIP;
+  (void)hipEventDestroy(a);
+  (void)hipEventDestroy(b);
+  return rc == DFLASH_OK ? rc : fail(nullptr, DFLASH_EHIP, "probe: the device reported an error");
+}
+}  // namespace
+
 // =====================================================================================================
 extern "C" {
 
@@ -870,6 +889,33 @@ int dflash_profile_read(dflash_ctx* ctx, void* stream, float* ms, int32_t* count
   for (hipEvent_t e : ctx->ev) (void)hipEventDestroy(e);
   ctx->ev.clear(); ctx->ev_cls.clear(); ctx->ev_bytes.clear();
   return DFLASH_OK;
+}
+
+int dflash_probe_hbm_read(const void* buf, size_t bytes_per_launch, int32_t launches, float* ms_total, void* stream) {
+  if (!buf || !ms_total || launches < 1 || bytes_per_launch < 1024 || bytes_per_launch % 1024)
+    return fail(nullptr, DFLASH_EINVAL, "probe_hbm_read: need a buffer, launches >= 1 and a multiple of 1024 bytes per launch");
+  hipStream_t st = (hipStream_t)stream;
+  unsigned* sink = nullptr;
+  if (hipMalloc((void**)&sink, 256) != hipSuccess) return fail(nullptr, DFLASH_EHIP, "probe_hbm_read: no device memory for the sink");
+  const int rc = timed(st, ms_total, [&] {
+    for (int i = 0; i < launches; ++i)
+      hipLaunchKernelGGL(probe_read_kernel, dim3(256), dim3(256), 0, st,
+                         reinterpret_cast<const u32x4*>(static_cast<const char*>(buf) + (size_t)i * bytes_per_launch), bytes_per_launch / 1024, sink);
+  });
+  (void)hipFree(sink);
+  return rc;
+}
+
+int dflash_probe_mfma(int32_t workgroups, int32_t iters, float* ms, double* flops, void* stream) {
+  if (!ms || !flops || workgroups < 1 || workgroups > 65536 || iters < 1)
+    return fail(nullptr, DFLASH_EINVAL, "probe_mfma: need outputs, 1..65536 workgroups and iters >= 1");
+  hipStream_t st = (hipStream_t)stream;
+  float* out = nullptr;
+  if (hipMalloc((void**)&out, 256) != hipSuccess) return fail(nullptr, DFLASH_EHIP, "probe_mfma: no device memory for the sink");
+  const int rc = timed(st, ms, [&] { hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(256), 0, st, iters, out); });
+  (void)hipFree(out);
+  *flops = (double)workgroups * 4 * iters * 16 * (2.0 * 16 * 16 * 32);
+  return rc;
 }
 
 const char* dflash_last_error(const dflash_ctx* ctx) { return ctx ? ctx->err : g_err; }

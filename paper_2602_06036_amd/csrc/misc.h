@@ -418,3 +418,35 @@ __global__ __launch_bounds__(128) void kv_copy_kernel(T* __restrict__ pool, SeqG
     }
   }
 }
+
+// ---- machine probes ---------------------------------------------------------------------------------
+// read-only streaming: wavefronts interleave 8 KB pieces across the whole grid
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ p, size_t n_chunks, unsigned* __restrict__ sink) {
+  const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
+  const size_t n_waves = ((size_t)gridDim.x * blockDim.x) >> 6;
+  unsigned acc = 0;
+  for (size_t c = wave * 8; c < n_chunks; c += n_waves * 8) {
+    u32x4 v[8];
+#pragma unroll
+    for (int u = 0; u < 8; ++u) v[u] = __builtin_nontemporal_load(p + (c + u < n_chunks ? c + u : c) * 64 + lane);
+#pragma unroll
+    for (int u = 0; u < 8; ++u) acc ^= v[u][0] ^ v[u][3];
+  }
+  if (acc == 0x12345677u) *sink = acc;   // keeps the loads alive; practically never true
+}
+
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __restrict__ out) {
+  const u32x4 a = {threadIdx.x, 1u, 2u, 3u}, b = {4u, 5u, threadIdx.x, 7u};
+  f32x4 acc[16];
+#pragma unroll
+  for (int i = 0; i < 16; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 16; ++i)
+      acc[i] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
+  if (s == 12345.678f) out[0] = s;       // keeps the MFMAs alive
+}

@@ -136,3 +136,22 @@ def test_step_without_materialised_logits_gives_the_same_tokens():
             dfl.dflash_accept(g.e, g.batch(), g.draft_tokens, g.tgt_argmax, g.accept_len, g.out_tokens, 1.0, u, key)
         assert ei.value.code == B.DFLASH_EINVAL
         g.e.close()
+
+
+def test_machine_probes_report_plausible_rates():
+    """The two probe entry points (read-only HBM streaming, register-resident MFMA loop) run and land between
+    a loose lower bound and the published peaks of the part."""
+    import torch
+    from paper_2602_06036_amd import binding as B
+    buf = torch.zeros(2 << 30, dtype=torch.uint8, device="cuda:0")
+    torch.cuda.synchronize()
+    n = 10
+    B.dflash_probe_hbm_read(buf, 201326592, n)
+    ms = B.dflash_probe_hbm_read(buf, 201326592, n)
+    gbps = 201326592 * n / ms / 1e6
+    assert 1000 < gbps < 8000, gbps
+    B.dflash_probe_mfma(512, 2000)
+    ms, fl = B.dflash_probe_mfma(512, 20000)
+    assert 300 < fl / ms / 1e9 < 2500, fl / ms / 1e9
+    with pytest.raises(B.DFlashError):
+        B.dflash_probe_hbm_read(buf, 1000, 1)
