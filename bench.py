@@ -102,10 +102,11 @@ def measure_peaks(dev):
         B.dflash_probe_hbm_read(buf, nbytes, n)                       # warm-up (code, clocks)
         ms = B.dflash_probe_hbm_read(buf, nbytes, n)
         out["hbm_read"][name] = {"us_per_launch": 1e3 * ms / n, "GBps": nbytes * n / ms / 1e6}
-    for wgs in (256, 512, 1024):
-        B.dflash_probe_mfma(wgs, 2000)
-        ms, fl = B.dflash_probe_mfma(wgs, 20000)
-        out["mfma_bf16"][f"{wgs // 256}_waves_per_simd"] = {"ms": ms, "TFLOPs": fl / ms / 1e9}
+    for shape, name in ((0, "16x16x32"), (1, "32x32x16")):
+        for wgs in (256, 512, 1024):
+            B.dflash_probe_mfma(shape, wgs, 2000)
+            ms, fl = B.dflash_probe_mfma(shape, wgs, 20000)
+            out["mfma_bf16"][f"{name}_{wgs // 256}_waves_per_simd"] = {"ms": ms, "TFLOPs": fl / ms / 1e9}
     return out
 
 

@@ -194,11 +194,12 @@ int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count
  * loads in flight per wavefront), launch i reading bytes_per_launch bytes at buf + i * bytes_per_launch
  * (device memory, at least launches * bytes_per_launch bytes, a multiple of 1024; use more than the 256 MB
  * memory-side cache in total so that every launch reads HBM).  *ms_total (host) = time of all launches.
- * dflash_probe_mfma: one kernel of `workgroups` x 4 wavefronts, each issuing iters x 16 independent
- * v_mfma_f32_16x16x32_bf16 on register operands.  *ms (host) = its time, *flops (host) = 2*16*16*32 per MFMA.
+ * dflash_probe_mfma: one kernel of `workgroups` x 4 wavefronts, each issuing iters rounds of independent bf16
+ * MFMAs on register operands: shape 0 = 16 x v_mfma_f32_16x16x32_bf16 per round, shape 1 = 4 x
+ * v_mfma_f32_32x32x16_bf16 per round.  *ms (host) = its time, *flops (host) = 2*m*n*k per MFMA.
  * Both synchronise the stream.  DFLASH_EINVAL on bad arguments, DFLASH_EHIP if the device reports an error. */
 int dflash_probe_hbm_read(const void *buf, size_t bytes_per_launch, int32_t launches, float *ms_total, void *stream);
-int dflash_probe_mfma(int32_t workgroups, int32_t iters, float *ms, double *flops, void *stream);
+int dflash_probe_mfma(int32_t shape, int32_t workgroups, int32_t iters, float *ms, double *flops, void *stream);
 
 /* ---- cache import / export (state migration, tests) ------------------------------------------ */
 /* Copies rows [start, start+count) of sequence `seq` of one layer between the paged pool and

@@ -266,8 +266,8 @@ def dflash_probe_hbm_read(buf: torch.Tensor, bytes_per_launch: int, launches: in
     return float(ms.value)
 
 
-def dflash_probe_mfma(workgroups: int, iters: int):
-    """(milliseconds, flops) of one kernel of register-resident bf16 MFMAs."""
+def dflash_probe_mfma(shape: int, workgroups: int, iters: int):
+    """(milliseconds, flops) of one kernel of register-resident bf16 MFMAs (shape 0: 16x16x32, 1: 32x32x16)."""
     ms, fl = C.c_float(), C.c_double()
-    _check(lib().dflash_probe_mfma(workgroups, iters, C.byref(ms), C.byref(fl), _stream()))
+    _check(lib().dflash_probe_mfma(shape, workgroups, iters, C.byref(ms), C.byref(fl), _stream()))
     return float(ms.value), float(fl.value)

@@ -906,15 +906,18 @@ int dflash_probe_hbm_read(const void* buf, size_t bytes_per_launch, int32_t laun
   return rc;
 }
 
-int dflash_probe_mfma(int32_t workgroups, int32_t iters, float* ms, double* flops, void* stream) {
-  if (!ms || !flops || workgroups < 1 || workgroups > 65536 || iters < 1)
-    return fail(nullptr, DFLASH_EINVAL, "probe_mfma: need outputs, 1..65536 workgroups and iters >= 1");
+int dflash_probe_mfma(int32_t shape, int32_t workgroups, int32_t iters, float* ms, double* flops, void* stream) {
+  if (!ms || !flops || workgroups < 1 || workgroups > 65536 || iters < 1 || shape < 0 || shape > 1)
+    return fail(nullptr, DFLASH_EINVAL, "probe_mfma: need outputs, shape 0 or 1, 1..65536 workgroups and iters >= 1");
   hipStream_t st = (hipStream_t)stream;
   float* out = nullptr;
   if (hipMalloc((void**)&out, 256) != hipSuccess) return fail(nullptr, DFLASH_EHIP, "probe_mfma: no device memory for the sink");
-  const int rc = timed(st, ms, [&] { hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(256), 0, st, iters, out); });
+  const int rc = timed(st, ms, [&] {
+    if (shape == 0) hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(256), 0, st, iters, out);
+    else hipLaunchKernelGGL(probe_mfma32_kernel, dim3(workgroups), dim3(256), 0, st, iters, out);
+  });
   (void)hipFree(out);
-  *flops = (double)workgroups * 4 * iters * 16 * (2.0 * 16 * 16 * 32);
+  *flops = (double)workgroups * 4 * iters * (shape == 0 ? 16 * (2.0 * 16 * 16 * 32) : 4 * (2.0 * 32 * 32 * 16));
   return rc;
 }
 

@@ -450,3 +450,24 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __res
   for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
   if (s == 12345.678f) out[0] = s;       // keeps the MFMAs alive
 }
+
+typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
+__global__ __launch_bounds__(256) void probe_mfma32_kernel(int iters, float* __restrict__ out) {
+  const u32x4 a = {threadIdx.x, 1u, 2u, 3u}, b = {4u, 5u, threadIdx.x, 7u};
+  probe_f32x16 acc[4];
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) acc[i][e] = 0.f;
+  for (int it = 0; it < iters; ++it) {
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      acc[i] = __builtin_amdgcn_mfma_f32_32x32x16_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc[i], 0, 0, 0);
+  }
+  float s = 0.f;
+#pragma unroll
+  for (int i = 0; i < 4; ++i)
+#pragma unroll
+    for (int e = 0; e < 16; ++e) s += acc[i][e];
+  if (s == 12345.678f) out[0] = s;       // keeps the MFMAs alive
+}

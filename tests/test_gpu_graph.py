@@ -150,8 +150,9 @@ def test_machine_probes_report_plausible_rates():
     ms = B.dflash_probe_hbm_read(buf, 201326592, n)
     gbps = 201326592 * n / ms / 1e6
     assert 1000 < gbps < 8000, gbps
-    B.dflash_probe_mfma(512, 2000)
-    ms, fl = B.dflash_probe_mfma(512, 20000)
-    assert 300 < fl / ms / 1e9 < 2500, fl / ms / 1e9
+    for shape in (0, 1):
+        B.dflash_probe_mfma(shape, 512, 2000)
+        ms, fl = B.dflash_probe_mfma(shape, 512, 20000)
+        assert 300 < fl / ms / 1e9 < 2500, (shape, fl / ms / 1e9)
     with pytest.raises(B.DFlashError):
         B.dflash_probe_hbm_read(buf, 1000, 1)
