@@ -259,6 +259,23 @@ def test_small_bf16_other_block_sizes(block):
     assert ls.stats["reseeds"] <= 1
 
 
+def test_bf16_head_dim_64_without_qk_norm():
+    """A bf16 model of another shape family: head_dim 64 (the MFMA attention kernel's second instantiation), two
+    query heads per kv head, no q/k norm (the LLaMA-style layer of Section 5), B = 8."""
+    w = tiny_workload(seed=41, n_layers=3, draft_layers=2, vocab=1024, block=8, qk_norm=False, kv_heads=2, dtype="bf16",
+                      n_seqs=3, taps=(0, 1), d=256, heads=4, hd=64, ffn=1024)
+    prompts = [p[:n] for p, n in zip(si.make_prompts(replace(w, ctx_min=70, ctx_max=70)), (70, 33, 51))]
+    ls = Lockstep(w, prompts, max_len=70 + 6 * 8)
+    ls.prefill()
+    ls.check_cache([0, 2], [0, 1])
+    for i, plan in enumerate([None, [7, 0, 3], [2, 7, 7], None]):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([2], [1])
+    print("bf16 hd=64 stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
 def test_prefill_as_one_many_row_pass():
     """Prefill (Section 4.1) run as a single verify + forced commit over all prompt chunks at once (here 21 chunks,
     336 rows through the tiled GEMM) instead of chunk after chunk: caches, first tokens and the following
