@@ -276,6 +276,42 @@ def test_bf16_head_dim_64_without_qk_norm():
     assert ls.stats["reseeds"] <= 1
 
 
+@pytest.mark.parametrize("n_seqs", [2, 12])
+def test_bf16_awkward_matrix_shapes(n_seqs):
+    """Matrix shapes that are not multiples of the preferred tiles: vocabulary 1008 (63 row bands: the LM head runs
+    with one band per workgroup, or with a clamped last tile in the many-row kernel, and the fused argmax must
+    still cover every column exactly once), FFN 1056 (132 gate/up bands: four per workgroup).  16 rows per step
+    (streaming kernels) and 96 rows (tiled kernels)."""
+    w = tiny_workload(seed=43, n_layers=2, draft_layers=1, vocab=1008, block=8, qk_norm=True, kv_heads=2, dtype="bf16",
+                      n_seqs=n_seqs, taps=(0,), d=256, heads=4, hd=64, ffn=1056)
+    lens = [30 + (7 * i) % 23 for i in range(n_seqs)]
+    prompts = [p[:n] for p, n in zip(si.make_prompts(replace(w, ctx_min=60, ctx_max=60)), lens)]
+    ls = Lockstep(w, prompts, max_len=60 + 5 * 8)
+    ls.prefill()
+    ls.check_cache([0, 1], [0])
+    for i, plan in enumerate([None, [(3 * s) % 8 for s in range(n_seqs)], None]):
+        ls.step(plan=plan, step_idx=i)
+    print(f"bf16 awkward shapes ({n_seqs} sequences) stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
+def test_bf16_shapes_outside_the_mfma_attention_kernels():
+    """head_dim 32 with eight query heads per kv head (64 query rows per kv head, the most a context accepts): no
+    MFMA attention kernel for that head size, the generic split-KV kernel runs on the bf16 cache."""
+    w = tiny_workload(seed=47, n_layers=2, draft_layers=1, vocab=512, block=8, qk_norm=True, kv_heads=1, dtype="bf16",
+                      n_seqs=2, taps=(0,), d=256, heads=8, hd=32, ffn=512)
+    prompts = [p[:n] for p, n in zip(si.make_prompts(replace(w, ctx_min=90, ctx_max=90)), (90, 41))]
+    ls = Lockstep(w, prompts, max_len=90 + 4 * 8)
+    ls.prefill()
+    ls.check_cache([0, 1], [0])
+    for i, plan in enumerate([None, [7, 4], None]):
+        ls.step(plan=plan, step_idx=i)
+    print("bf16 generic attention stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
 def test_prefill_as_one_many_row_pass():
     """Prefill (Section 4.1) run as a single verify + forced commit over all prompt chunks at once (here 21 chunks,
     336 rows through the tiled GEMM) instead of chunk after chunk: caches, first tokens and the following
