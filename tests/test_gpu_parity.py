@@ -403,6 +403,21 @@ def test_empty_context_exact_fit_partial_and_empty_batch():
     print("empty-context / exact-fit stats", ls.stats)
 
 
+def test_bf16_sampling_at_temperature_0_7_matches_oracle_decisions():
+    """Speculative sampling on the small bf16 model at a temperature other than 1: Gumbel-max drafts from the fused
+    LM-head epilogue, accept tests on softmax(logits / T) of both models, residual / bonus draws."""
+    w = replace(si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=90, seed=53), temperature=0.7)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=90 + 6 * 16)
+    ls.prefill()
+    accepts = []
+    for i in range(4):
+        out, res = ls.step(temperature=0.7, step_idx=i, key=99 + i)
+        accepts += list(out["accept_len"])
+    print("bf16 sampling stats", ls.stats, accepts)
+    assert ls.stats["reseeds"] <= 2
+
+
 def test_device_status_reports_a_sequence_that_outgrew_its_pages():
     import torch
     w = tiny_workload(seed=2, n_layers=1, draft_layers=1, vocab=128, block=8, taps=(0,))
