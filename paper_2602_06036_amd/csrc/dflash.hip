@@ -895,28 +895,21 @@ int dflash_probe_hbm_read(const void* buf, size_t bytes_per_launch, int32_t laun
   if (!buf || !ms_total || launches < 1 || bytes_per_launch < 1024 || bytes_per_launch % 1024)
     return fail(nullptr, DFLASH_EINVAL, "probe_hbm_read: need a buffer, launches >= 1 and a multiple of 1024 bytes per launch");
   hipStream_t st = (hipStream_t)stream;
-  unsigned* sink = nullptr;
-  if (hipMalloc((void**)&sink, 256) != hipSuccess) return fail(nullptr, DFLASH_EHIP, "probe_hbm_read: no device memory for the sink");
-  const int rc = timed(st, ms_total, [&] {
+  return timed(st, ms_total, [&] {
     for (int i = 0; i < launches; ++i)
       hipLaunchKernelGGL(probe_read_kernel, dim3(256), dim3(256), 0, st,
-                         reinterpret_cast<const u32x4*>(static_cast<const char*>(buf) + (size_t)i * bytes_per_launch), bytes_per_launch / 1024, sink);
+                         reinterpret_cast<const u32x4*>(static_cast<const char*>(buf) + (size_t)i * bytes_per_launch), bytes_per_launch / 1024);
   });
-  (void)hipFree(sink);
-  return rc;
 }
 
 int dflash_probe_mfma(int32_t shape, int32_t workgroups, int32_t iters, float* ms, double* flops, void* stream) {
   if (!ms || !flops || workgroups < 1 || workgroups > 65536 || iters < 1 || shape < 0 || shape > 1)
     return fail(nullptr, DFLASH_EINVAL, "probe_mfma: need outputs, shape 0 or 1, 1..65536 workgroups and iters >= 1");
   hipStream_t st = (hipStream_t)stream;
-  float* out = nullptr;
-  if (hipMalloc((void**)&out, 256) != hipSuccess) return fail(nullptr, DFLASH_EHIP, "probe_mfma: no device memory for the sink");
   const int rc = timed(st, ms, [&] {
-    if (shape == 0) hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(256), 0, st, iters, out);
-    else hipLaunchKernelGGL(probe_mfma32_kernel, dim3(workgroups), dim3(256), 0, st, iters, out);
+    if (shape == 0) hipLaunchKernelGGL(probe_mfma_kernel, dim3(workgroups), dim3(256), 0, st, iters);
+    else hipLaunchKernelGGL(probe_mfma32_kernel, dim3(workgroups), dim3(256), 0, st, iters);
   });
-  (void)hipFree(out);
   *flops = (double)workgroups * 4 * iters * (shape == 0 ? 16 * (2.0 * 16 * 16 * 32) : 4 * (2.0 * 32 * 32 * 16));
   return rc;
 }

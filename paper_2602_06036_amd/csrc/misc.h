@@ -420,8 +420,11 @@ __global__ __launch_bounds__(128) void kv_copy_kernel(T* __restrict__ pool, SeqG
 }
 
 // ---- machine probes ---------------------------------------------------------------------------------
+// where the probes drop a value when an impossible condition holds, so that the compiler keeps their work
+__device__ unsigned g_probe_sink;
+
 // read-only streaming: wavefronts interleave 8 KB pieces across the whole grid
-__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ p, size_t n_chunks, unsigned* __restrict__ sink) {
+__global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict__ p, size_t n_chunks) {
   const size_t wave = ((size_t)blockIdx.x * blockDim.x + threadIdx.x) >> 6, lane = threadIdx.x & 63;
   const size_t n_waves = ((size_t)gridDim.x * blockDim.x) >> 6;
   unsigned acc = 0;
@@ -432,10 +435,10 @@ __global__ __launch_bounds__(256) void probe_read_kernel(const u32x4* __restrict
 #pragma unroll
     for (int u = 0; u < 8; ++u) acc ^= v[u][0] ^ v[u][3];
   }
-  if (acc == 0x12345677u) *sink = acc;   // keeps the loads alive; practically never true
+  if (acc == 0x12345677u) g_probe_sink = acc;   // keeps the loads alive; practically never true
 }
 
-__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __restrict__ out) {
+__global__ __launch_bounds__(256) void probe_mfma_kernel(int iters) {
   const u32x4 a = {threadIdx.x, 1u, 2u, 3u}, b = {4u, 5u, threadIdx.x, 7u};
   f32x4 acc[16];
 #pragma unroll
@@ -448,11 +451,11 @@ __global__ __launch_bounds__(256) void probe_mfma_kernel(int iters, float* __res
   float s = 0.f;
 #pragma unroll
   for (int i = 0; i < 16; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
-  if (s == 12345.678f) out[0] = s;       // keeps the MFMAs alive
+  if (s == 12345.678f) g_probe_sink = 1u;   // keeps the MFMAs alive
 }
 
 typedef float probe_f32x16 __attribute__((ext_vector_type(16)));
-__global__ __launch_bounds__(256) void probe_mfma32_kernel(int iters, float* __restrict__ out) {
+__global__ __launch_bounds__(256) void probe_mfma32_kernel(int iters) {
   const u32x4 a = {threadIdx.x, 1u, 2u, 3u}, b = {4u, 5u, threadIdx.x, 7u};
   probe_f32x16 acc[4];
 #pragma unroll
@@ -469,5 +472,5 @@ __global__ __launch_bounds__(256) void probe_mfma32_kernel(int iters, float* __r
   for (int i = 0; i < 4; ++i)
 #pragma unroll
     for (int e = 0; e < 16; ++e) s += acc[i][e];
-  if (s == 12345.678f) out[0] = s;       // keeps the MFMAs alive
+  if (s == 12345.678f) g_probe_sink = 1u;   // keeps the MFMAs alive
 }
