@@ -108,6 +108,13 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict
   const int d = threadIdx.x;
   __shared__ float wgt[64];
   __shared__ float s_L;
+  // the first PRE splits' outputs are requested before the weights are known: their loads do not depend on the
+  // (max, sum) loads, so the two memory round trips overlap instead of following each other
+  constexpr int PRE = 20;
+  float pre[PRE];
+  const float* po = part_o + (size_t)row * n_splits * hd + (d < hd ? d : 0);
+#pragma unroll
+  for (int c = 0; c < PRE; ++c) pre[c] = c < n_splits ? po[(size_t)c * hd] : 0.f;
   if (threadIdx.x < 64) {
     const int c = threadIdx.x;
     float2 ml = make_float2(-INFINITY, 0.f);
@@ -122,9 +129,11 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict
   }
   __syncthreads();
   if (d < hd) {
-    const float* po = part_o + (size_t)row * n_splits * hd + d;
     float o = 0.f;
-    int c = 0;
+#pragma unroll
+    for (int c = 0; c < PRE; ++c)
+      if (c < n_splits) o += wgt[c] * pre[c];
+    int c = PRE;
     for (; c + 4 <= n_splits; c += 4) {
       const float a0 = po[(size_t)(c + 0) * hd], a1 = po[(size_t)(c + 1) * hd], a2 = po[(size_t)(c + 2) * hd], a3 = po[(size_t)(c + 3) * hd];
       o += wgt[c] * a0;
