@@ -63,8 +63,13 @@ __global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const 
   // The first KEEP chunks of a thread stay in registers between the two passes (rows up to 8192 wide);
   // wider rows re-read the rest from where it was written
   constexpr int KEEP = 8192 / (NTHR * 4);
-  float4 keep[KEEP];
+  float4 keep[KEEP], gk[KEEP];   // the gains are requested together with the row: no extra round trip after the barrier
   float ss = 0.f;
+#pragma unroll
+  for (int c = 0; c < KEEP; ++c) {
+    const int d = (c * NTHR + (int)threadIdx.x) * 4;
+    gk[c] = d < D ? *reinterpret_cast<const float4*>(gain + d) : make_float4(0.f, 0.f, 0.f, 0.f);
+  }
 #pragma unroll
   for (int c = 0; c < KEEP; ++c) {
     const int d = (c * NTHR + (int)threadIdx.x) * 4;
@@ -90,8 +95,7 @@ __global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const 
   for (int c = 0; c < KEEP; ++c) {
     const int d = (c * NTHR + (int)threadIdx.x) * 4;
     if (d < D) {
-      const float4 v = keep[c];
-      const float4 g = *reinterpret_cast<const float4*>(gain + d);
+      const float4 v = keep[c], g = gk[c];
       Act<T>::store4(out, m, d, D, make_float4(v.x * rstd * g.x, v.y * rstd * g.y, v.z * rstd * g.z, v.w * rstd * g.w));
     }
   }
