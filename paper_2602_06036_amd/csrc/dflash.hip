@@ -463,13 +463,15 @@ struct Engine {
                          EpiArgs{arena, D, 0, nullptr, 0});
     norm(nullptr, fs, ws<float>(c->ws.fuse), reinterpret_cast<const float*>(c->dblob + c->dl.gc), ht, M, D, d.rms_eps);
     const Slab kvs = gemm(reinterpret_cast<const T*>(c->dblob + c->dl.wkv_all), ht, M, nkv, D, EPI_STORE, EpiArgs{arena, nkv, 0, nullptr, 0});
-    for (int i = 0; i < d.n_layers; ++i) {
+    {   // k-norm, RoPE and page write of all draft layers' context K/V in one launch (grid.z = layer)
       RopeArgs ra;
       ra.n_q_heads = 0; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = d.head_dim;
-      ra.q_off = 0; ra.k_off = i * 2 * kd; ra.v_off = i * 2 * kd + kd;
-      ra.qk_norm = d.qk_norm; ra.eps = d.rms_eps; ra.log_theta = log((double)d.rope_theta); ra.layer = i;
-      const char* lbase = c->dblob + c->dl.layer0 + c->dl.lo.end * i;
-      hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, 2 * d.n_kv_heads), dim3(64), 0, st, kvs.p, nkv, (const float*)nullptr,
+      ra.q_off = 0; ra.k_off = 0; ra.v_off = kd;
+      ra.qk_norm = d.qk_norm; ra.eps = d.rms_eps; ra.log_theta = log((double)d.rope_theta); ra.layer = 0;
+      ra.col_stride = 2 * kd;
+      ra.kn_stride = c->dl.lo.end / sizeof(float);     // layer records are 256-byte aligned
+      const char* lbase = c->dblob + c->dl.layer0;
+      hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, 2 * d.n_kv_heads, d.n_layers), dim3(64), 0, st, kvs.p, nkv, (const float*)nullptr,
                          reinterpret_cast<const float*>(lbase + c->dl.lo.kn), (T*)nullptr, reinterpret_cast<T*>(c->rt.draft_kv_pool),
                          geom(b), ra, kvs.ks, kvs.stride);
       check();

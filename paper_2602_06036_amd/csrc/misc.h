@@ -121,6 +121,10 @@ struct RopeArgs {
   float eps;
   double log_theta;
   int layer;                // layer index inside the pool
+  // grid.z > 1 handles several layers in one launch (the draft's context K/V at commit): layer z reads its
+  // k/v columns z * col_stride further along the input row and its k-norm gain kn_stride floats further on
+  int col_stride = 0;
+  size_t kn_stride = 0;
 };
 
 template <typename T>
@@ -128,6 +132,10 @@ __global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ 
                                                       const float* __restrict__ kn, T* __restrict__ q_out,
                                                       T* __restrict__ pool, SeqGeom geo, RopeArgs ra, int ks, size_t slab) {
   const int m = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+  ra.layer += blockIdx.z;
+  ra.k_off += blockIdx.z * ra.col_stride;
+  ra.v_off += blockIdx.z * ra.col_stride;
+  kn += blockIdx.z * ra.kn_stride;
   const int hd = ra.head_dim, half = hd >> 1;
   const int s = m / geo.block_size, slot = m % geo.block_size;
   const int pos = geo.seq_lens[s] + slot;
