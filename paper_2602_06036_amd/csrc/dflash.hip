@@ -228,6 +228,7 @@ struct dflash_ctx {
   float draft_temperature = 0.f;                       // of the last dflash_draft_block call
   int ks_force = 0;     // tiled GEMM: forces the K split where a split is allowed (tuning knob)
   int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
+  int wm_force = 0;     // tiled GEMM: 4 or 2 forces 128 or 64 activation rows per tile (testing / tuning knob)
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
@@ -581,27 +582,32 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     // K split with the least estimated time: workgroups on the busiest CU x MFMA time of one workgroup (larger
     // tiles move fewer operand bytes per flop, hence the efficiency factors; a workgroup alone on its CU has
     // nobody to hide its barriers and LDS latency behind), plus the traffic of the partial slabs.
-    struct Cand { int wn; double eff; };
-    static const Cand cands[3] = {{8, 1.0}, {6, 0.95}, {4, 0.85}};
-    const int mb = ((M + 15) / 16 + 7) / 8;
-    int best_wn = 4;
+    struct Cand { int wn, wm; double eff; };
+    static const Cand cands[6] = {{8, 4, 1.0}, {6, 4, 0.95}, {4, 4, 0.85}, {8, 2, 0.8}, {6, 2, 0.75}, {4, 2, 0.65}};
+    int best_wn = 4, best_wm = 4;
     double best = 1e30;
     for (const Cand& cd : cands) {
       if (c->tile_force && cd.wn != c->tile_force) continue;
+      if (c->wm_force && cd.wm != c->wm_force) continue;
+      const int mb = ((M + 15) / 16 + 2 * cd.wm - 1) / (2 * cd.wm);
       const int wgs = ((nt + 2 * cd.wn - 1) / (2 * cd.wn)) * mb;
       for (int k = 1; k <= kMaxKSplit; k *= 2) {
         if (k > 1 && (!split || KT / k < 8 || k * M > arena)) break;
         if (c->ks_force && split && k != c->ks_force && c->ks_force * M <= arena && KT / c->ks_force >= 8) continue;
         const int per_cu = (wgs * k + 255) / 256;
-        const double mfma_us = 32.0 * cd.wn * 4 * ((KT + k - 1) / k) / 2400.0;   // MFMA issue time of one workgroup
+        const double mfma_us = 32.0 * cd.wn * cd.wm * ((KT + k - 1) / k) / 2400.0;   // MFMA issue time of one workgroup
         const double slab_us = k > 1 ? (double)k * M * N * 8 / 4e6 : 0.0;
         const double t = per_cu * mfma_us / cd.eff * (per_cu == 1 ? 1.4 : 1.0) + slab_us;
-        if (t < best) { best = t; best_wn = cd.wn; ks = k; }
+        if (t < best) { best = t; best_wn = cd.wn; best_wm = cd.wm; ks = k; }
       }
     }
     ep.slab = (size_t)M * ep.ld;
     static const int PD = env_int("DFLASH_GEMM_PD", 2);   // tuning knob: k tiles in flight from global memory (192/128-row tiles)
-    if (best_wn == 8) launch_tiled<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);   // no registers left for a second set
+    if (best_wm == 2) {
+      if (best_wn == 8) launch_tiled<8, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      else if (best_wn == 6) launch_tiled<6, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      else launch_tiled<4, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
+    } else if (best_wn == 8) launch_tiled<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);   // no registers left for a second set
     else if (best_wn == 6 && PD == 2) launch_tiled<6, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
     else if (best_wn == 6) launch_tiled<6, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
     else if (PD == 2) launch_tiled<4, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
@@ -853,6 +859,7 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->tblob = (const char*)target_blob; c->dblob = (const char*)draft_blob; c->wsp = (char*)rt->workspace;
   c->err[0] = 0;
   c->tile_force = env_int("DFLASH_GEMM_TILE", 0);
+  c->wm_force = env_int("DFLASH_GEMM_WM", 0);
   c->ks_force = env_int("DFLASH_GEMM_KS", 0);
   c->attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {

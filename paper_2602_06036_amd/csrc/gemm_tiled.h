@@ -6,13 +6,14 @@
 // 16x32 fragment), so a k tile is staged by copying whole fragments: global -> registers (PD k tiles in flight)
 // -> one of two LDS slots; every wavefront reads the WN weight and 2*WM activation fragments of its quadrant
 // (each lane its own 16 bytes: conflict-free ds_read_b128) and issues WN*WM*2 MFMAs per k tile.
-//
-// Register schedule of a k tile: the WN weight fragments stay resident, the activation (hi, lo) pair of one
-// row band rotates through a double buffer, read one step (2*WN MFMAs) ahead.  In the last step every weight
-// fragment is re-read for the next k tile right after its last MFMA, so the LDS latency hides behind the
-// remaining MFMAs and a wavefront that is alone on its SIMD does not idle on it.  One barrier per k tile,
-// before that last step: by then every wavefront has issued all its reads of the current slot (so it can be
-// refilled with k tile t+2) and has finished writing the other slot (k tile t+1, which the last step reads).
+// Schedule of a k tile (one barrier per k tile, order pinned with scheduling barriers): barrier -> all WN + 2*WM
+// fragment reads of the k tile -> the LDS writes of the next k tile (from registers loaded PD k tiles earlier) and
+// the global loads of k tile t+1+PD -> the WN*WM*2 MFMAs.  LDS operations of a wavefront complete in order and a
+// 1 KB ds_write occupies the LDS path several times longer than a read, so the reads go first: the MFMAs wait for
+// the reads only and the writes drain behind the MFMA stream; the second workgroup on the CU fills the gaps around
+// the barrier.  (Measured with an isolated loop of the same instruction mix, two workgroups per CU: MFMAs alone
+// 2.45 PFLOP/s, with the reads 2.35, with reads and writes 1.8; the same loop fed by direct-to-LDS loads 1.9, but
+// that needs a third LDS slot, which the 192 x 128 tile does not leave room for at two workgroups per CU.)
 //
 // Workgroup order: consecutive workgroup ids go to different XCDs (round-robin dispatch), so id = 8*j + x
 // is mapped to weight band block 8*(j / m_blocks) + x and activation block j % m_blocks: the workgroups that
@@ -73,47 +74,47 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
     for (int jj = 0; jj < WM; ++jj) acc[i][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   if (kb < ke) {
-    u32x4 g[PD][PER];   // k tiles t+2 .. t+1+PD on their way from global memory while k tile t is multiplied
+    u32x4 g[PD][PER];   // k tiles t+1 .. t+PD on their way from global memory while k tile t is multiplied
     load_global(g[0], kb);
     write_lds(0, g[0]);
-    load_global(g[0], min(kb + 1, ke - 1));
-    write_lds(1, g[0]);
 #pragma unroll
-    for (int d = 0; d < PD; ++d) load_global(g[d], min(kb + 2 + d, ke - 1));
-    __syncthreads();
+    for (int d = 0; d < PD; ++d) load_global(g[d], min(kb + 1 + d, ke - 1));
 
-    u32x4 wf[WN];      // weight fragments of the current k tile
-    u32x4 ap[2][2];    // activation (hi, lo) pair of row band jj in set jj & 1
-#pragma unroll
-    for (int i = 0; i < WN; ++i) wf[i] = stage[0][wy * WN + i][lane];
-    ap[0][0] = stage[0][BNT + 2 * wx * WM][lane];
-    ap[0][1] = stage[0][BNT + 2 * wx * WM + 1][lane];
-
-    // One k tile out of LDS slot S0, refilled afterwards from register set G.  Straight-line body: past the end
-    // of the K range the prefetches read a stale slot, the refill rewrites a slot nobody reads any more and the
-    // global loads repeat the last k tile, so no branch splits the MFMA stream.
+    // One k tile out of LDS slot S0; k tile t+1 goes from register set G into the other slot meanwhile.
+    // Order inside a k tile, pinned with scheduling barriers: barrier (k tile t is complete in S0, everybody is done
+    // with the other slot) -> all fragment reads of the k tile -> the LDS writes of k tile t+1 and the global loads
+    // of k tile t+1+PD -> the MFMAs.  LDS operations of a wavefront complete in order, so the reads must be issued
+    // before the (slow) writes: the MFMAs then wait for the reads only, and the writes drain behind the MFMA stream.
+    // Straight-line body: past the end of the K range the global loads repeat the last k tile and the write fills a
+    // slot nobody reads any more.
     auto k_tile = [&](auto s0_c, auto g_c, int kt) {
       constexpr int s0 = decltype(s0_c)::value, s1 = s0 ^ 1, G = decltype(g_c)::value;
+      u32x4 wf[WN], ap[WM][2];
+      __syncthreads();
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int i = 0; i < WN; ++i) wf[i] = stage[s0][wy * WN + i][lane];
 #pragma unroll
       for (int jj = 0; jj < WM; ++jj) {
-        constexpr int last = WM - 1;
-        if (jj == last) __syncthreads();
-        const int slot = jj == last ? s1 : s0, band = jj == last ? 0 : jj + 1;
-        ap[(jj + 1) & 1][0] = stage[slot][BNT + 2 * (wx * WM + band)][lane];
-        ap[(jj + 1) & 1][1] = stage[slot][BNT + 2 * (wx * WM + band) + 1][lane];
+        ap[jj][0] = stage[s0][BNT + 2 * (wx * WM + jj)][lane];
+        ap[jj][1] = stage[s0][BNT + 2 * (wx * WM + jj) + 1][lane];
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      write_lds(s1, g[G]);
+      load_global(g[G], min(kt + 1 + PD, ke - 1));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int jj = 0; jj < WM; ++jj) {
 #pragma unroll
         for (int i = 0; i < WN; ++i)
-          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj & 1][0]),
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj][0]),
                                                                acc[i][jj], 0, 0, 0);
 #pragma unroll
-        for (int i = 0; i < WN; ++i) {
-          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj & 1][1]),
+        for (int i = 0; i < WN; ++i)
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj][1]),
                                                                acc[i][jj], 0, 0, 0);
-          if (jj == last) wf[i] = stage[s1][wy * WN + i][lane];
-        }
       }
-      write_lds(s0, g[G]);
-      load_global(g[G], min(kt + 2 + PD, ke - 1));
+      __builtin_amdgcn_sched_barrier(0);
     };
     using I0 = std::integral_constant<int, 0>;
     using I1 = std::integral_constant<int, 1>;

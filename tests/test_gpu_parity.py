@@ -218,13 +218,15 @@ def test_small_bf16_model_steps_and_cache():
     assert ls.stats["reseeds"] <= 1
 
 
-@pytest.mark.parametrize("tile", ["0", "8", "6"])
-def test_small_bf16_many_rows_tiled_gemm(tile, monkeypatch):
+@pytest.mark.parametrize("tile,rows", [("0", "0"), ("8", "4"), ("6", "4"), ("8", "2"), ("6", "2"), ("4", "2")])
+def test_small_bf16_many_rows_tiled_gemm(tile, rows, monkeypatch):
     """The same small bf16 model with 10 sequences: 160 activation rows per step go through the LDS-staged
     GEMM for many rows (two activation blocks, the second with a ragged tail); the prefill chunks with 6
     sequences still alive exercise one partly filled block.  Run with the tile shapes the dispatcher picks at
-    this size and forced to 256 x 128 and 192 x 128, the shapes of the large matrices."""
+    this size and forced to 256 x 128 and 192 x 128, the shapes of the large matrices, and to the 64-row variants
+    used for a few hundred activation rows."""
     monkeypatch.setenv("DFLASH_GEMM_TILE", tile)
+    monkeypatch.setenv("DFLASH_GEMM_WM", rows)
     w = si.small_bf16_workload(n_seqs=10, ctx_min=17, ctx_max=90, seed=23)
     prompts = si.make_prompts(w)
     ls = Lockstep(w, prompts, max_len=90 + 4 * 16)
