@@ -26,8 +26,10 @@ struct AttnLane {          // per-lane constants of the kernel below
   int c0, c1, n_tok, last_vis, g, lane, kvh;
 };
 
-// issues the loads of page pair (pa, pb); pb < 0 means the chunk ends after page A
-template <int HD>
+// issues the loads of page pair (pa, pb); pb < 0 means the chunk ends after page A.  STREAM: the fragments are
+// used by this wavefront only (key-split kernel), so they are loaded non-temporally and do not displace anything
+// from the caches; the row-split kernel's four wavefronts read the same fragments and want them cached.
+template <int HD, bool STREAM = false>
 __device__ __forceinline__ void attn_load_pages(KvFrags<HD>& f, int pa, int pb, bool has_b, const bf16_t* __restrict__ pool,
                                                 const SeqGeom& geo, const AttnArgs& aa, const AttnLane& L) {
   f.ok_a = pa >= 0 && pa < geo.n_pages;
@@ -38,14 +40,19 @@ __device__ __forceinline__ void attn_load_pages(KvFrags<HD>& f, int pa, int pb, 
   const bf16_t* kb = pool + kv_head_base(aa.layer, geo.n_pages, pb, aa.n_kv_heads, L.kvh, HD);
 #pragma unroll
   for (int kt = 0; kt < HD / 32; ++kt) {
-    f.ka[kt] = reinterpret_cast<const u32x4*>(ka)[kt * 64 + L.lane];
-    f.kb[kt] = reinterpret_cast<const u32x4*>(kb)[kt * 64 + L.lane];
+    const u32x4* pa4 = reinterpret_cast<const u32x4*>(ka) + kt * 64 + L.lane;
+    const u32x4* pb4 = reinterpret_cast<const u32x4*>(kb) + kt * 64 + L.lane;
+    f.ka[kt] = STREAM ? __builtin_nontemporal_load(pa4) : *pa4;
+    f.kb[kt] = STREAM ? __builtin_nontemporal_load(pb4) : *pb4;
   }
 #pragma unroll
   for (int dt = 0; dt < HD / 16; ++dt) {
-    const uint2 a = reinterpret_cast<const uint2*>(ka + DF_PAGE * HD)[dt * 64 + L.lane];
-    const uint2 b = reinterpret_cast<const uint2*>(kb + DF_PAGE * HD)[dt * 64 + L.lane];
-    f.v[dt] = (u32x4){a.x, a.y, b.x, b.y};
+    typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
+    const u32x2* pa2 = reinterpret_cast<const u32x2*>(ka + DF_PAGE * HD) + dt * 64 + L.lane;
+    const u32x2* pb2 = reinterpret_cast<const u32x2*>(kb + DF_PAGE * HD) + dt * 64 + L.lane;
+    const u32x2 a = STREAM ? __builtin_nontemporal_load(pa2) : *pa2;
+    const u32x2 b = STREAM ? __builtin_nontemporal_load(pb2) : *pb2;
+    f.v[dt] = (u32x4){a[0], a[1], b[0], b[1]};
   }
 }
 
@@ -274,16 +281,18 @@ __device__ __forceinline__ void attn_process_pair_wide(KvFrags<HD>& f, int base,
         if (!(f.ok_b && pa0 + 16 + i < L.c1 && pa0 + 16 + i <= last_vis[rb])) v[4 + i] = -INFINITY;
       }
     }
-    float mx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7])));
-    mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
-    mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
-    mx *= scale2;   // the maximum commutes with the positive scale
-    // Lazy reference maximum: m_run only moves when the true maximum has grown by more than 8 (a factor 256),
+    // Lazy reference maximum: m_run only moves when the true row maximum has grown by more than 8 (a factor 256),
     // so the accumulators (which live in the MFMA accumulation registers, out of reach of plain ALU ops) are
-    // rescaled once or twice per sweep instead of after every pair.  exp2(v - m_run) <= 256 meanwhile.
+    // rescaled once or twice per sweep instead of after every pair.  exp2(v - m_run) <= 256 meanwhile.  A row's
+    // maximum has grown that much exactly when the maximum of one of its four lanes has, so the common case is
+    // decided from each lane's own scores and the cross-lane exchange happens only inside the rare branch.
+    const float lmx = fmaxf(fmaxf(fmaxf(v[0], v[1]), fmaxf(v[2], v[3])), fmaxf(fmaxf(v[4], v[5]), fmaxf(v[6], v[7]))) * scale2;
     const float m_old = m_run[rb];
-    const bool grow = mx > m_old + 8.f;
-    if (__builtin_amdgcn_ballot_w64(grow) != 0ull) {
+    if (__builtin_amdgcn_ballot_w64(lmx > m_old + 8.f) != 0ull) {
+      float mx = lmx;   // the maximum commutes with the positive scale
+      mx = fmaxf(mx, __shfl_xor(mx, 16, 64));
+      mx = fmaxf(mx, __shfl_xor(mx, 32, 64));
+      const bool grow = mx > m_old + 8.f;
       const float corr = grow ? (m_old == -INFINITY ? 0.f : exp2f(m_old - mx)) : 1.f;
       l_run[rb] *= corr;
       // through LDS: the accumulators can be stored from and loaded into the accumulation registers directly, so
@@ -396,7 +405,7 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
     // the same for every lane: tell the compiler, so addresses and validity branches stay scalar
     const int pa = __builtin_amdgcn_readfirstlane(s_pages[2 * p]);
     const int pb = has_b ? __builtin_amdgcn_readfirstlane(s_pages[2 * p + 1]) : pa;
-    attn_load_pages<HD>(f, pa, pb, has_b, pool, geo, aa, L);
+    attn_load_pages<HD, true>(f, pa, pb, has_b, pool, geo, aa, L);
   };
   // Two fragment sets per wavefront; no conditional load inside the loop (see the kernel above), tail peeled off.
   if (wave < n_pairs) {
