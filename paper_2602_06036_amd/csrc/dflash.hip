@@ -500,15 +500,15 @@ void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N,
   }
 }
 
-template <int WN, int WM, int PD>
+template <int WN, int WM, int PD, int NS = 2>
 void launch_tiled(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
   const int n_blocks = (N / 16 + 2 * WN - 1) / (2 * WN), m_blocks = ((M + 15) / 16 + 2 * WM - 1) / (2 * WM);
   const dim3 grid(((n_blocks + 7) / 8) * 8 * m_blocks, ks), block(256);
   g_launch_parts = n_blocks;
   if (epi == EPI_SWIGLU)
-    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_SWIGLU, NS>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
   else
-    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_STORE>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_STORE, NS>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
 }
 
 inline int gemm_class(int epi, int N, int vocab) { return (epi == EPI_STORE && N == vocab) ? DFLASH_PROF_GEMM_LMHEAD : epi; }
@@ -585,6 +585,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     struct Cand { int wn, wm; double eff; };
     static const Cand cands[6] = {{8, 4, 1.0}, {6, 4, 0.95}, {4, 4, 0.85}, {8, 2, 0.8}, {6, 2, 0.75}, {4, 2, 0.65}};
     int best_wn = 4, best_wm = 4;
+    bool best_solo = false;
     double best = 1e30;
     for (const Cand& cd : cands) {
       if (c->tile_force && cd.wn != c->tile_force) continue;
@@ -597,17 +598,28 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
         const int per_cu = (wgs * k + 255) / 256;
         const double mfma_us = 32.0 * cd.wn * cd.wm * ((KT + k - 1) / k) / 2400.0;   // MFMA issue time of one workgroup
         const double slab_us = k > 1 ? (double)k * M * N * 8 / 4e6 : 0.0;
-        const double t = per_cu * mfma_us / cd.eff * (per_cu == 1 ? 1.4 : 1.0) + slab_us;
-        if (t < best) { best = t; best_wn = cd.wn; best_wm = cd.wm; ks = k; }
+        // a workgroup alone on its CU has nobody to hide its barriers behind; the 128-row tiles then run as a
+        // three-slot direct-to-LDS ring (they have the LDS to themselves), which loses less
+        const bool solo = per_cu == 1, solo_ring = solo && !split && cd.wm == 4 && cd.wn >= 6;   // measured: only pays where K is not split
+        const double t = per_cu * mfma_us / cd.eff * (solo ? (solo_ring ? 1.15 : 1.4) : 1.0) + slab_us;
+        if (t < best) { best = t; best_wn = cd.wn; best_wm = cd.wm; ks = k; best_solo = solo_ring; }
       }
     }
     ep.slab = (size_t)M * ep.ld;
     static const int PD = env_int("DFLASH_GEMM_PD", 2);   // tuning knob: k tiles in flight from global memory (192/128-row tiles)
-    if (best_wm == 2) {
+    static const int RING = env_int("DFLASH_GEMM_RING", 1) == 1;   // tuning knob: 2 (or any other value) = register-staged variant for the small tiles
+    if (best_wm == 2 && RING) {
+      if (best_wn == 8) launch_tiled<8, 2, 1, 3>(st, W, A, M, N, K, kepi, ep, ks);
+      else if (best_wn == 6) launch_tiled<6, 2, 1, 3>(st, W, A, M, N, K, kepi, ep, ks);
+      else launch_tiled<4, 2, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
+    } else if (best_wm == 2) {
       if (best_wn == 8) launch_tiled<8, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else if (best_wn == 6) launch_tiled<6, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_tiled<4, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
-    } else if (best_wn == 8) launch_tiled<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);   // no registers left for a second set
+    } else if (best_wn == 4 && RING) launch_tiled<4, 4, 1, 3>(st, W, A, M, N, K, kepi, ep, ks);
+    else if (best_wn == 6 && best_solo && RING) launch_tiled<6, 4, 1, 3>(st, W, A, M, N, K, kepi, ep, ks);
+    else if (best_wn == 8 && best_solo && RING) launch_tiled<8, 4, 1, 3>(st, W, A, M, N, K, kepi, ep, ks);
+    else if (best_wn == 8) launch_tiled<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);   // no registers left for a second set
     else if (best_wn == 6 && PD == 2) launch_tiled<6, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
     else if (best_wn == 6) launch_tiled<6, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
     else if (PD == 2) launch_tiled<4, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);

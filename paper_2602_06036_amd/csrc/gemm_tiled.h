@@ -21,14 +21,14 @@
 #pragma once
 #include "gemm.h"
 
-template <int WN, int WM, int PD, int EPI>
-__global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W,
+template <int WN, int WM, int PD, int EPI, int NS = 2>
+__global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W,
                                                                                 const bf16_t* __restrict__ A, int M, int N, int K,
                                                                                 int n_blocks, int m_blocks, EpiArgs ep) {
   constexpr int BNT = 2 * WN, BMT = 2 * WM;        // fragments of a stage: BNT weight + 2*BMT activation (hi, lo)
   constexpr int FR = BNT + 2 * BMT, PER = FR / 4;  // fragments copied by each wavefront
-  static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % 4 == 0 && (PD == 1 || PD == 2), "tile shape");
-  __shared__ u32x4 stage[2][FR][64];
+  static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % 4 == 0 && (PD == 1 || PD == 2) && NS >= 2 && NS * FR <= 160, "tile shape");
+  __shared__ u32x4 stage[NS][FR][64];
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wy = wave >> 1, wx = wave & 1;
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
@@ -74,6 +74,7 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
     for (int jj = 0; jj < WM; ++jj) acc[i][jj] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   if (kb < ke) {
+   if constexpr (NS == 2) {
     u32x4 g[PD][PER];   // k tiles t+1 .. t+PD on their way from global memory while k tile t is multiplied
     load_global(g[0], kb);
     write_lds(0, g[0]);
@@ -125,6 +126,59 @@ __global__ __launch_bounds__(256, 2) void gemm_bf16_tiled_kernel(const bf16_t* _
       k_tile(I1{}, IG{}, kt + 1);
     }
     if (kt < ke) k_tile(I0{}, I0{}, kt);
+   } else {
+    // ---- ring of NS LDS slots filled by direct-to-LDS loads (global_load_lds_dwordx4: every lane's 16 bytes go
+    // straight to consecutive LDS addresses, which is exactly a fragment in operand order) -------------------
+    // No staging registers, no ds_write (a 1 KB ds_write holds up the wavefront's SIMD several times longer than the
+    // issue of such a load), k tiles t+1 .. t+NS-1 in flight while k tile t is multiplied.  The loads are inline
+    // assembly so that the compiler does not count them: it would otherwise wait for ALL of them before every LDS
+    // read.  Completion is tracked by hand: each wavefront issues PER loads per k tile, in order, so "at most
+    // PER*(NS-2) outstanding" means its share of k tile t has landed; the barrier extends that to the whole
+    // workgroup and also says that everybody is done reading k tile t-1, whose slot is refilled next.
+    const unsigned lds_base = (unsigned)(size_t)&stage[0][0][0];
+    auto dma_tile = [&](int slot, int kt) {
+#pragma unroll
+      for (int i = 0; i < PER; ++i) {
+        const u32x4* src = g_base[i] + g_off[i] + (size_t)kt * g_step[i];
+        const unsigned dst = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)((slot * FR + wave * PER + i) * 1024));
+        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+      }
+    };
+#pragma unroll
+    for (int d = 0; d < NS - 1; ++d) dma_tile(d, min(kb + d, ke - 1));
+    int slot = 0;
+    for (int kt = kb; kt < ke; ++kt) {
+      asm volatile("s_waitcnt vmcnt(%0)" ::"n"(PER * (NS - 2)) : "memory");
+      __builtin_amdgcn_s_barrier();
+      asm volatile("" ::: "memory");
+      u32x4 wf[WN], ap[WM][2];
+      const u32x4* sp = &stage[0][0][0] + (size_t)slot * (FR * 64) + lane;
+#pragma unroll
+      for (int i = 0; i < WN; ++i) wf[i] = sp[(wy * WN + i) * 64];
+#pragma unroll
+      for (int jj = 0; jj < WM; ++jj) {
+        ap[jj][0] = sp[(BNT + 2 * (wx * WM + jj)) * 64];
+        ap[jj][1] = sp[(BNT + 2 * (wx * WM + jj) + 1) * 64];
+      }
+      // past the end of the K range the last k tile is fetched again into a slot nobody reads any more
+      dma_tile(slot == 0 ? NS - 1 : slot - 1, min(kt + NS - 1, ke - 1));
+      __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+      for (int jj = 0; jj < WM; ++jj) {
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj][0]),
+                                                               acc[i][jj], 0, 0, 0);
+#pragma unroll
+        for (int i = 0; i < WN; ++i)
+          acc[i][jj] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, wf[i]), __builtin_bit_cast(bf16x8, ap[jj][1]),
+                                                               acc[i][jj], 0, 0, 0);
+      }
+      __builtin_amdgcn_sched_barrier(0);
+      slot = slot == NS - 1 ? 0 : slot + 1;
+    }
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");   // nothing may still be on its way into LDS when the slots are reused or released
+   }
   }
 
   // lane l holds y[m = band*16 + l%16][n = tile*16 + 4*(l/16) .. +3]

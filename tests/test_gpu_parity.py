@@ -218,7 +218,7 @@ def test_small_bf16_model_steps_and_cache():
     assert ls.stats["reseeds"] <= 1
 
 
-@pytest.mark.parametrize("tile,rows", [("0", "0"), ("8", "4"), ("6", "4"), ("8", "2"), ("6", "2"), ("4", "2")])
+@pytest.mark.parametrize("tile,rows", [("0", "0"), ("8", "4"), ("6", "4"), ("4", "4"), ("8", "2"), ("6", "2"), ("4", "2")])
 def test_small_bf16_many_rows_tiled_gemm(tile, rows, monkeypatch):
     """The same small bf16 model with 10 sequences: 160 activation rows per step go through the LDS-staged
     GEMM for many rows (two activation blocks, the second with a ragged tail); the prefill chunks with 6
