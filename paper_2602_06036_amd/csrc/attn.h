@@ -95,13 +95,14 @@ __global__ __launch_bounds__(256) void attn_partial_simple_kernel(const T* __res
 }
 
 // ------------------------------------------------------------------------------------------------
-// Merge of the splits in ascending split order; grid (M*Hq), block 128 (one thread per head dim).
+// Merge of the splits in ascending split order, few rows (M < 64, where the number of workgroups matters more than
+// the shape of the stores): grid (M*Hq), block 128 (one thread per head dim).
 // The (max, sum) pairs are fetched by the first wavefront with one load per split, the partial
 // outputs with independent loads four at a time, so the kernel is not a chain of dependent loads.
 // Output as GEMM activation operand (Act<T>), row length Hq*hd.  n_splits <= 64.
 // ------------------------------------------------------------------------------------------------
 template <typename T>
-__global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
+__global__ __launch_bounds__(128) void attn_merge_rows_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
                                                          T* __restrict__ out, int n_q_heads, int hd, int n_splits) {
   const int row = blockIdx.x;  // m*Hq + hq
   const int m = row / n_q_heads, hq = row % n_q_heads;
@@ -144,5 +145,74 @@ __global__ __launch_bounds__(128) void attn_merge_kernel(const float* __restrict
     for (; c < n_splits; ++c) o += wgt[c] * po[(size_t)c * hd];
     const float L = s_L;
     Act<T>::store(out, m, hq * hd + d, n_q_heads * hd, L > 0.f ? o / L : 0.f);
+  }
+}
+
+// ------------------------------------------------------------------------------------------------
+// Merge of the splits in ascending split order.  One workgroup per (band of 16 rows, query head): thread
+// (r = tid % 16, c = tid / 16) owns 4 head dims of row r, so that the 16 rows of a band write one contiguous piece
+// of the operand tile (the band's rows are interleaved inside a tile) instead of scattered 2-byte stores.
+// grid (ceil(M/16), Hq), block 16 * hd/4.  The (max, sum) pairs of a row are fetched by one wavefront with one
+// load per split; the partial outputs are requested before the weights are known (their loads do not depend on
+// the (max, sum) loads, so the two memory round trips overlap).  Output as GEMM activation operand (Act<T>), row
+// length Hq*hd.  n_splits <= 64.
+// ------------------------------------------------------------------------------------------------
+template <typename T>
+__global__ __launch_bounds__(512) void attn_merge_kernel(const float* __restrict__ part_o, const float2* __restrict__ part_ml,
+                                                         T* __restrict__ out, int n_q_heads, int hd, int n_splits, int M) {
+  const int r = threadIdx.x & 15, c = threadIdx.x >> 4, hq = blockIdx.y;
+  const int m_raw = blockIdx.x * 16 + r;
+  const bool live = m_raw < M;
+  const int m = live ? m_raw : M - 1;
+  __shared__ float wgt[16][64];
+  __shared__ float s_L[16];
+  constexpr int PRE = 8;
+  float4 pre[PRE];
+  const float* po = part_o + ((size_t)m * n_q_heads + hq) * n_splits * hd + c * 4;
+#pragma unroll
+  for (int i = 0; i < PRE; ++i) pre[i] = i < n_splits ? *reinterpret_cast<const float4*>(po + (size_t)i * hd) : make_float4(0.f, 0.f, 0.f, 0.f);
+  {
+    const int lane = threadIdx.x & 63, wave = threadIdx.x >> 6, n_waves = blockDim.x >> 6;
+    for (int rr = wave; rr < 16; rr += n_waves) {
+      const int mm = min(blockIdx.x * 16 + rr, M - 1);
+      float2 ml = make_float2(-INFINITY, 0.f);
+      if (lane < n_splits) ml = part_ml[((size_t)mm * n_q_heads + hq) * n_splits + lane];
+      const float mx = wave_reduce_max(ml.y > 0.f ? ml.x : -INFINITY);
+      const float w = (ml.y > 0.f) ? expf(ml.x - mx) : 0.f;
+      wgt[rr][lane] = w;
+      // sum in ascending split order (fixed order, independent of the wavefront reduction tree)
+      float L = 0.f;
+      for (int i = 0; i < n_splits; ++i) L += __shfl(ml.y * w, i, 64);
+      if (lane == 0) s_L[rr] = L;
+    }
+  }
+  __syncthreads();
+  float4 o = make_float4(0.f, 0.f, 0.f, 0.f);
+#pragma unroll
+  for (int i = 0; i < PRE; ++i)
+    if (i < n_splits) {
+      const float w = wgt[r][i];
+      o.x += w * pre[i].x; o.y += w * pre[i].y; o.z += w * pre[i].z; o.w += w * pre[i].w;
+    }
+  int i = PRE;
+  for (; i + 4 <= n_splits; i += 4) {
+    float4 a[4];
+#pragma unroll
+    for (int u = 0; u < 4; ++u) a[u] = *reinterpret_cast<const float4*>(po + (size_t)(i + u) * hd);
+#pragma unroll
+    for (int u = 0; u < 4; ++u) {
+      const float w = wgt[r][i + u];
+      o.x += w * a[u].x; o.y += w * a[u].y; o.z += w * a[u].z; o.w += w * a[u].w;
+    }
+  }
+  for (; i < n_splits; ++i) {
+    const float4 a = *reinterpret_cast<const float4*>(po + (size_t)i * hd);
+    const float w = wgt[r][i];
+    o.x += w * a.x; o.y += w * a.y; o.z += w * a.z; o.w += w * a.w;
+  }
+  if (live) {
+    const float L = s_L[r];
+    Act<T>::store4(out, m, hq * hd + c * 4, n_q_heads * hd,
+                   L > 0.f ? make_float4(o.x / L, o.y / L, o.z / L, o.w / L) : make_float4(0.f, 0.f, 0.f, 0.f));
   }
 }

@@ -38,21 +38,31 @@ __device__ __forceinline__ void attn_load_pages(KvFrags<HD>& f, int pa, int pb, 
   if (!f.ok_b) pb = pa;
   const bf16_t* ka = pool + kv_head_base(aa.layer, geo.n_pages, pa, aa.n_kv_heads, L.kvh, HD);
   const bf16_t* kb = pool + kv_head_base(aa.layer, geo.n_pages, pb, aa.n_kv_heads, L.kvh, HD);
-#pragma unroll
-  for (int kt = 0; kt < HD / 32; ++kt) {
-    const u32x4* pa4 = reinterpret_cast<const u32x4*>(ka) + kt * 64 + L.lane;
-    const u32x4* pb4 = reinterpret_cast<const u32x4*>(kb) + kt * 64 + L.lane;
-    f.ka[kt] = STREAM ? __builtin_nontemporal_load(pa4) : *pa4;
-    f.kb[kt] = STREAM ? __builtin_nontemporal_load(pb4) : *pb4;
-  }
-#pragma unroll
-  for (int dt = 0; dt < HD / 16; ++dt) {
+  if constexpr (STREAM) {
     typedef unsigned int u32x2 __attribute__((ext_vector_type(2)));
-    const u32x2* pa2 = reinterpret_cast<const u32x2*>(ka + DF_PAGE * HD) + dt * 64 + L.lane;
-    const u32x2* pb2 = reinterpret_cast<const u32x2*>(kb + DF_PAGE * HD) + dt * 64 + L.lane;
-    const u32x2 a = STREAM ? __builtin_nontemporal_load(pa2) : *pa2;
-    const u32x2 b = STREAM ? __builtin_nontemporal_load(pb2) : *pb2;
-    f.v[dt] = (u32x4){a[0], a[1], b[0], b[1]};
+#pragma unroll
+    for (int kt = 0; kt < HD / 32; ++kt) {
+      f.ka[kt] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(ka) + kt * 64 + L.lane);
+      f.kb[kt] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kb) + kt * 64 + L.lane);
+    }
+#pragma unroll
+    for (int dt = 0; dt < HD / 16; ++dt) {
+      const u32x2 a = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(ka + DF_PAGE * HD) + dt * 64 + L.lane);
+      const u32x2 b = __builtin_nontemporal_load(reinterpret_cast<const u32x2*>(kb + DF_PAGE * HD) + dt * 64 + L.lane);
+      f.v[dt] = (u32x4){a[0], a[1], b[0], b[1]};
+    }
+  } else {
+#pragma unroll
+    for (int kt = 0; kt < HD / 32; ++kt) {
+      f.ka[kt] = reinterpret_cast<const u32x4*>(ka)[kt * 64 + L.lane];
+      f.kb[kt] = reinterpret_cast<const u32x4*>(kb)[kt * 64 + L.lane];
+    }
+#pragma unroll
+    for (int dt = 0; dt < HD / 16; ++dt) {
+      const uint2 a = reinterpret_cast<const uint2*>(ka + DF_PAGE * HD)[dt * 64 + L.lane];
+      const uint2 b = reinterpret_cast<const uint2*>(kb + DF_PAGE * HD)[dt * 64 + L.lane];
+      f.v[dt] = (u32x4){a.x, a.y, b.x, b.y};
+    }
   }
 }
 

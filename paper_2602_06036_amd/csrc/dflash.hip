@@ -357,7 +357,7 @@ struct Engine {
     ra.n_q_heads = m.n_q_heads; ra.n_kv_heads = m.n_kv_heads; ra.head_dim = m.head_dim;
     ra.q_off = 0; ra.k_off = qd; ra.v_off = qd + kd;
     ra.qk_norm = m.qk_norm; ra.eps = m.rms_eps; ra.log_theta = log((double)m.rope_theta); ra.layer = l;
-    hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, m.n_q_heads + 2 * m.n_kv_heads), dim3(64), 0, st, qs.p, nqkv,
+    hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, (m.n_q_heads + 2 * m.n_kv_heads + 3) / 4), dim3(256), 0, st, qs.p, nqkv,
                        reinterpret_cast<const float*>(lbase + lo.qn), reinterpret_cast<const float*>(lbase + lo.kn), q, pool,
                        geom(b), ra, qs.ks, qs.stride);
     check();
@@ -472,7 +472,7 @@ struct Engine {
       ra.col_stride = 2 * kd;
       ra.kn_stride = c->dl.lo.end / sizeof(float);     // layer records are 256-byte aligned
       const char* lbase = c->dblob + c->dl.layer0;
-      hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, 2 * d.n_kv_heads, d.n_layers), dim3(64), 0, st, kvs.p, nkv, (const float*)nullptr,
+      hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, (2 * d.n_kv_heads + 3) / 4, d.n_layers), dim3(256), 0, st, kvs.p, nkv, (const float*)nullptr,
                          reinterpret_cast<const float*>(lbase + c->dl.lo.kn), (T*)nullptr, reinterpret_cast<T*>(c->rt.draft_kv_pool),
                          geom(b), ra, kvs.ks, kvs.stride);
       check();
@@ -677,8 +677,12 @@ void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const 
   }
   {
     ProfScope prof(c, st, DFLASH_PROF_ATTN_MERGE, 0.0);
-    hipLaunchKernelGGL(attn_merge_kernel<T>, dim3(M * m.n_q_heads), dim3(128), 0, st, part_o, part_ml, ws<T>(c->ws.o), m.n_q_heads,
-                       m.head_dim, p.n_splits);
+    if (M < 64)
+      hipLaunchKernelGGL(attn_merge_rows_kernel<T>, dim3(M * m.n_q_heads), dim3(128), 0, st, part_o, part_ml, ws<T>(c->ws.o), m.n_q_heads,
+                         m.head_dim, p.n_splits);
+    else
+      hipLaunchKernelGGL(attn_merge_kernel<T>, dim3((M + 15) / 16, m.n_q_heads), dim3(16 * (m.head_dim / 4)), 0, st, part_o, part_ml,
+                         ws<T>(c->ws.o), m.n_q_heads, m.head_dim, p.n_splits, M);
     check();
   }
 }

@@ -108,7 +108,7 @@ __global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const 
 }
 
 // ---- q/k RMSNorm + RoPE + cache write ------------------------------------------------------------
-// One wavefront per (row m, head); lane i owns the rotate-half pair (i, i + hd/2) [hd <= 128].
+// One wavefront per (row m, head), four heads per workgroup; lane i owns the rotate-half pair (i, i + hd/2) [hd <= 128].
 // Input row: fp32 [.. q heads | k heads | v heads ..] starting at in + m*in_ld, given as `ks` partial
 // slabs (K ranges of the producing GEMM) `slab` elements apart that are added in ascending order.
 // q heads -> q_out [M, Hq, hd] row-major storage type; k/v heads -> page of position seq_len + slot.
@@ -128,10 +128,11 @@ struct RopeArgs {
 };
 
 template <typename T>
-__global__ __launch_bounds__(64) void qkv_post_kernel(const float* __restrict__ in, int in_ld, const float* __restrict__ qn,
-                                                      const float* __restrict__ kn, T* __restrict__ q_out,
-                                                      T* __restrict__ pool, SeqGeom geo, RopeArgs ra, int ks, size_t slab) {
-  const int m = blockIdx.x, head = blockIdx.y, lane = threadIdx.x;
+__global__ __launch_bounds__(256) void qkv_post_kernel(const float* __restrict__ in, int in_ld, const float* __restrict__ qn,
+                                                       const float* __restrict__ kn, T* __restrict__ q_out,
+                                                       T* __restrict__ pool, SeqGeom geo, RopeArgs ra, int ks, size_t slab) {
+  const int m = blockIdx.x, head = blockIdx.y * 4 + (int)(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (head >= ra.n_q_heads + 2 * ra.n_kv_heads) return;   // no barrier in this kernel
   ra.layer += blockIdx.z;
   ra.k_off += blockIdx.z * ra.col_stride;
   ra.v_off += blockIdx.z * ra.col_stride;
