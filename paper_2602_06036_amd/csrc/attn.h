@@ -95,7 +95,7 @@ __global__ __launch_bounds__(256) void attn_partial_simple_kernel(const T* __res
 }
 
 // ------------------------------------------------------------------------------------------------
-// Merge of the splits in ascending split order, few rows (M < 64, where the number of workgroups matters more than
+// Merge of the splits in ascending split order, few rows (M < 128, where the number of workgroups matters more than
 // the shape of the stores): grid (M*Hq), block 128 (one thread per head dim).
 // The (max, sum) pairs are fetched by the first wavefront with one load per split, the partial
 // outputs with independent loads four at a time, so the kernel is not a chain of dependent loads.
