@@ -146,7 +146,7 @@ inline int arena_rows(int max_rows) { return std::max(1024, 4 * max_rows); }
 constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row in the argmax
 
 struct Workspace {
-  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, total;
+  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, rope_t, rope_d, total;
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
   const size_t es = esize(t.dtype);
@@ -189,6 +189,8 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.stats_p = take((size_t)M * 8);
   w.stats_q = take((size_t)M * 8);
   w.amax = take((size_t)M * std::max(ARGMAX_CHUNKS, t.vocab / 16 + 1) * 8);   // one partial per weight row band at most
+  w.rope_t = take((size_t)M * (t.head_dim / 2) * 8);   // rotary tables of the call's rows (target, draft)
+  w.rope_d = take((size_t)M * (d.head_dim / 2) * 8);
   w.total = off;
   return w;
 }
@@ -356,7 +358,8 @@ struct Engine {
     RopeArgs ra;
     ra.n_q_heads = m.n_q_heads; ra.n_kv_heads = m.n_kv_heads; ra.head_dim = m.head_dim;
     ra.q_off = 0; ra.k_off = qd; ra.v_off = qd + kd;
-    ra.qk_norm = m.qk_norm; ra.eps = m.rms_eps; ra.log_theta = log((double)m.rope_theta); ra.layer = l;
+    ra.qk_norm = m.qk_norm; ra.eps = m.rms_eps; ra.layer = l;
+    ra.rope = ws<float2>(&m == &c->t ? c->ws.rope_t : c->ws.rope_d);
     hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, (m.n_q_heads + 2 * m.n_kv_heads + 3) / 4), dim3(256), 0, st, qs.p, nqkv,
                        reinterpret_cast<const float*>(lbase + lo.qn), reinterpret_cast<const float*>(lbase + lo.kn), q, pool,
                        geom(b), ra, qs.ks, qs.stride);
@@ -392,7 +395,8 @@ struct Engine {
     hipLaunchKernelGGL(build_block_kernel, dim3((M + 255) / 256), dim3(256), 0, st, b->anchor, draft_tokens, S, B, c->rt.mask_token_id);
     check();
     hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), draft_tokens,
-                       ws<float>(c->ws.h), d.d_model, d.vocab, status());
+                       ws<float>(c->ws.h), d.d_model, d.vocab, status(), b->seq_lens, B,
+                       RopeTab{ws<float2>(c->ws.rope_d), log((double)d.rope_theta), d.head_dim}, RopeTab{nullptr, 0.0, 0});
     check();
     for (int i = 0; i < d.n_layers; ++i)
       layer(d, c->dblob + c->dl.layer0 + c->dl.lo.end * i, c->dl.lo, reinterpret_cast<T*>(c->rt.draft_kv_pool), i, b, false);
@@ -414,8 +418,11 @@ struct Engine {
   int verify(const dflash_batch* b, const int32_t* tokens, int32_t* tgt_argmax, float* logits_out) {
     const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
     const dflash_dims& t = c->t;
+    // the draft's table is for the context K/V rows that the commit of this verification will project
     hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), tokens,
-                       ws<float>(c->ws.h), t.d_model, t.vocab, status());
+                       ws<float>(c->ws.h), t.d_model, t.vocab, status(), b->seq_lens, B,
+                       RopeTab{ws<float2>(c->ws.rope_t), log((double)t.rope_theta), t.head_dim},
+                       RopeTab{ws<float2>(c->ws.rope_d), log((double)c->d.rope_theta), c->d.head_dim});
     check();
     int tap = 0;
     for (int l = 0; l < t.n_layers; ++l) {
@@ -468,7 +475,8 @@ struct Engine {
       RopeArgs ra;
       ra.n_q_heads = 0; ra.n_kv_heads = d.n_kv_heads; ra.head_dim = d.head_dim;
       ra.q_off = 0; ra.k_off = 0; ra.v_off = kd;
-      ra.qk_norm = d.qk_norm; ra.eps = d.rms_eps; ra.log_theta = log((double)d.rope_theta); ra.layer = 0;
+      ra.qk_norm = d.qk_norm; ra.eps = d.rms_eps; ra.layer = 0;
+      ra.rope = ws<float2>(c->ws.rope_d);   // written by the verify call whose taps are being committed
       ra.col_stride = 2 * kd;
       ra.kn_stride = c->dl.lo.end / sizeof(float);     // layer records are 256-byte aligned
       const char* lbase = c->dblob + c->dl.layer0;

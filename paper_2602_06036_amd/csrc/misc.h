@@ -12,11 +12,32 @@ __global__ void build_block_kernel(const int32_t* __restrict__ anchor, int32_t* 
   if (i < S * B) tokens_out[i] = (i % B == 0) ? anchor[i / B] : mask_id;
 }
 
-// h[m, :] = float(E[tokens[m], :]); ids outside the vocabulary raise the status flag and read row 0
+// Rotary table of one model for the rows of a call: out[m * hd/2 + i] = (cos, sin) of pos(m) * theta^(-2i/hd),
+// pos(m) = seq_lens[m / B] + m % B.  Angles are formed in double precision (reduced by sincos) so that long
+// contexts do not lose phase accuracy; every layer and head of the call then reads the same rounded pair.
+struct RopeTab {
+  float2* out;   // null: no table
+  double log_theta;
+  int hd;
+};
+
+// h[m, :] = float(E[tokens[m], :]); ids outside the vocabulary raise the status flag and read row 0.
+// The first two wavefronts also write the row's entries of up to two rotary tables.
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
-                                                    float* __restrict__ h, int D, int vocab, int32_t* status) {
+                                                    float* __restrict__ h, int D, int vocab, int32_t* status,
+                                                    const int32_t* __restrict__ seq_lens, int B, RopeTab t0, RopeTab t1) {
   const int m = blockIdx.x;
+  {
+    const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
+    const RopeTab rt = w == 0 ? t0 : t1;
+    if (w < 2 && rt.out && lane < (rt.hd >> 1)) {
+      const int pos = seq_lens[m / B] + m % B;
+      double sn, cs;
+      sincos((double)pos * exp(-rt.log_theta * (2.0 * lane / rt.hd)), &sn, &cs);
+      rt.out[(size_t)m * (rt.hd >> 1) + lane] = make_float2((float)cs, (float)sn);
+    }
+  }
   int tok = tokens[m];
   if (tok < 0 || tok >= vocab) {
     if (threadIdx.x == 0) atomicOr(status, DF_STATUS_CAPACITY);
@@ -112,14 +133,13 @@ __global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const 
 // Input row: fp32 [.. q heads | k heads | v heads ..] starting at in + m*in_ld, given as `ks` partial
 // slabs (K ranges of the producing GEMM) `slab` elements apart that are added in ascending order.
 // q heads -> q_out [M, Hq, hd] row-major storage type; k/v heads -> page of position seq_len + slot.
-// Angles are formed in double precision (pos * theta^(-2i/hd), reduced by sincos) so that long
-// contexts do not lose phase accuracy.
+// (cos, sin) come from the call's rotary table (RopeTab), written by embed_kernel.
 struct RopeArgs {
   int n_q_heads, n_kv_heads, head_dim;
   int q_off, k_off, v_off;  // element offsets inside an input row
   int qk_norm;
   float eps;
-  double log_theta;
+  const float2* rope;       // rotary table [M, hd/2] of this model for the rows of the call
   int layer;                // layer index inside the pool
   // grid.z > 1 handles several layers in one launch (the draft's context K/V at commit): layer z reads its
   // k/v columns z * col_stride further along the input row and its k-norm gain kn_stride floats further on
@@ -174,9 +194,8 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(const float* __restrict__
       if (active) { x1 *= rstd * kn[lane]; x2 *= rstd * kn[lane + half]; }
     }
     if (active) {
-      double sn, cs;
-      sincos((double)pos * exp(-ra.log_theta * (2.0 * lane / hd)), &sn, &cs);
-      const float c = (float)cs, sf = (float)sn;
+      const float2 r = ra.rope[(size_t)m * half + lane];
+      const float c = r.x, sf = r.y;
       base[k_in_page(key, lane)] = Store<T>::from(x1 * c - x2 * sf);
       base[k_in_page(key, lane + half)] = Store<T>::from(x2 * c + x1 * sf);
     }
@@ -188,9 +207,8 @@ __global__ __launch_bounds__(256) void qkv_post_kernel(const float* __restrict__
     if (active) { x1 *= rstd * qn[lane]; x2 *= rstd * qn[lane + half]; }
   }
   if (active) {
-    double sn, cs;
-    sincos((double)pos * exp(-ra.log_theta * (2.0 * lane / hd)), &sn, &cs);
-    const float c = (float)cs, sf = (float)sn;
+    const float2 r = ra.rope[(size_t)m * half + lane];
+    const float c = r.x, sf = r.y;
     T* dst = q_out + ((size_t)m * ra.n_q_heads + head) * hd;
     dst[lane] = Store<T>::from(x1 * c - x2 * sf);
     dst[lane + half] = Store<T>::from(x2 * c + x1 * sf);
