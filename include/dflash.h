@@ -166,7 +166,9 @@ int dflash_accept(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *dra
  * Rows beyond the accepted prefix stay in the pools but are invisible (rolled back) and are
  * overwritten by the next step.  accept_len[s] = -1 commits nothing for sequence s (length and anchor
  * unchanged): an idle slot of the batch, or a prompt that ended in an earlier prefill chunk.  kv_slots_out (device, nullable) [S,B] int64: page*16+offset of
- * each committed row, -1 for rolled-back rows. */
+ * each committed row, -1 for rolled-back rows.
+ * The call belongs to the preceding dflash_verify on this context with the same batch (same rows, same seq_lens):
+ * it reads that call's tapped hidden states and rotary angles from the workspace. */
 int dflash_kv_commit(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *accept_len,
                      const int32_t *out_tokens, int64_t *kv_slots_out, void *stream);
 

@@ -553,7 +553,27 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   if (ep.amax && lm_skip_store) ep.out = nullptr;
   if (M <= 16) {
     static const int NT8 = env_int("DFLASH_GEMM_NT8", 1);   // tuning knob: matrices with at least 8*this row bands use 8 weight tiles per activation fragment
-    if (NT8 && nt % 8 == 0 && nt >= 8 * NT8) {
+    static const int FILL = env_int("DFLASH_GEMM_FILL", 1);   // tuning knob: 1 = weight tiles per wavefront (8 or 6) and K split chosen to fill whole rounds of the 256 CUs
+    if (FILL == 1 && NT8 && nt >= 8 * NT8 && (nt % 8 == 0 || nt % 6 == 0)) {
+      // a launch of 192 workgroups leaves a quarter of the CUs idle: among 8 or 6 weight tiles per wavefront and
+      // any K split (not only powers of two) take the fullest last round; ties go to 8 tiles, then to fewer K ranges
+      int best_nt = 0, best_ks = 1;
+      double best_fill = -1.0;
+      for (int cand : {8, 6}) {
+        if (nt % cand) continue;
+        const int nb = nt / cand;
+        for (int k = 1; k <= (split ? kMaxKSplit : 1); ++k) {
+          if (k > 1 && (KT / (k * 4) < 2 || k * M > arena)) break;
+          const int wgs = nb * k, rounds = (wgs + 255) / 256;
+          const double fill = (double)wgs / (rounds * 256.0) - 0.02 * (rounds - 1);   // a single round beats several
+          if (fill > best_fill + 1e-9) { best_fill = fill; best_nt = cand; best_ks = k; }
+        }
+      }
+      ks = best_ks;
+      ep.slab = (size_t)M * ep.ld;
+      if (best_nt == 8) launch_bf16<8, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      else launch_bf16<6, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
+    } else if (NT8 && nt % 8 == 0 && nt >= 8 * NT8) {
       if (split) ks = pick_ksplit(nt / 8, KT, M, arena);
       ep.slab = (size_t)M * ep.ld;
       if (U >= 2) launch_bf16<8, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
