@@ -89,7 +89,9 @@ def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
 
 def measure_peaks(dev):
     """Machine probes through the library: back-to-back read-only launches over fresh memory (sizes of the O, QKV,
-    down, gate/up projections and the LM head) and a bf16 MFMA loop at 1, 2 and 4 wavefronts per SIMD."""
+    down, gate/up projections and the LM head), a bf16 MFMA loop at 1, 2 and 4 wavefronts per SIMD, and the
+    per-k-tile instruction mix of the LDS-staged GEMM (fragment reads, LDS fills, MFMAs) with the fills left out,
+    done by ds_write, and done by direct-to-LDS loads."""
     import torch
     from paper_2602_06036_amd import binding as B
     buf = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
@@ -107,6 +109,14 @@ def measure_peaks(dev):
             B.dflash_probe_mfma(shape, wgs, 2000)
             ms, fl = B.dflash_probe_mfma(shape, wgs, 20000)
             out["mfma_bf16"][f"{name}_{wgs // 256}_waves_per_simd"] = {"ms": ms, "TFLOPs": fl / ms / 1e9}
+    out["lds_mix_TFLOPs"] = {}
+    for mix, name in ((3, "256x128_r16_f8_m64"), (0, "192x128_r14_f7_m48"), (1, "128x128_r12_f6_m32"), (2, "192x64_r10_f5_m24")):
+        row = {}
+        for fill, fname in ((0, "no_fill"), (1, "ds_write"), (2, "direct_to_lds"), (3, "direct_to_lds_first")):
+            B.dflash_probe_lds_mix(buf, mix, fill, 2000)
+            ms, fl = B.dflash_probe_lds_mix(buf, mix, fill, 20000)
+            row[fname] = fl / ms / 1e9
+        out["lds_mix_TFLOPs"][name] = row
     return out
 
 

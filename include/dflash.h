@@ -202,6 +202,13 @@ int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count
  * Both synchronise the stream.  DFLASH_EINVAL on bad arguments, DFLASH_EHIP if the device reports an error. */
 int dflash_probe_hbm_read(const void *buf, size_t bytes_per_launch, int32_t launches, float *ms_total, void *stream);
 int dflash_probe_mfma(int32_t shape, int32_t workgroups, int32_t iters, float *ms, double *flops, void *stream);
+/* dflash_probe_lds_mix: the per-k-tile instruction mix of the LDS-staged GEMM in isolation (512 workgroups of 4
+ * wavefronts, two per CU, one barrier per round): per wavefront and round mix 0: 14 fragment reads, 7 fills, 48 MFMAs
+ * (192 x 128 tile); 1: 12 / 6 / 32 (128 x 128); 2: 10 / 5 / 24 (192 x 64); 3: 16 / 8 / 64 (256 x 128).  fill 0: no
+ * fills, 1: ds_write_b128 from registers, 2: direct-to-LDS global loads issued after the reads, 3: before them (buf:
+ * (device) 32 KB, read only).  *ms =
+ * elapsed time of `iters` rounds, *flops = MFMA flops issued.  Synchronises `stream`. */
+int dflash_probe_lds_mix(const void *buf, int32_t mix, int32_t fill, int32_t iters, float *ms, double *flops, void *stream);
 
 /* ---- cache import / export (state migration, tests) ------------------------------------------ */
 /* Copies rows [start, start+count) of sequence `seq` of one layer between the paged pool and

@@ -26,7 +26,7 @@ EXPORTS = [
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
     "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read",
-    "dflash_probe_hbm_read", "dflash_probe_mfma",
+    "dflash_probe_hbm_read", "dflash_probe_mfma", "dflash_probe_lds_mix",
 ]
 
 
@@ -264,6 +264,15 @@ def dflash_probe_hbm_read(buf: torch.Tensor, bytes_per_launch: int, launches: in
     ms = C.c_float()
     _check(lib().dflash_probe_hbm_read(C.c_void_p(buf.data_ptr()), C.c_size_t(bytes_per_launch), launches, C.byref(ms), _stream()))
     return float(ms.value)
+
+
+def dflash_probe_lds_mix(buf: torch.Tensor, mix: int, fill: int, iters: int):
+    """(milliseconds, flops) of `iters` rounds of one k tile's instruction mix of the LDS-staged GEMM
+    (mix 0..3: tile shape; fill 0: none, 1: ds_write, 2: direct-to-LDS loads from `buf`, at least 32 KB)."""
+    assert buf.is_cuda and buf.is_contiguous() and buf.numel() * buf.element_size() >= 32768
+    ms, fl = C.c_float(), C.c_double()
+    _check(lib().dflash_probe_lds_mix(C.c_void_p(buf.data_ptr()), mix, fill, iters, C.byref(ms), C.byref(fl), _stream()))
+    return float(ms.value), float(fl.value)
 
 
 def dflash_probe_mfma(shape: int, workgroups: int, iters: int):

@@ -808,6 +808,16 @@ int timed(hipStream_t st, float* ms, F&& enqueue) {
 }
 }  // namespace
 
+namespace {
+template <int NR, int NF, int NM>
+void launch_lds_mix(hipStream_t st, int fill, const u32x4* in, int iters) {
+  if (fill == 0) hipLaunchKernelGGL((probe_lds_mix_kernel<NR, 0, NM, 0>), dim3(512), dim3(256), 0, st, in, iters);
+  else if (fill == 1) hipLaunchKernelGGL((probe_lds_mix_kernel<NR, NF, NM, 1>), dim3(512), dim3(256), 0, st, in, iters);
+  else if (fill == 2) hipLaunchKernelGGL((probe_lds_mix_kernel<NR, NF, NM, 2>), dim3(512), dim3(256), 0, st, in, iters);
+  else hipLaunchKernelGGL((probe_lds_mix_kernel<NR, NF, NM, 3>), dim3(512), dim3(256), 0, st, in, iters);
+}
+}  // namespace
+
 // =====================================================================================================
 extern "C" {
 
@@ -964,6 +974,24 @@ int dflash_probe_mfma(int32_t shape, int32_t workgroups, int32_t iters, float* m
     else hipLaunchKernelGGL(probe_mfma32_kernel, dim3(workgroups), dim3(256), 0, st, iters);
   });
   *flops = (double)workgroups * 4 * iters * (shape == 0 ? 16 * (2.0 * 16 * 16 * 32) : 4 * (2.0 * 32 * 32 * 16));
+  return rc;
+}
+
+int dflash_probe_lds_mix(const void* buf, int32_t mix, int32_t fill, int32_t iters, float* ms, double* flops, void* stream) {
+  if (!buf || !ms || !flops || mix < 0 || mix > 3 || fill < 0 || fill > 3 || iters < 1)
+    return fail(nullptr, DFLASH_EINVAL, "probe_lds_mix: need a 32 KB buffer, outputs, mix 0..3, fill 0..2 and iters >= 1");
+  hipStream_t st = (hipStream_t)stream;
+  const u32x4* in = reinterpret_cast<const u32x4*>(buf);
+  static const int mfmas[4] = {48, 32, 24, 64};
+  const int rc = timed(st, ms, [&] {
+    switch (mix) {
+      case 0: launch_lds_mix<14, 7, 48>(st, fill, in, iters); break;   // 192 x 128 tile
+      case 1: launch_lds_mix<12, 6, 32>(st, fill, in, iters); break;   // 128 x 128 and 256 x 64
+      case 2: launch_lds_mix<10, 5, 24>(st, fill, in, iters); break;   // 192 x 64
+      default: launch_lds_mix<16, 8, 64>(st, fill, in, iters); break;  // 256 x 128
+    }
+  });
+  *flops = 512.0 * 4 * iters * mfmas[mix] * (2.0 * 16 * 16 * 32);
   return rc;
 }
 
