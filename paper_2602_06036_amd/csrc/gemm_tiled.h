@@ -6,14 +6,16 @@
 // 16x32 fragment), so a k tile is staged by copying whole fragments: global -> registers (PD k tiles in flight)
 // -> one of two LDS slots; every wavefront reads the WN weight and 2*WM activation fragments of its quadrant
 // (each lane its own 16 bytes: conflict-free ds_read_b128) and issues WN*WM*2 MFMAs per k tile.
-// Schedule of a k tile (one barrier per k tile, order pinned with scheduling barriers): barrier -> all WN + 2*WM
-// fragment reads of the k tile -> the LDS writes of the next k tile (from registers loaded PD k tiles earlier) and
-// the global loads of k tile t+1+PD -> the WN*WM*2 MFMAs.  LDS operations of a wavefront complete in order and a
-// 1 KB ds_write occupies the LDS path several times longer than a read, so the reads go first: the MFMAs wait for
-// the reads only and the writes drain behind the MFMA stream; the second workgroup on the CU fills the gaps around
-// the barrier.  (Measured with an isolated loop of the same instruction mix, two workgroups per CU: MFMAs alone
-// 2.45 PFLOP/s, with the reads 2.35, with reads and writes 1.8; the same loop fed by direct-to-LDS loads 1.9, but
-// that needs a third LDS slot, which the 192 x 128 tile does not leave room for at two workgroups per CU.)
+// Schedule of a k tile, register-staged variant (NS = 2; one barrier per k tile, order pinned with scheduling
+// barriers): barrier -> all WN + 2*WM fragment reads of the k tile -> the LDS writes of the next k tile (from
+// registers loaded PD k tiles earlier) and the global loads of k tile t+1+PD -> the WN*WM*2 MFMAs.  LDS operations
+// of a wavefront complete in order and a 1 KB ds_write occupies the LDS path several times longer than a read, so
+// the reads go first: the MFMAs wait for the reads only and the writes drain behind the MFMA stream; the second
+// workgroup on the CU fills the gaps around the barrier.
+// Ring variant (NS >= 3): the k tiles arrive by direct-to-LDS loads, see the comment at the loop.  It is used where
+// NS slots fit next to a second workgroup on the CU (128 x 128 and the 64-row tiles) and for the 128-row tiles of
+// an unsplit GEMM whose workgroups each have a CU to themselves.
+// (The probe kernel probe_lds_mix_kernel runs the per-k-tile instruction mix of these loops in isolation.)
 //
 // Workgroup order: consecutive workgroup ids go to different XCDs (round-robin dispatch), so id = 8*j + x
 // is mapped to weight band block 8*(j / m_blocks) + x and activation block j % m_blocks: the workgroups that
