@@ -126,12 +126,14 @@ def llama31_8b_workload(n_seqs: int = 1, ctx: int = 2048) -> Workload:
 
 
 def small_bf16_workload(n_seqs: int = 3, ctx_min: int = 20, ctx_max: int = 150, seed: int = 11,
-                        block_size: int = 16, temperature: float = 0.0) -> Workload:
+                        block_size: int = 16, temperature: float = 0.0, draft_layers: int = 2,
+                        n_taps: int = 5) -> Workload:
     """A scaled-down bf16 model with the 8B model's structure (GQA 4:1, head_dim 128, QK-norm,
-    five taps) that the oracle can prefill and step in seconds."""
+    five taps) that the oracle can prefill and step in seconds.  draft_layers / n_taps give the drafter depth
+    and the number of tapped target layers of the ablations in Section 5.5 (3, 5, 8 layers; 3 or 5 features)."""
     t = ModelDims(8, 512, 8, 2, 128, 1536, 4096, 1e6, 1e-6, True)
-    d = replace(t, n_layers=2)
-    return Workload("small_bf16", "bf16", t, d, tap_layers_for(8, 5), t.vocab - 1, block_size,
+    d = replace(t, n_layers=draft_layers)
+    return Workload("small_bf16", "bf16", t, d, tap_layers_for(8, n_taps), t.vocab - 1, block_size,
                     n_seqs, ctx_min, ctx_max, temperature, seed)
 
 

@@ -261,6 +261,25 @@ def test_small_bf16_other_block_sizes(block):
     assert ls.stats["reseeds"] <= 1
 
 
+@pytest.mark.parametrize("draft_layers,n_taps", [(8, 5), (3, 3)])
+def test_small_bf16_drafter_depth_and_feature_count(draft_layers, n_taps):
+    """The drafter variants of the ablations in Section 5.5: an 8-layer drafter with 5 tapped target layers and a
+    3-layer drafter with 3 (the fusion matrix W_c then has 3*D columns; every draft layer has its own context
+    K/V rows in the draft pool)."""
+    w = si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=120, seed=37, draft_layers=draft_layers, n_taps=n_taps)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=120 + 6 * 16)
+    ls.prefill()
+    ls.check_cache([0, 7], list(range(0, draft_layers, max(1, draft_layers // 3))))
+    plans = [None, [15, 0, 9], [3, 15, 15], None]
+    for i, plan in enumerate(plans):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([0, 7], [0, draft_layers - 1])
+    print(f"small bf16 ({draft_layers}-layer drafter, {n_taps} taps) stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
 def test_bf16_head_dim_64_without_qk_norm():
     """A bf16 model of another shape family: head_dim 64 (the MFMA attention kernel's second instantiation), two
     query heads per kv head, no q/k norm (the LLaMA-style layer of Section 5), B = 8."""
