@@ -17,10 +17,11 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 HBM_PEAK_GBS = 8000.0
-# HBM bytes per launch of the dominant kernel (gate/up GEMM at the 8B shape, M = 16) from two rocprofv3 --pmc
-# runs (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): profiles/cfg2_gateup_gemm_hbm_traffic.md
+# HBM bytes per launch of the dominant kernel (gate/up GEMM at the 8B shape) from two rocprofv3 --pmc runs per
+# workload (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): profiles/gateup_gemm_attention_hbm_traffic.md
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
-MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": 198764 * 1024 + 768 * 1024}
+MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": int(99374.8 * 2 + 768) * 1024, "cfg3_8b_b16_ctx2560": int(114806.3 * 2 + 12288) * 1024,
+                          "cfg4_8b_b4_ctx16k": int(102485.9 * 2 + 3072) * 1024, "cfg5_8b_b32_ctx8k": int(131284.2 * 2 + 24576) * 1024}
 
 WORKLOADS = {
     # name: (synth workload index, n_seqs, context)
@@ -300,12 +301,14 @@ def main():
             # MFMA instructions that are issued, which is not counted here
             ach = (by / cnt) * M_rows / (ms / cnt) / 1e9
             roof = dict(bound="mfma", kernel="gemm_bf16_tiled_kernel<SWIGLU> (gate/up projection)", achieved=ach,
-                        peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS, traffic=None,
+                        peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS,
+                        traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
                         flops_per_launch=(by / cnt) * M_rows, issued_mfma_flops_per_launch=2 * (by / cnt) * M_rows,
                         avg_launch_us=1e3 * ms / cnt)
         else:
             ach = (by / cnt) / (ms / cnt) / 1e6
-            roof = dict(bound="hbm", kernel="gemm_bf16_kernel<SWIGLU> (gate/up projection)", achieved=ach, peak=HBM_PEAK_GBS,
+            kname = "gemm_bf16_tiled_kernel<SWIGLU>" if M_rows > 64 else "gemm_bf16_kernel<SWIGLU>"
+            roof = dict(bound="hbm", kernel=kname + " (gate/up projection)", achieved=ach, peak=HBM_PEAK_GBS,
                         unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
                         bytes_per_launch=by / cnt, avg_launch_us=1e3 * ms / cnt)
 
