@@ -146,7 +146,7 @@ inline int arena_rows(int max_rows) { return std::max(1024, 4 * max_rows); }
 constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row in the argmax
 
 struct Workspace {
-  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, rope_t, rope_d, total;
+  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, total;
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
   const size_t es = esize(t.dtype);
@@ -189,6 +189,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.stats_p = take((size_t)M * 8);
   w.stats_q = take((size_t)M * 8);
   w.amax = take((size_t)M * std::max(ARGMAX_CHUNKS, t.vocab / 16 + 1) * 8);   // one partial per weight row band at most
+  w.lsep = take((size_t)M * (t.vocab / 16 + 1) * 8);    // per-workgroup softmax statistics of an LM-head launch
   w.rope_t = take((size_t)M * (t.head_dim / 2) * 8);   // rotary tables of the call's rows (target, draft)
   w.rope_d = take((size_t)M * (d.head_dim / 2) * 8);
   w.total = off;
@@ -228,6 +229,7 @@ struct dflash_ctx {
   int attn_wide_min_chunk = 512;   // keys per workgroup from which the key-split attention kernel is used (tuning knob)
   bool have_logits_d = false, have_logits_t = false;   // the workspace holds this step's draft / target logits
   float draft_temperature = 0.f;                       // of the last dflash_draft_block call
+  float stats_q_T = 0.f, stats_p_T = 0.f;              // > 0: ws.stats_q / ws.stats_p hold this step's (max, log-sum-exp) rows at that temperature
   int ks_force = 0;     // tiled GEMM: forces the K split where a split is allowed (tuning knob)
   int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
   int wm_force = 0;     // tiled GEMM: 4 or 2 forces 128 or 64 activation rows per tile (testing / tuning knob)
@@ -300,6 +302,7 @@ struct Engine {
   };
   Slab pending;          // partial sums that the next RMSNorm adds into the residual stream ws.h
   int amax_parts = 0;    // > 0: the last LM-head GEMM left that many per-row argmax partials in ws.amax (fused epilogue)
+  int lse_parts = 0;     // > 0: ... and that many per-row softmax-statistics partials in ws.lsep
   bool lm_skip_store = false;   // the LM-head GEMM may drop its logits when its argmax is fused (nobody will read them)
   int pending_tap = -1;  // tap index to be taken from the completed residual stream by the next RMSNorm
 
@@ -373,8 +376,10 @@ struct Engine {
 
   // final norm + LM head with the row argmax fused into the GEMM epilogue where the kernel supports it (then
   // amax_parts > 0 and, unless want_logits, the [M, V] logits are never written); argmax() finishes the job
-  void lm_head(const float* final_gain, float eps, int M, float* logits, bool want_logits, int B, int mode, float inv_T,
-               const uint64_t* key) {
+  // stats_T > 0: the epilogue also leaves the softmax statistics of logits / stats_T, combined into stats_out; returns
+  // whether that happened (kernels without the fused epilogue leave it to row_lse_kernel)
+  bool lm_head(const float* final_gain, float eps, int M, float* logits, bool want_logits, int B, int mode, float inv_T,
+               const uint64_t* key, float stats_T = 0.f, float2* stats_out = nullptr) {
     const dflash_dims& t = c->t;
     norm_h(final_gain, M, t.d_model, eps);
     EpiArgs ep{logits, t.vocab, 0, nullptr, 0};
@@ -383,10 +388,20 @@ struct Engine {
     ep.amax_inv_T = inv_T;
     ep.amax_key = key;
     ep.amax_B = B;
+    if (stats_T > 0.f) {
+      ep.lse = ws<float2>(c->ws.lsep);
+      ep.lse_inv_T = 1.0f / stats_T;
+    }
     lm_skip_store = !want_logits;
     amax_parts = 0;
+    lse_parts = 0;
     gemm(reinterpret_cast<const T*>(c->tblob + c->tl.lm), ws<T>(c->ws.a), M, t.vocab, t.d_model, EPI_STORE, ep, false);
     lm_skip_store = false;
+    if (lse_parts == 0) return false;
+    hipLaunchKernelGGL(lse_finish_kernel, dim3(M), dim3(64), 0, st, ws<float2>(c->ws.lsep), lse_parts, stats_out);
+    check();
+    lse_parts = 0;
+    return true;
   }
 
   int draft_block(const dflash_batch* b, float temperature, const uint64_t* rng_key, int32_t* draft_tokens, float* logits_out) {
@@ -404,7 +419,9 @@ struct Engine {
     const int mode = temperature > 0.f ? 1 : 0;
     const float inv_T = mode ? 1.0f / temperature : 1.0f;
     const bool want_logits = logits_out || mode;        // sampling: dflash_accept needs the proposal distribution
-    lm_head(reinterpret_cast<const float*>(c->dblob + c->dl.gf), d.rms_eps, M, logits, want_logits, B, mode, inv_T, rng_key);
+    const bool st_q = lm_head(reinterpret_cast<const float*>(c->dblob + c->dl.gf), d.rms_eps, M, logits, want_logits, B, mode, inv_T, rng_key,
+                              mode ? temperature : 0.f, ws<float2>(c->ws.stats_q));
+    c->stats_q_T = st_q ? temperature : 0.f;
     c->have_logits_d = want_logits || amax_parts == 0;
     c->draft_temperature = temperature;
     argmax(logits, d.vocab, M, B, draft_tokens, 1, mode, inv_T, rng_key);
@@ -431,7 +448,10 @@ struct Engine {
     }
     float* logits = ws<float>(c->ws.logits_t);
     const bool want_logits = logits_out || c->draft_temperature > 0.f;   // sampling: dflash_accept needs the target distribution
-    lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits, want_logits, B, 0, 1.0f, nullptr);
+    const float sT = c->draft_temperature > 0.f ? c->draft_temperature : 0.f;
+    const bool st_p = lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits, want_logits, B, 0, 1.0f, nullptr, sT,
+                              ws<float2>(c->ws.stats_p));
+    c->stats_p_T = st_p ? sT : 0.f;
     c->have_logits_t = want_logits || amax_parts == 0;
     argmax(logits, t.vocab, M, B, tgt_argmax, 0, 0, 1.0f, (const uint64_t*)nullptr);
     if (logits_out) {
@@ -449,10 +469,16 @@ struct Engine {
       check();
     } else {
       const float inv_T = 1.0f / temperature;
-      hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, ws<float>(c->ws.logits_t), V, inv_T, ws<float2>(c->ws.stats_p));
-      check();
-      hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, ws<float>(c->ws.logits_d), V, inv_T, ws<float2>(c->ws.stats_q));
-      check();
+      // the (max, log-sum-exp) rows normally come out of the LM-head epilogues; another temperature than the one
+      // the draft was sampled at, or a kernel without that epilogue, takes them from the stored logits
+      if (c->stats_p_T != temperature) {
+        hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, ws<float>(c->ws.logits_t), V, inv_T, ws<float2>(c->ws.stats_p));
+        check();
+      }
+      if (c->stats_q_T != temperature) {
+        hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, ws<float>(c->ws.logits_d), V, inv_T, ws<float2>(c->ws.stats_q));
+        check();
+      }
       hipLaunchKernelGGL(accept_sampling_kernel, dim3(S), dim3(1024), 0, st, ws<float>(c->ws.logits_t), ws<float>(c->ws.logits_d),
                          ws<float2>(c->ws.stats_p), ws<float2>(c->ws.stats_q), draft_tokens, uniforms, rng_key, V, B, inv_T,
                          accept_len, out_tokens);
@@ -550,6 +576,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   const int arena = arena_rows(c->rt.max_seqs * c->rt.block_size);
   int ks = 1;
   if (ep.amax && (split || epi != EPI_STORE)) ep.amax = nullptr;   // the fused argmax needs complete sums
+  if (ep.lse && (split || epi != EPI_STORE)) ep.lse = nullptr;      // so do the fused softmax statistics
   if (ep.amax && lm_skip_store) ep.out = nullptr;
   if (M <= 16) {
     static const int NT8 = env_int("DFLASH_GEMM_NT8", 1);   // tuning knob: matrices with at least 8*this row bands use 8 weight tiles per activation fragment
@@ -666,6 +693,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   }
   check();
   if (ep.amax) amax_parts = g_launch_parts;
+  if (ep.lse) lse_parts = g_launch_parts;
   if (epi == EPI_SWIGLU) return Slab{};
   return Slab{ep.out, ks, ep.slab};
 }

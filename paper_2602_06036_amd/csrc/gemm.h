@@ -22,6 +22,11 @@ struct EpiArgs {
   float amax_inv_T = 1.f;
   const uint64_t* amax_key = nullptr;
   int amax_B = 1;
+  // STORE with a single K range, LM head only: fused softmax statistics.  Every workgroup also writes, for each of its
+  // rows, (max, sum of exp(y * lse_inv_T - max)) over its columns to lse[m * parts + part] (same partition as amax); a
+  // second, tiny kernel combines the parts in ascending order into (max, log-sum-exp).
+  float2* lse = nullptr;
+  float lse_inv_T = 1.f;
 };
 
 // score of logit y at (row m, column col) for the fused argmax
@@ -33,6 +38,26 @@ __device__ __forceinline__ float amax_score(const EpiArgs& ep, uint64_t key, flo
 // the kernel that consumes the result (RMSNorm, q/k-norm + RoPE) adds the slabs in ascending order.
 // The kernel boundary provides the ordering: no atomics, no fences, and a sum that does not depend on
 // which workgroup finished first.
+
+// (max, sum of exponentials relative to that max) of the union of two sets; an empty set is (-inf, 0)
+__device__ __forceinline__ void lse_combine(float& m, float& s, float m2, float s2) {
+  const float M = fmaxf(m, m2);
+  s = (m == -INFINITY ? 0.f : s * __expf(m - M)) + (m2 == -INFINITY ? 0.f : s2 * __expf(m2 - M));
+  m = M;
+}
+// the same over the 4 lanes that hold the other columns of a row (lane bits 4 and 5)
+__device__ __forceinline__ void lse_combine_row(float& m, float& s) {
+#pragma unroll
+  for (int o = 16; o <= 32; o <<= 1) {
+    const float om = __shfl_xor(m, o, 64), os = __shfl_xor(s, o, 64);
+    lse_combine(m, s, om, os);
+  }
+}
+__device__ __forceinline__ void lse_add4(float& m, float& s, float4 y, float inv_T) {
+  const float a = y.x * inv_T, b = y.y * inv_T, c = y.z * inv_T, d = y.w * inv_T;
+  const float mx = fmaxf(fmaxf(a, b), fmaxf(c, d));
+  lse_combine(m, s, mx, __expf(a - mx) + __expf(b - mx) + __expf(c - mx) + __expf(d - mx));
+}
 
 __device__ __forceinline__ float silu_f(float x) { return x / (1.0f + __expf(-x)); }
 
@@ -203,6 +228,26 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
 #pragma unroll
         for (int w = 1; w < 4; ++w) argmax_combine(bv, bi, wbest[w][r].x, __float_as_int(wbest[w][r].y));
         ep.amax[(size_t)m * gridDim.x + blockIdx.x] = make_float2(bv, __int_as_float(bi));
+      }
+    }
+    if (ep.lse) {   // fused softmax statistics over this workgroup's NT*16 columns (single K range)
+      __shared__ float2 wl[4][MT * 16];
+      __syncthreads();
+#pragma unroll
+      for (int j = 0; j < MT; ++j) {
+        float lm = -INFINITY, ls = 0.f;
+        for (int i = wave; i < NT; i += 4) lse_add4(lm, ls, tile_sum(i * MT + j), ep.lse_inv_T);
+        lse_combine_row(lm, ls);
+        if (g == 0) wl[wave][j * 16 + mrow] = make_float2(lm, ls);
+      }
+      __syncthreads();
+      for (int r = threadIdx.x; r < MT * 16; r += 256) {
+        const int m = mt0 * 16 + r;
+        if (m >= M) continue;
+        float lm = wl[0][r].x, ls = wl[0][r].y;
+#pragma unroll
+        for (int w = 1; w < 4; ++w) lse_combine(lm, ls, wl[w][r].x, wl[w][r].y);
+        ep.lse[(size_t)m * gridDim.x + blockIdx.x] = make_float2(lm, ls);
       }
     }
   }

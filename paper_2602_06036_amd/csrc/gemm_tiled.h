@@ -244,4 +244,27 @@ __global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void g
       ep.amax[(size_t)m * n_blocks + nb] = make_float2(bv, __int_as_float(bi));
     }
   }
+  if (EPI == EPI_STORE && ep.lse) {   // fused softmax statistics over this workgroup's columns (single K range)
+    __syncthreads();                  // the staging slots (and the argmax scratch in them) are free now
+    float2* wl = reinterpret_cast<float2*>(&stage[0][0][0]);   // [wy][BMT * 16 rows]
+#pragma unroll
+    for (int jj = 0; jj < WM; ++jj) {
+      float lm = -INFINITY, ls = 0.f;
+#pragma unroll
+      for (int i = 0; i < WN; ++i) {
+        if (nt0 + wy * WN + i >= n_tiles) continue;
+        lse_add4(lm, ls, make_float4(acc[i][jj][0], acc[i][jj][1], acc[i][jj][2], acc[i][jj][3]), ep.lse_inv_T);
+      }
+      lse_combine_row(lm, ls);
+      if (gq == 0) wl[wy * (BMT * 16) + (wx * WM + jj) * 16 + mrow] = make_float2(lm, ls);
+    }
+    __syncthreads();
+    for (int r = threadIdx.x; r < BMT * 16; r += 256) {
+      const int m = mt0 * 16 + r;
+      if (m >= M) continue;
+      float lm = wl[r].x, ls = wl[r].y;
+      lse_combine(lm, ls, wl[BMT * 16 + r].x, wl[BMT * 16 + r].y);
+      ep.lse[(size_t)m * n_blocks + nb] = make_float2(lm, ls);
+    }
+  }
 }

@@ -314,6 +314,24 @@ __global__ __launch_bounds__(1024) void row_lse_kernel(const float* __restrict__
   }
 }
 
+// combines the per-workgroup (max, sum) partials that the LM-head epilogue left for row m, in ascending order of the
+// column blocks: stats[m] = (max, log-sum-exp) of logits * inv_T, the pair row_lse_kernel computes from stored logits
+__global__ __launch_bounds__(64) void lse_finish_kernel(const float2* __restrict__ part, int n_parts, float2* __restrict__ stats) {
+  const int m = blockIdx.x, lane = threadIdx.x;
+  float mx = -INFINITY;
+  for (int c = lane; c < n_parts; c += 64) mx = fmaxf(mx, part[(size_t)m * n_parts + c].x);
+  mx = wave_reduce_max(mx);
+  // every lane sums its stride of the parts in ascending order, then the 64 lane sums are added in lane order
+  float s = 0.f;
+  for (int c = lane; c < n_parts; c += 64) {
+    const float2 p = part[(size_t)m * n_parts + c];
+    s += p.x == -INFINITY ? 0.f : p.y * expf(p.x - mx);
+  }
+  float tot = 0.f;
+  for (int i = 0; i < 64; ++i) tot += __shfl(s, i, 64);
+  if (lane == 0) stats[m] = make_float2(mx, mx + logf(tot));
+}
+
 // One block per sequence.  Thread 0 walks the slots: slot j accepted iff u_j * q_j(d_j) < p_{j-1}(d_j).
 // Then the whole block draws the final token by Gumbel-max over
 //   first rejected slot j: log max(p_{j-1} - q_j, 0)   (purpose 1, slot j)
