@@ -233,6 +233,7 @@ struct dflash_ctx {
   int ks_force = 0;     // tiled GEMM: forces the K split where a split is allowed (tuning knob)
   int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
   int wm_force = 0;     // tiled GEMM: 4 or 2 forces 128 or 64 activation rows per tile (testing / tuning knob)
+  bool lm_stats = true; // softmax statistics from the LM-head epilogue (testing knob: off = always from the stored logits)
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
@@ -388,7 +389,7 @@ struct Engine {
     ep.amax_inv_T = inv_T;
     ep.amax_key = key;
     ep.amax_B = B;
-    if (stats_T > 0.f) {
+    if (stats_T > 0.f && c->lm_stats) {
       ep.lse = ws<float2>(c->ws.lsep);
       ep.lse_inv_T = 1.0f / stats_T;
     }
@@ -942,6 +943,7 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->err[0] = 0;
   c->tile_force = env_int("DFLASH_GEMM_TILE", 0);
   c->wm_force = env_int("DFLASH_GEMM_WM", 0);
+  c->lm_stats = env_int("DFLASH_LM_STATS", 1) == 1;
   c->ks_force = env_int("DFLASH_GEMM_KS", 0);
   c->attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {

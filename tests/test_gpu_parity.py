@@ -424,9 +424,13 @@ def test_empty_context_exact_fit_partial_and_empty_batch():
     print("empty-context / exact-fit stats", ls.stats)
 
 
-def test_bf16_sampling_at_temperature_0_7_matches_oracle_decisions():
+@pytest.mark.parametrize("lm_stats", ["1", "2"])
+def test_bf16_sampling_at_temperature_0_7_matches_oracle_decisions(lm_stats, monkeypatch):
     """Speculative sampling on the small bf16 model at a temperature other than 1: Gumbel-max drafts from the fused
-    LM-head epilogue, accept tests on softmax(logits / T) of both models, residual / bonus draws."""
+    LM-head epilogue, accept tests on softmax(logits / T) of both models, residual / bonus draws.  Run with the
+    softmax statistics taken from the LM-head epilogue (the default) and from the stored logits (the path of fp32
+    models and of an accept temperature other than the draft's)."""
+    monkeypatch.setenv("DFLASH_LM_STATS", lm_stats)
     w = replace(si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=90, seed=53), temperature=0.7)
     prompts = si.make_prompts(w)
     ls = Lockstep(w, prompts, max_len=90 + 6 * 16)
