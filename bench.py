@@ -34,6 +34,9 @@ WORKLOADS = {
     "tiny_f32": (1, 1, 128),
     # block-size variant: LLaMA-3.1-8B shape, B = 10 (synth.inputs.llama31_8b_workload)
     "llama31_8b_b1_ctx2048_B10": ("llama31", 1, 2048),
+    # smaller block at the large batch, where verification is compute-bound (the adaptive block size the paper's
+    # Section 5.5 discusses): configuration 5 with B = 8
+    "cfg5_8b_b32_ctx8k_B8": ((5, 8), 32, 8192),
 }
 
 
@@ -213,7 +216,13 @@ def main():
         print(json.dumps(measure_peaks(dev)))
         return
     idx, S, ctx = WORKLOADS[args.workload]
-    w = si.llama31_8b_workload(S, ctx) if idx == "llama31" else si.workload(idx)
+    if idx == "llama31":
+        w = si.llama31_8b_workload(S, ctx)
+    elif isinstance(idx, tuple):     # (configuration, block size)
+        import dataclasses
+        w = dataclasses.replace(si.workload(idx[0]), block_size=idx[1])
+    else:
+        w = si.workload(idx)
     Bk = w.block_size
     K, Wm = args.steps, args.warmup
     passes = 1 if args.no_profile else 2
