@@ -241,9 +241,10 @@ def test_small_bf16_many_rows_tiled_gemm(tile, rows, monkeypatch):
     assert ls.stats["reseeds"] <= 1
 
 
-@pytest.mark.parametrize("block", [8, 10])
+@pytest.mark.parametrize("block", [2, 5, 8, 10])
 def test_small_bf16_other_block_sizes(block):
-    """Block sizes other than 16 (Section 5, Implementation: B = 10 for the LLaMA-3.1 drafter; the block-size ablation of Section 5.5 uses B = 8):
+    """Block sizes other than 16 (Section 5, Implementation: B = 10 for the LLaMA-3.1 drafter; the block-size ablation of Section 5.5 uses B = 8;
+    2 is the smallest block the library accepts: one anchor and one drafted token; 5 is an odd size):
     30 or 24 activation rows per step (not a multiple of the 16-row MFMA band), 40 or 32 query rows per kv head,
     blocks that straddle page boundaries at every offset."""
     w = si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=150, seed=31, block_size=block)
@@ -252,7 +253,7 @@ def test_small_bf16_other_block_sizes(block):
     ls.prefill()
     ls.check_cache([0, 7], [0, 1])
     k = block - 1
-    plans = [None, [k, 0, 5], [3, k, k], None, [k, k, k]]
+    plans = [None, [k, 0, min(5, k)], [min(3, k), k, k], None, [k, k, k]]
     for i, plan in enumerate(plans):
         ls.step(plan=plan, step_idx=i)
     ls.check_cache([0, 7], [0, 1])
