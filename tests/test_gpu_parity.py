@@ -352,6 +352,65 @@ def test_prefill_as_one_many_row_pass():
     assert ls.stats["reseeds"] <= 1
 
 
+def test_draft_many_anchor_blocks_of_one_sequence_in_one_call():
+    """The attention pattern of DFlash training (Section 4.2, 'DFlash training attention'): several masked blocks of
+    one sequence in one pass, each block seeing the context features before its anchor and its own rows, never another
+    block.  With the paged cache this needs no kernel of its own: every block is a pseudo-sequence whose committed
+    length is its anchor's position, whose block-table row is its sequence's, and whose own rows live in a private
+    page (anchors at page boundaries, so the page of positions p .. p+15 belongs to the block alone).  One
+    dflash_draft_block call over all blocks against the oracle's draft forward per block."""
+    import copy
+    import torch
+    import paper_2602_06036_amd as dfl
+    w = si.small_bf16_workload(n_seqs=2, ctx_min=100, ctx_max=150, seed=41)
+    prompts = si.make_prompts(w)
+    Bk = w.block_size
+    blocks = [(s, p) for s, pr in enumerate(prompts) for p in range(16, len(pr), 16)]   # (sequence, anchor position)
+    ls = Lockstep(w, prompts, max_len=150 + 16 * 16, max_seqs=len(blocks))
+    ls.prefill()
+    g = ls.g
+    pps = g.block_table.shape[1]
+    table = torch.empty((len(blocks), pps), dtype=torch.int32, device=g.dev)
+    lens = np.zeros(len(blocks), dtype=np.int32)
+    anchors = np.zeros(len(blocks), dtype=np.int32)
+    used = {}
+    for i, (sq, pos) in enumerate(blocks):
+        k = used.get(sq, 0)
+        used[sq] = k + 1
+        free = pps - 1 - k                                  # a page of this sequence's row that no committed row uses
+        assert free > (len(prompts[sq]) + Bk) // 16 + 1
+        table[i] = g.block_table[sq]
+        table[i, pos // 16] = g.block_table[sq, free]
+        lens[i] = pos
+        anchors[i] = prompts[sq][pos]
+    d_lens = torch.from_numpy(lens).to(g.dev)
+    d_anchor = torch.from_numpy(anchors).to(g.dev)
+    tokens = torch.zeros((len(blocks), Bk), dtype=torch.int32, device=g.dev)
+    logits = torch.zeros((len(blocks), Bk, w.target.vocab), dtype=torch.float32, device=g.dev)
+    b = g.e.batch(d_lens, table, d_anchor, int(lens.max()))
+    dfl.dflash_draft_block(g.e, b, tokens, 0.0, None, logits)
+    torch.cuda.synchronize(g.dev)
+    g.e.device_status()
+    got_tok, got_log = tokens.cpu().numpy(), logits.cpu().numpy()
+    flips = 0
+    for i, (sq, pos) in enumerate(blocks):
+        ctx = copy.copy(ls.states[sq].ctx)
+        ctx.n = pos                                        # the context features before the anchor only
+        ref = O.draft_block_forward(ls.Wd, w.draft, int(anchors[i]), pos, ctx, Bk, w.mask_token_id, ls.rnd)
+        err = np.abs(got_log[i, 1:] - ref[1:]).max()
+        assert err <= ls.tol, f"block {i} (sequence {sq}, anchor at {pos}): {err}"
+        assert got_tok[i, 0] == anchors[i]
+        for j in range(1, Bk):
+            if got_tok[i, j] != int(np.argmax(ref[j])):
+                assert O.top2_margin(ref[j]) < MARGIN, f"block {i} slot {j}"
+                flips += 1
+    assert flips <= 0.02 * len(blocks) * Bk + 2
+    # the committed caches were not touched: the sequences still step like any other
+    ls.check_cache([0, 7], [0, 1])
+    ls.step(plan=[15, 3], step_idx=0)
+    print("many anchor blocks:", len(blocks), "blocks, low-margin flips", flips)
+
+
 def test_small_bf16_key_split_attention(monkeypatch):
     """The attention kernel for long chunks (wavefronts split the keys of a chunk, merged through LDS) forced on
     at small context lengths: chunks of 1 to 5 page pairs, so some wavefronts get no keys at all, the ragged
