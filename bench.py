@@ -124,6 +124,32 @@ def measure_peaks(dev):
     return out
 
 
+def step_roofline(w, S, ctx, ms_step):
+    """The whole step against the HBM roofline: algorithmic bytes = every weight matrix the step multiplies with once
+    (target and draft layers, the LM head twice, the fusion matrix and the context K/V projections) plus every cached
+    K and V row of both pools once; algorithmic flops = 2 per weight element and row plus the attention products.
+    The time at the published peaks (max of the two bounds per step) is what `frac` compares the measured step to."""
+    t, d = w.target, w.draft
+    es = 2 if w.dtype == "bf16" else 4
+
+    def layer_elems(m):
+        qd, kd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+        return (qd + 2 * kd) * m.d_model + m.d_model * qd + 3 * m.d_ffn * m.d_model
+
+    w_elems = t.n_layers * layer_elems(t) + d.n_layers * layer_elems(d) + 2 * t.vocab * t.d_model \
+        + d.d_model * len(w.tap_layers) * t.d_model + d.n_layers * 2 * d.n_kv_heads * d.head_dim * d.d_model
+    kv_bytes = S * ctx * es * 2 * (t.n_layers * t.n_kv_heads * t.head_dim + d.n_layers * d.n_kv_heads * d.head_dim)
+    M = S * w.block_size
+    gemm_flops = 2.0 * w_elems * M
+    attn_flops = 4.0 * M * ctx * (t.n_layers * t.n_q_heads * t.head_dim + d.n_layers * d.n_q_heads * d.head_dim)
+    nbytes = w_elems * es + kv_bytes
+    t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
+    t_mfma = (gemm_flops + attn_flops) / (MFMA_BF16_PEAK_TFLOPS * 1e12)
+    return dict(algorithmic_bytes=nbytes, algorithmic_flops=gemm_flops + attn_flops, ms_at_hbm_peak=1e3 * t_hbm,
+                ms_at_mfma_peak=1e3 * t_mfma, achieved_GBps=nbytes / (ms_step * 1e-3) / 1e9,
+                frac=max(t_hbm, t_mfma) / (ms_step * 1e-3))
+
+
 def cpu_baseline(w, ctx, time_budget_s=25.0):
     """Times the oracle, as it stands, on a bounded sample of the same step: one target layer and one
     draft layer of the workload's shape over one 16-token block with `ctx` cached rows, plus the final
@@ -337,6 +363,7 @@ def main():
         # length the paper reports for its trained Qwen3-8B drafter (average tau of about 6.5 over its tasks, Table 1 of Section 5.1) to the measured step time
         "committed_tokens_per_s_at_paper_tau_6p5": 6.5 * S / (ms_step * 1e-3),
         "roofline": roof,
+        "step_roofline": step_roofline(w, S, ctx, ms_step),
     }
     out.update(extra)
     if not args.no_cpu_baseline:
