@@ -140,8 +140,9 @@ int dflash_draft_block(dflash_ctx *ctx, const dflash_batch *batch, float tempera
  * n_s .. n_s+B-1 against the paged KV cache; row j sees cache rows 0..n_s-1 and block rows <= j.
  * Writes the B new K/V rows of every layer into the target pool (speculatively: they become
  * visible only when dflash_kv_commit advances seq_lens) and the tapped hidden states into the
- * workspace.  tgt_argmax (device) [S,B]: greedy token after row j.  logits_out (device, nullable)
- * [S,B,V] fp32.  The logits are materialised only if logits_out is given or the last
+ * workspace.  tgt_argmax (device, nullable) [S,B]: greedy token after row j.  logits_out (device, nullable)
+ * [S,B,V] fp32.  With both null the LM head is skipped: the call then only writes K/V rows and taps (a prefill
+ * chunk that ends no prompt).  The logits are materialised only if logits_out is given or the last
  * dflash_draft_block call on this context sampled (temperature > 0), i.e. dflash_accept will need them. */
 int dflash_verify(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *tokens /*(device) [S,B]*/,
                   int32_t *tgt_argmax, float *logits_out, void *stream);

@@ -227,7 +227,7 @@ def dflash_draft_block(e: Engine, batch: Batch, draft_tokens: torch.Tensor, temp
                                   _ptr(logits_out), _stream()), e.ctx)
 
 
-def dflash_verify(e: Engine, batch: Batch, tokens: torch.Tensor, tgt_argmax: torch.Tensor,
+def dflash_verify(e: Engine, batch: Batch, tokens: torch.Tensor, tgt_argmax: Optional[torch.Tensor],
                   logits_out: Optional[torch.Tensor] = None):
     _check(e.l.dflash_verify(e.ctx, C.byref(batch), _ptr(tokens), _ptr(tgt_argmax), _ptr(logits_out), _stream()), e.ctx)
 

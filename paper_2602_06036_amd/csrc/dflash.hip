@@ -448,13 +448,23 @@ struct Engine {
       if (tap < c->rt.n_taps && c->rt.tap_layers[tap] == l) pending_tap = tap++;   // taken by the next RMSNorm
     }
     float* logits = ws<float>(c->ws.logits_t);
+    if (!tgt_argmax && !logits_out) {
+      // nobody wants the tokens after these rows (a prefill chunk that ends no prompt): K/V rows and taps are all the
+      // call is for, so the final norm runs only if the last layer's output is itself tapped, and the LM head not at all
+      if (pending_tap >= 0) norm_h(reinterpret_cast<const float*>(c->tblob + c->tl.gf), M, t.d_model, t.rms_eps);
+      pending = Slab{};
+      c->have_logits_t = false;
+      c->stats_p_T = 0.f;
+      return hip_err ? DFLASH_EHIP : DFLASH_OK;
+    }
     const bool want_logits = logits_out || c->draft_temperature > 0.f;   // sampling: dflash_accept needs the target distribution
     const float sT = c->draft_temperature > 0.f ? c->draft_temperature : 0.f;
     const bool st_p = lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits, want_logits, B, 0, 1.0f, nullptr, sT,
                               ws<float2>(c->ws.stats_p));
     c->stats_p_T = st_p ? sT : 0.f;
     c->have_logits_t = want_logits || amax_parts == 0;
-    argmax(logits, t.vocab, M, B, tgt_argmax, 0, 0, 1.0f, (const uint64_t*)nullptr);
+    if (tgt_argmax) argmax(logits, t.vocab, M, B, tgt_argmax, 0, 0, 1.0f, (const uint64_t*)nullptr);
+    else amax_parts = 0;
     if (logits_out) {
       if (hipMemcpyAsync(logits_out, logits, (size_t)M * t.vocab * 4, hipMemcpyDeviceToDevice, st) != hipSuccess)
         return CTX_FAIL(c, DFLASH_EHIP, "logits copy failed");
@@ -1058,7 +1068,7 @@ int dflash_verify(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* tok
   int rc;
   if ((rc = check_batch(ctx, batch))) return rc;
   if (batch->n_seqs == 0) return DFLASH_OK;
-  if (!tokens || !tgt_argmax) return CTX_FAIL(ctx, DFLASH_EINVAL, "verify: null tokens or tgt_argmax");
+  if (!tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "verify: null tokens");
   return DISPATCH(ctx, verify(batch, tokens, tgt_argmax, logits_out));
 }
 

@@ -80,7 +80,9 @@ class GpuModel:
                 toks[s, : r[s]] = prompts[s][c * Bk: c * Bk + r[s]]
             tokens = torch.from_numpy(toks).to(self.dev)
             b = self.batch()
-            dfl.dflash_verify(self.e, b, tokens, self.tgt_argmax)
+            # a chunk that ends no prompt needs no token out of the target: the LM head is skipped
+            ends_one = bool(((lens > c * Bk) & (lens <= (c + 1) * Bk)).any())
+            dfl.dflash_verify(self.e, b, tokens, self.tgt_argmax if ends_one else None)
             acc = torch.from_numpy((r - 1).astype(np.int32)).to(self.dev)
             dfl.dflash_kv_commit(self.e, b, acc, self.tgt_argmax)
             self.host_lens += r
