@@ -91,6 +91,63 @@ def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
     return e, table, max_len
 
 
+def run_prefill(args, dev):
+    """Prefill of one prompt of args.prefill tokens (8B shape of configuration 2) as ONE many-row pass: every 16-token
+    chunk is a pseudo-sequence whose committed length is the chunk's offset and whose block-table row is the
+    prompt's, handed to one dflash_verify (tokens out: greedy token after every row) and one forced
+    dflash_kv_commit (context K/V of all rows into the draft cache).  Prints one JSON line: prompt tokens per second."""
+    import torch
+    import paper_2602_06036_amd as dfl
+    from synth import inputs as si
+    w = si.workload(2)
+    Bk = w.block_size
+    n_tok = (args.prefill // Bk) * Bk
+    n = n_tok // Bk
+    e, table, _ = build_engine(w, n, n_tok, 1, dev, args.page_order)   # rows long enough for the prompt; the pool is larger than needed
+    pps = table.shape[1]
+    pages = table.reshape(-1)[: (n_tok + Bk + 15) // 16]      # the prompt's pages, taken from the shuffled pool
+    if pages.numel() > pps:
+        raise SystemExit("bench --prefill: prompt longer than a block-table row of this engine")
+    prow = torch.zeros(pps, dtype=torch.int32, device=dev)
+    prow[: pages.numel()] = pages
+    ptable = prow.repeat(n, 1).contiguous()
+    lens0 = (torch.arange(n, dtype=torch.int32, device=dev) * Bk).contiguous()
+    lens = lens0.clone()
+    anchor = torch.zeros(n, dtype=torch.int32, device=dev)
+    tokens = torch.randint(0, w.target.vocab - 1, (n, Bk), dtype=torch.int32, device=dev)
+    argmax = torch.zeros((n, Bk), dtype=torch.int32, device=dev)
+    acc = torch.full((n,), Bk - 1, dtype=torch.int32, device=dev)
+
+    def one_pass():
+        lens.copy_(lens0)
+        b = e.batch(lens, ptable, anchor, n_tok - Bk)
+        dfl.dflash_verify(e, b, tokens, argmax)
+        dfl.dflash_kv_commit(e, b, acc, argmax)
+
+    for _ in range(args.warmup):
+        one_pass()
+    torch.cuda.synchronize(dev)
+    e.device_status()
+    t0 = torch.cuda.Event(enable_timing=True)
+    t1 = torch.cuda.Event(enable_timing=True)
+    t0.record()
+    for _ in range(args.steps):
+        one_pass()
+    t1.record()
+    torch.cuda.synchronize(dev)
+    e.device_status()
+    ms = t0.elapsed_time(t1) / args.steps
+    t = w.target
+    qd, kd = t.n_q_heads * t.head_dim, t.n_kv_heads * t.head_dim
+    flops = 2.0 * n_tok * (t.n_layers * ((qd + 2 * kd) * t.d_model + t.d_model * qd + 3 * t.d_ffn * t.d_model) + t.vocab * t.d_model)
+    print(json.dumps({"metric": "prefill tokens/sec/GPU (8B-shape, one many-row pass)", "value": n_tok / (ms * 1e-3), "unit": "tokens/s",
+                      "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
+                      "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
+                      "config": {"workload": "prefill_8b", "prompt_tokens": n_tok, "rows_per_pass": n_tok, "page_order": args.page_order},
+                      "target_gemm_TFLOPs_algorithmic": flops / (ms * 1e-3) / 1e12}))
+    e.close()
+
+
 def measure_peaks(dev):
     """Machine probes through the library: back-to-back read-only launches over fresh memory (sizes of the O, QKV,
     down, gate/up projections and the LM head), a bf16 MFMA loop at 1, 2 and 4 wavefronts per SIMD, and the
@@ -211,6 +268,9 @@ def main():
     ap.add_argument("--steps", type=int, default=30)
     ap.add_argument("--warmup", type=int, default=5)
     ap.add_argument("--workload", default="cfg2_8b_b1_ctx2048", choices=sorted(WORKLOADS))
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="instead of the step: prefill of one prompt of this many tokens (8B shape) as one many-row "
+                         "verify + forced commit; one JSON line with prompt tokens per second")
     ap.add_argument("--page-order", default="shuffled", choices=["shuffled", "contiguous"],
                     help="how cache pages are assigned to sequences (shuffled = scattered 16-token pages, the harder case)")
     ap.add_argument("--graph", action="store_true",
@@ -240,6 +300,9 @@ def main():
     torch.cuda.set_device(dev)
     if args.peaks:
         print(json.dumps(measure_peaks(dev)))
+        return
+    if args.prefill:
+        run_prefill(args, dev)
         return
     idx, S, ctx = WORKLOADS[args.workload]
     if idx == "llama31":
