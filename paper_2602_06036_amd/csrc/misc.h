@@ -57,7 +57,11 @@ __global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const 
                                                       size_t slab, float* h_out, const float* __restrict__ gain,
                                                       T* __restrict__ out, int D, float eps, T* __restrict__ taps, int tap_idx,
                                                       int tap_K) {
-  const int m = blockIdx.x;
+  // Consecutive workgroup ids go to different XCDs (round-robin dispatch), and the 16 rows of a band share the cache
+  // lines of an operand tile: with many rows, XCD x takes the rows [x * M/8, (x+1) * M/8), so that the 16-byte pieces
+  // of a line are merged in one L2 and leave it as whole lines instead of eight partial writes from eight L2s.
+  const int n_rows = (int)gridDim.x;
+  const int m = (n_rows % 128 == 0) ? (int)(blockIdx.x & 7) * (n_rows >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
   const size_t ro = (size_t)m * D;
   // completed row chunk d..d+3: base + pending slabs (four independent loads in flight, added in ascending order)
   auto gather = [&](int d) {
@@ -151,7 +155,10 @@ template <typename T>
 __global__ __launch_bounds__(256) void qkv_post_kernel(const float* __restrict__ in, int in_ld, const float* __restrict__ qn,
                                                        const float* __restrict__ kn, T* __restrict__ q_out,
                                                        T* __restrict__ pool, SeqGeom geo, RopeArgs ra, int ks, size_t slab) {
-  const int m = blockIdx.x, head = blockIdx.y * 4 + (int)(threadIdx.x >> 6), lane = threadIdx.x & 63;
+  // rows of one 16-key page on one XCD (see rmsnorm_kernel): their 16-byte pieces of a K/V page line meet in one L2
+  const int n_rows = (int)gridDim.x;
+  const int m = (n_rows % 128 == 0) ? (int)(blockIdx.x & 7) * (n_rows >> 3) + (int)(blockIdx.x >> 3) : (int)blockIdx.x;
+  const int head = blockIdx.y * 4 + (int)(threadIdx.x >> 6), lane = threadIdx.x & 63;
   if (head >= ra.n_q_heads + 2 * ra.n_kv_heads) return;   // no barrier in this kernel
   ra.layer += blockIdx.z;
   ra.k_off += blockIdx.z * ra.col_stride;
