@@ -667,7 +667,9 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
         // a workgroup alone on its CU has nobody to hide its barriers behind; the 128-row tiles then run as a
         // three-slot direct-to-LDS ring (they have the LDS to themselves), which loses less
         const bool solo = per_cu == 1, solo_ring = solo && !split && cd.wm == 4 && cd.wn >= 6;   // measured: only pays where K is not split
-        const double t = per_cu * mfma_us / cd.eff * (solo ? (solo_ring ? 1.15 : 1.4) : 1.0) + slab_us;
+        static const double solo_pen = env_int("DFLASH_GEMM_SOLO_PCT", 120) / 100.0;   // tuning knob: percent; measured 120 against 140 and 100
+        const bool small_ring = cd.wm == 2 || cd.wn == 4;   // tiles that run as a direct-to-LDS ring anyway
+        const double t = per_cu * mfma_us / cd.eff * (solo ? (solo_ring ? 1.15 : (small_ring ? solo_pen : 1.4)) : 1.0) + slab_us;
         if (t < best) { best = t; best_wn = cd.wn; best_wm = cd.wm; ks = k; best_solo = solo_ring; }
       }
     }
