@@ -12,7 +12,10 @@ What each function follows (arxiv 2602.06036):
   * shared (frozen) embedding and LM head ................................ Section 4.2
   * losslessness of the verified output .................................. Abstract, Section 1
 The target is a standard pre-norm decoder (RMSNorm, RoPE, GQA, SwiGLU) of the Qwen3 / LLaMA
-family the paper evaluates (Section 5).  The temperature-1 rule is the standard speculative
+family the paper evaluates (Section 5).  The Qwen3-Coder-30B-A3B target named there is a
+mixture-of-experts model; the paper gives no routing rule, so `_ffn` follows that public model
+family's: top-k router logits, weights = softmax over the chosen logits, weighted sum of the
+chosen SwiGLU experts.  The temperature-1 rule is the standard speculative
 sampling rule of the cited Leviathan et al. work, which the paper uses without restating.
 
 Precision: float64 throughout.  `rnd` is the storage-rounding hook (class Rounding): the identity
@@ -34,7 +37,8 @@ Pins (tests/test_oracle_*.py): RoPE vs complex rotation and shift invariance; RM
 invariance; layer with empty cache vs torch CPU scaled_dot_product_attention; sequence (matrix)
 form vs token loop; draft with no context vs non-causal SDPA; joint softmax vs log-sum-exp merge;
 context-permutation invariance; W_c only reaches K/V; losslessness of greedy speculative decoding
-vs plain greedy decoding; greedy acceptance vs brute force; speculative sampling vs exact
+vs plain greedy decoding; routed experts vs the dense FFN (identical experts), the full softmax
+mixture (top_k = all), expert relabelling and a hand-routed case; greedy acceptance vs brute force; speculative sampling vs exact
 enumeration and chi-square; Appendix A.3 memory figures.
 Parity unpinned: draft tokens / accept lengths produced by a random-weight drafter have no
 independent definition beyond these steps; they are pinned only through the component pins above.
@@ -166,8 +170,34 @@ def _attend(m, q: np.ndarray, K: np.ndarray, V: np.ndarray) -> np.ndarray:
     return out
 
 
+ROUTE_MARGINS: Optional[List[float]] = None   # a test may set this to a list: every routing decision then appends
+                                              # the gap between the last chosen and the best rejected router logit
+
+
+def moe_route(logits: np.ndarray, top_k: int):
+    """Routing of one token (the public Qwen3-MoE rule; the paper names the model, Section 5, but not the rule): the
+    top_k experts by router logit (ties -> lowest index), weighted by the softmax over those top_k logits (the
+    softmax over all experts renormalised over the chosen ones is the same thing).  Returns (indices in order of
+    decreasing logit, weights)."""
+    idx = np.argsort(-logits, kind="stable")[:top_k]
+    return idx, softmax(logits[idx])
+
+
 def _ffn(W, m, pre: str, h: np.ndarray, rnd: "Rounding") -> np.ndarray:
     a = rnd(rmsnorm(h, W(pre + "g2"), m.rms_eps))
+    if getattr(m, "n_experts", 0):
+        # routed experts: y_t = sum over the token's top_k experts e of w_e * W_d^e (silu(W_g^e a_t) * (W_u^e a_t))
+        Wr, Wg, Wu, Wd = W(pre + "wr"), W(pre + "wg"), W(pre + "wu"), W(pre + "wd")
+        router = a @ Wr.T
+        out = np.zeros_like(h)
+        for t in range(h.shape[0]):
+            idx, wts = moe_route(router[t], m.top_k)
+            if ROUTE_MARGINS is not None and m.top_k < m.n_experts:
+                ROUTE_MARGINS.append(float(router[t, idx[-1]] - np.delete(router[t], idx).max()))
+            for e, wt in zip(idx, wts):
+                act = rnd(silu(Wg[e] @ a[t]) * (Wu[e] @ a[t]))
+                out[t] += wt * (Wd[e] @ act)
+        return h + out
     act = rnd(silu(a @ W(pre + "wg").T) * (a @ W(pre + "wu").T))
     return h + act @ W(pre + "wd").T
 

@@ -46,6 +46,11 @@ class ModelDims:
     rope_theta: float
     rms_eps: float
     qk_norm: bool
+    # routed-expert FFN (the Qwen3-Coder-30B-A3B target of Section 5 is a mixture-of-experts model): n_experts > 0
+    # replaces the dense FFN by n_experts SwiGLU experts of width d_expert, top_k of them per token
+    n_experts: int = 0
+    top_k: int = 0
+    d_expert: int = 0
 
     @property
     def q_dim(self) -> int:
@@ -125,6 +130,15 @@ def llama31_8b_workload(n_seqs: int = 1, ctx: int = 2048) -> Workload:
     return Workload("llama31_8b_b10", "bf16", t, d, tap_layers_for(32, 5), t.vocab - 1, 10, n_seqs, ctx, ctx, 0.0, 6)
 
 
+def small_moe_workload(n_seqs: int = 3, ctx_min: int = 20, ctx_max: int = 100, seed: int = 61, n_experts: int = 16,
+                       top_k: int = 2, d_expert: int = 256) -> Workload:
+    """The small bf16 model with a routed-expert target (structure of the Qwen3-Coder-30B-A3B target of Section 5:
+    every target layer's FFN is n_experts SwiGLU experts, top_k per token) and the usual dense 2-layer drafter."""
+    t = ModelDims(4, 512, 8, 2, 128, 1536, 4096, 1e6, 1e-6, True, n_experts, top_k, d_expert)
+    d = ModelDims(2, 512, 8, 2, 128, 1536, 4096, 1e6, 1e-6, True)
+    return Workload("small_moe", "bf16", t, d, (0, 1), t.vocab - 1, 16, n_seqs, ctx_min, ctx_max, 0.0, seed)
+
+
 def small_bf16_workload(n_seqs: int = 3, ctx_min: int = 20, ctx_max: int = 150, seed: int = 11,
                         block_size: int = 16, temperature: float = 0.0, draft_layers: int = 2,
                         n_taps: int = 5) -> Workload:
@@ -145,7 +159,16 @@ LAYER_GAINS = ("g1", "g2", "qn", "kn")
 
 
 def layer_shapes(m: ModelDims) -> Dict[str, Tuple[int, ...]]:
-    """Every linear map is stored [out_features, in_features] (y = W x, the paper's notation)."""
+    """Every linear map is stored [out_features, in_features] (y = W x, the paper's notation).  A routed-expert
+    layer has the router "wr" [E, D] and the experts' matrices stacked along a leading expert axis."""
+    if m.n_experts:
+        return {
+            "g1": (m.d_model,), "g2": (m.d_model,), "qn": (m.head_dim,), "kn": (m.head_dim,),
+            "wq": (m.q_dim, m.d_model), "wk": (m.kv_dim, m.d_model), "wv": (m.kv_dim, m.d_model),
+            "wo": (m.d_model, m.q_dim), "wr": (m.n_experts, m.d_model),
+            "wg": (m.n_experts, m.d_expert, m.d_model), "wu": (m.n_experts, m.d_expert, m.d_model),
+            "wd": (m.n_experts, m.d_model, m.d_expert),
+        }
     return {
         "g1": (m.d_model,), "g2": (m.d_model,), "qn": (m.head_dim,), "kn": (m.head_dim,),
         "wq": (m.q_dim, m.d_model), "wk": (m.kv_dim, m.d_model), "wv": (m.kv_dim, m.d_model),

@@ -243,6 +243,106 @@ def test_block_rows_see_each_other_bidirectionally():
     assert np.array_equal(a1[:3], a2[:3]) and not np.allclose(a1[3], a2[3])
 
 
+# ---- routed-expert target (the mixture-of-experts target named in Section 5) -----------------------------------
+def _moe_case(seed, E, k, T=9, d=64, fe=48):
+    m = si.ModelDims(1, d, 2, 2, 32, 4 * d, 50, 1e4, 1e-6, False, E, k, fe)
+    r = np.random.default_rng(seed)
+    t = {"L0.g2": 1.0 + 0.1 * r.uniform(-1, 1, d), "L0.wr": r.standard_normal((E, d)),
+         "L0.wg": r.standard_normal((E, fe, d)) / 8, "L0.wu": r.standard_normal((E, fe, d)) / 8,
+         "L0.wd": r.standard_normal((E, d, fe)) / 8}
+    return m, t, r.standard_normal((T, d))
+
+
+def _dense_ffn_torch(h, g2, wg, wu, wd, eps):
+    a = F.rms_norm(_t(h), (h.shape[-1],), _t(g2), eps)
+    return (_t(h) + F.linear(F.silu(F.linear(a, _t(wg))) * F.linear(a, _t(wu)), _t(wd))).numpy()
+
+
+def test_route_weights_closed_form_and_tie_rule():
+    idx, wts = O.moe_route(np.array([1.0, 3.0, 2.0, 0.0]), 2)
+    assert list(idx) == [1, 2]
+    assert np.allclose(wts, [1 / (1 + np.exp(-1.0)), 1 / (1 + np.exp(1.0))], atol=1e-15)
+    idx, wts = O.moe_route(np.array([0.5, 2.0, 2.0, 2.0]), 2)          # ties go to the lower index
+    assert list(idx) == [1, 2] and np.allclose(wts, [0.5, 0.5])
+    # the full softmax renormalised over the chosen experts is the same weighting
+    lg = np.random.default_rng(0).standard_normal(11)
+    idx, wts = O.moe_route(lg, 4)
+    p = np.exp(lg) / np.exp(lg).sum()
+    assert np.allclose(wts, p[idx] / p[idx].sum(), atol=1e-15) and set(idx) == set(np.argsort(-lg)[:4])
+
+
+@pytest.mark.parametrize("k", [1, 2, 5])
+def test_identical_experts_reduce_to_the_dense_ffn(k):
+    m, t, h = _moe_case(1, 5, k)
+    for key in ("wg", "wu", "wd"):
+        t["L0." + key][:] = t["L0." + key][0]
+    got = O._ffn(lambda n: t[n], m, "L0.", h, O.identity)
+    ref = _dense_ffn_torch(h, t["L0.g2"], t["L0.wg"][0], t["L0.wu"][0], t["L0.wd"][0], m.rms_eps)
+    assert np.allclose(got, ref, atol=1e-11)
+
+
+def test_all_experts_chosen_is_the_full_softmax_mixture():
+    m, t, h = _moe_case(2, 6, 6)
+    got = O._ffn(lambda n: t[n], m, "L0.", h, O.identity)
+    a = F.rms_norm(_t(h), (h.shape[-1],), _t(t["L0.g2"]), m.rms_eps)
+    p = torch.softmax(F.linear(a, _t(t["L0.wr"])), -1)                                   # [T, E]
+    act = F.silu(torch.einsum("efd,td->tef", _t(t["L0.wg"]), a)) * torch.einsum("efd,td->tef", _t(t["L0.wu"]), a)
+    ref = _t(h) + torch.einsum("te,edf,tef->td", p, _t(t["L0.wd"]), act)
+    assert np.allclose(got, ref.numpy(), atol=1e-11)
+
+
+def test_hand_routed_tokens_get_exactly_their_expert():
+    """Router rows are scaled unit vectors and token t is (a multiple of) router row t mod E before the norm gain is
+    undone, so with top_k = 1 token t must come out of expert t mod E alone, with weight 1."""
+    m, t, h = _moe_case(3, 4, 1, T=8)
+    t["L0.g2"][:] = 1.0
+    q, _ = np.linalg.qr(np.random.default_rng(5).standard_normal((m.d_model, m.d_model)))
+    t["L0.wr"] = 3.0 * q[:4]
+    h = np.stack([(1.0 + 0.3 * i) * q[i % 4] for i in range(8)])
+    got = O._ffn(lambda n: t[n], m, "L0.", h, O.identity)
+    for i in range(8):
+        e = i % 4
+        ref = _dense_ffn_torch(h[i:i + 1], t["L0.g2"], t["L0.wg"][e], t["L0.wu"][e], t["L0.wd"][e], m.rms_eps)
+        assert np.allclose(got[i], ref[0], atol=1e-11)
+
+
+def test_relabelling_the_experts_changes_nothing_and_margins_are_reported():
+    m, t, h = _moe_case(4, 7, 3)
+    O.ROUTE_MARGINS = []
+    try:
+        a = O._ffn(lambda n: t[n], m, "L0.", h, O.identity)
+        margins = list(O.ROUTE_MARGINS)
+    finally:
+        O.ROUTE_MARGINS = None
+    assert len(margins) == h.shape[0] and min(margins) > 0
+    perm = np.random.default_rng(9).permutation(7)
+    t2 = {k: (v[perm] if k != "L0.g2" else v) for k, v in t.items()}
+    assert np.allclose(O._ffn(lambda n: t2[n], m, "L0.", h, O.identity), a, atol=1e-12)
+    # dropping the chosen experts' weighting (plain sum) or the renormalisation is visible
+    t3 = dict(t)
+    t3["L0.wr"] = t["L0.wr"] * 0.0                                       # flat router: first k experts, weights 1/k
+    flat = O._ffn(lambda n: t3[n], m, "L0.", h, O.identity)
+    mean3 = np.mean([_dense_ffn_torch(h, t["L0.g2"], t["L0.wg"][e], t["L0.wu"][e], t["L0.wd"][e], m.rms_eps) - h
+                     for e in range(3)], axis=0)
+    assert np.allclose(flat - h, mean3, atol=1e-11)
+
+
+def test_moe_target_sequence_form_equals_token_loop():
+    w = si.small_moe_workload(n_experts=6, top_k=2, d_expert=64)
+    w = replace(w, dtype="f32", target=replace(w.target, n_layers=2, d_model=128, n_q_heads=2, n_kv_heads=1, head_dim=64,
+                                               vocab=300), mask_token_id=299)
+    w = replace(w, draft=replace(w.draft, d_model=128, n_q_heads=2, n_kv_heads=1, head_dim=64, vocab=300, d_ffn=256))
+    wt, _ = si.make_weights(w, 1)
+    W = W64(wt)
+    toks = si.make_prompts(replace(w, ctx_min=13, ctx_max=13))[0]
+    m = w.target
+    kv_a, kv_b = O.KVList(2, 1, 64, 16), O.KVList(2, 1, 64, 16)
+    la, ta = O.target_forward_sequence(W, m, toks, kv_a, w.tap_layers)
+    lb0, _ = O.target_forward_tokens(W, m, toks[:5], 0, kv_b, w.tap_layers)
+    lb1, _ = O.target_forward_tokens(W, m, toks[5:], 5, kv_b, w.tap_layers)
+    assert np.allclose(np.concatenate([lb0, lb1]), la, atol=1e-11)
+
+
 def test_tap_layers_follow_the_paper():
     assert si.tap_layers_for(36, 5) == (1, 9, 17, 25, 33)      # second layer .. third-to-last
     assert si.workload(1).tap_layers == (0,)
