@@ -51,14 +51,21 @@ typedef struct {
   float rope_theta, rms_eps;
   int32_t qk_norm; /* 1: per-head RMSNorm on q and k before RoPE */
   int32_t dtype;   /* DFLASH_F32 | DFLASH_BF16: storage type of weights, activations fed to GEMMs, KV */
+  /* Routed-expert FFN (the mixture-of-experts target of Section 5, Qwen3-Coder-30B-A3B; the paper names the model and
+   * leaves the rule to it): n_experts > 0 replaces every layer's dense FFN by n_experts SwiGLU experts of width
+   * d_expert; a token goes to the top_k experts by router logit (ties -> lowest index), weighted by the softmax over
+   * the chosen logits.  d_ffn is then unused.  Target only, bf16 only; n_experts a multiple of 16 up to 256,
+   * top_k <= 16, d_expert a multiple of 64, d_model a multiple of 128.  All three 0 = dense model. */
+  int32_t n_experts, top_k, d_expert;
 } dflash_dims;
 
 /* One Transformer layer's weights (device), canonical layout. */
 typedef struct {
   const void *wq, *wk, *wv, *wo; /* [Hq*hd, D], [Hkv*hd, D], [Hkv*hd, D], [D, Hq*hd] */
-  const void *wg, *wu, *wd;      /* [F, D], [F, D], [D, F] */
+  const void *wg, *wu, *wd;      /* [F, D], [F, D], [D, F]; routed experts: stacked [E, Fe, D], [E, Fe, D], [E, D, Fe] */
   const float *g1, *g2;          /* [D] pre-attention / pre-FFN RMSNorm gains */
   const float *qn, *kn;          /* [hd] per-head q / k norm gains (ignored unless qk_norm) */
+  const void *wr;                /* [E, D] router (ignored unless n_experts) */
 } dflash_layer_weights;
 
 /* Runtime geometry and caller-owned buffers. */

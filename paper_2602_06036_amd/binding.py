@@ -32,11 +32,12 @@ EXPORTS = [
 
 class Dims(C.Structure):
     _fields_ = [(n, C.c_int32) for n in ("n_layers", "d_model", "n_q_heads", "n_kv_heads", "head_dim", "d_ffn", "vocab")] + \
-               [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("qk_norm", C.c_int32), ("dtype", C.c_int32)]
+               [("rope_theta", C.c_float), ("rms_eps", C.c_float), ("qk_norm", C.c_int32), ("dtype", C.c_int32)] + \
+               [(n, C.c_int32) for n in ("n_experts", "top_k", "d_expert")]
 
 
 class LayerWeights(C.Structure):
-    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "qn", "kn")]
+    _fields_ = [(n, C.c_void_p) for n in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "qn", "kn", "wr")]
 
 
 class Runtime(C.Structure):
@@ -105,7 +106,8 @@ def make_dims(m, dtype: str) -> Dims:
     """m: any object with the ModelDims attributes."""
     return Dims(m.n_layers, m.d_model, m.n_q_heads, m.n_kv_heads, m.head_dim, m.d_ffn, m.vocab,
                 float(m.rope_theta), float(m.rms_eps), int(bool(m.qk_norm)),
-                DFLASH_BF16 if dtype == "bf16" else DFLASH_F32)
+                DFLASH_BF16 if dtype == "bf16" else DFLASH_F32,
+                int(getattr(m, "n_experts", 0)), int(getattr(m, "top_k", 0)), int(getattr(m, "d_expert", 0)))
 
 
 def _ptr(t: Optional[torch.Tensor]) -> Optional[int]:
@@ -125,7 +127,7 @@ def _check(rc: int, ctx=None):
 
 
 def _layer_struct(w: Dict[str, torch.Tensor]) -> LayerWeights:
-    return LayerWeights(*[_ptr(w.get(k)) for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "qn", "kn")])
+    return LayerWeights(*[_ptr(w.get(k)) for k in ("wq", "wk", "wv", "wo", "wg", "wu", "wd", "g1", "g2", "qn", "kn", "wr")])
 
 
 class Engine:

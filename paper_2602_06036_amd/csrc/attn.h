@@ -14,6 +14,8 @@ struct AttnArgs {
   int chunk;     // context tokens per split (multiple of 64)
   int n_splits;
   float scale;   // 1/sqrt(head_dim)
+  int q_shift = 0;   // MFMA kernels: the query heads of one kv head are shared out over 2^q_shift workgroups (a workgroup
+                     // holds at most 64 query rows = block_size * heads; 8 heads per kv head at block size 16 need two)
 };
 
 // partial results: for pr = (m*Hq + hq)*n_splits + split : ml[pr] = (running max, sum exp), o[pr*hd + d]

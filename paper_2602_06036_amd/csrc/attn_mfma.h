@@ -160,7 +160,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int B = geo.block_size;
-  const int group = aa.n_q_heads / aa.n_kv_heads;
+  const int group = (aa.n_q_heads / aa.n_kv_heads) >> aa.q_shift;   // query heads of this workgroup: blockIdx.y ("kvh") counts such head groups
   const int rows = B * group;
   const int n_s = geo.seq_lens[s];
   const int cap = geo.max_pages_per_seq * DF_PAGE;
@@ -179,7 +179,7 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
   L.last_vis = valid ? (aa.causal ? n_s + slot : 0x7FFFFFFF) : -1;
   L.g = g;
   L.lane = lane;
-  L.kvh = kvh;
+  L.kvh = kvh >> aa.q_shift;
 
   // query fragments (B operand of S^T): lane (n, g) holds Q[row][kt*32 + g*8 .. +8]
   u32x4 qf[KT];
@@ -358,7 +358,7 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int B = geo.block_size;
-  const int group = aa.n_q_heads / aa.n_kv_heads;
+  const int group = (aa.n_q_heads / aa.n_kv_heads) >> aa.q_shift;   // query heads of this workgroup: blockIdx.y ("kvh") counts such head groups
   const int rows = B * group;
   const int n_s = geo.seq_lens[s];
   const int cap = geo.max_pages_per_seq * DF_PAGE;
@@ -373,7 +373,7 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
   L.last_vis = 0;
   L.g = g;
   L.lane = lane;
-  L.kvh = kvh;
+  L.kvh = kvh >> aa.q_shift;
   const int n_all_vis = min(L.c1, aa.causal ? n_s : L.n_tok);   // keys below this are visible to every row
 
   // query fragments of the RB row blocks: lane (n, g) holds Q[row rb*16 + n][kt*32 + g*8 .. +8]; wavefront w
@@ -498,9 +498,9 @@ inline bool attn_mfma_launch(hipStream_t, const T*, const T*, SeqGeom, AttnArgs,
 template <>
 inline bool attn_mfma_launch<bf16_t>(hipStream_t st, const bf16_t* q, const bf16_t* pool, SeqGeom geo, AttnArgs aa, int S,
                                      float* part_o, float2* part_ml, int wide_min_chunk) {
-  const int rows = geo.block_size * (aa.n_q_heads / aa.n_kv_heads);
-  if (rows > 64 || (aa.head_dim != 128 && aa.head_dim != 64)) return false;
-  const dim3 grid(aa.n_splits, aa.n_kv_heads, S), block(256);
+  const int rows = (geo.block_size * (aa.n_q_heads / aa.n_kv_heads)) >> aa.q_shift;
+  if (rows > 64 || (aa.n_q_heads / aa.n_kv_heads) % (1 << aa.q_shift) || (aa.head_dim != 128 && aa.head_dim != 64)) return false;
+  const dim3 grid(aa.n_splits, aa.n_kv_heads << aa.q_shift, S), block(256);
   // long chunks: wavefronts split the keys (the chunk's page ids must fit the kernel's LDS slice)
   if (aa.head_dim == 128 && aa.chunk >= wide_min_chunk && aa.chunk / DF_PAGE + 2 <= 16384)
     hipLaunchKernelGGL(attn_mfma_wide_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);

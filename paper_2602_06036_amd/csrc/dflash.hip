@@ -20,6 +20,7 @@
 #include "gemm.h"
 #include "gemm_tiled.h"
 #include "misc.h"
+#include "moe.h"
 
 namespace {
 
@@ -39,8 +40,16 @@ inline size_t esize(int dtype) { return dtype == DFLASH_BF16 ? 2 : 4; }
 inline int round_rows(int dtype, int M) { return dtype == DFLASH_BF16 ? (M + 15) & ~15 : M; }
 
 struct LayerOff {
-  size_t wqkv, wo, wgu, wd, g1, g2, qn, kn, end;
+  size_t wqkv, wo, wgu, wd, wr, g1, g2, qn, kn, end;
 };
+
+// routed-expert layers: rows of the expert-sorted token list (every used expert's share padded to whole 16-row bands)
+// and work items of the grouped GEMMs, both as upper bounds for M token rows
+inline int moe_positions(const dflash_dims& d, int M) {
+  const int mk = M * d.top_k, used = std::min(d.n_experts, mk);
+  return (mk + 15 * used + 15) & ~15;
+}
+inline int moe_items(const dflash_dims& d, int M, int MT) { return std::min(d.n_experts, M * d.top_k) + moe_positions(d, M) / 16 / MT + 1; }
 
 LayerOff layer_layout(const dflash_dims& d) {
   const size_t es = esize(d.dtype);
@@ -49,8 +58,11 @@ LayerOff layer_layout(const dflash_dims& d) {
   size_t off = 0;
   o.wqkv = off; off += align256((qd + 2 * kd) * d.d_model * es);
   o.wo = off;   off += align256((size_t)d.d_model * qd * es);
-  o.wgu = off;  off += align256((size_t)2 * d.d_ffn * d.d_model * es);
-  o.wd = off;   off += align256((size_t)d.d_model * d.d_ffn * es);
+  // routed experts: the experts' packed gate/up and down matrices one after the other, and the router
+  const size_t ffn = d.n_experts ? (size_t)d.n_experts * d.d_expert : (size_t)d.d_ffn;
+  o.wgu = off;  off += align256(2 * ffn * d.d_model * es);
+  o.wd = off;   off += align256((size_t)d.d_model * ffn * es);
+  o.wr = off;   off += align256((size_t)d.n_experts * d.d_model * es);
   o.g1 = off;   off += align256((size_t)d.d_model * 4);
   o.g2 = off;   off += align256((size_t)d.d_model * 4);
   o.qn = off;   off += align256((size_t)d.head_dim * 4);
@@ -110,10 +122,29 @@ int check_dims(const dflash_dims* d, const char* who) {
     if (d->d_model % 8 || d->d_ffn % 16 || qd % 8) return fail(nullptr, DFLASH_EINVAL, "%s: fp32 needs d_model, Hq*hd multiples of 8 and d_ffn a multiple of 16", who);
   }
   if (!(d->rope_theta > 1.f) || !(d->rms_eps >= 0.f)) return fail(nullptr, DFLASH_EINVAL, "%s: bad rope_theta / rms_eps", who);
+  if (d->n_experts) {
+    if (d->dtype != DFLASH_BF16) return fail(nullptr, DFLASH_EINVAL, "%s: routed experts need the bf16 dtype", who);
+    if (d->n_experts < 0 || d->n_experts > MOE_MAX_EXPERTS || d->n_experts % 16)
+      return fail(nullptr, DFLASH_EINVAL, "%s: n_experts must be a multiple of 16 in [16,%d]", who, MOE_MAX_EXPERTS);
+    if (d->top_k < 1 || d->top_k > MOE_MAX_TOPK || d->top_k > d->n_experts) return fail(nullptr, DFLASH_EINVAL, "%s: top_k must be in [1,min(%d,n_experts)]", who, MOE_MAX_TOPK);
+    if (d->d_expert < 64 || d->d_expert % 64 || d->d_model % 128) return fail(nullptr, DFLASH_EINVAL, "%s: routed experts need d_expert a multiple of 64 and d_model a multiple of 128", who);
+  } else if (d->top_k || d->d_expert) {
+    return fail(nullptr, DFLASH_EINVAL, "%s: top_k / d_expert set without n_experts", who);
+  }
   return DFLASH_OK;
 }
 
 // ---- attention split policy -----------------------------------------------------------------------
+// log2 of the workgroups that share one kv head's query heads in the MFMA attention kernels (64 query rows each at
+// most); -1: this shape does not fit them
+inline int attn_q_shift(const dflash_dims& m, int block_size) {
+  const int group = m.n_q_heads / m.n_kv_heads;
+  int sh = 0;
+  while (((block_size * group) >> sh) > 64) ++sh;
+  if (sh == 0) return 0;
+  return (m.dtype == DFLASH_BF16 && (m.head_dim == 128 || m.head_dim == 64) && group % (1 << sh) == 0) ? sh : -1;
+}
+
 struct SplitPlan {
   int n_splits, chunk;
   int bound;  // >= n_splits for this and every smaller max_tokens (sizes the partial buffers)
@@ -147,6 +178,7 @@ constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row 
 
 struct Workspace {
   size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, total;
+  size_t moe_sel_e, moe_sel_w, moe_sel_pos, moe_row_of, moe_items, moe_act, moe_y;   // routed-expert target only
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
   const size_t es = esize(t.dtype);
@@ -179,7 +211,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   const int max_tokens = rt.max_pages_per_seq * DFLASH_PAGE_SIZE;
   for (int S = 1; S <= rt.max_seqs; ++S) {
     for (const dflash_dims* m : {&t, &d}) {
-      const SplitPlan p = plan_splits(S, m->n_kv_heads, max_tokens);
+      const SplitPlan p = plan_splits(S, m->n_kv_heads << attn_q_shift(*m, rt.block_size), max_tokens);
       part_rows = std::max(part_rows, (size_t)S * rt.block_size * m->n_q_heads * p.bound);
     }
   }
@@ -192,6 +224,17 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.lsep = take((size_t)M * (t.vocab / 16 + 1) * 8);    // per-workgroup softmax statistics of an LM-head launch
   w.rope_t = take((size_t)M * (t.head_dim / 2) * 8);   // rotary tables of the call's rows (target, draft)
   w.rope_d = take((size_t)M * (d.head_dim / 2) * 8);
+  w.moe_sel_e = w.moe_sel_w = w.moe_sel_pos = w.moe_row_of = w.moe_items = w.moe_act = w.moe_y = 0;
+  if (t.n_experts) {
+    const size_t mk = (size_t)M * t.top_k, np = moe_positions(t, M);
+    w.moe_sel_e = take(mk * 4);
+    w.moe_sel_w = take(mk * 4);
+    w.moe_sel_pos = take(mk * 4);
+    w.moe_row_of = take(np * 4);
+    w.moe_items = take((size_t)moe_items(t, M, 1) * 16);
+    w.moe_act = take(np * t.d_expert * es * planes);   // SwiGLU products of the sorted list, GEMM operand layout
+    w.moe_y = take(np * D * 4);                        // the experts' outputs, one row per list position
+  }
   w.total = off;
   return w;
 }
@@ -208,9 +251,11 @@ int check_runtime(const dflash_dims* t, const dflash_dims* d, const dflash_runti
   if (rt->mask_token_id < 0 || rt->mask_token_id >= t->vocab) return fail(nullptr, DFLASH_EINVAL, "mask_token_id outside the vocabulary");
   if (t->dtype != d->dtype) return fail(nullptr, DFLASH_EINVAL, "target and draft must share the dtype");
   if (t->d_model != d->d_model || t->vocab != d->vocab) return fail(nullptr, DFLASH_EINVAL, "draft shares embedding and LM head: d_model and vocab must match the target");
+  if (d->n_experts) return fail(nullptr, DFLASH_EINVAL, "the draft model is dense: n_experts must be 0");
   if (t->dtype == DFLASH_BF16 && ((size_t)rt->n_taps * t->d_model) % 32) return fail(nullptr, DFLASH_EINVAL, "n_taps*d_model must be a multiple of 32");
   for (const dflash_dims* m : {t, d})
-    if (rt->block_size * (m->n_q_heads / m->n_kv_heads) > 64) return fail(nullptr, DFLASH_EINVAL, "block_size * (n_q_heads/n_kv_heads) must not exceed 64");
+    if (attn_q_shift(*m, rt->block_size) < 0)
+      return fail(nullptr, DFLASH_EINVAL, "block_size * (n_q_heads/n_kv_heads) above 64 needs bf16, head_dim 64 or 128 and a group size that halves evenly");
   return DFLASH_OK;
 }
 
@@ -371,9 +416,18 @@ struct Engine {
     attention(m, pool, l, b, causal);
     pending = gemm(reinterpret_cast<const T*>(lbase + lo.wo), o, M, D, qd, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
     norm_h(reinterpret_cast<const float*>(lbase + lo.g2), M, D, m.rms_eps);
+    if (m.n_experts) {
+      pending = moe_ffn(m, lbase, lo, M);
+      return;
+    }
     gemm(reinterpret_cast<const T*>(lbase + lo.wgu), a, M, 2 * m.d_ffn, D, EPI_SWIGLU, EpiArgs{nullptr, 0, 0, act, m.d_ffn});
     pending = gemm(reinterpret_cast<const T*>(lbase + lo.wd), act, M, D, m.d_ffn, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
   }
+
+  // Routed-expert FFN on the normalised rows in ws.a: router GEMM -> top-k routing into an expert-sorted row list ->
+  // gate/up (+ SwiGLU) and down projections as grouped launches, every workgroup streaming the matrix of the expert
+  // its bands belong to -> weighted sum per token, left as a slab that the next RMSNorm adds to the residual stream.
+  Slab moe_ffn(const dflash_dims& m, const char* lbase, const LayerOff& lo, int M);
 
   // final norm + LM head with the row argmax fused into the GEMM epilogue where the kernel supports it (then
   // amax_parts > 0 and, unless want_logits, the [M, V] logits are never written); argmax() finishes the job
@@ -711,6 +765,59 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   return Slab{ep.out, ks, ep.slab};
 }
 
+template <int MT, int U, int EPI>
+void launch_grouped(hipStream_t st, const bf16_t* W, const bf16_t* A, int rows, int N, int K, EpiArgs ep, int n_items) {
+  const dim3 grid((N / 16) / 8, n_items, 1), block(256);
+  hipLaunchKernelGGL((gemm_bf16_kernel<8, MT, U, EPI, true>), grid, block, 0, st, W, A, rows, N, K, ep);
+}
+
+template <>
+Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* lbase, const LayerOff& lo, int M) {
+  const int D = m.d_model, E = m.n_experts, Fe = m.d_expert, k = m.top_k;
+  float* arena = ws<float>(c->ws.arena);
+  const bf16_t* a = ws<bf16_t>(c->ws.a);
+  const Slab rs = gemm(reinterpret_cast<const bf16_t*>(lbase + lo.wr), a, M, E, D, EPI_STORE, EpiArgs{arena, E, 0, nullptr, 0});
+  // bands per work item: about the rows an expert gets on average
+  const int avg = (M * k + E - 1) / E, MT = avg <= 16 ? 1 : (avg <= 32 ? 2 : 4);
+  const int n_items = moe_items(m, M, MT), n_pos = moe_positions(m, M);
+  MoeRoute r;
+  r.logits = rs.p; r.ks = rs.ks; r.stride = rs.stride;
+  r.M = M; r.E = E; r.k = k; r.MT = MT;
+  r.sel_e = ws<int32_t>(c->ws.moe_sel_e); r.sel_w = ws<float>(c->ws.moe_sel_w); r.sel_pos = ws<int32_t>(c->ws.moe_sel_pos);
+  r.row_of = ws<int32_t>(c->ws.moe_row_of);
+  r.items = ws<int4>(c->ws.moe_items); r.max_items = n_items;
+  hipLaunchKernelGGL(moe_route_kernel, dim3(1), dim3(1024), 0, st, r);
+  check();
+  bf16_t* act = ws<bf16_t>(c->ws.moe_act);
+  float* y = ws<float>(c->ws.moe_y);
+  const double used = (double)std::min(E, M * k);   // experts whose matrices are streamed, at most
+  {
+    ProfScope prof(c, st, DFLASH_PROF_GEMM_SWIGLU, used * 2 * Fe * D * 2);
+    EpiArgs ep{nullptr, 0, 0, act, Fe};
+    ep.grp_items = r.items; ep.grp_w_stride = (size_t)2 * Fe * D; ep.grp_rows = r.row_of;
+    const bf16_t* W = reinterpret_cast<const bf16_t*>(lbase + lo.wgu);
+    if (MT == 1) launch_grouped<1, 2, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
+    else if (MT == 2) launch_grouped<2, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
+    else launch_grouped<4, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
+    check();
+  }
+  {
+    ProfScope prof(c, st, DFLASH_PROF_GEMM_RESID, used * Fe * D * 2);
+    EpiArgs ep{y, D, 0, nullptr, 0};
+    ep.grp_items = r.items; ep.grp_w_stride = (size_t)D * Fe;
+    const bf16_t* W = reinterpret_cast<const bf16_t*>(lbase + lo.wd);
+    if (MT == 1) launch_grouped<1, 2, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
+    else if (MT == 2) launch_grouped<2, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
+    else launch_grouped<4, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
+    check();
+  }
+  hipLaunchKernelGGL(moe_combine_kernel, dim3(M), dim3(256), 0, st, y, r.sel_pos, r.sel_w, k, D, arena);
+  check();
+  return Slab{arena, 1, (size_t)M * D};
+}
+template <>
+Engine<float>::Slab Engine<float>::moe_ffn(const dflash_dims&, const char*, const LayerOff&, int) { return Slab{}; }   // rejected at create: bf16 only
+
 template <>
 Engine<float>::Slab Engine<float>::gemm(const float* W, const float* A, int M, int N, int K, int epi, EpiArgs ep, bool) {
   ProfScope prof(c, st, gemm_class(epi, N, c->t.vocab), (double)N * K * 4);
@@ -730,10 +837,12 @@ template <typename T>
 void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const dflash_batch* b, bool causal) {
   const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
   const int max_tokens = std::min(b->max_seq_len + B, c->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
-  const SplitPlan p = plan_splits(S, m.n_kv_heads, max_tokens);
+  const int q_shift = attn_q_shift(m, B);
+  const SplitPlan p = plan_splits(S, m.n_kv_heads << q_shift, max_tokens);
   AttnArgs aa;
   aa.n_q_heads = m.n_q_heads; aa.n_kv_heads = m.n_kv_heads; aa.head_dim = m.head_dim; aa.layer = layer;
   aa.causal = causal ? 1 : 0; aa.chunk = p.chunk; aa.n_splits = p.n_splits; aa.scale = 1.0f / sqrtf((float)m.head_dim);
+  aa.q_shift = q_shift;
   float* part_o = ws<float>(c->ws.part_o);
   float2* part_ml = ws<float2>(c->ws.part_ml);
   {
@@ -782,6 +891,7 @@ int copy_f32(hipStream_t st, void* dst, const float* src, size_t n) {
 int pack_layer_common(const dflash_dims& d, const LayerOff& lo, char* lbase, const dflash_layer_weights* w, hipStream_t st) {
   if (!w || !w->wq || !w->wk || !w->wv || !w->wo || !w->wg || !w->wu || !w->wd || !w->g1 || !w->g2)
     return fail(nullptr, DFLASH_EINVAL, "layer weights: null pointer");
+  if (d.n_experts && !w->wr) return fail(nullptr, DFLASH_EINVAL, "layer weights: n_experts set but the router wr is null");
   if (d.qk_norm && (!w->qn || !w->kn)) return fail(nullptr, DFLASH_EINVAL, "layer weights: qk_norm set but qn/kn null");
   const int qd = d.n_q_heads * d.head_dim, kd = d.n_kv_heads * d.head_dim;
   int rc;
@@ -790,10 +900,22 @@ int pack_layer_common(const dflash_dims& d, const LayerOff& lo, char* lbase, con
   qkv.rows[0] = qd; qkv.rows[1] = kd; qkv.rows[2] = kd; qkv.n_src = 3; qkv.mode = 0;
   if ((rc = pack_any(d.dtype, st, qkv, d.d_model, qd + 2 * kd, lbase + lo.wqkv))) return rc;
   if ((rc = pack_any(d.dtype, st, one(w->wo, d.d_model), qd, d.d_model, lbase + lo.wo))) return rc;
-  PackSrc gu{};
-  gu.src[0] = w->wg; gu.src[1] = w->wu; gu.rows[0] = gu.rows[1] = d.d_ffn; gu.n_src = 2; gu.mode = 1;
-  if ((rc = pack_any(d.dtype, st, gu, d.d_model, 2 * d.d_ffn, lbase + lo.wgu))) return rc;
-  if ((rc = pack_any(d.dtype, st, one(w->wd, d.d_model), d.d_ffn, d.d_model, lbase + lo.wd))) return rc;
+  if (d.n_experts) {   // every expert is packed as a matrix of its own, the blobs one after the other
+    const size_t es = esize(d.dtype), fd = (size_t)d.d_expert * d.d_model;
+    for (int e = 0; e < d.n_experts; ++e) {
+      PackSrc gu{};
+      gu.src[0] = (const char*)w->wg + e * fd * es; gu.src[1] = (const char*)w->wu + e * fd * es;
+      gu.rows[0] = gu.rows[1] = d.d_expert; gu.n_src = 2; gu.mode = 1;
+      if ((rc = pack_any(d.dtype, st, gu, d.d_model, 2 * d.d_expert, lbase + lo.wgu + e * 2 * fd * es))) return rc;
+      if ((rc = pack_any(d.dtype, st, one((const char*)w->wd + e * fd * es, d.d_model), d.d_expert, d.d_model, lbase + lo.wd + e * fd * es))) return rc;
+    }
+    if ((rc = pack_any(d.dtype, st, one(w->wr, d.n_experts), d.d_model, d.n_experts, lbase + lo.wr))) return rc;
+  } else {
+    PackSrc gu{};
+    gu.src[0] = w->wg; gu.src[1] = w->wu; gu.rows[0] = gu.rows[1] = d.d_ffn; gu.n_src = 2; gu.mode = 1;
+    if ((rc = pack_any(d.dtype, st, gu, d.d_model, 2 * d.d_ffn, lbase + lo.wgu))) return rc;
+    if ((rc = pack_any(d.dtype, st, one(w->wd, d.d_model), d.d_ffn, d.d_model, lbase + lo.wd))) return rc;
+  }
   if ((rc = copy_f32(st, lbase + lo.g1, w->g1, d.d_model))) return rc;
   if ((rc = copy_f32(st, lbase + lo.g2, w->g2, d.d_model))) return rc;
   if (d.qk_norm) {

@@ -27,6 +27,13 @@ struct EpiArgs {
   // second, tiny kernel combines the parts in ascending order into (max, log-sum-exp).
   float2* lse = nullptr;
   float lse_inv_T = 1.f;
+  // grouped launch (routed experts): blockIdx.y indexes grp_items = (expert, first band, end band, -) instead of a
+  // fixed band range; the workgroup multiplies those bands by the expert's matrix W + expert * grp_w_stride
+  // (elements), an item with expert < 0 has nothing to do.  grp_rows (nullable) [bands * 16]: the activation row
+  // behind each row of a band (the operand is then read through this list; < 0 = padding, any row will do).
+  const int4* grp_items = nullptr;
+  size_t grp_w_stride = 0;
+  const int32_t* grp_rows = nullptr;
 };
 
 // score of logit y at (row m, column col) for the fused argmax
@@ -75,13 +82,20 @@ struct GemmBuf {
   u32x4 w[U][NT], ah[U][MT], al[U][MT];
 };
 
-template <int NT, int MT, int U, int EPI>
+template <int NT, int MT, int U, int EPI, bool GRP = false>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
                                                         int M, int N, int K, EpiArgs ep) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nt0 = blockIdx.x * NT, mt0 = blockIdx.y * MT, kz = blockIdx.z;
+  const int nt0 = blockIdx.x * NT, kz = blockIdx.z;
   const int KT = K >> 5, n_tiles = N >> 4;
-  const int m_tiles = (M + 15) >> 4;
+  int mt0 = blockIdx.y * MT, m_tiles = (M + 15) >> 4;   // bands mt0 .. min(mt0 + MT, m_tiles) - 1 are this workgroup's
+  if constexpr (GRP) {
+    const int4 item = ep.grp_items[blockIdx.y];
+    if (item.x < 0) return;
+    W += (size_t)item.x * ep.grp_w_stride;
+    mt0 = item.y;
+    m_tiles = item.z;
+  }
   const int ks = gridDim.z;
   const int per = (KT + ks * 4 - 1) / (ks * 4);
   const int kb = min(KT, (kz * 4 + wave) * per);
@@ -94,12 +108,21 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     for (int j = 0; j < MT; ++j) acc[i][j] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const u32x4* Wp = reinterpret_cast<const u32x4*>(W) + lane;
-  const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + lane;
+  const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + (GRP && ep.grp_rows ? 0 : lane);   // row lists carry the lane's offset
   // activation bands past the last one alias the last band (their results are never stored);
   // a band holds, per k tile, the hi tile then the lo tile (64 lanes x 16 bytes each)
   size_t a_band[MT];
 #pragma unroll
-  for (int j = 0; j < MT; ++j) a_band[j] = (size_t)min(mt0 + j, m_tiles - 1) * KT * 128;
+  for (int j = 0; j < MT; ++j) {
+    const int band = min(mt0 + j, m_tiles - 1);
+    a_band[j] = (size_t)band * KT * 128;
+    if constexpr (GRP) {
+      if (ep.grp_rows) {   // lane (row r = lane % 16, k chunk lane / 16) of the fragment reads row grp_rows[16 * band + r]
+        const int t = max(ep.grp_rows[band * 16 + (lane & 15)], 0);
+        a_band[j] = (size_t)(t >> 4) * KT * 128 + (size_t)((lane >> 4) * 16 + (t & 15));
+      }
+    }
+  }
 
   auto load = [&](GemmBuf<NT, MT, U>& b, int k0) {
 #pragma unroll

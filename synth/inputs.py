@@ -130,6 +130,15 @@ def llama31_8b_workload(n_seqs: int = 1, ctx: int = 2048) -> Workload:
     return Workload("llama31_8b_b10", "bf16", t, d, tap_layers_for(32, 5), t.vocab - 1, 10, n_seqs, ctx, ctx, 0.0, 6)
 
 
+def qwen3_30b_a3b_workload(n_seqs: int = 1, ctx: int = 2048) -> Workload:
+    """The shape of the mixture-of-experts target of Section 5 (Qwen3-Coder-30B-A3B: 48 layers, d_model 2048, 32 query /
+    4 KV heads of 128, 128 experts of width 768 with 8 per token, QK-norm) with the paper's drafter for it (8 dense
+    layers, Section 5 "Implementation"; dense FFN width: this build's choice of 6144) and block size 16."""
+    t = ModelDims(48, 2048, 32, 4, 128, 6144, 151936, 1e7, 1e-6, True, 128, 8, 768)
+    d = ModelDims(8, 2048, 32, 4, 128, 6144, 151936, 1e7, 1e-6, True)
+    return Workload("qwen3_30b_a3b", "bf16", t, d, tap_layers_for(48, 5), t.vocab - 1, 16, n_seqs, ctx, ctx, 0.0, 7)
+
+
 def small_moe_workload(n_seqs: int = 3, ctx_min: int = 20, ctx_max: int = 100, seed: int = 61, n_experts: int = 16,
                        top_k: int = 2, d_expert: int = 256) -> Workload:
     """The small bf16 model with a routed-expert target (structure of the Qwen3-Coder-30B-A3B target of Section 5:

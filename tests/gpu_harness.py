@@ -40,7 +40,7 @@ class GpuModel:
         e = self.e
         e.pack_target_head(to_dev(wt.raw("E"), self.dev), to_dev(wt.raw("lm"), self.dev), to_dev(wt.raw("gf"), self.dev))
         for l in range(w.target.n_layers):
-            e.pack_target_layer(l, {k: to_dev(wt.raw(f"L{l}.{k}"), self.dev) for k in si.LAYER_MATS + si.LAYER_GAINS})
+            e.pack_target_layer(l, {k: to_dev(wt.raw(f"L{l}.{k}"), self.dev) for k in si.layer_shapes(w.target)})
             torch.cuda.synchronize(self.dev)
         e.pack_draft_head(to_dev(wd.raw("wc"), self.dev), to_dev(wd.raw("gc"), self.dev), to_dev(wd.raw("gf"), self.dev))
         for l in range(w.draft.n_layers):

@@ -30,8 +30,8 @@ def test_every_declared_symbol_is_exported(B):
 
 
 def test_struct_sizes_match_the_header(B):
-    assert C.sizeof(B.Dims) == 11 * 4
-    assert C.sizeof(B.LayerWeights) == 11 * 8
+    assert C.sizeof(B.Dims) == 14 * 4
+    assert C.sizeof(B.LayerWeights) == 12 * 8
     assert C.sizeof(B.Batch) == 8 + 3 * 8
     assert C.sizeof(B.Runtime) == 4 * 4 + 4 + 8 * 4 + 4 + 4 * 8   # incl. no padding surprises
     
@@ -48,6 +48,37 @@ def test_sizes_for_the_8b_shape(B):
     assert l.dflash_kv_pool_bytes(C.byref(dd), 10) == 10 * 16 * 20480
     db = l.dflash_draft_blob_bytes(C.byref(dd), 5, 4096)
     assert db >= 5 * per_layer + 4096 * 20480 * 2 + 5 * 2 * 1024 * 4096 * 2
+
+
+def test_routed_expert_sizes_and_shape_checks(B):
+    """Blob and workspace sizes of the 30B-A3B-shaped mixture-of-experts target (48 layers, 128 experts of width 768,
+    8 per token), and the shapes the routed-expert path refuses."""
+    from dataclasses import replace
+    w = si.qwen3_30b_a3b_workload(1, 2048)
+    l = B.lib()
+    td, dd = B.make_dims(w.target, "bf16"), B.make_dims(w.draft, "bf16")
+    m = w.target
+    experts = 128 * 3 * 768 * 2048 * 2
+    attn = ((32 + 2 * 4) * 128 * 2048 + 2048 * 32 * 128) * 2
+    tb = l.dflash_target_blob_bytes(C.byref(td))
+    lo = 48 * (experts + attn + 128 * 2048 * 2) + 2 * m.vocab * 2048 * 2
+    assert lo <= tb <= lo + 48 * 40000 + 20000
+    rt = B.Runtime()
+    rt.block_size, rt.max_seqs, rt.max_pages_per_seq, rt.n_pages, rt.n_taps, rt.mask_token_id = 16, 32, 130, 32 * 130, 5, 7
+    for i, t in enumerate(w.tap_layers):
+        rt.tap_layers[i] = t
+    ws_moe = l.dflash_workspace_bytes(C.byref(td), C.byref(dd), C.byref(rt))
+    dense = B.make_dims(replace(m, n_experts=0, top_k=0, d_expert=0), "bf16")
+    ws_dense = l.dflash_workspace_bytes(C.byref(dense), C.byref(dd), C.byref(rt))
+    n_pos = 512 * 8 + 15 * 128        # every expert's share of the 4096 (row, expert) pairs padded to 16 rows, at most
+    assert ws_moe - ws_dense >= n_pos * (768 * 4 + 2048 * 4)
+    assert ws_moe - ws_dense <= n_pos * (768 * 4 + 2048 * 4) + 3 * 4096 * 4 + n_pos * 4 + 600 * 16 + 16 * 256
+    for bad in (replace(m, n_experts=24), replace(m, top_k=0), replace(m, top_k=17), replace(m, d_expert=96),
+                replace(m, n_experts=512), replace(m, n_experts=0)):
+        assert l.dflash_target_blob_bytes(C.byref(B.make_dims(bad, "bf16"))) == 0
+        assert l.dflash_last_error(None)
+    assert l.dflash_target_blob_bytes(C.byref(B.make_dims(m, "f32"))) == 0            # bf16 only
+    assert l.dflash_workspace_bytes(C.byref(td), C.byref(td), C.byref(rt)) == 0       # the drafter is dense
 
 
 def test_bad_shapes_are_rejected_with_a_message(B):
