@@ -37,6 +37,11 @@ WORKLOADS = {
     # smaller block at the large batch, where verification is compute-bound (the adaptive block size the paper's
     # Section 5.5 discusses): configuration 5 with B = 8
     "cfg5_8b_b32_ctx8k_B8": ((5, 8), 32, 8192),
+    # mixture-of-experts target of the paper's Section 5 (Qwen3-Coder-30B-A3B shape: 128 experts, 8 per token) with its
+    # 8-layer dense drafter (synth.inputs.qwen3_30b_a3b_workload); router inputs are synthetic, so the tokens of a
+    # block spread over the experts as independent uniform draws would (a trained router clusters them more)
+    "moe_30b_a3b_b1_ctx2048": ("moe30b", 1, 2048),
+    "moe_30b_a3b_b32_ctx2048": ("moe30b", 32, 2048),
 }
 
 
@@ -181,6 +186,11 @@ def measure_peaks(dev):
     return out
 
 
+def expected_experts(m, rows):
+    """Experts reached by `rows` tokens that each pick top_k of n_experts uniformly at random (the synthetic router)."""
+    return m.n_experts * (1.0 - (1.0 - m.top_k / m.n_experts) ** rows)
+
+
 def step_roofline(w, S, ctx, ms_step):
     """The whole step against the HBM roofline: algorithmic bytes = every weight matrix the step multiplies with once
     (target and draft layers, the LM head twice, the fusion matrix and the context K/V projections) plus every cached
@@ -189,15 +199,24 @@ def step_roofline(w, S, ctx, ms_step):
     t, d = w.target, w.draft
     es = 2 if w.dtype == "bf16" else 4
 
-    def layer_elems(m):
-        qd, kd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
-        return (qd + 2 * kd) * m.d_model + m.d_model * qd + 3 * m.d_ffn * m.d_model
-
-    w_elems = t.n_layers * layer_elems(t) + d.n_layers * layer_elems(d) + 2 * t.vocab * t.d_model \
-        + d.d_model * len(w.tap_layers) * t.d_model + d.n_layers * 2 * d.n_kv_heads * d.head_dim * d.d_model
-    kv_bytes = S * ctx * es * 2 * (t.n_layers * t.n_kv_heads * t.head_dim + d.n_layers * d.n_kv_heads * d.head_dim)
     M = S * w.block_size
-    gemm_flops = 2.0 * w_elems * M
+
+    def layer_elems(m):
+        """(weight elements read once, multiply-adds per activation row) of one layer.  Routed experts: the experts that
+        M rows with top_k uniform draws each reach in expectation are read; a row multiplies with top_k of them."""
+        qd, kd = m.n_q_heads * m.head_dim, m.n_kv_heads * m.head_dim
+        attn = (qd + 2 * kd) * m.d_model + m.d_model * qd
+        if m.n_experts:
+            per_expert = 3 * m.d_expert * m.d_model
+            router = m.n_experts * m.d_model
+            return attn + router + expected_experts(m, M) * per_expert, attn + router + m.top_k * per_expert
+        return attn + 3 * m.d_ffn * m.d_model, attn + 3 * m.d_ffn * m.d_model
+
+    (te, tf), (de, df) = layer_elems(t), layer_elems(d)
+    head = 2 * t.vocab * t.d_model + d.d_model * len(w.tap_layers) * t.d_model + d.n_layers * 2 * d.n_kv_heads * d.head_dim * d.d_model
+    w_elems = t.n_layers * te + d.n_layers * de + head
+    kv_bytes = S * ctx * es * 2 * (t.n_layers * t.n_kv_heads * t.head_dim + d.n_layers * d.n_kv_heads * d.head_dim)
+    gemm_flops = 2.0 * (t.n_layers * tf + d.n_layers * df + head) * M
     attn_flops = 4.0 * M * ctx * (t.n_layers * t.n_q_heads * t.head_dim + d.n_layers * d.n_q_heads * d.head_dim)
     nbytes = w_elems * es + kv_bytes
     t_hbm = nbytes / (HBM_PEAK_GBS * 1e9)
@@ -307,6 +326,8 @@ def main():
     idx, S, ctx = WORKLOADS[args.workload]
     if idx == "llama31":
         w = si.llama31_8b_workload(S, ctx)
+    elif idx == "moe30b":
+        w = si.qwen3_30b_a3b_workload(S, ctx)
     elif isinstance(idx, tuple):     # (configuration, block size)
         import dataclasses
         w = dataclasses.replace(si.workload(idx[0]), block_size=idx[1])
@@ -378,23 +399,45 @@ def main():
     if not args.no_profile:
         # the same K steps again with an event pair around every GEMM / attention launch
         e.profile_enable(True)
+        if w.target.n_experts:
+            e.moe_stats()
         for _ in range(K):
             step()
         prof = e.profile_read()
         e.profile_enable(False)
-        names = {0: "gemm_store", 1: "gemm_resid", 2: "gemm_swiglu", 3: "attn", 4: "attn_merge", 5: "gemm_lmhead"}
+        names = {0: "gemm_store", 1: "gemm_resid", 2: "gemm_swiglu", 3: "attn", 4: "attn_merge", 5: "gemm_lmhead",
+                 6: "moe_gateup", 7: "moe_down"}
         per = {}
         gemm_ms = gemm_bytes = 0.0
         for k, (ms, cnt, by) in prof.items():
             per[names[k]] = dict(launches_per_step=cnt / K, avg_us=1e3 * ms / cnt, gbs=(by / cnt) / (ms / cnt) / 1e6 if by else None)
-            if k in (0, 1, 2, 5):
+            if k in (0, 1, 2, 5, 6, 7):
                 gemm_ms += ms
                 gemm_bytes += by
         extra["kernels"] = per
         extra["all_gemm"] = dict(ms_per_step=gemm_ms / K, gbs=gemm_bytes / gemm_ms / 1e6)
         ms, cnt, by = prof[2]        # dominant kernel: gate/up projection with fused SwiGLU
         M_rows = S * Bk
-        if M_rows * 2 > 620:         # above the ridge (2.5 PFLOP/s / 8 TB/s = 310 flop per weight byte = M rows): MFMA-bound
+        if w.target.n_experts:
+            # grouped gate/up launch of the routed experts (a timing class of its own).  Bytes: the experts the rows
+            # reached (counted on the device, averaged over the launches), read once; flops: top_k experts per row.
+            t_ = w.target
+            ms_e, cnt_e, _ = prof[6]
+            n_route, n_reached, n_bands = e.moe_stats()       # totals of the profiled steps (cleared before them)
+            extra["moe"] = dict(experts_reached_per_layer=n_reached / n_route, bands_per_layer=n_bands / n_route,
+                                expected_if_uniform=expected_experts(t_, M_rows))
+            e_by = (n_reached / n_route) * 2 * t_.d_expert * t_.d_model * 2
+            us_e = 1e3 * ms_e / cnt_e
+            flops = 2.0 * M_rows * t_.top_k * 2 * t_.d_expert * t_.d_model
+            if flops / e_by > MFMA_BF16_PEAK_TFLOPS * 1e3 / HBM_PEAK_GBS:
+                ach = flops / (us_e * 1e-6) / 1e12
+                roof = dict(bound="mfma", achieved=ach, peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS)
+            else:
+                ach = e_by / (us_e * 1e-6) / 1e9
+                roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS)
+            roof.update(kernel="gemm_bf16_kernel<SWIGLU, grouped> (routed experts' gate/up projection)", traffic=None,
+                        bytes_per_launch=e_by, flops_per_launch=flops, avg_launch_us=us_e)
+        elif M_rows * 2 > 620:         # above the ridge (2.5 PFLOP/s / 8 TB/s = 310 flop per weight byte = M rows): MFMA-bound
             # algorithmic flops: 2 * M * N * K = M flops per weight byte (bf16); the hi+lo activation pair doubles the
             # MFMA instructions that are issued, which is not counted here
             ach = (by / cnt) * M_rows / (ms / cnt) / 1e9

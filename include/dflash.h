@@ -193,10 +193,18 @@ enum {
   DFLASH_PROF_GEMM_SWIGLU = 2, /* gate/up projection (+ SwiGLU) */
   DFLASH_PROF_ATTN = 3,        /* split-KV block attention */
   DFLASH_PROF_ATTN_MERGE = 4,
-  DFLASH_PROF_GEMM_LMHEAD = 5
+  DFLASH_PROF_GEMM_LMHEAD = 5,
+  DFLASH_PROF_MOE_GATEUP = 6,  /* routed experts: grouped gate/up (+ SwiGLU) launch; bytes = an upper bound, every expert */
+  DFLASH_PROF_MOE_DOWN = 7     /*   that the rows can reach; grouped down projection */
 };
 int dflash_profile_enable(dflash_ctx *ctx, int32_t enable);
 int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count, double *bytes);
+
+/* Routed-expert targets: totals since the last read (or create) of routing launches (one per target layer and
+ * dflash_verify call), experts reached by at least one row, and 16-row bands of the expert-sorted row list, into
+ * out[0..2] (host).  experts / launches * bytes of one expert's matrices = what a layer's expert GEMMs had to read.
+ * Synchronises the stream and clears the totals. */
+int dflash_moe_stats(dflash_ctx *ctx, void *stream, int64_t *out);
 
 /* ---- machine probes (benchmarks; not part of the method) -----------------------------------------
  * What one launch can reach on this GPU, to put the kernels' figures beside: neither needs a context.

@@ -25,7 +25,7 @@ EXPORTS = [
     "dflash_pack_target_head", "dflash_pack_target_layer", "dflash_pack_draft_head", "dflash_pack_draft_layer",
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
-    "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read",
+    "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats",
     "dflash_probe_hbm_read", "dflash_probe_mfma", "dflash_probe_lds_mix",
 ]
 
@@ -94,6 +94,7 @@ def lib() -> C.CDLL:
         l.dflash_kv_write.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
         l.dflash_profile_enable.argtypes = [P, I]
         l.dflash_profile_read.argtypes = [P, P, C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
+        l.dflash_moe_stats.argtypes = [P, P, C.POINTER(C.c_int64)]
         for name in EXPORTS:
             if name not in ("dflash_target_blob_bytes", "dflash_draft_blob_bytes", "dflash_kv_pool_bytes",
                             "dflash_workspace_bytes", "dflash_last_error"):
@@ -217,6 +218,12 @@ class Engine:
         ms, cnt, by = (C.c_float * n)(), (C.c_int32 * n)(), (C.c_double * n)()
         _check(self.l.dflash_profile_read(self.ctx, _stream(), ms, cnt, by), self.ctx)
         return {i: (float(ms[i]), int(cnt[i]), float(by[i])) for i in range(n) if cnt[i]}
+
+    def moe_stats(self):
+        """(routing launches, experts reached, 16-row bands) since the last read; routed-expert targets only."""
+        out = (C.c_int64 * 3)()
+        _check(self.l.dflash_moe_stats(self.ctx, _stream(), out), self.ctx)
+        return int(out[0]), int(out[1]), int(out[2])
 
     def device_status(self):
         _check(self.l.dflash_device_status(self.ctx, _stream()), self.ctx)

@@ -178,7 +178,7 @@ constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row 
 
 struct Workspace {
   size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, total;
-  size_t moe_sel_e, moe_sel_w, moe_sel_pos, moe_row_of, moe_items, moe_act, moe_y;   // routed-expert target only
+  size_t moe_sel_e, moe_sel_w, moe_sel_pos, moe_row_of, moe_items, moe_a, moe_act, moe_y;   // routed-expert target only
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
   const size_t es = esize(t.dtype);
@@ -224,7 +224,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.lsep = take((size_t)M * (t.vocab / 16 + 1) * 8);    // per-workgroup softmax statistics of an LM-head launch
   w.rope_t = take((size_t)M * (t.head_dim / 2) * 8);   // rotary tables of the call's rows (target, draft)
   w.rope_d = take((size_t)M * (d.head_dim / 2) * 8);
-  w.moe_sel_e = w.moe_sel_w = w.moe_sel_pos = w.moe_row_of = w.moe_items = w.moe_act = w.moe_y = 0;
+  w.moe_sel_e = w.moe_sel_w = w.moe_sel_pos = w.moe_row_of = w.moe_items = w.moe_a = w.moe_act = w.moe_y = 0;
   if (t.n_experts) {
     const size_t mk = (size_t)M * t.top_k, np = moe_positions(t, M);
     w.moe_sel_e = take(mk * 4);
@@ -232,6 +232,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
     w.moe_sel_pos = take(mk * 4);
     w.moe_row_of = take(np * 4);
     w.moe_items = take((size_t)moe_items(t, M, 1) * 16);
+    w.moe_a = take(np * D * es * planes);              // the normalised rows in list order, GEMM operand layout
     w.moe_act = take(np * t.d_expert * es * planes);   // SwiGLU products of the sorted list, GEMM operand layout
     w.moe_y = take(np * D * 4);                        // the experts' outputs, one row per list position
   }
@@ -252,6 +253,8 @@ int check_runtime(const dflash_dims* t, const dflash_dims* d, const dflash_runti
   if (t->dtype != d->dtype) return fail(nullptr, DFLASH_EINVAL, "target and draft must share the dtype");
   if (t->d_model != d->d_model || t->vocab != d->vocab) return fail(nullptr, DFLASH_EINVAL, "draft shares embedding and LM head: d_model and vocab must match the target");
   if (d->n_experts) return fail(nullptr, DFLASH_EINVAL, "the draft model is dense: n_experts must be 0");
+  if (t->n_experts && (int64_t)t->n_experts * ((rt->max_seqs * rt->block_size + 31) / 32) > MOE_MASK_WORDS)
+    return fail(nullptr, DFLASH_EINVAL, "routed experts: n_experts * ceil(max_seqs * block_size / 32) must not exceed %d", MOE_MASK_WORDS);
   if (t->dtype == DFLASH_BF16 && ((size_t)rt->n_taps * t->d_model) % 32) return fail(nullptr, DFLASH_EINVAL, "n_taps*d_model must be a multiple of 32");
   for (const dflash_dims* m : {t, d})
     if (attn_q_shift(*m, rt->block_size) < 0)
@@ -777,8 +780,10 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   float* arena = ws<float>(c->ws.arena);
   const bf16_t* a = ws<bf16_t>(c->ws.a);
   const Slab rs = gemm(reinterpret_cast<const bf16_t*>(lbase + lo.wr), a, M, E, D, EPI_STORE, EpiArgs{arena, E, 0, nullptr, 0});
-  // bands per work item: about the rows an expert gets on average
-  const int avg = (M * k + E - 1) / E, MT = avg <= 16 ? 1 : (avg <= 32 ? 2 : 4);
+  // bands per work item: enough for the rows an expert gets on average plus two standard deviations of an even spread,
+  // so that nearly every expert's matrix is streamed by one row of workgroups only
+  const double avg = (double)M * k / E, want = avg + 2.0 * sqrt(avg);
+  const int MT = want <= 16.0 ? 1 : (want <= 32.0 ? 2 : 4);
   const int n_items = moe_items(m, M, MT), n_pos = moe_positions(m, M);
   MoeRoute r;
   r.logits = rs.p; r.ks = rs.ks; r.stride = rs.stride;
@@ -786,15 +791,34 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   r.sel_e = ws<int32_t>(c->ws.moe_sel_e); r.sel_w = ws<float>(c->ws.moe_sel_w); r.sel_pos = ws<int32_t>(c->ws.moe_sel_pos);
   r.row_of = ws<int32_t>(c->ws.moe_row_of);
   r.items = ws<int4>(c->ws.moe_items); r.max_items = n_items;
-  hipLaunchKernelGGL(moe_route_kernel, dim3(1), dim3(1024), 0, st, r);
+  r.counters = reinterpret_cast<unsigned long long*>(c->wsp + c->ws.status + 64);
+  r.n_bands_out = reinterpret_cast<int32_t*>(c->wsp + c->ws.status + 128);
+  if (M <= MOE_FUSED_ROWS) {
+    hipLaunchKernelGGL(moe_route_kernel<true>, dim3(1), dim3(1024), 0, st, r);
+  } else {
+    hipLaunchKernelGGL(moe_topk_kernel, dim3((M + 3) / 4), dim3(256), 0, st, r);
+    check();
+    hipLaunchKernelGGL(moe_route_kernel<false>, dim3(1), dim3(1024), 0, st, r);
+  }
   check();
   bf16_t* act = ws<bf16_t>(c->ws.moe_act);
   float* y = ws<float>(c->ws.moe_y);
+  // tuning knob: from this many rows on the listed rows are first copied into list order (the GEMM then reads whole
+  // fragments); below, the GEMM reads them through the list
+  static const int gather_min = env_int("DFLASH_MOE_GATHER_MIN_ROWS", 64);
+  const bool gathered = M >= gather_min;
+  if (gathered) {
+    hipLaunchKernelGGL(moe_gather_kernel, dim3((D / 32 + 3) / 4, n_pos / 16), dim3(256), 0, st, reinterpret_cast<const u32x4*>(a), r.row_of,
+                       r.n_bands_out, D / 32, ws<u32x4>(c->ws.moe_a));
+    check();
+    a = ws<bf16_t>(c->ws.moe_a);
+  }
   const double used = (double)std::min(E, M * k);   // experts whose matrices are streamed, at most
   {
-    ProfScope prof(c, st, DFLASH_PROF_GEMM_SWIGLU, used * 2 * Fe * D * 2);
+    ProfScope prof(c, st, DFLASH_PROF_MOE_GATEUP, used * 2 * Fe * D * 2);
     EpiArgs ep{nullptr, 0, 0, act, Fe};
     ep.grp_items = r.items; ep.grp_w_stride = (size_t)2 * Fe * D; ep.grp_rows = r.row_of;
+    if (gathered) ep.grp_rows = nullptr;
     const bf16_t* W = reinterpret_cast<const bf16_t*>(lbase + lo.wgu);
     if (MT == 1) launch_grouped<1, 2, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
     else if (MT == 2) launch_grouped<2, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
@@ -802,7 +826,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     check();
   }
   {
-    ProfScope prof(c, st, DFLASH_PROF_GEMM_RESID, used * Fe * D * 2);
+    ProfScope prof(c, st, DFLASH_PROF_MOE_DOWN, used * Fe * D * 2);
     EpiArgs ep{y, D, 0, nullptr, 0};
     ep.grp_items = r.items; ep.grp_w_stride = (size_t)D * Fe;
     const bf16_t* W = reinterpret_cast<const bf16_t*>(lbase + lo.wd);
@@ -1170,6 +1194,14 @@ int dflash_device_status(dflash_ctx* ctx, void* stream) {
     if (hipMemset(ctx->wsp + ctx->ws.status, 0, 4) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "status clear failed");
     return CTX_FAIL(ctx, DFLASH_ECAPACITY, "device: a row addressed a page outside the block table / pool, or a token id outside the vocabulary");
   }
+  return DFLASH_OK;
+}
+
+int dflash_moe_stats(dflash_ctx* ctx, void* stream, int64_t* out) {
+  if (!ctx || !out) return fail(ctx ? ctx->err : nullptr, DFLASH_EINVAL, "moe_stats: null argument");
+  if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "stream synchronise failed");
+  if (hipMemcpy(out, ctx->wsp + ctx->ws.status + 64, 24, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics read failed");
+  if (hipMemset(ctx->wsp + ctx->ws.status + 64, 0, 24) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics clear failed");
   return DFLASH_OK;
 }
 

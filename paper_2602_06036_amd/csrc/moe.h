@@ -9,6 +9,9 @@
 constexpr int MOE_MAX_EXPERTS = 256;
 constexpr int MOE_MAX_TOPK = 16;
 
+constexpr int MOE_MASK_WORDS = 8192;    // LDS words of the (expert x row) bitmap: n_experts * ceil(rows / 32) must fit
+constexpr int MOE_FUSED_ROWS = 64;      // up to this many rows the routing kernel also picks the experts itself
+
 struct MoeRoute {
   const float* logits;   // router logits as K-range slabs: logits[z * stride + t * E + e], z < ks
   int ks;
@@ -21,83 +24,130 @@ struct MoeRoute {
   int32_t* row_of;       // [n_pos_max] expert-sorted list: token row behind each position, -1 = padding
   int4* items;           // [max_items] (expert, first band, end band, 0), expert = -1: unused
   int max_items;
+  unsigned long long* counters;   // [3] running totals: routing launches, experts reached, 16-row bands (statistics)
+  int32_t* n_bands_out;           // [1] bands of the list this launch built
 };
 
-// One workgroup of 16 wavefronts.  Wavefront w owns a contiguous range of token rows; it picks their experts and counts
-// them per expert (its own counters: the experts of one row are distinct and its rows come one after the other, so
-// plain increments do).  The counts become, per expert, a 16-row-padded range of the sorted list with the wavefronts'
-// shares in row order inside it, so that the list -- and everything downstream -- is the same in every run.
+// One wavefront picks row t's experts: lane j < k ends up with the j-th best (expert, weight); returns the expert.
+__device__ __forceinline__ int moe_topk_row(const MoeRoute& a, int t, int lane, float& weight) {
+  float v[4];   // lane holds experts lane, lane + 64, ...
+#pragma unroll
+  for (int i = 0; i < 4; ++i) {
+    const int e = lane + 64 * i;
+    float x = -INFINITY;
+    if (e < a.E) {
+      x = 0.f;
+      for (int z = 0; z < a.ks; ++z) x += a.logits[(size_t)z * a.stride + (size_t)t * a.E + e];
+      x = x == x ? fmaxf(x, -3.0e38f) : -3.0e38f;   // a real expert always beats the padding, whatever the logit
+    }
+    v[i] = x;
+  }
+  float mine = 0.f, top = 0.f;
+  int mine_e = 0;
+  for (int j = 0; j < a.k; ++j) {
+    float bv = v[0];
+    int bi = lane;
+#pragma unroll
+    for (int i = 1; i < 4; ++i)
+      if (v[i] > bv) { bv = v[i]; bi = lane + 64 * i; }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) {
+      const float ov = __shfl_xor(bv, o, 64);
+      const int oi = __shfl_xor(bi, o, 64);
+      if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
+    }
+    if (j == 0) top = bv;
+    if (lane == j) { mine = bv; mine_e = bi; }
+#pragma unroll
+    for (int i = 0; i < 4; ++i)
+      if (bi == lane + 64 * i) v[i] = -INFINITY;
+  }
+  float ex = lane < a.k ? __expf(mine - top) : 0.f, sum = ex;
+#pragma unroll
+  for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
+  weight = ex / sum;
+  return mine_e;
+}
+
+// Expert choice for many rows: one wavefront per row, four rows per workgroup.
+__global__ __launch_bounds__(256) void moe_topk_kernel(MoeRoute a) {
+  const int lane = threadIdx.x & 63, t = blockIdx.x * 4 + (threadIdx.x >> 6);
+  if (t >= a.M) return;
+  float w;
+  const int e = moe_topk_row(a, t, lane, w);
+  if (lane < a.k) {
+    a.sel_e[(size_t)t * a.k + lane] = e;
+    a.sel_w[(size_t)t * a.k + lane] = w;
+  }
+}
+
+// Builds the expert-sorted row list: one workgroup.  A bitmap (expert x row) in LDS records who goes where; an entry's
+// place inside its expert's 16-row-padded range is the number of lower rows with the same expert (a popcount over the
+// bitmap), so the list -- and everything downstream -- is the same in every run.  FUSED: also picks the experts
+// (few rows; saves a launch), else reads the choices moe_topk_kernel left.
+template <bool FUSED>
 __global__ __launch_bounds__(1024) void moe_route_kernel(MoeRoute a) {
-  __shared__ int cnt[16][MOE_MAX_EXPERTS];
+  __shared__ uint32_t mask[MOE_MASK_WORDS];
+  __shared__ uint16_t before[MOE_MASK_WORDS];   // rows of the same expert in lower words
   __shared__ int tot[MOE_MAX_EXPERTS], base[MOE_MAX_EXPERTS], item0[MOE_MAX_EXPERTS];
-  __shared__ int n_items;
+  __shared__ int sel_l[FUSED ? MOE_FUSED_ROWS * MOE_MAX_TOPK : 1];
+  __shared__ int n_items, n_bands, n_used;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  for (int i = tid; i < 16 * MOE_MAX_EXPERTS; i += 1024) (&cnt[0][0])[i] = 0;
+  const int W = (a.M + 31) >> 5, n_entries = a.M * a.k;
+  for (int i = tid; i < a.E * W; i += 1024) mask[i] = 0u;
   __syncthreads();
-  const int chunk = (a.M + 15) / 16, r0 = min(a.M, wave * chunk), r1 = min(a.M, r0 + chunk);
-  for (int t = r0; t < r1; ++t) {
-    float v[4];   // lane holds experts lane, lane + 64, ...
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const int e = lane + 64 * i;
-      float x = -INFINITY;
-      if (e < a.E) {
-        x = 0.f;
-        for (int z = 0; z < a.ks; ++z) x += a.logits[(size_t)z * a.stride + (size_t)t * a.E + e];
-        x = x == x ? fmaxf(x, -3.0e38f) : -3.0e38f;   // a real expert always beats the padding, whatever the logit
+  if constexpr (FUSED) {
+    for (int t = wave; t < a.M; t += 16) {
+      float w;
+      const int e = moe_topk_row(a, t, lane, w);
+      if (lane < a.k) {
+        a.sel_e[(size_t)t * a.k + lane] = e;
+        a.sel_w[(size_t)t * a.k + lane] = w;
+        sel_l[t * a.k + lane] = e;
+        atomicOr(&mask[e * W + (t >> 5)], 1u << (t & 31));
       }
-      v[i] = x;
     }
-    float mine = 0.f, top = 0.f;
-    int mine_e = 0;
-    for (int j = 0; j < a.k; ++j) {
-      float bv = v[0];
-      int bi = lane;
-#pragma unroll
-      for (int i = 1; i < 4; ++i)
-        if (v[i] > bv) { bv = v[i]; bi = lane + 64 * i; }
-#pragma unroll
-      for (int o = 32; o >= 1; o >>= 1) {
-        const float ov = __shfl_xor(bv, o, 64);
-        const int oi = __shfl_xor(bi, o, 64);
-        if (ov > bv || (ov == bv && oi < bi)) { bv = ov; bi = oi; }
-      }
-      if (j == 0) top = bv;
-      if (lane == j) { mine = bv; mine_e = bi; }
-#pragma unroll
-      for (int i = 0; i < 4; ++i)
-        if (bi == lane + 64 * i) v[i] = -INFINITY;
-    }
-    float ex = lane < a.k ? __expf(mine - top) : 0.f, sum = ex;
-#pragma unroll
-    for (int o = 32; o >= 1; o >>= 1) sum += __shfl_xor(sum, o, 64);
-    if (lane < a.k) {
-      a.sel_e[(size_t)t * a.k + lane] = mine_e;
-      a.sel_w[(size_t)t * a.k + lane] = ex / sum;
-      cnt[wave][mine_e] += 1;
+  } else {
+    for (int i = tid; i < n_entries; i += 1024) {
+      const int t = i / a.k, e = min(max(a.sel_e[i], 0), a.E - 1);
+      atomicOr(&mask[e * W + (t >> 5)], 1u << (t & 31));
     }
   }
   __syncthreads();
-  if (tid < a.E) {   // per expert: total, and each wavefront's offset inside the expert's range
+  if (tid < a.E) {
     int s = 0;
-    for (int w = 0; w < 16; ++w) {
-      const int n = cnt[w][tid];
-      cnt[w][tid] = s;
-      s += n;
+    for (int w = 0; w < W; ++w) {
+      before[tid * W + w] = (uint16_t)s;
+      s += __popc(mask[tid * W + w]);
     }
     tot[tid] = s;
   }
   __syncthreads();
-  if (tid == 0) {
-    int p = 0, it = 0;
-    for (int e = 0; e < a.E; ++e) {
-      base[e] = p;
-      item0[e] = it;
-      const int nb = (tot[e] + 15) >> 4;
-      p += nb * 16;
-      it += (nb + a.MT - 1) / a.MT;
+  if (wave == 0) {   // exclusive scans over the experts (bands, work items): lane owns experts 4*lane .. 4*lane+3
+    int nb[4], ni[4], sb = 0, si = 0, su = 0;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = 4 * lane + i;
+      nb[i] = e < a.E ? (tot[e] + 15) >> 4 : 0;
+      ni[i] = (nb[i] + a.MT - 1) / a.MT;
+      sb += nb[i]; si += ni[i]; su += nb[i] > 0;
     }
-    n_items = it;
+    int ib = sb, ii = si;
+#pragma unroll
+    for (int o = 1; o < 64; o <<= 1) {
+      const int ob = __shfl_up(ib, o, 64), oi = __shfl_up(ii, o, 64);
+      if (lane >= o) { ib += ob; ii += oi; }
+    }
+#pragma unroll
+    for (int o = 32; o >= 1; o >>= 1) su += __shfl_xor(su, o, 64);
+    int eb = ib - sb, ei = ii - si;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const int e = 4 * lane + i;
+      if (e < a.E) { base[e] = eb * 16; item0[e] = ei; }
+      eb += nb[i]; ei += ni[i];
+    }
+    if (lane == 63) { n_items = ii; n_bands = ib; n_used = su; }
   }
   __syncthreads();
   if (tid < a.E && tot[tid] > 0) {
@@ -107,15 +157,40 @@ __global__ __launch_bounds__(1024) void moe_route_kernel(MoeRoute a) {
     for (int p = base[tid] + tot[tid]; p < base[tid] + nb * 16; ++p) a.row_of[p] = -1;
   }
   for (int i = n_items + tid; i < a.max_items; i += 1024) a.items[i] = make_int4(-1, 0, 0, 0);
-  for (int t = r0; t < r1; ++t) {
-    if (lane < a.k) {
-      const int e = a.sel_e[(size_t)t * a.k + lane];   // written by this very lane above
-      const int pos = base[e] + cnt[wave][e];
-      cnt[wave][e] += 1;
-      a.sel_pos[(size_t)t * a.k + lane] = pos;
-      a.row_of[pos] = t;
-    }
+  for (int i = tid; i < n_entries; i += 1024) {
+    const int t = i / a.k;
+    int e;
+    if constexpr (FUSED) e = sel_l[i];
+    else e = min(max(a.sel_e[i], 0), a.E - 1);
+    const int pos = base[e] + before[e * W + (t >> 5)] + __popc(mask[e * W + (t >> 5)] & ((1u << (t & 31)) - 1u));
+    a.sel_pos[i] = pos;
+    a.row_of[pos] = t;
   }
+  if (tid == 0) {
+    a.n_bands_out[0] = n_bands;
+    a.counters[0] += 1ull;
+    a.counters[1] += (unsigned long long)n_used;
+    a.counters[2] += (unsigned long long)n_bands;
+  }
+}
+
+// Copies the listed rows of a GEMM operand (hi+lo bf16 tiles, layout of common.h) into list order, so that the grouped
+// GEMM reads whole 1 KB fragments instead of sixteen-byte pieces of sixteen different rows.  One wavefront per
+// (band, k tile), both planes; padding rows become zeros.  grid = (ceil(KT / 4), bands bound).
+__global__ __launch_bounds__(256) void moe_gather_kernel(const u32x4* __restrict__ src, const int32_t* __restrict__ row_of,
+                                                         const int32_t* __restrict__ n_bands, int KT, u32x4* __restrict__ dst) {
+  const int band = blockIdx.y, kt = blockIdx.x * 4 + (threadIdx.x >> 6), lane = threadIdx.x & 63;
+  if (band >= n_bands[0] || kt >= KT) return;
+  const int t = row_of[band * 16 + (lane & 15)];
+  u32x4 hi = {0u, 0u, 0u, 0u}, lo = {0u, 0u, 0u, 0u};
+  if (t >= 0) {
+    const u32x4* p = src + ((size_t)(t >> 4) * KT + kt) * 128 + (lane >> 4) * 16 + (t & 15);
+    hi = p[0];
+    lo = p[64];
+  }
+  u32x4* q = dst + ((size_t)band * KT + kt) * 128 + lane;
+  q[0] = hi;
+  q[64] = lo;
 }
 
 // out[t, :] = sum_j w[t, j] * y[pos[t, j], :], j ascending (decreasing router logit)

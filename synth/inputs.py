@@ -139,6 +139,15 @@ def qwen3_30b_a3b_workload(n_seqs: int = 1, ctx: int = 2048) -> Workload:
     return Workload("qwen3_30b_a3b", "bf16", t, d, tap_layers_for(48, 5), t.vocab - 1, 16, n_seqs, ctx, ctx, 0.0, 7)
 
 
+def wide_moe_workload(n_seqs: int, ctx_min: int = 12, ctx_max: int = 40, seed: int = 91) -> Workload:
+    """Two target layers at the full width of the Section 5 mixture-of-experts target (d_model 2048, 32 query / 4 KV
+    heads, 128 experts of width 768, 8 per token) with a small vocabulary and a one-layer dense drafter: the expert
+    GEMMs, routing and attention run in the launch shapes of the full model at a size the oracle handles."""
+    t = ModelDims(2, 2048, 32, 4, 128, 1024, 4096, 1e7, 1e-6, True, 128, 8, 768)
+    d = ModelDims(1, 2048, 32, 4, 128, 1024, 4096, 1e7, 1e-6, True)
+    return Workload("wide_moe", "bf16", t, d, (0, 1), t.vocab - 1, 16, n_seqs, ctx_min, ctx_max, 0.0, seed)
+
+
 def small_moe_workload(n_seqs: int = 3, ctx_min: int = 20, ctx_max: int = 100, seed: int = 61, n_experts: int = 16,
                        top_k: int = 2, d_expert: int = 256) -> Workload:
     """The small bf16 model with a routed-expert target (structure of the Qwen3-Coder-30B-A3B target of Section 5:

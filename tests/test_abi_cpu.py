@@ -71,8 +71,9 @@ def test_routed_expert_sizes_and_shape_checks(B):
     dense = B.make_dims(replace(m, n_experts=0, top_k=0, d_expert=0), "bf16")
     ws_dense = l.dflash_workspace_bytes(C.byref(dense), C.byref(dd), C.byref(rt))
     n_pos = 512 * 8 + 15 * 128        # every expert's share of the 4096 (row, expert) pairs padded to 16 rows, at most
-    assert ws_moe - ws_dense >= n_pos * (768 * 4 + 2048 * 4)
-    assert ws_moe - ws_dense <= n_pos * (768 * 4 + 2048 * 4) + 3 * 4096 * 4 + n_pos * 4 + 600 * 16 + 16 * 256
+    # list-ordered copy of the rows, their SwiGLU products (hi+lo bf16 pairs), the experts' fp32 outputs
+    assert ws_moe - ws_dense >= n_pos * (2048 * 4 + 768 * 4 + 2048 * 4)
+    assert ws_moe - ws_dense <= n_pos * (2048 * 4 + 768 * 4 + 2048 * 4) + 3 * 4096 * 4 + n_pos * 4 + 600 * 16 + 16 * 256
     for bad in (replace(m, n_experts=24), replace(m, top_k=0), replace(m, top_k=17), replace(m, d_expert=96),
                 replace(m, n_experts=512), replace(m, n_experts=0)):
         assert l.dflash_target_blob_bytes(C.byref(B.make_dims(bad, "bf16"))) == 0

@@ -16,8 +16,12 @@ pytestmark = pytest.mark.gpu
 
 TOL = {"f32": 1e-4, "bf16": 2e-2}
 MARGIN = 1e-2
-ROUTE_TIE = 2e-4     # router-logit gap below which a token may go to another expert than the oracle's (noise is ~1e-5)
-ROUTE_CLEAR = 5e-5   # prompts of the routed-expert tests have no gap below this: their cache rows are compared strictly
+# Router logits of the two sides differ by the noise of their inputs: mostly ~1e-5 (hi+lo GEMM operands), now and then
+# more where a stored bf16 K/V/q element rounded the other way.  A comparison that fails is excused only if the
+# oracle's call had a gap below ROUTE_TIE between a chosen and the best rejected expert; prompts of the small
+# routed-expert tests have no gap below ROUTE_CLEAR and are compared strictly.
+ROUTE_TIE = 1e-3
+ROUTE_CLEAR = 5e-5
 
 
 def _gpu():
@@ -31,11 +35,13 @@ def _gpu():
 class Lockstep:
     """Runs oracle and GPU side by side."""
 
-    def __init__(self, w, prompts, max_len, n_threads=8, max_seqs=None):
+    def __init__(self, w, prompts, max_len, n_threads=8, max_seqs=None, weights=None):
         GpuModel = _gpu()
         self.w = w
-        self.wt, self.wd = si.make_weights(w, n_threads)
-        self.Wt, self.Wd = W64(self.wt), W64(self.wd)
+        if weights is None:
+            wt, wd = si.make_weights(w, n_threads)
+            weights = (wt, wd, W64(wt), W64(wd))
+        self.wt, self.wd, self.Wt, self.Wd = weights
         self.rnd = O.rounding_for(w.dtype)
         self.tol = TOL[w.dtype]
         self.prompts = prompts
@@ -161,8 +167,8 @@ class Lockstep:
             out.append(wrong)
         return np.array(out, dtype=np.int32)
 
-    def check_cache(self, layers_t, layers_d):
-        """Committed rows of the pools against the oracle's lists."""
+    def check_cache(self, layers_t, layers_d, seqs=None):
+        """Committed rows of the pools against the oracle's lists (all sequences, or those in `seqs`)."""
         from paper_2602_06036_amd import binding as B
         # fp32: plain tolerance.  bf16: both sides round GEMM inputs and stored rows to bf16.  One flipped
         # rounding (from a different summation order) perturbs everything downstream a little, which
@@ -170,6 +176,8 @@ class Lockstep:
         # noise itself (~0.3 % of a vector's scale per stage, measured with the oracle alone).  Allow a
         # bf16 step or two on the element plus 2 % of the row's rms; indexing or gain mistakes are O(1).
         for s, st in enumerate(self.states):
+            if seqs is not None and s not in seqs:
+                continue
             for pool, layers, lists in ((B.DFLASH_POOL_TARGET, layers_t, st.kv), (B.DFLASH_POOL_DRAFT, layers_d, st.ctx)):
                 for l in layers:
                     k, v = self.g.read_kv(pool, l, s, 0, st.n)
@@ -177,7 +185,8 @@ class Lockstep:
                         d = np.abs(got - ref)
                         lim = 1e-4 if self.w.dtype == "f32" else \
                             2.0 ** -6 * np.abs(ref) + 0.02 * np.sqrt((ref ** 2).mean(-1, keepdims=True))
-                        assert (d <= lim).all(), f"pool {pool} layer {l} seq {s} {nm}: {d.max()}"
+                        bad = np.argwhere((d > lim).any(axis=tuple(range(1, d.ndim))))[:, 0]
+                        assert bad.size == 0, f"pool {pool} layer {l} seq {s} {nm}: {d.max()} in rows {bad[:8]} of {st.n}"
 
 
 def test_config1_fp32_20_steps_lossless():
@@ -260,6 +269,43 @@ def test_small_moe_target_routed_experts(n_seqs, ctx_max, experts, top_k, seed):
     ls.check_cache([1, 3], [1])
     print("small moe stats", ls.stats, "smallest router gaps", sorted(ls.route_gaps)[:4])
     assert ls.stats["route_ties"] <= 2
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1 + ls.stats["route_ties"]
+
+
+_WIDE_MOE = {}
+
+
+def _wide_moe_weights(w):
+    """The two test cases share one set of weights (and of float64 copies for the oracle): half a minute to make."""
+    if not _WIDE_MOE:
+        wt, wd = si.make_weights(w, 16)
+        _WIDE_MOE["w"] = (wt, wd, W64(wt), W64(wd))
+    return _WIDE_MOE["w"]
+
+
+@pytest.mark.parametrize("n_seqs", [1, 32])
+def test_moe_layers_at_the_full_width_of_the_section5_target(n_seqs):
+    """Two layers with the dimensions of the mixture-of-experts target of Section 5 (128 experts of width 768, 8 per
+    token, d_model 2048, 8 query heads per kv head, B = 16), in the launch shapes bench.py times: one sequence (16
+    rows: fused routing, one band per work item, rows read through the list) and 32 sequences (512 rows: separate
+    expert choice, rows copied into list order, 4 bands per work item).  With thousands of routing decisions some
+    router gap is bound to be tiny; a prompt with one is continued from the oracle's state instead of being compared."""
+    _gpu()
+    w = si.wide_moe_workload(n_seqs)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=40 + 3 * 16, weights=_wide_moe_weights(w))
+    ls.prefill()
+    print("wide moe: prompts done, smallest router gaps", sorted(ls.route_gaps)[:3], flush=True)
+    clear = [s for s, gap in enumerate(ls.route_gaps) if gap > ROUTE_TIE]     # one gap per prompt, in order
+    assert len(clear) >= n_seqs // 4
+    ls.check_cache([0, 1], [0], seqs=clear)
+    if len(clear) < n_seqs:
+        ls.g.load_state(ls.states)
+    for i in range(2):
+        ls.step(plan=None if i == 0 else list(np.arange(n_seqs) % 16), step_idx=i)
+        print("wide moe: step", i, ls.stats, flush=True)
+    assert ls.stats["route_ties"] <= 2 + n_seqs // 8
     assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
     assert ls.stats["reseeds"] <= 1 + ls.stats["route_ties"]
 
