@@ -30,17 +30,26 @@ struct MoeRoute {
 
 // One wavefront picks row t's experts: lane j < k ends up with the j-th best (expert, weight); returns the expert.
 __device__ __forceinline__ int moe_topk_row(const MoeRoute& a, int t, int lane, float& weight) {
-  float v[4];   // lane holds experts lane, lane + 64, ...
+  float v[4] = {0.f, 0.f, 0.f, 0.f};   // lane holds experts lane, lane + 64, ...
+  for (int z0 = 0; z0 < a.ks; z0 += 4) {   // four slabs' loads in flight at a time, added in ascending order
+    float part[4][4];
+#pragma unroll
+    for (int zz = 0; zz < 4; ++zz)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const int e = lane + 64 * i;
+        part[zz][i] = (e < a.E && z0 + zz < a.ks) ? a.logits[(size_t)(z0 + zz) * a.stride + (size_t)t * a.E + e] : 0.f;
+      }
+#pragma unroll
+    for (int zz = 0; zz < 4; ++zz)
+#pragma unroll
+      for (int i = 0; i < 4; ++i) v[i] += part[zz][i];
+  }
 #pragma unroll
   for (int i = 0; i < 4; ++i) {
-    const int e = lane + 64 * i;
-    float x = -INFINITY;
-    if (e < a.E) {
-      x = 0.f;
-      for (int z = 0; z < a.ks; ++z) x += a.logits[(size_t)z * a.stride + (size_t)t * a.E + e];
-      x = x == x ? fmaxf(x, -3.0e38f) : -3.0e38f;   // a real expert always beats the padding, whatever the logit
-    }
-    v[i] = x;
+    const float x = v[i];
+    // a real expert always beats the padding, whatever the logit
+    v[i] = lane + 64 * i < a.E ? (x == x ? fmaxf(x, -3.0e38f) : -3.0e38f) : -INFINITY;
   }
   float mine = 0.f, top = 0.f;
   int mine_e = 0;
