@@ -55,7 +55,8 @@ typedef struct {
    * leaves the rule to it): n_experts > 0 replaces every layer's dense FFN by n_experts SwiGLU experts of width
    * d_expert; a token goes to the top_k experts by router logit (ties -> lowest index), weighted by the softmax over
    * the chosen logits.  d_ffn is then unused.  Target only, bf16 only; n_experts a multiple of 16 up to 256,
-   * top_k <= 16, d_expert a multiple of 64, d_model a multiple of 128.  All three 0 = dense model. */
+   * top_k <= 16, d_expert a multiple of 64, d_model a multiple of 128, and n_experts * ceil(max_seqs * block_size / 32)
+   * <= 8192 (checked by dflash_workspace_bytes / dflash_create).  All three 0 = dense model. */
   int32_t n_experts, top_k, d_expert;
 } dflash_dims;
 

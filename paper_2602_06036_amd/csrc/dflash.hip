@@ -348,6 +348,7 @@ struct Engine {
     const float* p = nullptr;
     int ks = 0;
     size_t stride = 0;
+    RowMix mix;   // routed experts: p holds the experts' outputs per list position, to be mixed per row (see rmsnorm_kernel)
   };
   Slab pending;          // partial sums that the next RMSNorm adds into the residual stream ws.h
   int amax_parts = 0;    // > 0: the last LM-head GEMM left that many per-row argmax partials in ws.amax (fused epilogue)
@@ -364,12 +365,15 @@ struct Engine {
   void norm(const float* base, Slab delta, float* h_out, const float* gain, T* out, int M, int D, float eps, int tap = -1) {
     T* taps = tap >= 0 ? ws<T>(c->ws.taps) : (T*)nullptr;
     const int tap_K = c->rt.n_taps * c->t.d_model;
-    if (D >= 4096)   // one 16-byte chunk per thread: the row's loads are all in flight at once
+    if (delta.mix.pos)
+      hipLaunchKernelGGL((rmsnorm_kernel<T, 256, true>), dim3(M), dim3(256), 0, st, base, delta.p, delta.ks, delta.stride, h_out, gain, out, D,
+                         eps, taps, tap, tap_K, delta.mix);
+    else if (D >= 4096)   // one 16-byte chunk per thread: the row's loads are all in flight at once
       hipLaunchKernelGGL((rmsnorm_kernel<T, 1024>), dim3(M), dim3(1024), 0, st, base, delta.p, delta.ks, delta.stride, h_out, gain, out, D,
-                         eps, taps, tap, tap_K);
+                         eps, taps, tap, tap_K, RowMix{});
     else
       hipLaunchKernelGGL((rmsnorm_kernel<T, 256>), dim3(M), dim3(256), 0, st, base, delta.p, delta.ks, delta.stride, h_out, gain, out, D,
-                         eps, taps, tap, tap_K);
+                         eps, taps, tap, tap_K, RowMix{});
     check();
   }
   // row-wise argmax (or Gumbel-perturbed argmax) in two launches: per-chunk winners, then one wavefront per row
@@ -820,7 +824,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     ep.grp_items = r.items; ep.grp_w_stride = (size_t)2 * Fe * D; ep.grp_rows = r.row_of;
     if (gathered) ep.grp_rows = nullptr;
     const bf16_t* W = reinterpret_cast<const bf16_t*>(lbase + lo.wgu);
-    if (MT == 1) launch_grouped<1, 2, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
+    if (MT == 1) launch_grouped<1, 2, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);   // one k tile per stage: no faster (78.9 us)
     else if (MT == 2) launch_grouped<2, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
     else launch_grouped<4, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
     check();
@@ -830,14 +834,20 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     EpiArgs ep{y, D, 0, nullptr, 0};
     ep.grp_items = r.items; ep.grp_w_stride = (size_t)D * Fe;
     const bf16_t* W = reinterpret_cast<const bf16_t*>(lbase + lo.wd);
-    if (MT == 1) launch_grouped<1, 2, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
+    // tuning knob: k tiles per prefetch stage of the one-band down projection.  Its K is short (6 k tiles per wavefront
+    // at the 30B-A3B shape): one tile per stage leaves registers for four workgroups per CU, whose prologues and
+    // epilogues overlap (measured 48 us against 54 with two tiles per stage and 60 with four)
+    static const int down_u = env_int("DFLASH_MOE_DOWN_U", 1);
+    if (MT == 1 && down_u == 1) launch_grouped<1, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
+    else if (MT == 1) launch_grouped<1, 2, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (MT == 2) launch_grouped<2, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else launch_grouped<4, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     check();
   }
-  hipLaunchKernelGGL(moe_combine_kernel, dim3(M), dim3(256), 0, st, y, r.sel_pos, r.sel_w, k, D, arena);
-  check();
-  return Slab{arena, 1, (size_t)M * D};
+  // the weighted sum of a row's experts' outputs is taken by the next RMSNorm, which adds it to the residual stream
+  Slab out{y, 1, 0};
+  out.mix.pos = r.sel_pos; out.mix.w = r.sel_w; out.mix.k = k;
+  return out;
 }
 template <>
 Engine<float>::Slab Engine<float>::moe_ffn(const dflash_dims&, const char*, const LayerOff&, int) { return Slab{}; }   // rejected at create: bf16 only

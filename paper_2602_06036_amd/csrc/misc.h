@@ -52,11 +52,19 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
 // the preceding GEMM).  When delta is given the completed row is written to h_out (the residual stream).
 // Optionally the completed row is also stored as tap `tap_idx` (GEMM activation operand, row length tap_K).
 // out[m,:] = x * gain / sqrt(mean(x^2) + eps) as GEMM activation operand (Act<T>).
-template <typename T, int NTHR>
+// MIX (routed experts): the pending sum of row m is instead sum_j mix.w[m*k + j] * delta[mix.pos[m*k + j] * D + :], j
+// ascending -- the weighted sum of the row's experts' outputs, which sit at the row's positions of the expert-sorted list.
+struct RowMix {
+  const int32_t* pos = nullptr;
+  const float* w = nullptr;
+  int k = 0;
+};
+
+template <typename T, int NTHR, bool MIX = false>
 __global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const float* __restrict__ delta, int ks,
                                                       size_t slab, float* h_out, const float* __restrict__ gain,
                                                       T* __restrict__ out, int D, float eps, T* __restrict__ taps, int tap_idx,
-                                                      int tap_K) {
+                                                      int tap_K, RowMix mix = RowMix{}) {
   // Consecutive workgroup ids go to different XCDs (round-robin dispatch), and the 16 rows of a band share the cache
   // lines of an operand tile: with many rows, XCD x takes the rows [x * M/8, (x+1) * M/8), so that the 16-byte pieces
   // of a line are merged in one L2 and leave it as whole lines instead of eight partial writes from eight L2s.
@@ -66,6 +74,30 @@ __global__ __launch_bounds__(NTHR) void rmsnorm_kernel(const float* base, const 
   // completed row chunk d..d+3: base + pending slabs (four independent loads in flight, added in ascending order)
   auto gather = [&](int d) {
     float4 v = base ? *reinterpret_cast<const float4*>(base + ro + d) : make_float4(0.f, 0.f, 0.f, 0.f);
+    if constexpr (MIX) {
+      const int32_t* pj = mix.pos + (size_t)m * mix.k;
+      const float* wj = mix.w + (size_t)m * mix.k;
+      int j = 0;
+      for (; j + 4 <= mix.k; j += 4) {   // four experts' rows in flight at a time
+        const float4 p0 = *reinterpret_cast<const float4*>(delta + (size_t)pj[j] * D + d);
+        const float4 p1 = *reinterpret_cast<const float4*>(delta + (size_t)pj[j + 1] * D + d);
+        const float4 p2 = *reinterpret_cast<const float4*>(delta + (size_t)pj[j + 2] * D + d);
+        const float4 p3 = *reinterpret_cast<const float4*>(delta + (size_t)pj[j + 3] * D + d);
+        const float w0 = wj[j], w1 = wj[j + 1], w2 = wj[j + 2], w3 = wj[j + 3];
+        v.x += w0 * p0.x; v.y += w0 * p0.y; v.z += w0 * p0.z; v.w += w0 * p0.w;
+        v.x += w1 * p1.x; v.y += w1 * p1.y; v.z += w1 * p1.z; v.w += w1 * p1.w;
+        v.x += w2 * p2.x; v.y += w2 * p2.y; v.z += w2 * p2.z; v.w += w2 * p2.w;
+        v.x += w3 * p3.x; v.y += w3 * p3.y; v.z += w3 * p3.z; v.w += w3 * p3.w;
+      }
+      for (; j < mix.k; ++j) {
+        const float4 p = *reinterpret_cast<const float4*>(delta + (size_t)pj[j] * D + d);
+        const float w0 = wj[j];
+        v.x += w0 * p.x; v.y += w0 * p.y; v.z += w0 * p.z; v.w += w0 * p.w;
+      }
+      *reinterpret_cast<float4*>(h_out + ro + d) = v;
+      if (taps) Act<T>::store4(taps, m, tap_idx * D + d, tap_K, v);
+      return v;
+    }
     int z = 0;
     for (; z + 4 <= ks; z += 4) {
       const float* pz = delta + (size_t)z * slab + ro + d;

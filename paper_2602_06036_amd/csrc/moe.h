@@ -1,5 +1,6 @@
-// Routed-expert FFN of a mixture-of-experts target (the Qwen3-Coder-30B-A3B target of Section 5): routing and the
-// weighted combination.  The expert GEMMs themselves are grouped launches of the weight-streaming kernel (gemm.h).
+// Routed-expert FFN of a mixture-of-experts target (the Qwen3-Coder-30B-A3B target of Section 5): routing.  The expert
+// GEMMs themselves are grouped launches of the weight-streaming kernel (gemm.h); the weighted sum of a row's experts'
+// outputs is taken by the RMSNorm kernel that follows (misc.h).
 //
 // Routing rule (that model family's; the paper does not restate it): a token goes to the top_k experts by router
 // logit (ties -> lowest index) with weights softmax(chosen logits); y_t = sum_j w_tj FFN_{e_tj}(a_t).
@@ -200,19 +201,4 @@ __global__ __launch_bounds__(256) void moe_gather_kernel(const u32x4* __restrict
   u32x4* q = dst + ((size_t)band * KT + kt) * 128 + lane;
   q[0] = hi;
   q[64] = lo;
-}
-
-// out[t, :] = sum_j w[t, j] * y[pos[t, j], :], j ascending (decreasing router logit)
-__global__ __launch_bounds__(256) void moe_combine_kernel(const float* __restrict__ y, const int32_t* __restrict__ pos,
-                                                          const float* __restrict__ w, int k, int D, float* __restrict__ out) {
-  const int t = blockIdx.x;
-  for (int d4 = threadIdx.x; d4 < D / 4; d4 += 256) {
-    float4 acc = make_float4(0.f, 0.f, 0.f, 0.f);
-    for (int j = 0; j < k; ++j) {
-      const float wj = w[(size_t)t * k + j];
-      const float4 v = reinterpret_cast<const float4*>(y + (size_t)pos[(size_t)t * k + j] * D)[d4];
-      acc.x += wj * v.x; acc.y += wj * v.y; acc.z += wj * v.z; acc.w += wj * v.w;
-    }
-    reinterpret_cast<float4*>(out + (size_t)t * D)[d4] = acc;
-  }
 }
