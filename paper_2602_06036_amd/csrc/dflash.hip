@@ -787,7 +787,8 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   // bands per work item: enough for the rows an expert gets on average plus two standard deviations of an even spread,
   // so that nearly every expert's matrix is streamed by one row of workgroups only
   const double avg = (double)M * k / E, want = avg + 2.0 * sqrt(avg);
-  const int MT = want <= 16.0 ? 1 : (want <= 32.0 ? 2 : 4);
+  static const int mt_force = env_int("DFLASH_MOE_MT", 0);   // tuning / testing knob: 1, 2 or 4 forces the bands per work item
+  const int MT = (mt_force == 1 || mt_force == 2 || mt_force == 4) ? mt_force : (want <= 16.0 ? 1 : (want <= 32.0 ? 2 : 4));
   const int n_items = moe_items(m, M, MT), n_pos = moe_positions(m, M);
   MoeRoute r;
   r.logits = rs.p; r.ks = rs.ks; r.stride = rs.stride;
