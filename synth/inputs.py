@@ -237,42 +237,49 @@ def _gain(seed: int, name: str, n: int) -> np.ndarray:
     return (1.0 + 0.1 * _rng(seed, name).uniform(-1.0, 1.0, n)).astype(np.float32)
 
 
+def tensor_specs(w: Workload) -> Dict[Tuple[str, str], Tuple[tuple, bool]]:
+    """(model prefix "t" | "d", tensor name) -> (shape, is a norm gain) for every tensor of the workload, in the order
+    make_weights creates them.  The shared embedding "E" and LM head "lm" are listed once, under the target."""
+    t, d = w.target, w.draft
+    specs: Dict[Tuple[str, str], Tuple[tuple, bool]] = {}
+    specs[("t", "E")] = ((t.vocab, t.d_model), False)
+    specs[("t", "lm")] = ((t.vocab, t.d_model), False)
+    specs[("t", "gf")] = ((t.d_model,), True)
+    for l in range(t.n_layers):
+        for k, shp in layer_shapes(t).items():
+            specs[("t", f"L{l}.{k}")] = (tuple(shp), k in LAYER_GAINS)
+    specs[("d", "wc")] = ((d.d_model, len(w.tap_layers) * t.d_model), False)
+    specs[("d", "gc")] = ((d.d_model,), True)
+    specs[("d", "gf")] = ((d.d_model,), True)
+    for l in range(d.n_layers):
+        for k, shp in layer_shapes(d).items():
+            specs[("d", f"L{l}.{k}")] = (tuple(shp), k in LAYER_GAINS)
+    return specs
+
+
+def make_tensor(w: Workload, prefix: str, key: str, specs=None) -> np.ndarray:
+    """One tensor of the workload, exactly as make_weights would hold it (every tensor has a random stream of its
+    own, keyed by seed and name): lets a model too large for the host be walked layer by layer."""
+    shape, gain = (specs or tensor_specs(w))[(prefix, key)]
+    full = f"{prefix}.{key}"
+    return _gain(w.wseed, full, shape[0]) if gain else _matrix(w.wseed, full, shape, w.dtype)
+
+
 def make_weights(w: Workload, n_threads: int = 8) -> Tuple[Weights, Weights]:
     """(target, draft) weights.  The draft shares the target's embedding and LM head (by
     reference), has its own layers, final-norm gain, fusion matrix W_c and fusion-norm gain."""
     tgt, drf = Weights(w.dtype), Weights(w.dtype)
-    jobs: List[Tuple[Weights, str, str, tuple, bool]] = []
-
-    def add(dst: Weights, prefix: str, key: str, shape, gain: bool):
-        jobs.append((dst, prefix, key, tuple(shape), gain))
-
-    t, d = w.target, w.draft
-    add(tgt, "t", "E", (t.vocab, t.d_model), False)
-    add(tgt, "t", "lm", (t.vocab, t.d_model), False)
-    add(tgt, "t", "gf", (t.d_model,), True)
-    for l in range(t.n_layers):
-        for k, shp in layer_shapes(t).items():
-            add(tgt, "t", f"L{l}.{k}", shp, k in LAYER_GAINS)
-    add(drf, "d", "wc", (d.d_model, len(w.tap_layers) * t.d_model), False)
-    add(drf, "d", "gc", (d.d_model,), True)
-    add(drf, "d", "gf", (d.d_model,), True)
-    for l in range(d.n_layers):
-        for k, shp in layer_shapes(d).items():
-            add(drf, "d", f"L{l}.{k}", shp, k in LAYER_GAINS)
+    specs = tensor_specs(w)
 
     def run(job):
-        dst, prefix, key, shape, gain = job
-        full = f"{prefix}.{key}"
-        if gain:
-            dst.t[key] = _gain(w.wseed, full, shape[0])
-        else:
-            dst.t[key] = _matrix(w.wseed, full, shape, w.dtype)
+        prefix, key = job
+        (tgt if prefix == "t" else drf).t[key] = make_tensor(w, prefix, key, specs)
 
     if n_threads > 1:
         with ThreadPoolExecutor(n_threads) as ex:
-            list(ex.map(run, jobs))
+            list(ex.map(run, list(specs)))
     else:
-        for j in jobs:
+        for j in specs:
             run(j)
     drf.t["E"] = tgt.t["E"]
     drf.t["lm"] = tgt.t["lm"]

@@ -33,13 +33,13 @@ def shared():
     return dict(golden=golden, wt=wt, wd=wd, blobs=None)
 
 
-def _run_config(shared, cfg):
+def _run_config(shared, cfg, w=None):
     from tests.gpu_harness import GpuModel
     from paper_2602_06036_amd import binding as B
     golden = {k: v for k, v in shared["golden"].items() if v["config"] == cfg}
     if not golden:
         pytest.skip(f"no goldens for configuration {cfg}")
-    w = si.workload(cfg)
+    w = w or si.workload(cfg)
     Bk, S = w.block_size, w.n_seqs
     lens = si.make_context_lengths(w)
     print(f"cfg {cfg}: building engine, S={S}, lens {lens.min()}..{lens.max()}", flush=True)
@@ -126,6 +126,39 @@ def _run_config(shared, cfg):
     print(f"cfg {cfg} stats {stats} accept_len {list(a_all)}", flush=True)
     g.e.close()
     return stats
+
+
+GOLDEN_MOE = os.path.join(os.path.dirname(__file__), "golden", "golden_moe_30b.json")
+
+
+@pytest.fixture(scope="module")
+def shared_moe():
+    """The mixture-of-experts target of the paper's Section 5 at its full shape (48 layers, 128 experts of width 768, 8 per
+    token; 30.5 G parameters, 61 GB on the host while they are packed) with its 8-layer drafter."""
+    import torch
+    if not torch.cuda.is_available():
+        pytest.skip("no GPU")
+    if not os.path.exists(GOLDEN_MOE):
+        pytest.skip("golden_moe_30b.json has not been generated")
+    golden = json.load(open(GOLDEN_MOE))
+    print("generating the 30B-A3B-shaped weights ...", flush=True)
+    wt, wd = si.make_weights(si.qwen3_30b_a3b_workload(1, 2048), 16)
+    return dict(golden=golden, wt=wt, wd=wd, blobs=None)
+
+
+def test_moe_30b_a3b_batch1_ctx2048(shared_moe):
+    """One step of bench.py's `moe_30b_a3b_b1_ctx2048` launch configuration against the oracle's stored result: fused
+    routing, one band per work item, rows read through the list, 8 query heads per kv head."""
+    _run_config(shared_moe, "moe_b1", si.qwen3_30b_a3b_workload(1, 2048))
+    shared_moe["wt"] = shared_moe["wd"] = None        # packed on the device now: free the host copy
+
+
+def test_moe_30b_a3b_batch32_ctx2048(shared_moe):
+    """`moe_30b_a3b_b32_ctx2048`: 512 rows per step (separate expert choice, rows copied into list order, 4 bands per work
+    item); one sampled sequence against the oracle, the others by the properties that hold for every sequence."""
+    if shared_moe["blobs"] is None:
+        pytest.skip("needs the packed weights of the batch-1 case")
+    _run_config(shared_moe, "moe_b32", si.qwen3_30b_a3b_workload(32, 2048))
 
 
 def test_config2_batch1_ctx2048(shared):
