@@ -454,7 +454,8 @@ def main():
                         bytes_per_launch=by / cnt, avg_launch_us=1e3 * ms / cnt)
 
     out = {
-        "metric": "draft+verify tokens/sec/GPU (8B-shape, B=16)",
+        # the headline metric's name as given for the default workload; other shapes and block sizes say so
+        "metric": "draft+verify tokens/sec/GPU (%s, B=%d)" % ("30B-A3B-shape" if w.target.n_experts else ("tiny fp32 shape" if w.dtype == "f32" else "8B-shape"), Bk),
         "value": S * Bk / (ms_step * 1e-3),
         "unit": "tokens/s",
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_step,

@@ -343,6 +343,39 @@ def test_moe_target_sequence_form_equals_token_loop():
     assert np.allclose(np.concatenate([lb0, lb1]), la, atol=1e-11)
 
 
+def test_routed_stack_is_discontinuous_at_router_ties_and_a_dense_stack_is_not():
+    """Why routed-expert parity tests look at router gaps: perturb every embedding row by a relative 1e-4 (the size of
+    the bf16 storage noise between two correct evaluations).  A dense 24-layer stack answers with a uniformly small
+    change of the logits.  The routed stack of the same size answers the same way on every row -- except the one whose
+    smallest router gap (1.5e-5) is below the perturbation of its router logits: that row takes another expert and
+    ends up an order of magnitude further away.  The oracle's ROUTE_MARGINS find that row in advance."""
+    T, n_layers, eps = 48, 24, 1e-4
+
+    def logits_pair(t):
+        w = si.Workload("deep", "f32", t, replace(t, n_layers=1, n_experts=0, top_k=0, d_expert=0), (0,), 511, 16, 1, T, T, 0.0, 0)
+        wt, _ = si.make_weights(w, 4)
+        W = W64(wt)
+        toks = si.make_prompts(w)[0]
+        O.ROUTE_MARGINS = []
+        try:
+            la, _ = O.target_forward_sequence(W, t, toks, O.KVList(n_layers, 1, 64, T), ())
+            gaps = np.array(O.ROUTE_MARGINS).reshape(n_layers, T).min(0) if t.n_experts else None
+        finally:
+            O.ROUTE_MARGINS = None
+        E0 = W("E")
+        E1 = E0 * (1.0 + eps * np.random.default_rng(1).standard_normal(E0.shape))
+        lb, _ = O.target_forward_sequence(lambda n: E1 if n == "E" else W(n), t, toks, O.KVList(n_layers, 1, 64, T), ())
+        return np.abs(la - lb).max(1) / la.std(), gaps
+
+    dense, _ = logits_pair(si.ModelDims(n_layers, 128, 2, 1, 64, 256, 512, 1e4, 1e-6, True))
+    assert dense.max() < 2 * np.median(dense) < 40 * eps
+    moe, gaps = logits_pair(si.ModelDims(n_layers, 128, 2, 1, 64, 256, 512, 1e4, 1e-6, True, 32, 4, 64))
+    worst = int(np.argmax(moe))
+    assert worst == int(np.argmin(gaps)) and gaps[worst] < eps
+    assert moe[worst] > 10 * np.median(moe)
+    assert moe[gaps > 2e-3].max() < 4 * np.median(moe) < 40 * eps
+
+
 def test_tap_layers_follow_the_paper():
     assert si.tap_layers_for(36, 5) == (1, 9, 17, 25, 33)      # second layer .. third-to-last
     assert si.workload(1).tap_layers == (0,)
