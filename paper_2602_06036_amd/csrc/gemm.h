@@ -27,11 +27,12 @@ struct EpiArgs {
   // second, tiny kernel combines the parts in ascending order into (max, log-sum-exp).
   float2* lse = nullptr;
   float lse_inv_T = 1.f;
-  // grouped launch (routed experts): blockIdx.y indexes grp_items = (expert, first band, end band, -) instead of a
-  // fixed band range; the workgroup multiplies those bands by the expert's matrix W + expert * grp_w_stride
+  // grouped launch (routed experts): a 1-D grid over (work item, column block); grp_items[item] = (expert, first band,
+  // end band, -) replaces the fixed band range; the workgroup multiplies those bands by the expert's matrix W + expert * grp_w_stride
   // (elements), an item with expert < 0 has nothing to do.  grp_rows (nullable) [bands * 16]: the activation row
   // behind each row of a band (the operand is then read through this list; < 0 = padding, any row will do).
   const int4* grp_items = nullptr;
+  int grp_n_items = 0;
   size_t grp_w_stride = 0;
   const int32_t* grp_rows = nullptr;
 };
@@ -86,13 +87,21 @@ template <int NT, int MT, int U, int EPI, bool GRP = false>
 __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
                                                         int M, int N, int K, EpiArgs ep) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  const int nt0 = blockIdx.x * NT, kz = blockIdx.z;
+  const int kz = blockIdx.z;
   const int KT = K >> 5, n_tiles = N >> 4;
+  int nt0 = blockIdx.x * NT;
   int mt0 = blockIdx.y * MT, m_tiles = (M + 15) >> 4;   // bands mt0 .. min(mt0 + MT, m_tiles) - 1 are this workgroup's
   if constexpr (GRP) {
-    const int4 item = ep.grp_items[blockIdx.y];
+    // 1-D grid; consecutive workgroup ids go to different XCDs (round-robin dispatch), so id = 8*j + x is work item
+    // 8*(j / columns) + x, column block j % columns: the workgroups that share an item's activation rows run back to
+    // back on one XCD and fetch them into one L2 instead of eight
+    const int cols = n_tiles / NT, x = blockIdx.x & 7, j = blockIdx.x >> 3;
+    const int it = (j / cols) * 8 + x;
+    if (it >= ep.grp_n_items) return;
+    const int4 item = ep.grp_items[it];
     if (item.x < 0) return;
     W += (size_t)item.x * ep.grp_w_stride;
+    nt0 = (j % cols) * NT;
     mt0 = item.y;
     m_tiles = item.z;
   }
