@@ -21,7 +21,9 @@ HBM_PEAK_GBS = 8000.0
 # workload (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): profiles/gateup_gemm_attention_hbm_traffic.md
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
 MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": int(99374.8 * 2 + 768) * 1024, "cfg3_8b_b16_ctx2560": int(114806.3 * 2 + 12288) * 1024,
-                          "cfg4_8b_b4_ctx16k": int(102485.9 * 2 + 3072) * 1024, "cfg5_8b_b32_ctx8k": int(131284.2 * 2 + 24576) * 1024}
+                          "cfg4_8b_b4_ctx16k": int(102485.9 * 2 + 3072) * 1024, "cfg5_8b_b32_ctx8k": int(131284.2 * 2 + 24576) * 1024,
+                          # grouped gate/up launch of the routed experts: profiles/moe_expert_gemm_hbm_traffic.md
+                          "moe_30b_a3b_b1_ctx2048": int(230241.5 * 2 + 3588.2) * 1024, "moe_30b_a3b_b32_ctx2048": int(413442.9 * 2 + 15089.0) * 1024}
 
 WORKLOADS = {
     # name: (synth workload index, n_seqs, context)
@@ -435,7 +437,7 @@ def main():
             else:
                 ach = e_by / (us_e * 1e-6) / 1e9
                 roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS)
-            roof.update(kernel="gemm_bf16_kernel<SWIGLU, grouped> (routed experts' gate/up projection)", traffic=None,
+            roof.update(kernel="gemm_bf16_kernel<SWIGLU, grouped> (routed experts' gate/up projection)", traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
                         bytes_per_launch=e_by, flops_per_launch=flops, avg_launch_us=us_e)
         elif M_rows * 2 > 620:         # above the ridge (2.5 PFLOP/s / 8 TB/s = 310 flop per weight byte = M rows): MFMA-bound
             # algorithmic flops: 2 * M * N * K = M flops per weight byte (bf16); the hi+lo activation pair doubles the
