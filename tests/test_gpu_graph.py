@@ -109,6 +109,15 @@ def test_graph_replay_small_bf16_greedy_and_sampling():
     _run(replace(w, temperature=1.0), prompts, 1.0)
 
 
+@pytest.mark.parametrize("n_seqs", [3, 10])
+def test_graph_replay_routed_expert_target(n_seqs):
+    """The routed-expert step is graph-capturable too: routing, the expert-sorted row list and the work items live on the
+    device and are rebuilt by every replay (48 rows: fused routing, rows read through the list; 160 rows: separate
+    expert choice, rows copied into list order)."""
+    w = si.small_moe_workload(n_seqs=n_seqs, ctx_min=12, ctx_max=40, seed=72, n_experts=16, top_k=4)
+    _run(w, si.make_prompts(w), 0.0)
+
+
 def test_step_without_materialised_logits_gives_the_same_tokens():
     """Greedy steps that ask for no logits (the LM-head GEMMs then only leave their fused per-row argmax partials
     and never write the [S, B, V] logits) choose exactly the tokens of steps that do; a sampling accept after a
