@@ -701,6 +701,8 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
       if (U4 >= 2) launch_bf16<8, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<8, 2, 1>(st, W, A, M, N, K, kepi, ep, ks);
     } else {
+      // (the single-buffered two-workgroups-per-CU form of this kernel that the routed experts use was measured here
+      // too: 58.7 us against 48.2 for gate/up at 64 rows -- a dense launch has fewer workgroups than CUs)
       if (U4 >= 2) launch_bf16<8, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
     }
@@ -773,11 +775,11 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
 }
 
 // (four weight tiles per wavefront instead of eight were measured at 512 rows: 192 us against 174 for gate/up)
-template <int MT, int U, int EPI>
+template <int MT, int U, int EPI, int PH = 1>
 void launch_grouped(hipStream_t st, const bf16_t* W, const bf16_t* A, int rows, int N, int K, EpiArgs ep, int n_items) {
   const dim3 grid(((n_items + 7) / 8) * 8 * ((N / 16) / 8), 1, 1), block(256);
   ep.grp_n_items = n_items;
-  hipLaunchKernelGGL((gemm_bf16_kernel<8, MT, U, EPI, true>), grid, block, 0, st, W, A, rows, N, K, ep);
+  hipLaunchKernelGGL((gemm_bf16_kernel<8, MT, U, EPI, true, PH>), grid, block, 0, st, W, A, rows, N, K, ep);
 }
 
 template <>
@@ -821,6 +823,11 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     a = ws<bf16_t>(c->ws.moe_a);
   }
   const double used = (double)std::min(E, M * k);   // experts whose matrices are streamed, at most
+  // tuning knob: the 4-band grouped down projection runs single-buffered with the cross-wavefront sum in two halves (200
+  // registers, 64 KB of LDS: two workgroups per CU cover each other's waits); 1 = the double-buffered form, one
+  // workgroup per CU.  Measured at 512 rows: 91-95 us against 104-106.  The gate/up launch gains nothing from it (165-181
+  // us from run to run against 167-176) and stays double-buffered.
+  static const int ph4 = env_int("DFLASH_MOE_PHASES", 2);
   {
     ProfScope prof(c, st, DFLASH_PROF_MOE_GATEUP, used * 2 * Fe * D * 2);
     EpiArgs ep{nullptr, 0, 0, act, Fe};
@@ -844,6 +851,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     if (MT == 1 && down_u == 1) launch_grouped<1, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (MT == 1) launch_grouped<1, 2, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (MT == 2) launch_grouped<2, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
+    else if (ph4 == 2) launch_grouped<4, 1, EPI_STORE, 2>(st, W, act, n_pos, D, Fe, ep, n_items);
     else launch_grouped<4, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     check();
   }

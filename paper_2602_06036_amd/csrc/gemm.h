@@ -3,6 +3,8 @@
 //         (two MFMAs per weight tile), fp32 accumulation.
 //   fp32: one wavefront per output column (tiny models only).
 #pragma once
+#include <type_traits>
+
 #include "common.h"
 
 enum { EPI_STORE = 0, EPI_RESID = 1, EPI_SWIGLU = 2 };
@@ -83,8 +85,8 @@ struct GemmBuf {
   u32x4 w[U][NT], ah[U][MT], al[U][MT];
 };
 
-template <int NT, int MT, int U, int EPI, bool GRP = false>
-__global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
+template <int NT, int MT, int U, int EPI, bool GRP = false, int PH = 1>
+__global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
                                                         int M, int N, int K, EpiArgs ep) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kz = blockIdx.z;
@@ -167,7 +169,15 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
   // time, and the wait for the older buffer would then have to drain the newer one as well.  The last one or two
   // stages are peeled off; if the range has an odd number of stages the final load re-reads the last tile
   // (still in cache) and meets zeroed activations.
-  if (kb < ke) {
+  if constexpr (PH == 2) {
+    // one buffer only (and the cross-wavefront sum below in two halves): half the registers and half the LDS, so that
+    // two workgroups share a CU and their wavefronts cover each other's waits
+    GemmBuf<NT, MT, U> b;
+    for (int k0 = kb; k0 < ke; k0 += U) {
+      load(b, k0);
+      compute(b);
+    }
+  } else if (kb < ke) {
     GemmBuf<NT, MT, U> b0, b1;
     load(b0, kb);
     int k0 = kb;
@@ -182,15 +192,12 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     compute(b1);
   }
 
-  __shared__ float4 red[4][NT * MT][64];
-#pragma unroll
-  for (int i = 0; i < NT; ++i)
-#pragma unroll
-    for (int j = 0; j < MT; ++j)
-      red[wave][i * MT + j][lane] = make_float4(acc[i][j][0], acc[i][j][1], acc[i][j][2], acc[i][j][3]);
-  __syncthreads();
-
-  auto wg_sum = [&](int t) {   // the four wavefronts' partial sums of tile t, in wavefront order
+  // The four wavefronts' partial sums meet in LDS, PH phases of NT / PH weight tiles each (PH = 2 halves the buffer).
+  constexpr int HT = NT / PH;
+  static_assert(NT % PH == 0 && (EPI != EPI_SWIGLU || HT % 2 == 0), "phases");
+  __shared__ float4 red[4][HT * MT][64];
+  const int mrow = lane & 15, g = lane >> 4;
+  auto tile_sum = [&](int t) {   // the four wavefronts' partial sums of tile t of the current phase, in wavefront order
     float4 s = red[0][t][lane];
 #pragma unroll
     for (int w = 1; w < 4; ++w) {
@@ -199,34 +206,43 @@ __global__ __launch_bounds__(256) void gemm_bf16_kernel(const bf16_t* __restrict
     }
     return s;
   };
-
-  auto tile_sum = wg_sum;
-
-  const int mrow = lane & 15, g = lane >> 4;
-  if (EPI == EPI_SWIGLU) {
-    bf16_t* act = reinterpret_cast<bf16_t*>(ep.act);
-    for (int t = wave; t < (NT / 2) * MT; t += 4) {
-      const int p = t / MT, j = t % MT;
-      const float4 gs = tile_sum((2 * p) * MT + j), us = tile_sum((2 * p + 1) * MT + j);
-      const int m = (mt0 + j) * 16 + mrow;
-      if (mt0 + j < m_tiles && m < M) {
-        const int col = ((nt0 + 2 * p) >> 1) * 16 + 4 * g;
-        Act<bf16_t>::store4(act, m, col, ep.act_K,
-                            make_float4(silu_f(gs.x) * us.x, silu_f(gs.y) * us.y, silu_f(gs.z) * us.z, silu_f(gs.w) * us.w));
+  auto phase = [&](auto phc) {
+    constexpr int ph = decltype(phc)::value;
+    if (ph) __syncthreads();   // everybody is done reading the previous phase
+#pragma unroll
+    for (int i = 0; i < HT; ++i)
+#pragma unroll
+      for (int j = 0; j < MT; ++j)
+        red[wave][i * MT + j][lane] = make_float4(acc[ph * HT + i][j][0], acc[ph * HT + i][j][1], acc[ph * HT + i][j][2], acc[ph * HT + i][j][3]);
+    __syncthreads();
+    if (EPI == EPI_SWIGLU) {
+      bf16_t* act = reinterpret_cast<bf16_t*>(ep.act);
+      for (int t = wave; t < (HT / 2) * MT; t += 4) {
+        const int p = t / MT, j = t % MT;
+        const float4 gs = tile_sum((2 * p) * MT + j), us = tile_sum((2 * p + 1) * MT + j);
+        const int m = (mt0 + j) * 16 + mrow;
+        if (mt0 + j < m_tiles && m < M) {
+          const int col = ((nt0 + ph * HT + 2 * p) >> 1) * 16 + 4 * g;
+          Act<bf16_t>::store4(act, m, col, ep.act_K,
+                              make_float4(silu_f(gs.x) * us.x, silu_f(gs.y) * us.y, silu_f(gs.z) * us.z, silu_f(gs.w) * us.w));
+        }
       }
-    }
-  } else {
-    if (ep.out) {
-      for (int t = wave; t < NT * MT; t += 4) {
+    } else if (ep.out) {
+      for (int t = wave; t < HT * MT; t += 4) {
         const int i = t / MT, j = t % MT;
         const float4 s = tile_sum(t);
         const int m = (mt0 + j) * 16 + mrow;
         if (mt0 + j < m_tiles && m < M) {
-          float4* dst = reinterpret_cast<float4*>(ep.out + (size_t)kz * ep.slab + (size_t)m * ep.ld + (nt0 + i) * 16 + 4 * g);
+          float4* dst = reinterpret_cast<float4*>(ep.out + (size_t)kz * ep.slab + (size_t)m * ep.ld + (nt0 + ph * HT + i) * 16 + 4 * g);
           *dst = s;
         }
       }
     }
+  };
+  phase(std::integral_constant<int, 0>{});
+  if constexpr (PH == 2) phase(std::integral_constant<int, 1>{});
+
+  if constexpr (EPI != EPI_SWIGLU && PH == 1) {
     if (ep.amax) {   // fused argmax over this workgroup's NT*16 columns (host guarantees a single K range)
       __shared__ float2 wbest[4][MT * 16];
       const uint64_t key = ep.amax_mode ? ep.amax_key[0] : 0ull;
