@@ -693,17 +693,37 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
       launch_bf16<1, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
     }
   } else if (M <= 64 && nt % 8 == 0) {
-    // still bandwidth-bound: the same streaming kernel with four activation bands per weight tile
-    if (split) ks = pick_ksplit(nt / 8, KT, M, arena);
+    // still bandwidth-bound: the same streaming kernel with two or four activation bands per weight tile.  As for a
+    // single band, 8 or 6 weight tiles per wavefront and the K split are chosen for the fullest rounds of the 256 CUs
+    // (gate/up of the 8B shape: 192 workgroups with 8 tiles, 256 with 6)
+    static const int FILL4 = env_int("DFLASH_GEMM_FILL4", 1);   // tuning knob: any other value = 8 tiles and power-of-two K splits only
+    int best_nt = 8;
+    if (FILL4 == 1) {
+      double best_fill = -1.0;
+      for (int cand : {8, 6}) {
+        if (nt % cand) continue;
+        const int nb = nt / cand;
+        for (int k = 1; k <= (split ? kMaxKSplit : 1); ++k) {
+          if (k > 1 && (KT / (k * 4) < 2 || k * M > arena)) break;
+          const int wgs = nb * k, rounds = (wgs + 255) / 256;
+          const double fill = (double)wgs / (rounds * 256.0) - 0.02 * (rounds - 1);
+          if (fill > best_fill + 1e-9) { best_fill = fill; best_nt = cand; ks = k; }
+        }
+      }
+    } else if (split) {
+      ks = pick_ksplit(nt / 8, KT, M, arena);
+    }
     ep.slab = (size_t)M * ep.ld;
     static const int U4 = env_int("DFLASH_GEMM_U4", 1);   // tuning knob: k-tiles per prefetch stage for 16 < M <= 64 (2 measured slower)
     if (M <= 32) {
-      if (U4 >= 2) launch_bf16<8, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      if (best_nt == 6) launch_bf16<6, 2, 1>(st, W, A, M, N, K, kepi, ep, ks);
+      else if (U4 >= 2) launch_bf16<8, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<8, 2, 1>(st, W, A, M, N, K, kepi, ep, ks);
     } else {
       // (the single-buffered two-workgroups-per-CU form of this kernel that the routed experts use was measured here
       // too: 58.7 us against 48.2 for gate/up at 64 rows -- a dense launch has fewer workgroups than CUs)
-      if (U4 >= 2) launch_bf16<8, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
+      if (best_nt == 6) launch_bf16<6, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
+      else if (U4 >= 2) launch_bf16<8, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<8, 4, 1>(st, W, A, M, N, K, kepi, ep, ks);
     }
   } else if (M > 64 && nt % 2 == 0) {
