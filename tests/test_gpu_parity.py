@@ -251,15 +251,18 @@ def test_small_bf16_model_steps_and_cache():
     assert ls.stats["reseeds"] <= 1
 
 
-@pytest.mark.parametrize("n_seqs,ctx_max,experts,top_k,seed", [(3, 60, 16, 2, 61), (12, 40, 16, 2, 63), (10, 40, 16, 4, 72), (3, 30, 32, 8, 83), (2, 30, 16, 16, 85)])
-def test_small_moe_target_routed_experts(n_seqs, ctx_max, experts, top_k, seed):
+@pytest.mark.parametrize("n_seqs,ctx_max,experts,top_k,seed,d_expert",
+                         [(3, 60, 16, 2, 61, 256), (12, 40, 16, 2, 63, 256), (10, 40, 16, 4, 72, 256), (3, 30, 32, 8, 83, 256),
+                          (2, 30, 16, 16, 85, 256), (3, 30, 256, 8, 86, 64)])
+def test_small_moe_target_routed_experts(n_seqs, ctx_max, experts, top_k, seed, d_expert):
     """Routed-expert target (the mixture-of-experts target of Section 5) with a dense drafter: router, top-k routing,
     grouped expert GEMMs and the weighted sum against the oracle, with 1, 2 and 4 bands per work item (48, 192 and 160
     rows per step, 2 or 4 of 16 experts), with 8 of 32 experts, and with all 16 of 16 (the full softmax mixture: no
-    routing decision is left, every expert gets every row).  A token whose k-th and (k+1)-th router logits
+    routing decision is left, every expert gets every row), and with 8 of 256 narrow experts (the largest expert
+    count the routing kernel takes).  A token whose k-th and (k+1)-th router logits
     nearly tie may legitimately go to another expert: the oracle reports the smallest such gap of every call, the
     seeds are ones whose prompts have no close gap, and a step with one is continued from the oracle's state."""
-    w = si.small_moe_workload(n_seqs=n_seqs, ctx_min=12, ctx_max=ctx_max, seed=seed, n_experts=experts, top_k=top_k)
+    w = si.small_moe_workload(n_seqs=n_seqs, ctx_min=12, ctx_max=ctx_max, seed=seed, n_experts=experts, top_k=top_k, d_expert=d_expert)
     prompts = si.make_prompts(w)
     ls = Lockstep(w, prompts, max_len=ctx_max + 4 * 16)
     ls.prefill()
