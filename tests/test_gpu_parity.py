@@ -448,6 +448,26 @@ def test_prefill_as_one_many_row_pass():
     assert ls.stats["reseeds"] <= 1
 
 
+def test_prefill_of_a_routed_expert_target_as_one_many_row_pass():
+    """The same single-pass prefill with the routed-expert target: 400-odd rows at once (13 rows per expert on average,
+    2 bands per work item, rows copied into list order), then steps at 48 rows.  Prompts with a router near-tie are
+    continued from the oracle's state instead of being compared."""
+    w = si.small_moe_workload(n_seqs=3, ctx_min=100, ctx_max=160, seed=64, n_experts=16, top_k=2)
+    prompts = si.make_prompts(w)
+    n_chunks = sum((len(p) + 15) // 16 for p in prompts)
+    ls = Lockstep(w, prompts, max_len=160 + 4 * 16, max_seqs=n_chunks)
+    ls.prefill(one_pass=True)
+    clear = [s for s, gap in enumerate(ls.route_gaps) if gap > 2 * ROUTE_CLEAR]     # small model: noise ~1e-5
+    print("one-pass routed prefill: chunks", n_chunks, "router gaps", ls.route_gaps, flush=True)
+    assert len(clear) >= 2
+    ls.check_cache([0, 3], [0, 1], seqs=clear)
+    if len(clear) < len(prompts):
+        ls.g.load_state(ls.states)
+    for i, plan in enumerate([None, [15, 0, 9]]):
+        ls.step(plan=plan, step_idx=i)
+    assert ls.stats["route_ties"] <= 2 and ls.stats["reseeds"] <= 1 + ls.stats["route_ties"]
+
+
 def test_draft_many_anchor_blocks_of_one_sequence_in_one_call():
     """The attention pattern of DFlash training (Section 4.2, 'DFlash training attention'): several masked blocks of
     one sequence in one pass, each block seeing the context features before its anchor and its own rows, never another
