@@ -99,14 +99,15 @@ def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
 
 
 def run_prefill(args, dev):
-    """Prefill of one prompt of args.prefill tokens (8B shape of configuration 2) as ONE many-row pass: every 16-token
+    """Prefill of one prompt of args.prefill tokens (8B shape of configuration 2; with a `moe_*` --workload the
+    mixture-of-experts shape, up to 2048 tokens) as ONE many-row pass: every 16-token
     chunk is a pseudo-sequence whose committed length is the chunk's offset and whose block-table row is the
     prompt's, handed to one dflash_verify (tokens out: greedy token after every row) and one forced
     dflash_kv_commit (context K/V of all rows into the draft cache).  Prints one JSON line: prompt tokens per second."""
     import torch
     import paper_2602_06036_amd as dfl
     from synth import inputs as si
-    w = si.workload(2)
+    w = si.qwen3_30b_a3b_workload(1, 2048) if args.workload.startswith("moe_") else si.workload(2)
     Bk = w.block_size
     n_tok = (args.prefill // Bk) * Bk
     n = n_tok // Bk
@@ -146,11 +147,12 @@ def run_prefill(args, dev):
     ms = t0.elapsed_time(t1) / args.steps
     t = w.target
     qd, kd = t.n_q_heads * t.head_dim, t.n_kv_heads * t.head_dim
-    flops = 2.0 * n_tok * (t.n_layers * ((qd + 2 * kd) * t.d_model + t.d_model * qd + 3 * t.d_ffn * t.d_model) + t.vocab * t.d_model)
-    print(json.dumps({"metric": "prefill tokens/sec/GPU (8B-shape, one many-row pass)", "value": n_tok / (ms * 1e-3), "unit": "tokens/s",
+    ffn = (t.n_experts + t.top_k * 3 * t.d_expert) * t.d_model if t.n_experts else 3 * t.d_ffn * t.d_model   # per row: router + top_k experts
+    flops = 2.0 * n_tok * (t.n_layers * ((qd + 2 * kd) * t.d_model + t.d_model * qd + ffn) + t.vocab * t.d_model)
+    print(json.dumps({"metric": "prefill tokens/sec/GPU (%s, one many-row pass)" % ("30B-A3B-shape" if w.target.n_experts else "8B-shape"), "value": n_tok / (ms * 1e-3), "unit": "tokens/s",
                       "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
                       "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-                      "config": {"workload": "prefill_8b", "prompt_tokens": n_tok, "rows_per_pass": n_tok, "page_order": args.page_order},
+                      "config": {"workload": "prefill_moe_30b_a3b" if w.target.n_experts else "prefill_8b", "prompt_tokens": n_tok, "rows_per_pass": n_tok, "page_order": args.page_order},
                       "target_gemm_TFLOPs_algorithmic": flops / (ms * 1e-3) / 1e12}))
     e.close()
 
