@@ -71,7 +71,9 @@ typedef struct {
 
 /* Runtime geometry and caller-owned buffers. */
 typedef struct {
-  int32_t block_size;        /* B, 2..DFLASH_MAX_BLOCK */
+  int32_t block_size;        /* B, 2..DFLASH_MAX_BLOCK; B * (n_q_heads / n_kv_heads) <= 64 for both models, or, for bf16 models
+                                with head_dim 64 or 128, a larger value whose repeated halving stays whole down to 64
+                                (8 query heads per kv head at B = 16: two attention workgroups per kv head) */
   int32_t max_seqs;          /* largest n_seqs of any call */
   int32_t max_pages_per_seq; /* row length of the block table */
   int32_t n_pages;           /* pages in each pool; page ids are 0..n_pages-1 in both pools */
