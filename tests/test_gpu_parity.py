@@ -639,6 +639,20 @@ def test_bf16_sampling_at_temperature_0_7_matches_oracle_decisions(lm_stats, mon
     assert ls.stats["reseeds"] <= 2
 
 
+def test_routed_expert_target_sampling_at_temperature_0_7():
+    """Speculative sampling with the routed-expert target: the accept tests run on softmax(target logits / T) that
+    come out of the routed layers."""
+    w = replace(si.small_moe_workload(n_seqs=3, ctx_min=12, ctx_max=60, seed=61, n_experts=16, top_k=2), temperature=0.7)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=60 + 6 * 16)
+    ls.prefill()
+    assert min(ls.route_gaps) > ROUTE_CLEAR
+    for i in range(3):
+        ls.step(temperature=0.7, step_idx=i, key=199 + i)
+    print("routed-expert sampling stats", ls.stats)
+    assert ls.stats["route_ties"] <= 2 and ls.stats["reseeds"] <= 2 + ls.stats["route_ties"]
+
+
 def test_device_status_reports_a_sequence_that_outgrew_its_pages():
     import torch
     w = tiny_workload(seed=2, n_layers=1, draft_layers=1, vocab=128, block=8, taps=(0,))
