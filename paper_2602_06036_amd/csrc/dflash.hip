@@ -802,6 +802,14 @@ void launch_grouped(hipStream_t st, const bf16_t* W, const bf16_t* A, int rows, 
   hipLaunchKernelGGL((gemm_bf16_kernel<8, MT, U, EPI, true, PH>), grid, block, 0, st, W, A, rows, N, K, ep);
 }
 
+// grouped launch of the LDS-staged kernel: items of up to 8 bands (one 128-row activation block each)
+template <int WN, int PD, int EPI, int NS>
+void launch_grouped_tiled(hipStream_t st, const bf16_t* W, const bf16_t* A, int rows, int N, int K, EpiArgs ep, int n_items) {
+  const int n_blocks = (N / 16 + 2 * WN - 1) / (2 * WN);
+  const dim3 grid(((n_items + 7) / 8) * 8 * n_blocks, 1), block(256);
+  hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, 4, PD, EPI, NS, true>), grid, block, 0, st, W, A, rows, N, K, n_blocks, n_items, ep);
+}
+
 template <>
 Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* lbase, const LayerOff& lo, int M) {
   const int D = m.d_model, E = m.n_experts, Fe = m.d_expert, k = m.top_k;
@@ -811,8 +819,11 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   // bands per work item: enough for the rows an expert gets on average plus two standard deviations of an even spread,
   // so that nearly every expert's matrix is streamed by one row of workgroups only
   const double avg = (double)M * k / E, want = avg + 2.0 * sqrt(avg);
-  static const int mt_force = env_int("DFLASH_MOE_MT", 0);   // tuning / testing knob: 1, 2 or 4 forces the bands per work item
-  const int MT = (mt_force == 1 || mt_force == 2 || mt_force == 4) ? mt_force : (want <= 16.0 ? 1 : (want <= 32.0 ? 2 : 4));
+  static const int mt_force = env_int("DFLASH_MOE_MT", 0);   // tuning / testing knob: 1, 2, 4 or 8 forces the bands per work item
+  // from about a hundred rows per expert on (a many-row prefill pass) the items are 128-row blocks of the LDS-staged
+  // kernel: the streaming kernel would need two or more 64-row items per expert, each streaming the expert's matrices
+  const int MT = (mt_force == 1 || mt_force == 2 || mt_force == 4 || mt_force == 8) ? mt_force
+                 : (want <= 16.0 ? 1 : (want <= 32.0 ? 2 : (avg < 96.0 ? 4 : 8)));
   const int n_items = moe_items(m, M, MT), n_pos = moe_positions(m, M);
   MoeRoute r;
   r.logits = rs.p; r.ks = rs.ks; r.stride = rs.stride;
@@ -835,7 +846,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   // tuning knob: from this many rows on the listed rows are first copied into list order (the GEMM then reads whole
   // fragments); below, the GEMM reads them through the list
   static const int gather_min = env_int("DFLASH_MOE_GATHER_MIN_ROWS", 64);
-  const bool gathered = M >= gather_min;
+  const bool gathered = M >= gather_min || MT == 8;   // the LDS-staged kernel copies whole fragments: list order only
   if (gathered) {
     hipLaunchKernelGGL(moe_gather_kernel, dim3((D / 32 + 3) / 4, n_pos / 16), dim3(256), 0, st, reinterpret_cast<const u32x4*>(a), r.row_of,
                        r.n_bands_out, D / 32, ws<u32x4>(c->ws.moe_a));
@@ -854,7 +865,11 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     ep.grp_items = r.items; ep.grp_w_stride = (size_t)2 * Fe * D; ep.grp_rows = r.row_of;
     if (gathered) ep.grp_rows = nullptr;
     const bf16_t* W = reinterpret_cast<const bf16_t*>(lbase + lo.wgu);
-    if (MT == 1) launch_grouped<1, 2, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);   // one k tile per stage: no faster (78.9 us)
+    if (MT == 8) {
+      ep.slab = 0;
+      if ((2 * Fe / 16) % 12 == 0) launch_grouped_tiled<6, 1, EPI_SWIGLU, 3>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
+      else launch_grouped_tiled<4, 1, EPI_SWIGLU, 3>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
+    } else if (MT == 1) launch_grouped<1, 2, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);   // one k tile per stage: no faster (78.9 us)
     else if (MT == 2) launch_grouped<2, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
     else launch_grouped<4, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
     check();
@@ -868,7 +883,8 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     // at the 30B-A3B shape): one tile per stage leaves registers for four workgroups per CU, whose prologues and
     // epilogues overlap (measured 48 us against 54 with two tiles per stage and 60 with four)
     static const int down_u = env_int("DFLASH_MOE_DOWN_U", 1);
-    if (MT == 1 && down_u == 1) launch_grouped<1, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
+    if (MT == 8) launch_grouped_tiled<4, 1, EPI_STORE, 3>(st, W, act, n_pos, D, Fe, ep, n_items);
+    else if (MT == 1 && down_u == 1) launch_grouped<1, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (MT == 1) launch_grouped<1, 2, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (MT == 2) launch_grouped<2, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (ph4 == 2) launch_grouped<4, 1, EPI_STORE, 2>(st, W, act, n_pos, D, Fe, ep, n_items);

@@ -23,7 +23,7 @@
 #pragma once
 #include "gemm.h"
 
-template <int WN, int WM, int PD, int EPI, int NS = 2>
+template <int WN, int WM, int PD, int EPI, int NS = 2, bool GRP = false>
 __global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W,
                                                                                 const bf16_t* __restrict__ A, int M, int N, int K,
                                                                                 int n_blocks, int m_blocks, EpiArgs ep) {
@@ -34,13 +34,26 @@ __global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void g
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wy = wave >> 1, wx = wave & 1;
   const int xcd = blockIdx.x & 7, j = blockIdx.x >> 3;
-  const int nb = (j / m_blocks) * 8 + xcd, mb = j % m_blocks;
+  int nb = (j / m_blocks) * 8 + xcd, mb = j % m_blocks;
+  const int KT = K >> 5, n_tiles = N >> 4;
+  int m_tiles = (M + 15) >> 4, mt0 = mb * BMT;
+  if constexpr (GRP) {
+    // grouped launch (routed experts, see EpiArgs): m_blocks counts work items of up to BMT bands; the workgroups of
+    // one item (its n_blocks weight blocks) run back to back on one XCD and share the item's activation rows there
+    mb = (j / n_blocks) * 8 + xcd;
+    nb = j % n_blocks;
+    if (mb >= m_blocks) return;
+    const int4 item = ep.grp_items[mb];
+    if (item.x < 0) return;
+    W += (size_t)item.x * ep.grp_w_stride;
+    mt0 = item.y;
+    m_tiles = item.z;
+  }
   if (nb >= n_blocks) return;                      // whole workgroup leaves before any barrier
-  const int KT = K >> 5, n_tiles = N >> 4, m_tiles = (M + 15) >> 4;
   const int ks = gridDim.y, kz = blockIdx.y;
   const int per = (KT + ks - 1) / ks;
   const int kb = min(KT, kz * per), ke = min(KT, kb + per);
-  const int nt0 = nb * BNT, mt0 = mb * BMT;
+  const int nt0 = nb * BNT;
 
   // the PER fragments this wavefront copies per stage: offset at k tile 0 and stride per k tile (u32x4 units)
   size_t g_off[PER];

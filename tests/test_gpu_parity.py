@@ -448,6 +448,23 @@ def test_prefill_as_one_many_row_pass():
     assert ls.stats["reseeds"] <= 1
 
 
+@pytest.mark.parametrize("n_seqs,top_k,seed", [(10, 4, 72), (3, 2, 61)])
+def test_small_moe_target_with_128_row_expert_items(n_seqs, top_k, seed, monkeypatch):
+    """The grouped launches of the LDS-staged GEMM (work items of up to 8 bands, used from about a hundred rows per expert
+    on) forced onto small batches: 160 and 48 rows per step, so the items hold 1 to 4 real bands."""
+    monkeypatch.setenv("DFLASH_MOE_MT", "8")
+    w = si.small_moe_workload(n_seqs=n_seqs, ctx_min=12, ctx_max=40 if n_seqs == 10 else 60, seed=seed, n_experts=16, top_k=top_k)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=60 + 4 * 16)
+    ls.prefill()
+    assert min(ls.route_gaps) > ROUTE_CLEAR
+    ls.check_cache([0, 3], [0, 1])
+    for i, plan in enumerate([None, list(np.arange(n_seqs) % 16)]):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([1, 3], [1])
+    assert ls.stats["route_ties"] <= 2 and ls.stats["reseeds"] <= 1 + ls.stats["route_ties"]
+
+
 def test_prefill_of_a_routed_expert_target_as_one_many_row_pass():
     """The same single-pass prefill with the routed-expert target: 400-odd rows at once (13 rows per expert on average,
     2 bands per work item, rows copied into list order), then steps at 48 rows.  Prompts with a router near-tie are
