@@ -820,10 +820,13 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   // so that nearly every expert's matrix is streamed by one row of workgroups only
   const double avg = (double)M * k / E, want = avg + 2.0 * sqrt(avg);
   static const int mt_force = env_int("DFLASH_MOE_MT", 0);   // tuning / testing knob: 1, 2, 4 or 8 forces the bands per work item
-  // from about a hundred rows per expert on (a many-row prefill pass) the items are 128-row blocks of the LDS-staged
-  // kernel: the streaming kernel would need two or more 64-row items per expert, each streaming the expert's matrices
+  // from 64 rows per expert on (a many-row prefill pass) the items are 128-row blocks of the LDS-staged kernel: the
+  // streaming kernel would need two or more 64-row items for many experts, each streaming the expert's matrices.
+  // Measured on one-pass prefills of the 30B-A3B shape (rows spread evenly): 1024 rows 23.9 ms against 28.6, 2048 rows
+  // 40.5 against 51.9; at 512 rows the evenly spread prefill still gains (14.9 against 16.9) but the decode step of 32
+  // sequences, whose rows crowd on fewer experts, loses (26.8 against 24.5 ms), so smaller batches keep the 64-row items
   const int MT = (mt_force == 1 || mt_force == 2 || mt_force == 4 || mt_force == 8) ? mt_force
-                 : (want <= 16.0 ? 1 : (want <= 32.0 ? 2 : (avg < 96.0 ? 4 : 8)));
+                 : (want <= 16.0 ? 1 : (want <= 32.0 ? 2 : (avg < 64.0 ? 4 : 8)));
   const int n_items = moe_items(m, M, MT), n_pos = moe_positions(m, M);
   MoeRoute r;
   r.logits = rs.p; r.ks = rs.ks; r.stride = rs.stride;
