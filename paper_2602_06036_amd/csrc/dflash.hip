@@ -823,8 +823,8 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   // from 64 rows per expert on (a many-row prefill pass) the items are 128-row blocks of the LDS-staged kernel: the
   // streaming kernel would need two or more 64-row items for many experts, each streaming the expert's matrices.
   // Measured on one-pass prefills of the 30B-A3B shape (rows spread evenly): 1024 rows 23.9 ms against 28.6, 2048 rows
-  // 40.5 against 51.9; at 512 rows the evenly spread prefill still gains (14.9 against 16.9) but the decode step of 32
-  // sequences, whose rows crowd on fewer experts, loses (26.8 against 24.5 ms), so smaller batches keep the 64-row items
+  // 40.5 against 51.9; at 512 rows the prefill pass still gains (14.9 against 16.9) but the decode step of 32
+  // sequences loses (26.8 against 24.5 ms; why the two differ is not established), so smaller batches keep the 64-row items
   const int MT = (mt_force == 1 || mt_force == 2 || mt_force == 4 || mt_force == 8) ? mt_force
                  : (want <= 16.0 ? 1 : (want <= 32.0 ? 2 : (avg < 64.0 ? 4 : 8)));
   const int n_items = moe_items(m, M, MT), n_pos = moe_positions(m, M);
