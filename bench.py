@@ -153,7 +153,8 @@ def run_prefill(args, dev):
                       "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
                       "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
                       "config": {"workload": "prefill_moe_30b_a3b" if w.target.n_experts else "prefill_8b", "prompt_tokens": n_tok, "rows_per_pass": n_tok, "page_order": args.page_order},
-                      "target_gemm_TFLOPs_algorithmic": flops / (ms * 1e-3) / 1e12}))
+                      "target_gemm_TFLOPs_algorithmic": flops / (ms * 1e-3) / 1e12,
+                      "moe_stats_launches_experts_bands_items": list(e.moe_stats()) if t.n_experts else None}))
     e.close()
 
 
@@ -427,8 +428,8 @@ def main():
             # reached (counted on the device, averaged over the launches), read once; flops: top_k experts per row.
             t_ = w.target
             ms_e, cnt_e, _ = prof[6]
-            n_route, n_reached, n_bands = e.moe_stats()       # totals of the profiled steps (cleared before them)
-            extra["moe"] = dict(experts_reached_per_layer=n_reached / n_route, bands_per_layer=n_bands / n_route,
+            n_route, n_reached, n_bands, n_work = e.moe_stats()       # totals of the profiled steps (cleared before them)
+            extra["moe"] = dict(experts_reached_per_layer=n_reached / n_route, bands_per_layer=n_bands / n_route, work_items_per_layer=n_work / n_route,
                                 expected_if_uniform=expected_experts(t_, M_rows))
             e_by = (n_reached / n_route) * 2 * t_.d_expert * t_.d_model * 2
             us_e = 1e3 * ms_e / cnt_e

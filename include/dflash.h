@@ -204,8 +204,8 @@ int dflash_profile_enable(dflash_ctx *ctx, int32_t enable);
 int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count, double *bytes);
 
 /* Routed-expert targets: totals since the last read (or create) of routing launches (one per target layer and
- * dflash_verify call), experts reached by at least one row, and 16-row bands of the expert-sorted row list, into
- * out[0..2] (host).  experts / launches * bytes of one expert's matrices = what a layer's expert GEMMs had to read.
+ * dflash_verify call), experts reached by at least one row, 16-row bands of the expert-sorted row list and work items
+ * of the grouped launches, into out[0..3] (host).  experts / launches * bytes of one expert's matrices = what a layer's expert GEMMs had to read.
  * Synchronises the stream and clears the totals. */
 int dflash_moe_stats(dflash_ctx *ctx, void *stream, int64_t *out);
 

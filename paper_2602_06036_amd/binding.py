@@ -220,10 +220,10 @@ class Engine:
         return {i: (float(ms[i]), int(cnt[i]), float(by[i])) for i in range(n) if cnt[i]}
 
     def moe_stats(self):
-        """(routing launches, experts reached, 16-row bands) since the last read; routed-expert targets only."""
-        out = (C.c_int64 * 3)()
+        """(routing launches, experts reached, 16-row bands, work items) since the last read; routed-expert targets only."""
+        out = (C.c_int64 * 4)()
         _check(self.l.dflash_moe_stats(self.ctx, _stream(), out), self.ctx)
-        return int(out[0]), int(out[1]), int(out[2])
+        return int(out[0]), int(out[1]), int(out[2]), int(out[3])
 
     def device_status(self):
         _check(self.l.dflash_device_status(self.ctx, _stream()), self.ctx)

@@ -822,9 +822,9 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   static const int mt_force = env_int("DFLASH_MOE_MT", 0);   // tuning / testing knob: 1, 2, 4 or 8 forces the bands per work item
   // from 64 rows per expert on (a many-row prefill pass) the items are 128-row blocks of the LDS-staged kernel: the
   // streaming kernel would need two or more 64-row items for many experts, each streaming the expert's matrices.
-  // Measured on one-pass prefills of the 30B-A3B shape (rows spread evenly): 1024 rows 23.9 ms against 28.6, 2048 rows
-  // 40.5 against 51.9; at 512 rows the prefill pass still gains (14.9 against 16.9) but the decode step of 32
-  // sequences loses (26.8 against 24.5 ms; why the two differ is not established), so smaller batches keep the 64-row items
+  // Measured on one-pass prefills of the 30B-A3B shape, whose rows crowd on about a quarter of the experts: 1024 rows
+  // 23.9 ms against 28.6, 2048 rows 40.5 against 51.9, 512 rows 14.9 against 16.9; the decode step of 32 sequences (32
+  // rows on every expert) loses, 26.8 against 24.5 ms, so batches below 64 rows per expert keep the 64-row items
   const int MT = (mt_force == 1 || mt_force == 2 || mt_force == 4 || mt_force == 8) ? mt_force
                  : (want <= 16.0 ? 1 : (want <= 32.0 ? 2 : (avg < 64.0 ? 4 : 8)));
   const int n_items = moe_items(m, M, MT), n_pos = moe_positions(m, M);
@@ -1260,8 +1260,8 @@ int dflash_device_status(dflash_ctx* ctx, void* stream) {
 int dflash_moe_stats(dflash_ctx* ctx, void* stream, int64_t* out) {
   if (!ctx || !out) return fail(ctx ? ctx->err : nullptr, DFLASH_EINVAL, "moe_stats: null argument");
   if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "stream synchronise failed");
-  if (hipMemcpy(out, ctx->wsp + ctx->ws.status + 64, 24, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics read failed");
-  if (hipMemset(ctx->wsp + ctx->ws.status + 64, 0, 24) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics clear failed");
+  if (hipMemcpy(out, ctx->wsp + ctx->ws.status + 64, 32, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics read failed");
+  if (hipMemset(ctx->wsp + ctx->ws.status + 64, 0, 32) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics clear failed");
   return DFLASH_OK;
 }
 
