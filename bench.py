@@ -44,6 +44,7 @@ WORKLOADS = {
     # block spread over the experts as independent uniform draws would (a trained router clusters them more)
     "moe_30b_a3b_b1_ctx2048": ("moe30b", 1, 2048),
     "moe_30b_a3b_b32_ctx2048": ("moe30b", 32, 2048),
+    "moe_30b_a3b_b64_ctx2048": ("moe30b", 64, 2048),      # 64 rows per expert on average
 }
 
 
