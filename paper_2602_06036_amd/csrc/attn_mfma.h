@@ -156,7 +156,12 @@ __global__ __launch_bounds__(256) void attn_mfma_kernel(const bf16_t* __restrict
                                                         SeqGeom geo, AttnArgs aa, float* __restrict__ part_o,
                                                         float2* __restrict__ part_ml) {
   constexpr int KT = HD / 32, DT = HD / 16;
-  const int split = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
+  // grid = (splits, kv heads, parts * sequences): the 2^q_shift workgroups that share a kv head's K/V (each with its
+  // share of the query heads) differ in blockIdx.z only, by a multiple of the (even) sequence count, and so land on the
+  // same XCD and read the K/V pages through one L2; "kvh" below counts head groups (kv head * parts + part)
+  const int n_seq = (int)gridDim.z >> aa.q_shift;
+  const int part = aa.q_shift ? (int)blockIdx.z / n_seq : 0;
+  const int split = blockIdx.x, kvh = ((int)blockIdx.y << aa.q_shift) + part, s = (int)blockIdx.z - part * n_seq;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int B = geo.block_size;
@@ -354,7 +359,12 @@ __global__ __launch_bounds__(256, 1) void attn_mfma_wide_kernel(const bf16_t* __
   float (*s_o)[64][LD] = reinterpret_cast<float (*)[64][LD]>(s_raw);
   u32x4* q_lds = reinterpret_cast<u32x4*>(s_raw);                      // [rb][kt][lane]
   int32_t* s_pages = reinterpret_cast<int32_t*>(s_raw) + RB * KT * 64 * 4;   // page ids of this chunk (behind the queries)
-  const int split = blockIdx.x, kvh = blockIdx.y, s = blockIdx.z;
+  // grid = (splits, kv heads, parts * sequences): the 2^q_shift workgroups that share a kv head's K/V (each with its
+  // share of the query heads) differ in blockIdx.z only, by a multiple of the (even) sequence count, and so land on the
+  // same XCD and read the K/V pages through one L2; "kvh" below counts head groups (kv head * parts + part)
+  const int n_seq = (int)gridDim.z >> aa.q_shift;
+  const int part = aa.q_shift ? (int)blockIdx.z / n_seq : 0;
+  const int split = blockIdx.x, kvh = ((int)blockIdx.y << aa.q_shift) + part, s = (int)blockIdx.z - part * n_seq;
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int B = geo.block_size;
@@ -500,7 +510,7 @@ inline bool attn_mfma_launch<bf16_t>(hipStream_t st, const bf16_t* q, const bf16
                                      float* part_o, float2* part_ml, int wide_min_chunk) {
   const int rows = (geo.block_size * (aa.n_q_heads / aa.n_kv_heads)) >> aa.q_shift;
   if (rows > 64 || (aa.n_q_heads / aa.n_kv_heads) % (1 << aa.q_shift) || (aa.head_dim != 128 && aa.head_dim != 64)) return false;
-  const dim3 grid(aa.n_splits, aa.n_kv_heads << aa.q_shift, S), block(256);
+  const dim3 grid(aa.n_splits, aa.n_kv_heads, S << aa.q_shift), block(256);
   // long chunks: wavefronts split the keys (the chunk's page ids must fit the kernel's LDS slice)
   if (aa.head_dim == 128 && aa.chunk >= wide_min_chunk && aa.chunk / DF_PAGE + 2 <= 16384)
     hipLaunchKernelGGL(attn_mfma_wide_kernel<128>, grid, block, 0, st, q, pool, geo, aa, part_o, part_ml);
