@@ -18,6 +18,7 @@
 #include "attn_mfma.h"
 #include "common.h"
 #include "gemm.h"
+#include "gemm_resid.h"
 #include "gemm_tiled.h"
 #include "misc.h"
 #include "moe.h"
@@ -177,7 +178,7 @@ inline int arena_rows(int max_rows) { return std::max(1024, 4 * max_rows); }
 constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row in the argmax
 
 struct Workspace {
-  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, total;
+  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, ssq, total;
   size_t moe_sel_e, moe_sel_w, moe_sel_pos, moe_row_of, moe_items, moe_a, moe_act, moe_y;   // routed-expert target only
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
@@ -224,6 +225,7 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.lsep = take((size_t)M * (t.vocab / 16 + 1) * 8);    // per-workgroup softmax statistics of an LM-head launch
   w.rope_t = take((size_t)M * (t.head_dim / 2) * 8);   // rotary tables of the call's rows (target, draft)
   w.rope_d = take((size_t)M * (d.head_dim / 2) * 8);
+  w.ssq = take((size_t)M * (D / 16 + 1) * 4);          // pieces of the rows' sums of squares (deferred RMSNorm, few-row path)
   w.moe_sel_e = w.moe_sel_w = w.moe_sel_pos = w.moe_row_of = w.moe_items = w.moe_a = w.moe_act = w.moe_y = 0;
   if (t.n_experts) {
     const size_t mk = (size_t)M * t.top_k, np = moe_positions(t, M);
@@ -282,6 +284,10 @@ struct dflash_ctx {
   int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
   int wm_force = 0;     // tiled GEMM: 4 or 2 forces 128 or 64 activation rows per tile (testing / tuning knob)
   bool lm_stats = true; // softmax statistics from the LM-head epilogue (testing knob: off = always from the stored logits)
+  int fuse = 1;         // few-row path (one band of rows, dense bf16 model): 1 = the O projection runs unsplit with the residual update
+                        // in its epilogue and the RMSNorm that follows deferred into the gate/up GEMM; 2 = the down projection
+                        // as well (then no separate normalisation launch is left in a layer); 0 = separate kernels throughout
+  int resid_nw = 4, resid_u = 8;   // wavefronts per workgroup and k tiles per stage of that projection kernel (tuning knobs)
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
@@ -356,6 +362,48 @@ struct Engine {
   bool lm_skip_store = false;   // the LM-head GEMM may drop its logits when its argmax is fused (nobody will read them)
   int pending_tap = -1;  // tap index to be taken from the completed residual stream by the next RMSNorm
 
+  // Few-row path: ws.a holds x * gain with the division by the row's rms deferred to the GEMM that reads it; the
+  // pieces of the rows' sums of squares are in ws.ssq (see gemm_resid.h)
+  int defer_parts = 0;
+  bool few_rows(const dflash_dims& m, int M, int level = 2) const {
+    return std::is_same<T, bf16_t>::value && c->fuse >= level && !m.n_experts && M <= 16 && m.d_model % 16 == 0;
+  }
+  EpiArgs deferred(EpiArgs ep, const dflash_dims& m) {
+    ep.ssq = ws<float>(c->ws.ssq);
+    ep.ssq_parts = defer_parts;
+    ep.ssq_inv_D = 1.0f / (float)m.d_model;
+    ep.ssq_eps = m.rms_eps;
+    return ep;
+  }
+  // h += A W^T, ws.a = h * gain_next, sums of squares -> ws.ssq, optional tap (gemm_bf16_resid_kernel)
+  void resid(const T* W, const T* A, int M, int N, int K, const float* gain_next, int tap);
+  void layer_few_rows(const dflash_dims& m, const char* lbase, const LayerOff& lo, T* pool, int l, const dflash_batch* b, bool causal,
+                      const float* gain_next, int tap) {
+    const int S = b->n_seqs, B = c->rt.block_size, M = S * B, D = m.d_model;
+    const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, nqkv = qd + 2 * kd;
+    float* arena = ws<float>(c->ws.arena);
+    T* a = ws<T>(c->ws.a);
+    const Slab qs = gemm(reinterpret_cast<const T*>(lbase + lo.wqkv), a, M, nqkv, D, EPI_STORE, deferred(EpiArgs{arena, nqkv, 0, nullptr, 0}, m));
+    qkv_post(m, lbase, lo, pool, l, b, qs);
+    attention(m, pool, l, b, causal);
+    resid(reinterpret_cast<const T*>(lbase + lo.wo), ws<T>(c->ws.o), M, D, qd, reinterpret_cast<const float*>(lbase + lo.g2), -1);
+    gemm(reinterpret_cast<const T*>(lbase + lo.wgu), a, M, 2 * m.d_ffn, D, EPI_SWIGLU, deferred(EpiArgs{nullptr, 0, 0, ws<T>(c->ws.act), m.d_ffn}, m));
+    resid(reinterpret_cast<const T*>(lbase + lo.wd), ws<T>(c->ws.act), M, D, m.d_ffn, gain_next, tap);
+  }
+  void qkv_post(const dflash_dims& m, const char* lbase, const LayerOff& lo, T* pool, int l, const dflash_batch* b, const Slab& qs) {
+    const int M = b->n_seqs * c->rt.block_size;
+    const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, nqkv = qd + 2 * kd;
+    RopeArgs ra;
+    ra.n_q_heads = m.n_q_heads; ra.n_kv_heads = m.n_kv_heads; ra.head_dim = m.head_dim;
+    ra.q_off = 0; ra.k_off = qd; ra.v_off = qd + kd;
+    ra.qk_norm = m.qk_norm; ra.eps = m.rms_eps; ra.layer = l;
+    ra.rope = ws<float2>(&m == &c->t ? c->ws.rope_t : c->ws.rope_d);
+    hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, (m.n_q_heads + 2 * m.n_kv_heads + 3) / 4), dim3(256), 0, st, qs.p, nqkv,
+                       reinterpret_cast<const float*>(lbase + lo.qn), reinterpret_cast<const float*>(lbase + lo.kn), ws<T>(c->ws.q), pool,
+                       geom(b), ra, qs.ks, qs.stride);
+    check();
+  }
+
   // ---- GEMM dispatch ------------------------------------------------------------------------------
   // STORE: partial slabs into ep.out (room for max_ks(M) * M * ld floats).  RESID: y is to be added to
   // ws.h: the bf16 path writes partial slabs into the arena and returns them as pending, the fp32 path
@@ -406,21 +454,20 @@ struct Engine {
     float* h = ws<float>(c->ws.h);
     float* arena = ws<float>(c->ws.arena);
     T* a = ws<T>(c->ws.a);
-    T* q = ws<T>(c->ws.q);
     T* o = ws<T>(c->ws.o);
     T* act = ws<T>(c->ws.act);
     norm_h(reinterpret_cast<const float*>(lbase + lo.g1), M, D, m.rms_eps);
     const Slab qs = gemm(reinterpret_cast<const T*>(lbase + lo.wqkv), a, M, nqkv, D, EPI_STORE, EpiArgs{arena, nqkv, 0, nullptr, 0});
-    RopeArgs ra;
-    ra.n_q_heads = m.n_q_heads; ra.n_kv_heads = m.n_kv_heads; ra.head_dim = m.head_dim;
-    ra.q_off = 0; ra.k_off = qd; ra.v_off = qd + kd;
-    ra.qk_norm = m.qk_norm; ra.eps = m.rms_eps; ra.layer = l;
-    ra.rope = ws<float2>(&m == &c->t ? c->ws.rope_t : c->ws.rope_d);
-    hipLaunchKernelGGL(qkv_post_kernel<T>, dim3(M, (m.n_q_heads + 2 * m.n_kv_heads + 3) / 4), dim3(256), 0, st, qs.p, nqkv,
-                       reinterpret_cast<const float*>(lbase + lo.qn), reinterpret_cast<const float*>(lbase + lo.kn), q, pool,
-                       geom(b), ra, qs.ks, qs.stride);
-    check();
+    qkv_post(m, lbase, lo, pool, l, b, qs);
     attention(m, pool, l, b, causal);
+    if (few_rows(m, M, 1)) {
+      // one band of rows: unsplit O projection with the residual update in its epilogue, the second RMSNorm deferred
+      // into the gate/up GEMM (gemm_resid.h); the down projection keeps its K split and the normalisation kernel
+      resid(reinterpret_cast<const T*>(lbase + lo.wo), o, M, D, qd, reinterpret_cast<const float*>(lbase + lo.g2), -1);
+      gemm(reinterpret_cast<const T*>(lbase + lo.wgu), a, M, 2 * m.d_ffn, D, EPI_SWIGLU, deferred(EpiArgs{nullptr, 0, 0, act, m.d_ffn}, m));
+      pending = gemm(reinterpret_cast<const T*>(lbase + lo.wd), act, M, D, m.d_ffn, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
+      return;
+    }
     pending = gemm(reinterpret_cast<const T*>(lbase + lo.wo), o, M, D, qd, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
     norm_h(reinterpret_cast<const float*>(lbase + lo.g2), M, D, m.rms_eps);
     if (m.n_experts) {
@@ -440,11 +487,17 @@ struct Engine {
   // amax_parts > 0 and, unless want_logits, the [M, V] logits are never written); argmax() finishes the job
   // stats_T > 0: the epilogue also leaves the softmax statistics of logits / stats_T, combined into stats_out; returns
   // whether that happened (kernels without the fused epilogue leave it to row_lse_kernel)
+  // few: the final norm is already deferred into ws.a / ws.ssq by the last layer's down projection
   bool lm_head(const float* final_gain, float eps, int M, float* logits, bool want_logits, int B, int mode, float inv_T,
-               const uint64_t* key, float stats_T = 0.f, float2* stats_out = nullptr) {
+               const uint64_t* key, float stats_T = 0.f, float2* stats_out = nullptr, bool few = false) {
     const dflash_dims& t = c->t;
-    norm_h(final_gain, M, t.d_model, eps);
     EpiArgs ep{logits, t.vocab, 0, nullptr, 0};
+    if (few) {
+      ep = deferred(ep, t);
+      ep.ssq_eps = eps;
+    } else {
+      norm_h(final_gain, M, t.d_model, eps);
+    }
     ep.amax = ws<float2>(c->ws.amax);
     ep.amax_mode = mode;
     ep.amax_inv_T = inv_T;
@@ -471,18 +524,35 @@ struct Engine {
     const dflash_dims& d = c->d;
     hipLaunchKernelGGL(build_block_kernel, dim3((M + 255) / 256), dim3(256), 0, st, b->anchor, draft_tokens, S, B, c->rt.mask_token_id);
     check();
+    const bool few = few_rows(d, M);
+    const char* l0 = c->dblob + c->dl.layer0;
+    EmbedFuse ef;
+    if (few) {
+      ef.gain = reinterpret_cast<const float*>(l0 + c->dl.lo.g1);
+      ef.a_out = ws<T>(c->ws.a);
+      ef.ssq = ws<float>(c->ws.ssq);
+      defer_parts = 1;
+    }
     hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), draft_tokens,
                        ws<float>(c->ws.h), d.d_model, d.vocab, status(), b->seq_lens, B,
-                       RopeTab{ws<float2>(c->ws.rope_d), log((double)d.rope_theta), d.head_dim}, RopeTab{nullptr, 0.0, 0});
+                       RopeTab{ws<float2>(c->ws.rope_d), log((double)d.rope_theta), d.head_dim}, RopeTab{nullptr, 0.0, 0}, ef);
     check();
-    for (int i = 0; i < d.n_layers; ++i)
-      layer(d, c->dblob + c->dl.layer0 + c->dl.lo.end * i, c->dl.lo, reinterpret_cast<T*>(c->rt.draft_kv_pool), i, b, false);
+    for (int i = 0; i < d.n_layers; ++i) {
+      const char* lb = l0 + c->dl.lo.end * i;
+      if (few) {
+        const float* gn = i + 1 < d.n_layers ? reinterpret_cast<const float*>(lb + c->dl.lo.end + c->dl.lo.g1)
+                                             : reinterpret_cast<const float*>(c->dblob + c->dl.gf);
+        layer_few_rows(d, lb, c->dl.lo, reinterpret_cast<T*>(c->rt.draft_kv_pool), i, b, false, gn, -1);
+      } else {
+        layer(d, lb, c->dl.lo, reinterpret_cast<T*>(c->rt.draft_kv_pool), i, b, false);
+      }
+    }
     float* logits = ws<float>(c->ws.logits_d);
     const int mode = temperature > 0.f ? 1 : 0;
     const float inv_T = mode ? 1.0f / temperature : 1.0f;
     const bool want_logits = logits_out || mode;        // sampling: dflash_accept needs the proposal distribution
     const bool st_q = lm_head(reinterpret_cast<const float*>(c->dblob + c->dl.gf), d.rms_eps, M, logits, want_logits, B, mode, inv_T, rng_key,
-                              mode ? temperature : 0.f, ws<float2>(c->ws.stats_q));
+                              mode ? temperature : 0.f, ws<float2>(c->ws.stats_q), few);
     c->stats_q_T = st_q ? temperature : 0.f;
     c->have_logits_d = want_logits || amax_parts == 0;
     c->draft_temperature = temperature;
@@ -498,15 +568,33 @@ struct Engine {
     const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
     const dflash_dims& t = c->t;
     // the draft's table is for the context K/V rows that the commit of this verification will project
+    const bool few = few_rows(t, M);
+    const char* l0 = c->tblob + c->tl.layer0;
+    EmbedFuse ef;
+    if (few) {
+      ef.gain = reinterpret_cast<const float*>(l0 + c->tl.lo.g1);
+      ef.a_out = ws<T>(c->ws.a);
+      ef.ssq = ws<float>(c->ws.ssq);
+      defer_parts = 1;
+    }
     hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), tokens,
                        ws<float>(c->ws.h), t.d_model, t.vocab, status(), b->seq_lens, B,
                        RopeTab{ws<float2>(c->ws.rope_t), log((double)t.rope_theta), t.head_dim},
-                       RopeTab{ws<float2>(c->ws.rope_d), log((double)c->d.rope_theta), c->d.head_dim});
+                       RopeTab{ws<float2>(c->ws.rope_d), log((double)c->d.rope_theta), c->d.head_dim}, ef);
     check();
     int tap = 0;
     for (int l = 0; l < t.n_layers; ++l) {
-      layer(t, c->tblob + c->tl.layer0 + c->tl.lo.end * l, c->tl.lo, reinterpret_cast<T*>(c->rt.target_kv_pool), l, b, true);
-      if (tap < c->rt.n_taps && c->rt.tap_layers[tap] == l) pending_tap = tap++;   // taken by the next RMSNorm
+      const char* lb = l0 + c->tl.lo.end * l;
+      const bool tapped = tap < c->rt.n_taps && c->rt.tap_layers[tap] == l;
+      if (few) {
+        const float* gn = l + 1 < t.n_layers ? reinterpret_cast<const float*>(lb + c->tl.lo.end + c->tl.lo.g1)
+                                             : reinterpret_cast<const float*>(c->tblob + c->tl.gf);
+        layer_few_rows(t, lb, c->tl.lo, reinterpret_cast<T*>(c->rt.target_kv_pool), l, b, true, gn, tapped ? tap : -1);
+      } else {
+        layer(t, lb, c->tl.lo, reinterpret_cast<T*>(c->rt.target_kv_pool), l, b, true);
+        if (tapped) pending_tap = tap;   // taken by the next RMSNorm
+      }
+      if (tapped) ++tap;
     }
     float* logits = ws<float>(c->ws.logits_t);
     if (!tgt_argmax && !logits_out) {
@@ -521,7 +609,7 @@ struct Engine {
     const bool want_logits = logits_out || c->draft_temperature > 0.f;   // sampling: dflash_accept needs the target distribution
     const float sT = c->draft_temperature > 0.f ? c->draft_temperature : 0.f;
     const bool st_p = lm_head(reinterpret_cast<const float*>(c->tblob + c->tl.gf), t.rms_eps, M, logits, want_logits, B, 0, 1.0f, nullptr, sT,
-                              ws<float2>(c->ws.stats_p));
+                              ws<float2>(c->ws.stats_p), few);
     c->stats_p_T = st_p ? sT : 0.f;
     c->have_logits_t = want_logits || amax_parts == 0;
     if (tgt_argmax) argmax(logits, t.vocab, M, B, tgt_argmax, 0, 0, 1.0f, (const uint64_t*)nullptr);
@@ -917,6 +1005,33 @@ Engine<float>::Slab Engine<float>::gemm(const float* W, const float* A, int M, i
   return Slab{};
 }
 
+template <int U, int NW>
+void launch_resid(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, ResidArgs ra) {
+  hipLaunchKernelGGL((gemm_bf16_resid_kernel<U, NW>), dim3(N / 16), dim3(64 * NW), 0, st, W, A, M, N, K, ra);
+}
+
+template <>
+void Engine<bf16_t>::resid(const bf16_t* W, const bf16_t* A, int M, int N, int K, const float* gain_next, int tap) {
+  ProfScope prof(c, st, DFLASH_PROF_GEMM_RESID, (double)N * K * 2);
+  ResidArgs ra;
+  ra.h = ws<float>(c->ws.h);
+  ra.gain_next = gain_next;
+  ra.a_out = ws<bf16_t>(c->ws.a);
+  ra.ssq = ws<float>(c->ws.ssq);
+  ra.taps = tap >= 0 ? ws<bf16_t>(c->ws.taps) : nullptr;
+  ra.tap_idx = tap;
+  ra.tap_K = c->rt.n_taps * c->t.d_model;
+  const int nw = c->resid_nw, u = c->resid_u;
+  if (nw == 16) launch_resid<4, 16>(st, W, A, M, N, K, ra);
+  else if (nw == 8 && u <= 4) launch_resid<4, 8>(st, W, A, M, N, K, ra);
+  else if (nw == 8) launch_resid<8, 8>(st, W, A, M, N, K, ra);
+  else launch_resid<8, 4>(st, W, A, M, N, K, ra);
+  check();
+  defer_parts = N / 16;
+}
+template <>
+void Engine<float>::resid(const float*, const float*, int, int, int, const float*, int) {}   // bf16 only (few_rows() is false for fp32)
+
 template <typename T>
 void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const dflash_batch* b, bool causal) {
   const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
@@ -1164,6 +1279,10 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->lm_stats = env_int("DFLASH_LM_STATS", 1) == 1;
   c->ks_force = env_int("DFLASH_GEMM_KS", 0);
   c->attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
+  c->fuse = env_int("DFLASH_FUSE", 1);   // 1, 2 as above; any other value: off
+  if (c->fuse != 1 && c->fuse != 2) c->fuse = 0;
+  c->resid_nw = env_int("DFLASH_RESID_NW", 4);
+  c->resid_u = env_int("DFLASH_RESID_U", 8);
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {
     delete c;
     return fail(nullptr, DFLASH_EHIP, "create: cannot clear the device status word");

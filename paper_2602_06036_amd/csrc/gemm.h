@@ -37,6 +37,12 @@ struct EpiArgs {
   int grp_n_items = 0;
   size_t grp_w_stride = 0;
   const int32_t* grp_rows = nullptr;
+  // Deferred RMSNorm (streaming kernel only): the operand holds x * gain without the division by the row's rms; row m
+  // of the result is multiplied by 1 / sqrt(sum_p ssq[m * ssq_parts + p] * ssq_inv_D + ssq_eps) before any epilogue
+  // sees it (the sums of squares come in ssq_parts pieces, added in ascending order; see gemm_resid.h).
+  const float* ssq = nullptr;
+  int ssq_parts = 0;
+  float ssq_inv_D = 0.f, ssq_eps = 0.f;
 };
 
 // score of logit y at (row m, column col) for the fused argmax
@@ -164,6 +170,36 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
         }
   };
 
+  // Deferred RMSNorm: 1 / rms of this workgroup's rows, 16 threads per row, each adding every 16th piece in
+  // ascending order, then the 16 partial sums by a fixed shuffle tree.  Written to LDS here, read after the
+  // barrier of the cross-wavefront sum.
+  __shared__ float s_rstd[MT * 16];
+  if (ep.ssq) {
+    const int r = threadIdx.x >> 4, c = threadIdx.x & 15;
+#pragma unroll
+    for (int j = 0; j < MT; ++j) {
+      const int m = min((mt0 + j) * 16 + r, M - 1);
+      const float* pp = ep.ssq + (size_t)m * ep.ssq_parts;
+      float t = 0.f;
+      if ((ep.ssq_parts & 3) == 0 && ep.ssq_parts <= 512) {
+        // all requests of the thread go out together (up to 8 pieces of 4 values, 64 values apart)
+        float4 v[8];
+#pragma unroll
+        for (int i = 0; i < 8; ++i) {
+          const int p = (c + 16 * i) * 4;
+          v[i] = p < ep.ssq_parts ? *reinterpret_cast<const float4*>(pp + p) : make_float4(0.f, 0.f, 0.f, 0.f);
+        }
+#pragma unroll
+        for (int i = 0; i < 8; ++i) t += (v[i].x + v[i].y) + (v[i].z + v[i].w);
+      } else {
+        for (int p = c; p < ep.ssq_parts; p += 16) t += pp[p];
+      }
+#pragma unroll
+      for (int o = 1; o < 16; o <<= 1) t += __shfl_xor(t, o, 64);
+      if (c == 0) s_rstd[j * 16 + r] = 1.0f / sqrtf(t * ep.ssq_inv_D + ep.ssq_eps);
+    }
+  }
+
   // Two register buffers, one being multiplied while the other is on its way.  No load inside the loop is
   // conditional: a load that is skipped on some path would make the number of loads in flight unknown at compile
   // time, and the wait for the older buffer would then have to drain the newer one as well.  The last one or two
@@ -197,12 +233,18 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
   static_assert(NT % PH == 0 && (EPI != EPI_SWIGLU || HT % 2 == 0), "phases");
   __shared__ float4 red[4][HT * MT][64];
   const int mrow = lane & 15, g = lane >> 4;
-  auto tile_sum = [&](int t) {   // the four wavefronts' partial sums of tile t of the current phase, in wavefront order
+  // the four wavefronts' partial sums of tile t (= weight tile * MT + band) of the current phase, in wavefront order,
+  // times the row's deferred 1 / rms
+  auto tile_sum = [&](int t) {
     float4 s = red[0][t][lane];
 #pragma unroll
     for (int w = 1; w < 4; ++w) {
       const float4 a = red[w][t][lane];
       s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
+    }
+    if (ep.ssq) {
+      const float rs = s_rstd[(t % MT) * 16 + mrow];
+      s.x *= rs; s.y *= rs; s.z *= rs; s.w *= rs;
     }
     return s;
   };

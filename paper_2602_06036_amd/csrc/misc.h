@@ -23,10 +23,19 @@ struct RopeTab {
 
 // h[m, :] = float(E[tokens[m], :]); ids outside the vocabulary raise the status flag and read row 0.
 // The first two wavefronts also write the row's entries of up to two rotary tables.
+// With `fuse.a_out` the row is also handed on as the first layer's GEMM operand with the RMSNorm deferred (see
+// gemm_resid.h): a_out[m, :] = h * gain, ssq[m] = sum of squares of the row (one piece per row).
+struct EmbedFuse {
+  const float* gain = nullptr;
+  void* a_out = nullptr;
+  float* ssq = nullptr;
+};
+
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
                                                     float* __restrict__ h, int D, int vocab, int32_t* status,
-                                                    const int32_t* __restrict__ seq_lens, int B, RopeTab t0, RopeTab t1) {
+                                                    const int32_t* __restrict__ seq_lens, int B, RopeTab t0, RopeTab t1,
+                                                    EmbedFuse fuse = EmbedFuse{}) {
   const int m = blockIdx.x;
   {
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
@@ -44,7 +53,22 @@ __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, con
     tok = 0;
   }
   const T* src = E + (size_t)tok * D;
-  for (int d = threadIdx.x; d < D; d += blockDim.x) h[(size_t)m * D + d] = Store<T>::to(src[d]);
+  float ss = 0.f;
+  for (int d = threadIdx.x; d < D; d += blockDim.x) {
+    const float v = Store<T>::to(src[d]);
+    h[(size_t)m * D + d] = v;
+    if (fuse.a_out) {
+      Act<T>::store(reinterpret_cast<T*>(fuse.a_out), m, d, D, v * fuse.gain[d]);
+      ss += v * v;
+    }
+  }
+  if (fuse.a_out) {   // uniform over the workgroup
+    __shared__ float part[4];
+    ss = wave_reduce_sum(ss);
+    if ((threadIdx.x & 63) == 0) part[threadIdx.x >> 6] = ss;
+    __syncthreads();
+    if (threadIdx.x == 0) fuse.ssq[m] = (part[0] + part[1]) + (part[2] + part[3]);
+  }
 }
 
 // ---- RMSNorm with pending-sum reduction -----------------------------------------------------------

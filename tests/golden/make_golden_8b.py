@@ -1,6 +1,9 @@
 #!/usr/bin/env python3
 """Writes tests/golden/golden_8b.json: the CPU oracle's result of ONE speculative step at the full
-8B shape (configurations 2-5) for a few sampled sequences, from a seeded synthetic cache state.
+8B shape (configurations 2-5) from a seeded synthetic cache state -- every sequence of configurations 2, 3
+and 4, two sampled sequences of configuration 5 -- and, for configuration 2, a true prefill of its 2048
+random prompt tokens (Section 4.1) followed by plain greedy decoding of six tokens and one speculative step
+(record "cfg2_prefill_seq0": first token, sampled cache rows, the plain continuation, the step).
 
 Calls only oracle/ and synth/ (never the HIP path).  Takes tens of minutes and ~35 GB of RAM on 8 cores;
 the GPU tests (tests/test_gpu_full_size.py) regenerate the same weights and states from the same seeds
@@ -27,8 +30,8 @@ from synth import inputs as si  # noqa: E402
 # configuration -> sampled sequences and, for greedy configurations, how many proposals are made correct
 CASES = {
     2: dict(seqs=[0], k=[3]),
-    3: dict(seqs=[0, 5, 11], k=[0, 2, 6]),
-    4: dict(seqs=[1], k=[1]),
+    3: dict(seqs=list(range(16)), k=[0, 1, 3, 0, 4, 2, 1, 0, 5, 2, 0, 6, 1, 3, 0, 9]),
+    4: dict(seqs=[0, 1, 2, 3], k=[0, 1, 2, 3]),
     5: dict(seqs=[0, 17], k=None),
 }
 N_COLS = 64
@@ -71,6 +74,85 @@ def sample_cols(w):
     return np.sort(np.random.default_rng(w.seed).choice(w.target.vocab, N_COLS, replace=False)).astype(int)
 
 
+def store_step(rec, r, st, w, n, cols, greedy, uniforms):
+    """What a speculative step of the oracle leaves in a record: tokens, margins, logits at the sampled columns, and the
+    committed context-feature rows of the first and last draft layer (first 8 dims of head 0)."""
+    Bk = w.block_size
+    ds = r["draft_scores"]
+    rec.update(
+        block=[int(x) for x in r["block"]],
+        oracle_draft=[int(np.argmax(ds[j])) for j in range(1, Bk)],
+        draft_margin=[O.top2_margin(ds[j]) for j in range(1, Bk)],
+        tgt_argmax=[int(x) for x in r["tgt_argmax"]],
+        tgt_margin=[O.top2_margin(r["logits"][j]) for j in range(Bk)],
+        accept_len=int(r["accept_len"]), emitted=[int(x) for x in r["emitted"]],
+        draft_logits_cols=[[float(x) for x in r["draft_logits"][j][cols]] for j in range(Bk)],
+        tgt_logits_cols=[[float(x) for x in r["logits"][j][cols]] for j in range(Bk)],
+        logit_std=float(r["logits"].std()),
+    )
+    if not greedy:
+        rec["key"] = RNG_KEY
+        rec["uniforms"] = [float(x) for x in uniforms]
+        rec["final_margin"] = O.top2_margin(r["final_scores"])
+        # how close each acceptance test was: |u q(d) - p(d)| / p(d) for the tested slots
+        p = O.softmax(r["logits"] / w.temperature)
+        q = O.softmax(r["draft_logits"] / w.temperature)
+        rec["accept_test_margin"] = [
+            float(abs(uniforms[j] * q[j][r["block"][j]] - p[j - 1][r["block"][j]]) / p[j - 1][r["block"][j]])
+            for j in range(1, min(Bk, r["accept_len"] + 2))]
+    a = r["accept_len"]
+    rec["ctx_k_new"] = [[float(x) for x in st.ctx.k[l][n + j, 0, :8]] for l in (0, w.draft.n_layers - 1) for j in range(a + 1)]
+    rec["ctx_v_new"] = [[float(x) for x in st.ctx.v[l][n + j, 0, :8]] for l in (0, w.draft.n_layers - 1) for j in range(a + 1)]
+
+
+def prefill_case(w, Wt, Wd, wt, rnd, cols, t0):
+    """Configuration 2 from a true prefill: prompt of 2048 random tokens through the oracle's sequence form, the
+    first generated token, a few cache rows of several layers, six tokens of plain greedy decoding (the sequence
+    that speculative steps must reproduce), and one speculative step whose first two proposals are that
+    continuation and the third a wrong token."""
+    Bk = w.block_size
+    prompt = [int(t) for t in si.make_prompts(w)[0]]
+    n = len(prompt)
+    st = O.SeqState(w.target, w.draft, n + 4 * Bk, cache_dtype=np.float32)
+    print(f"[{time.time()-t0:7.1f}s] cfg 2 prefill of {n} tokens", flush=True)
+    logits, taps = O.target_forward_sequence(Wt, w.target, prompt, st.kv, w.tap_layers, rnd, logit_rows=[n - 1])
+    H_t = O.fuse_taps(Wd, w.draft, taps, rnd)
+    for i, (k, v) in enumerate(O.draft_context_kv(Wd, w.draft, H_t, np.arange(n), rnd)):
+        st.ctx.k[i][:n] = k
+        st.ctx.v[i][:n] = v
+    st.ctx.n = st.n = n
+    st.anchor = int(np.argmax(logits[0]))
+    del taps, H_t
+    rec = dict(config="2p", seq=0, n=n, anchor=int(st.anchor), first_margin=O.top2_margin(logits[0]), cols=[int(c) for c in cols],
+               first_logits_cols=[float(x) for x in logits[0][cols]])
+    rows = [0, 1, 17, 1000, 2046, 2047]
+    rec["kv_rows"] = rows
+    rec["kv_layers"] = [0, 1, 17, 35]
+    rec["tgt_k"] = [[[float(x) for x in st.kv.k[l][r, 3, :8]] for r in rows] for l in rec["kv_layers"]]
+    rec["tgt_v"] = [[[float(x) for x in st.kv.v[l][r, 3, :8]] for r in rows] for l in rec["kv_layers"]]
+    rec["ctx_layers"] = [0, w.draft.n_layers - 1]
+    rec["ctx_k"] = [[[float(x) for x in st.ctx.k[l][r, 5, :8]] for r in rows] for l in rec["ctx_layers"]]
+    rec["ctx_v"] = [[[float(x) for x in st.ctx.v[l][r, 5, :8]] for r in rows] for l in rec["ctx_layers"]]
+    print(f"[{time.time()-t0:7.1f}s]   first token {st.anchor} (margin {rec['first_margin']:.4f}); plain greedy decoding", flush=True)
+    tok, cont, margins = st.anchor, [], []
+    for j in range(6):
+        lg, _ = O.target_forward_tokens(Wt, w.target, [tok], n + j, st.kv, (), rnd)
+        tok = int(np.argmax(lg[0]))
+        cont.append(tok)
+        margins.append(O.top2_margin(lg[0]))
+    st.kv.truncate(n)
+    rec["plain_greedy"] = cont
+    rec["plain_greedy_margin"] = margins
+    print(f"[{time.time()-t0:7.1f}s]   continuation {cont}", flush=True)
+    k = 2
+    dl = O.draft_block_forward(Wd, w.draft, st.anchor, n, st.ctx, Bk, w.mask_token_id, rnd)
+    drafted = [int(np.argmax(dl[j])) for j in range(1, Bk)]
+    wrong = drafted[k] if drafted[k] != cont[k] else (cont[k] + 1) % (w.target.vocab - 1)
+    proposal = cont[:k] + [wrong] + drafted[k + 1:]
+    rec["k_correct"] = k
+    return st, rec, proposal
+
+
 def main():
     out_path = os.path.join(os.path.dirname(os.path.abspath(__file__)), "golden_8b.json")
     only = [int(x) for x in sys.argv[1:] if x.isdigit()] or sorted(CASES)
@@ -89,6 +171,15 @@ def main():
         lens = si.make_context_lengths(w)
         cols = sample_cols(w)
         Bk = w.block_size
+        if cfg == 2 and ("cfg2_prefill_seq0" not in results or "--redo" in sys.argv):
+            st, rec, proposal = prefill_case(w, Wt, Wd, wt, rnd, cols, t0)
+            n = st.n
+            r = O.spec_step(Wt, Wd, w.target, w.draft, w.tap_layers, st, Bk, w.mask_token_id, rnd, proposal=proposal)
+            store_step(rec, r, st, w, n, cols, True, None)
+            results["cfg2_prefill_seq0"] = rec
+            json.dump(results, open(out_path, "w"), indent=0)
+            print(f"[{time.time()-t0:7.1f}s]   accept_len {rec['accept_len']} emitted {rec['emitted']}", flush=True)
+            del st
         for i, seq in enumerate(CASES[cfg]["seqs"]):
             n = int(lens[seq])
             if f"cfg{cfg}_seq{seq}" in results and "--redo" not in sys.argv:
@@ -118,32 +209,7 @@ def main():
             uniforms = si.make_uniforms(w, 0)[seq].astype(np.float64) if not greedy else None
             r = O.spec_step(Wt, Wd, w.target, w.draft, w.tap_layers, st, Bk, w.mask_token_id, rnd,
                             temperature=w.temperature, uniforms=uniforms, key=RNG_KEY, seq_id=seq, proposal=proposal)
-            ds = r["draft_scores"]
-            rec.update(
-                block=[int(x) for x in r["block"]],
-                oracle_draft=[int(np.argmax(ds[j])) for j in range(1, Bk)],
-                draft_margin=[O.top2_margin(ds[j]) for j in range(1, Bk)],
-                tgt_argmax=[int(x) for x in r["tgt_argmax"]],
-                tgt_margin=[O.top2_margin(r["logits"][j]) for j in range(Bk)],
-                accept_len=int(r["accept_len"]), emitted=[int(x) for x in r["emitted"]],
-                draft_logits_cols=[[float(x) for x in r["draft_logits"][j][cols]] for j in range(Bk)],
-                tgt_logits_cols=[[float(x) for x in r["logits"][j][cols]] for j in range(Bk)],
-                logit_std=float(r["logits"].std()),
-            )
-            if not greedy:
-                rec["key"] = RNG_KEY
-                rec["uniforms"] = [float(x) for x in uniforms]
-                rec["final_margin"] = O.top2_margin(r["final_scores"])
-                # how close each acceptance test was: |u q(d) - p(d)| / p(d) for the tested slots
-                p = O.softmax(r["logits"] / w.temperature)
-                q = O.softmax(r["draft_logits"] / w.temperature)
-                rec["accept_test_margin"] = [
-                    float(abs(uniforms[j] * q[j][r["block"][j]] - p[j - 1][r["block"][j]]) / p[j - 1][r["block"][j]])
-                    for j in range(1, min(Bk, r["accept_len"] + 2))]
-            # committed context-feature rows of the first and last draft layer (first 8 dims of head 0)
-            a = r["accept_len"]
-            rec["ctx_k_new"] = [[float(x) for x in st.ctx.k[l][n + j, 0, :8]] for l in (0, w.draft.n_layers - 1) for j in range(a + 1)]
-            rec["ctx_v_new"] = [[float(x) for x in st.ctx.v[l][n + j, 0, :8]] for l in (0, w.draft.n_layers - 1) for j in range(a + 1)]
+            store_step(rec, r, st, w, n, cols, greedy, uniforms)
             results[f"cfg{cfg}_seq{seq}"] = rec
             json.dump(results, open(out_path, "w"), indent=0)
             print(f"[{time.time()-t0:7.1f}s]   accept_len {rec['accept_len']} emitted {rec['emitted']} "

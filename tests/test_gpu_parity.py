@@ -358,6 +358,31 @@ def test_small_bf16_other_block_sizes(block):
     assert ls.stats["reseeds"] <= 1
 
 
+@pytest.mark.parametrize("n_seqs,block,fuse,temperature", [(1, 16, "1", 0.0), (1, 16, "2", 0.0), (1, 16, "3", 0.0), (2, 8, "1", 0.0),
+                                                          (2, 8, "2", 0.0), (1, 10, "1", 0.0), (1, 10, "2", 0.0), (1, 16, "1", 0.7),
+                                                          (1, 16, "2", 0.7), (3, 5, "2", 0.0)])
+def test_small_bf16_single_band_of_rows(n_seqs, block, fuse, temperature, monkeypatch):
+    """At most 16 rows per step (batch 1 at B = 16, the latency case of Section 3.2, Eq. 1).  DFLASH_FUSE=1 (the
+    default): the O projection runs unsplit with the residual update in its epilogue and the RMSNorm that follows is
+    deferred into the gate/up GEMM; 2: the down projection and the norm after it likewise (no separate normalisation
+    launch left); 3: the same rows through the separate kernels.  Full bands, ragged bands (10 and 15 rows), two
+    sequences in one band, greedy and sampled."""
+    monkeypatch.setenv("DFLASH_FUSE", fuse)
+    w = si.small_bf16_workload(n_seqs=n_seqs, ctx_min=20, ctx_max=150, seed=41, block_size=block, temperature=temperature)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=150 + 8 * block)
+    first, got, mism = ls.prefill()
+    ls.check_cache([0, 3, 7], [0, 1])
+    k = block - 1
+    plans = [None, [k] * n_seqs, [min(3, k)] * n_seqs, None, [0] * n_seqs] if temperature == 0 else [None] * 4
+    for i, plan in enumerate(plans):
+        ls.step(plan=plan, temperature=temperature, step_idx=i, key=77)
+    ls.check_cache([0, 7], [0, 1])
+    print(f"single band (S={n_seqs}, B={block}, fuse={fuse}, T={temperature}) stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
 @pytest.mark.parametrize("draft_layers,n_taps", [(8, 5), (3, 3)])
 def test_small_bf16_drafter_depth_and_feature_count(draft_layers, n_taps):
     """The drafter variants of the ablations in Section 5.5: an 8-layer drafter with 5 tapped target layers and a
