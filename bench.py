@@ -155,15 +155,13 @@ def run_prefill(args, dev):
                       "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
                       "config": {"workload": "prefill_moe_30b_a3b" if w.target.n_experts else "prefill_8b", "prompt_tokens": n_tok, "rows_per_pass": n_tok, "page_order": args.page_order},
                       "target_gemm_TFLOPs_algorithmic": flops / (ms * 1e-3) / 1e12,
-                      "moe_stats_launches_experts_bands_items": list(e.moe_stats()) if t.n_experts else None}))
+                      "moe_stats_launches_experts_bands_items": list(e.moe_stats())[:4] if t.n_experts else None}))
     e.close()
 
 
 def measure_peaks(dev):
     """Machine probes through the library: back-to-back read-only launches over fresh memory (sizes of the O, QKV,
-    down, gate/up projections and the LM head), a bf16 MFMA loop at 1, 2 and 4 wavefronts per SIMD, and the
-    per-k-tile instruction mix of the LDS-staged GEMM (fragment reads, LDS fills, MFMAs) with the fills left out,
-    done by ds_write, and done by direct-to-LDS loads."""
+    down, gate/up projections and the LM head) and a bf16 MFMA loop at 1, 2 and 4 wavefronts per SIMD."""
     import torch
     from paper_2602_06036_amd import binding as B
     buf = torch.empty(6 << 30, dtype=torch.uint8, device=dev)
@@ -181,14 +179,6 @@ def measure_peaks(dev):
             B.dflash_probe_mfma(shape, wgs, 2000)
             ms, fl = B.dflash_probe_mfma(shape, wgs, 20000)
             out["mfma_bf16"][f"{name}_{wgs // 256}_waves_per_simd"] = {"ms": ms, "TFLOPs": fl / ms / 1e9}
-    out["lds_mix_TFLOPs"] = {}
-    for mix, name in ((3, "256x128_r16_f8_m64"), (0, "192x128_r14_f7_m48"), (1, "128x128_r12_f6_m32"), (2, "192x64_r10_f5_m24")):
-        row = {}
-        for fill, fname in ((0, "no_fill"), (1, "ds_write"), (2, "direct_to_lds"), (3, "direct_to_lds_first")):
-            B.dflash_probe_lds_mix(buf, mix, fill, 2000)
-            ms, fl = B.dflash_probe_lds_mix(buf, mix, fill, 20000)
-            row[fname] = fl / ms / 1e9
-        out["lds_mix_TFLOPs"][name] = row
     return out
 
 
@@ -429,7 +419,7 @@ def main():
             # reached (counted on the device, averaged over the launches), read once; flops: top_k experts per row.
             t_ = w.target
             ms_e, cnt_e, _ = prof[6]
-            n_route, n_reached, n_bands, n_work = e.moe_stats()       # totals of the profiled steps (cleared before them)
+            n_route, n_reached, n_bands, n_work = e.moe_stats()[:4]       # totals of the profiled steps (cleared before them)
             extra["moe"] = dict(experts_reached_per_layer=n_reached / n_route, bands_per_layer=n_bands / n_route, work_items_per_layer=n_work / n_route,
                                 expected_if_uniform=expected_experts(t_, M_rows))
             e_by = (n_reached / n_route) * 2 * t_.d_expert * t_.d_model * 2

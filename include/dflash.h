@@ -13,8 +13,9 @@
  *   - Return value: DFLASH_OK or a negative DFLASH_E* code.  Errors that the host can see
  *     (null pointers, sizes, unsupported shapes) are reported before anything is enqueued;
  *     dflash_last_error() then gives a message.  Conditions only the device can see (a sequence
- *     that outgrew its pages, a page id outside the pool) raise a sticky device flag that
- *     dflash_device_status() reads; the offending rows are skipped, never accessed out of bounds.
+ *     that outgrew its pages or the host's max_seq_len hint, a page id outside the pool) raise a sticky
+ *     device flag that dflash_device_status() reads; the offending rows are skipped or incomplete, never
+ *     accessed out of bounds.
  *   - Linear maps are given as [out_features, in_features] row-major (y = W x, the paper's
  *     notation), in the model's dtype; norm gains are fp32.
  *   - `stream` is a hipStream_t passed as void* (NULL = the default stream).
@@ -90,10 +91,16 @@ typedef struct {
 typedef struct {
   int32_t n_seqs;             /* S in [0, max_seqs]; with S = 0 the four step calls return DFLASH_OK and enqueue nothing
                                  (the pointers below are then not looked at) */
-  int32_t max_seq_len;        /* (host) upper bound on seq_lens[s] over the batch; sizes launch grids only */
+  int32_t max_seq_len;        /* (host) upper bound on seq_lens[s] over the batch; sizes launch grids only.  A sequence that is
+                                 longer than this on the device may have its last cached rows left out of attention: the call
+                                 then raises the sticky device status (dflash_device_status returns DFLASH_ECAPACITY) */
   int32_t *seq_lens;          /* (device) [S] committed length n_s; updated by dflash_kv_commit */
   const int32_t *block_table; /* (device) [S, max_pages_per_seq] page ids; pages covering n_s + B tokens must be valid */
   int32_t *anchor;            /* (device) [S] clean token at position n_s; updated by dflash_kv_commit */
+  int32_t block_size;         /* rows per sequence of this call: 0 = the context's block_size, else 2..that value.  Section 5.5
+                                 discusses smaller blocks where verification is compute-bound (large batches): a caller may
+                                 choose the block per step.  The four calls of one step must use the same value; every [S,B]
+                                 array of a call has this many columns. */
 } dflash_batch;
 
 typedef struct dflash_ctx dflash_ctx;
@@ -205,8 +212,9 @@ int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count
 
 /* Routed-expert targets: totals since the last read (or create) of routing launches (one per target layer and
  * dflash_verify call), experts reached by at least one row, 16-row bands of the expert-sorted row list and work items
- * of the grouped launches, into out[0..3] (host).  experts / launches * bytes of one expert's matrices = what a layer's expert GEMMs had to read.
- * Synchronises the stream and clears the totals. */
+ * of the grouped launches, into out[0..3] (host); out[4] = the bands per work item (1, 2, 4, or 8 = grouped launches of the
+ * LDS-staged GEMM) of the last routing launch.  experts / launches * bytes of one expert's matrices = what a layer's expert
+ * GEMMs had to read.  Synchronises the stream and clears all five. */
 int dflash_moe_stats(dflash_ctx *ctx, void *stream, int64_t *out);
 
 /* ---- machine probes (benchmarks; not part of the method) -----------------------------------------
@@ -221,13 +229,6 @@ int dflash_moe_stats(dflash_ctx *ctx, void *stream, int64_t *out);
  * Both synchronise the stream.  DFLASH_EINVAL on bad arguments, DFLASH_EHIP if the device reports an error. */
 int dflash_probe_hbm_read(const void *buf, size_t bytes_per_launch, int32_t launches, float *ms_total, void *stream);
 int dflash_probe_mfma(int32_t shape, int32_t workgroups, int32_t iters, float *ms, double *flops, void *stream);
-/* dflash_probe_lds_mix: the per-k-tile instruction mix of the LDS-staged GEMM in isolation (512 workgroups of 4
- * wavefronts, two per CU, one barrier per round): per wavefront and round mix 0: 14 fragment reads, 7 fills, 48 MFMAs
- * (192 x 128 tile); 1: 12 / 6 / 32 (128 x 128); 2: 10 / 5 / 24 (192 x 64); 3: 16 / 8 / 64 (256 x 128).  fill 0: no
- * fills, 1: ds_write_b128 from registers, 2: direct-to-LDS global loads issued after the reads, 3: before them (buf:
- * (device) 32 KB, read only).  *ms =
- * elapsed time of `iters` rounds, *flops = MFMA flops issued.  Synchronises `stream`. */
-int dflash_probe_lds_mix(const void *buf, int32_t mix, int32_t fill, int32_t iters, float *ms, double *flops, void *stream);
 
 /* ---- cache import / export (state migration, tests) ------------------------------------------ */
 /* Copies rows [start, start+count) of sequence `seq` of one layer between the paged pool and

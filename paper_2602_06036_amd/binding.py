@@ -26,7 +26,7 @@ EXPORTS = [
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
     "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats",
-    "dflash_probe_hbm_read", "dflash_probe_mfma", "dflash_probe_lds_mix",
+    "dflash_probe_hbm_read", "dflash_probe_mfma",
 ]
 
 
@@ -49,7 +49,7 @@ class Runtime(C.Structure):
 
 class Batch(C.Structure):
     _fields_ = [("n_seqs", C.c_int32), ("max_seq_len", C.c_int32), ("seq_lens", C.c_void_p), ("block_table", C.c_void_p),
-                ("anchor", C.c_void_p)]
+                ("anchor", C.c_void_p), ("block_size", C.c_int32)]
 
 
 class DFlashError(RuntimeError):
@@ -204,10 +204,12 @@ class Engine:
             self.l.dflash_destroy(self.ctx)
             self.ctx = None
 
-    def batch(self, seq_lens: torch.Tensor, block_table: torch.Tensor, anchor: torch.Tensor, max_seq_len: int) -> Batch:
+    def batch(self, seq_lens: torch.Tensor, block_table: torch.Tensor, anchor: torch.Tensor, max_seq_len: int,
+              block_size: int = 0) -> Batch:
+        """block_size: rows per sequence of the calls made with this batch (0 = the context's block size)."""
         assert seq_lens.dtype == torch.int32 and block_table.dtype == torch.int32 and anchor.dtype == torch.int32
         assert block_table.shape == (seq_lens.shape[0], self.max_pages_per_seq)
-        return Batch(int(seq_lens.shape[0]), int(max_seq_len), _ptr(seq_lens), _ptr(block_table), _ptr(anchor))
+        return Batch(int(seq_lens.shape[0]), int(max_seq_len), _ptr(seq_lens), _ptr(block_table), _ptr(anchor), int(block_size))
 
     def profile_enable(self, on: bool):
         _check(self.l.dflash_profile_enable(self.ctx, int(on)), self.ctx)
@@ -220,10 +222,11 @@ class Engine:
         return {i: (float(ms[i]), int(cnt[i]), float(by[i])) for i in range(n) if cnt[i]}
 
     def moe_stats(self):
-        """(routing launches, experts reached, 16-row bands, work items) since the last read; routed-expert targets only."""
-        out = (C.c_int64 * 4)()
+        """(routing launches, experts reached, 16-row bands, work items) since the last read, and the bands per work
+        item of the last routing launch; routed-expert targets only."""
+        out = (C.c_int64 * 5)()
         _check(self.l.dflash_moe_stats(self.ctx, _stream(), out), self.ctx)
-        return int(out[0]), int(out[1]), int(out[2]), int(out[3])
+        return int(out[0]), int(out[1]), int(out[2]), int(out[3]), int(out[4])
 
     def device_status(self):
         _check(self.l.dflash_device_status(self.ctx, _stream()), self.ctx)
@@ -273,15 +276,6 @@ def dflash_probe_hbm_read(buf: torch.Tensor, bytes_per_launch: int, launches: in
     ms = C.c_float()
     _check(lib().dflash_probe_hbm_read(C.c_void_p(buf.data_ptr()), C.c_size_t(bytes_per_launch), launches, C.byref(ms), _stream()))
     return float(ms.value)
-
-
-def dflash_probe_lds_mix(buf: torch.Tensor, mix: int, fill: int, iters: int):
-    """(milliseconds, flops) of `iters` rounds of one k tile's instruction mix of the LDS-staged GEMM
-    (mix 0..3: tile shape; fill 0: none, 1: ds_write, 2: direct-to-LDS loads from `buf`, at least 32 KB)."""
-    assert buf.is_cuda and buf.is_contiguous() and buf.numel() * buf.element_size() >= 32768
-    ms, fl = C.c_float(), C.c_double()
-    _check(lib().dflash_probe_lds_mix(C.c_void_p(buf.data_ptr()), mix, fill, iters, C.byref(ms), C.byref(fl), _stream()))
-    return float(ms.value), float(fl.value)
 
 
 def dflash_probe_mfma(shape: int, workgroups: int, iters: int):

@@ -40,6 +40,64 @@ inline size_t align256(size_t x) { return (x + 255) & ~(size_t)255; }
 inline size_t esize(int dtype) { return dtype == DFLASH_BF16 ? 2 : 4; }
 inline int round_rows(int dtype, int M) { return dtype == DFLASH_BF16 ? (M + 15) & ~15 : M; }
 
+inline int env_int(const char* name, int dflt) {
+  const char* e = getenv(name);
+  const int v = e ? atoi(e) : 0;
+  return v > 0 ? v : dflt;
+}
+
+// Tuning and testing knobs, read from the environment whenever a context is created (or a workspace is sized): a
+// context keeps the values it was created with, so a test that sets one before dflash_create gets exactly that path
+// whatever ran earlier in the process.  Defaults are what the measurements in the documentation use.
+struct Knobs {
+  int attn_target_wgs;      // DFLASH_ATTN_TARGET_WGS: workgroups an attention launch aims at
+  int attn_wide_min_chunk;  // DFLASH_ATTN_WIDE_MIN_CHUNK: keys per workgroup from which the key-split attention kernel is used
+  int gemm_target_wgs;      // DFLASH_GEMM_TARGET_WGS: workgroups a K-split streaming GEMM aims at
+  int gemm_u;               // DFLASH_GEMM_U: k tiles per prefetch stage (one band of rows)
+  int gemm_nt8;             // DFLASH_GEMM_NT8: matrices with at least 8 * this row bands use 8 weight tiles per activation fragment
+  int gemm_fill;            // DFLASH_GEMM_FILL: 1 = weight tiles per wavefront (8 or 6) and K split chosen to fill whole rounds of the CUs
+  int gemm_fill4;           // DFLASH_GEMM_FILL4: the same for 17-64 rows
+  int gemm_u4;              // DFLASH_GEMM_U4: k tiles per prefetch stage for 17-64 rows
+  int gemm_solo_pct;        // DFLASH_GEMM_SOLO_PCT: tiled GEMM picker, time penalty (percent) of a ring tile alone on its CU
+  int gemm_pd;              // DFLASH_GEMM_PD: tiled GEMM, k tiles in flight from global memory (192/128-row tiles)
+  int gemm_ring;            // DFLASH_GEMM_RING: 1 = direct-to-LDS ring for the small tiles, other = register staging
+  int gemm_tile, gemm_wm, gemm_ks;   // DFLASH_GEMM_TILE / _WM / _KS: force the tiled GEMM's shape / rows per tile / K split (0 = by estimated time)
+  int lm_stats;             // DFLASH_LM_STATS: 1 = softmax statistics from the LM-head epilogue, other = from the stored logits
+  int moe_mt;               // DFLASH_MOE_MT: 1, 2, 4 or 8 forces the bands per routed-expert work item (0 = by rows per expert)
+  int moe_gather_min_rows;  // DFLASH_MOE_GATHER_MIN_ROWS: rows from which the routed-expert GEMMs get their rows copied into list order
+  int moe_phases;           // DFLASH_MOE_PHASES: 2 = two-half sum form of the 4-band down projection
+  int moe_down_u;           // DFLASH_MOE_DOWN_U: k tiles per stage of the one-band down projection
+  int fuse;                 // DFLASH_FUSE: few-row path, see dflash_ctx::fuse
+  int resid_nw, resid_u;    // DFLASH_RESID_NW / _U: wavefronts per workgroup and k tiles per stage of the unsplit projection kernel
+};
+Knobs read_knobs() {
+  Knobs k;
+  k.attn_target_wgs = env_int("DFLASH_ATTN_TARGET_WGS", 256);
+  k.attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
+  k.gemm_target_wgs = env_int("DFLASH_GEMM_TARGET_WGS", 256);
+  k.gemm_u = env_int("DFLASH_GEMM_U", 2);
+  k.gemm_nt8 = env_int("DFLASH_GEMM_NT8", 1);
+  k.gemm_fill = env_int("DFLASH_GEMM_FILL", 1);
+  k.gemm_fill4 = env_int("DFLASH_GEMM_FILL4", 1);
+  k.gemm_u4 = env_int("DFLASH_GEMM_U4", 1);
+  k.gemm_solo_pct = env_int("DFLASH_GEMM_SOLO_PCT", 120);
+  k.gemm_pd = env_int("DFLASH_GEMM_PD", 2);
+  k.gemm_ring = env_int("DFLASH_GEMM_RING", 1);
+  k.gemm_tile = env_int("DFLASH_GEMM_TILE", 0);
+  k.gemm_wm = env_int("DFLASH_GEMM_WM", 0);
+  k.gemm_ks = env_int("DFLASH_GEMM_KS", 0);
+  k.lm_stats = env_int("DFLASH_LM_STATS", 1);
+  k.moe_mt = env_int("DFLASH_MOE_MT", 0);
+  k.moe_gather_min_rows = env_int("DFLASH_MOE_GATHER_MIN_ROWS", 64);
+  k.moe_phases = env_int("DFLASH_MOE_PHASES", 2);
+  k.moe_down_u = env_int("DFLASH_MOE_DOWN_U", 1);
+  k.fuse = env_int("DFLASH_FUSE", 1);
+  if (k.fuse != 1 && k.fuse != 2) k.fuse = 0;
+  k.resid_nw = env_int("DFLASH_RESID_NW", 4);
+  k.resid_u = env_int("DFLASH_RESID_U", 8);
+  return k;
+}
+
 struct LayerOff {
   size_t wqkv, wo, wgu, wd, wr, g1, g2, qn, kn, end;
 };
@@ -111,16 +169,17 @@ DraftLayout draft_layout(const dflash_dims& d, int n_taps, int d_target) {
 int check_dims(const dflash_dims* d, const char* who) {
   if (!d) return fail(nullptr, DFLASH_EINVAL, "%s dims: null", who);
   if (d->dtype != DFLASH_F32 && d->dtype != DFLASH_BF16) return fail(nullptr, DFLASH_EINVAL, "%s: dtype must be DFLASH_F32 or DFLASH_BF16", who);
-  if (d->n_layers < 1 || d->d_model < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || d->d_ffn < 1 || d->vocab < 1)
+  const bool routed = d->n_experts != 0;   // d_ffn is unused (and unchecked) when every layer's FFN is routed experts
+  if (d->n_layers < 1 || d->d_model < 1 || d->n_q_heads < 1 || d->n_kv_heads < 1 || (!routed && d->d_ffn < 1) || d->vocab < 1)
     return fail(nullptr, DFLASH_EINVAL, "%s: non-positive dimension", who);
   if (d->n_q_heads % d->n_kv_heads) return fail(nullptr, DFLASH_EINVAL, "%s: n_q_heads must be a multiple of n_kv_heads", who);
   if (d->head_dim > 128 || d->head_dim < 16 || d->head_dim % 16) return fail(nullptr, DFLASH_EINVAL, "%s: head_dim must be a multiple of 16 in [16,128]", who);
   const int qd = d->n_q_heads * d->head_dim;
   if (d->dtype == DFLASH_BF16) {
-    if (d->d_model % 32 || d->d_ffn % 32 || qd % 32 || d->vocab % 16)
+    if (d->d_model % 32 || (!routed && d->d_ffn % 32) || qd % 32 || d->vocab % 16)
       return fail(nullptr, DFLASH_EINVAL, "%s: bf16 needs d_model, d_ffn, Hq*hd multiples of 32 and vocab a multiple of 16", who);
   } else {
-    if (d->d_model % 8 || d->d_ffn % 16 || qd % 8) return fail(nullptr, DFLASH_EINVAL, "%s: fp32 needs d_model, Hq*hd multiples of 8 and d_ffn a multiple of 16", who);
+    if (d->d_model % 8 || (!routed && d->d_ffn % 16) || qd % 8) return fail(nullptr, DFLASH_EINVAL, "%s: fp32 needs d_model, Hq*hd multiples of 8 and d_ffn a multiple of 16", who);
   }
   if (!(d->rope_theta > 1.f) || !(d->rms_eps >= 0.f)) return fail(nullptr, DFLASH_EINVAL, "%s: bad rope_theta / rms_eps", who);
   if (d->n_experts) {
@@ -150,14 +209,9 @@ struct SplitPlan {
   int n_splits, chunk;
   int bound;  // >= n_splits for this and every smaller max_tokens (sizes the partial buffers)
 };
-SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens) {
+SplitPlan plan_splits(int S, int n_kv_heads, int max_tokens, int target_wgs) {
   // the attention kernel runs one workgroup per CU (its accumulators fill the register file), so aim at
-  // one round of workgroups on the 256 CUs
-  static const int target_wgs = [] {
-    const char* e = getenv("DFLASH_ATTN_TARGET_WGS");   // tuning knob
-    const int v = e ? atoi(e) : 0;
-    return v > 0 ? v : 256;
-  }();
+  // one round of workgroups on the 256 CUs (target_wgs: Knobs::attn_target_wgs)
   const int max_splits = 64;
   int splits = (target_wgs + S * n_kv_heads - 1) / (S * n_kv_heads);
   const int by_len = (max_tokens + 63) / 64;
@@ -181,7 +235,7 @@ struct Workspace {
   size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, ssq, total;
   size_t moe_sel_e, moe_sel_w, moe_sel_pos, moe_row_of, moe_items, moe_a, moe_act, moe_y;   // routed-expert target only
 };
-Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt) {
+Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt, const Knobs& kn) {
   const size_t es = esize(t.dtype);
   const int M = rt.max_seqs * rt.block_size;
   const size_t Mr = round_rows(t.dtype, M);
@@ -212,8 +266,12 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   const int max_tokens = rt.max_pages_per_seq * DFLASH_PAGE_SIZE;
   for (int S = 1; S <= rt.max_seqs; ++S) {
     for (const dflash_dims* m : {&t, &d}) {
-      const SplitPlan p = plan_splits(S, m->n_kv_heads << attn_q_shift(*m, rt.block_size), max_tokens);
-      part_rows = std::max(part_rows, (size_t)S * rt.block_size * m->n_q_heads * p.bound);
+      for (int blk = 2; blk <= rt.block_size; ++blk) {   // a call may use a smaller block than the context's (dflash_batch::block_size)
+        const int sh = attn_q_shift(*m, blk);
+        if (sh < 0) continue;
+        const SplitPlan p = plan_splits(S, m->n_kv_heads << sh, max_tokens, kn.attn_target_wgs);
+        part_rows = std::max(part_rows, (size_t)S * blk * m->n_q_heads * p.bound);
+      }
     }
   }
   const size_t hd = std::max(t.head_dim, d.head_dim);
@@ -276,18 +334,13 @@ struct dflash_ctx {
   const char* dblob;
   char* wsp;
   char err[512];
-  int attn_wide_min_chunk = 512;   // keys per workgroup from which the key-split attention kernel is used (tuning knob)
+  Knobs k;                                             // tuning / testing knobs as they stood when the context was created
   bool have_logits_d = false, have_logits_t = false;   // the workspace holds this step's draft / target logits
   float draft_temperature = 0.f;                       // of the last dflash_draft_block call
   float stats_q_T = 0.f, stats_p_T = 0.f;              // > 0: ws.stats_q / ws.stats_p hold this step's (max, log-sum-exp) rows at that temperature
-  int ks_force = 0;     // tiled GEMM: forces the K split where a split is allowed (tuning knob)
-  int tile_force = 0;   // tiled GEMM: 8, 6 or 4 forces that tile shape (testing / tuning knob), 0 = pick by estimated time
-  int wm_force = 0;     // tiled GEMM: 4 or 2 forces 128 or 64 activation rows per tile (testing / tuning knob)
-  bool lm_stats = true; // softmax statistics from the LM-head epilogue (testing knob: off = always from the stored logits)
-  int fuse = 1;         // few-row path (one band of rows, dense bf16 model): 1 = the O projection runs unsplit with the residual update
-                        // in its epilogue and the RMSNorm that follows deferred into the gate/up GEMM; 2 = the down projection
-                        // as well (then no separate normalisation launch is left in a layer); 0 = separate kernels throughout
-  int resid_nw = 4, resid_u = 8;   // wavefronts per workgroup and k tiles per stage of that projection kernel (tuning knobs)
+  // k.fuse, few-row path (one band of rows, dense bf16 model): 1 = the O projection runs unsplit with the residual update in
+  // its epilogue and the RMSNorm that follows deferred into the gate/up GEMM; 2 = the down projection as well (then no
+  // separate normalisation launch is left in a layer); 0 = separate kernels throughout
   // optional per-launch timing (dflash_profile_*): event pairs around the GEMM and attention launches
   bool prof_on = false;
   std::vector<hipEvent_t> ev;
@@ -338,13 +391,15 @@ struct Engine {
   template <typename P> P* ws(size_t off) { return reinterpret_cast<P*>(c->wsp + off); }
   int32_t* status() { return ws<int32_t>(c->ws.status); }
 
+  // rows per sequence of this call: the batch's own block size if it gives one, else the context's
+  int blk(const dflash_batch* b) const { return b->block_size > 0 ? b->block_size : c->rt.block_size; }
   SeqGeom geom(const dflash_batch* b) {
     SeqGeom g;
     g.seq_lens = b->seq_lens;
     g.block_table = b->block_table;
     g.max_pages_per_seq = c->rt.max_pages_per_seq;
     g.n_pages = c->rt.n_pages;
-    g.block_size = c->rt.block_size;
+    g.block_size = blk(b);
     g.status = status();
     return g;
   }
@@ -366,7 +421,7 @@ struct Engine {
   // pieces of the rows' sums of squares are in ws.ssq (see gemm_resid.h)
   int defer_parts = 0;
   bool few_rows(const dflash_dims& m, int M, int level = 2) const {
-    return std::is_same<T, bf16_t>::value && c->fuse >= level && !m.n_experts && M <= 16 && m.d_model % 16 == 0;
+    return std::is_same<T, bf16_t>::value && c->k.fuse >= level && !m.n_experts && M <= 16 && m.d_model % 16 == 0;
   }
   EpiArgs deferred(EpiArgs ep, const dflash_dims& m) {
     ep.ssq = ws<float>(c->ws.ssq);
@@ -379,7 +434,7 @@ struct Engine {
   void resid(const T* W, const T* A, int M, int N, int K, const float* gain_next, int tap);
   void layer_few_rows(const dflash_dims& m, const char* lbase, const LayerOff& lo, T* pool, int l, const dflash_batch* b, bool causal,
                       const float* gain_next, int tap) {
-    const int S = b->n_seqs, B = c->rt.block_size, M = S * B, D = m.d_model;
+    const int S = b->n_seqs, B = blk(b), M = S * B, D = m.d_model;
     const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, nqkv = qd + 2 * kd;
     float* arena = ws<float>(c->ws.arena);
     T* a = ws<T>(c->ws.a);
@@ -391,7 +446,7 @@ struct Engine {
     resid(reinterpret_cast<const T*>(lbase + lo.wd), ws<T>(c->ws.act), M, D, m.d_ffn, gain_next, tap);
   }
   void qkv_post(const dflash_dims& m, const char* lbase, const LayerOff& lo, T* pool, int l, const dflash_batch* b, const Slab& qs) {
-    const int M = b->n_seqs * c->rt.block_size;
+    const int M = b->n_seqs * blk(b);
     const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, nqkv = qd + 2 * kd;
     RopeArgs ra;
     ra.n_q_heads = m.n_q_heads; ra.n_kv_heads = m.n_kv_heads; ra.head_dim = m.head_dim;
@@ -449,7 +504,7 @@ struct Engine {
 
   // one Transformer layer on the M block rows held in ws.h
   void layer(const dflash_dims& m, const char* lbase, const LayerOff& lo, T* pool, int l, const dflash_batch* b, bool causal) {
-    const int S = b->n_seqs, B = c->rt.block_size, M = S * B, D = m.d_model;
+    const int S = b->n_seqs, B = blk(b), M = S * B, D = m.d_model;
     const int qd = m.n_q_heads * m.head_dim, kd = m.n_kv_heads * m.head_dim, nqkv = qd + 2 * kd;
     float* h = ws<float>(c->ws.h);
     float* arena = ws<float>(c->ws.arena);
@@ -503,7 +558,7 @@ struct Engine {
     ep.amax_inv_T = inv_T;
     ep.amax_key = key;
     ep.amax_B = B;
-    if (stats_T > 0.f && c->lm_stats) {
+    if (stats_T > 0.f && c->k.lm_stats == 1) {
       ep.lse = ws<float2>(c->ws.lsep);
       ep.lse_inv_T = 1.0f / stats_T;
     }
@@ -520,7 +575,7 @@ struct Engine {
   }
 
   int draft_block(const dflash_batch* b, float temperature, const uint64_t* rng_key, int32_t* draft_tokens, float* logits_out) {
-    const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+    const int S = b->n_seqs, B = blk(b), M = S * B;
     const dflash_dims& d = c->d;
     hipLaunchKernelGGL(build_block_kernel, dim3((M + 255) / 256), dim3(256), 0, st, b->anchor, draft_tokens, S, B, c->rt.mask_token_id);
     check();
@@ -534,7 +589,7 @@ struct Engine {
       defer_parts = 1;
     }
     hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), draft_tokens,
-                       ws<float>(c->ws.h), d.d_model, d.vocab, status(), b->seq_lens, B,
+                       ws<float>(c->ws.h), d.d_model, d.vocab, status(), b->seq_lens, B, b->max_seq_len,
                        RopeTab{ws<float2>(c->ws.rope_d), log((double)d.rope_theta), d.head_dim}, RopeTab{nullptr, 0.0, 0}, ef);
     check();
     for (int i = 0; i < d.n_layers; ++i) {
@@ -565,7 +620,7 @@ struct Engine {
   }
 
   int verify(const dflash_batch* b, const int32_t* tokens, int32_t* tgt_argmax, float* logits_out) {
-    const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+    const int S = b->n_seqs, B = blk(b), M = S * B;
     const dflash_dims& t = c->t;
     // the draft's table is for the context K/V rows that the commit of this verification will project
     const bool few = few_rows(t, M);
@@ -578,7 +633,7 @@ struct Engine {
       defer_parts = 1;
     }
     hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), tokens,
-                       ws<float>(c->ws.h), t.d_model, t.vocab, status(), b->seq_lens, B,
+                       ws<float>(c->ws.h), t.d_model, t.vocab, status(), b->seq_lens, B, b->max_seq_len,
                        RopeTab{ws<float2>(c->ws.rope_t), log((double)t.rope_theta), t.head_dim},
                        RopeTab{ws<float2>(c->ws.rope_d), log((double)c->d.rope_theta), c->d.head_dim}, ef);
     check();
@@ -623,7 +678,7 @@ struct Engine {
 
   int accept(const dflash_batch* b, const int32_t* draft_tokens, const int32_t* tgt_argmax, float temperature, const float* uniforms,
              const uint64_t* rng_key, int32_t* accept_len, int32_t* out_tokens) {
-    const int S = b->n_seqs, B = c->rt.block_size, M = S * B, V = c->t.vocab;
+    const int S = b->n_seqs, B = blk(b), M = S * B, V = c->t.vocab;
     if (temperature <= 0.f) {
       hipLaunchKernelGGL(accept_greedy_kernel, dim3((S + 63) / 64), dim3(64), 0, st, draft_tokens, tgt_argmax, S, B, accept_len, out_tokens);
       check();
@@ -648,7 +703,7 @@ struct Engine {
   }
 
   int commit(const dflash_batch* b, const int32_t* accept_len, const int32_t* out_tokens, int64_t* kv_slots) {
-    const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+    const int S = b->n_seqs, B = blk(b), M = S * B;
     const dflash_dims& d = c->d;
     const int D = d.d_model, kd = d.n_kv_heads * d.head_dim, nkv = d.n_layers * 2 * kd;
     float* arena = ws<float>(c->ws.arena);
@@ -707,16 +762,9 @@ void launch_tiled(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N
 
 inline int gemm_class(int epi, int N, int vocab) { return (epi == EPI_STORE && N == vocab) ? DFLASH_PROF_GEMM_LMHEAD : epi; }
 
-inline int env_int(const char* name, int dflt) {
-  const char* e = getenv(name);
-  const int v = e ? atoi(e) : 0;
-  return v > 0 ? v : dflt;
-}
-
 // K split across workgroups: aim at enough workgroups that every CU keeps several wavefronts streaming,
 // keep at least 2 k-tiles per wavefront, and stay inside the arena.
-inline int pick_ksplit(int n_blocks, int KT, int M, int arena) {
-  static const int target = env_int("DFLASH_GEMM_TARGET_WGS", 256);   // tuning knob
+inline int pick_ksplit(int n_blocks, int KT, int M, int arena, int target) {
   int ks = 1;
   while (ks < kMaxKSplit && n_blocks * ks * 2 <= target && KT / (ks * 2 * 4) >= 2 && ks * 2 * M <= arena) ks *= 2;
   return ks;
@@ -725,7 +773,7 @@ inline int pick_ksplit(int n_blocks, int KT, int M, int arena) {
 template <>
 Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, bool allow_split) {
   ProfScope prof(c, st, gemm_class(epi, N, c->t.vocab), (double)N * K * 2);
-  static const int U = env_int("DFLASH_GEMM_U", 2);   // tuning knob: k-tiles per prefetch stage
+  const int U = c->k.gemm_u;   // k-tiles per prefetch stage
   const int nt = N / 16, KT = K / 32;
   int kepi = epi;
   if (epi == EPI_RESID) {   // partial slabs into the arena; the next RMSNorm adds them to the residual stream
@@ -739,8 +787,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   if (ep.lse && (split || epi != EPI_STORE)) ep.lse = nullptr;      // so do the fused softmax statistics
   if (ep.amax && lm_skip_store) ep.out = nullptr;
   if (M <= 16) {
-    static const int NT8 = env_int("DFLASH_GEMM_NT8", 1);   // tuning knob: matrices with at least 8*this row bands use 8 weight tiles per activation fragment
-    static const int FILL = env_int("DFLASH_GEMM_FILL", 1);   // tuning knob: 1 = weight tiles per wavefront (8 or 6) and K split chosen to fill whole rounds of the 256 CUs
+    const int NT8 = c->k.gemm_nt8, FILL = c->k.gemm_fill;
     if (FILL == 1 && NT8 && nt >= 8 * NT8 && (nt % 8 == 0 || nt % 6 == 0)) {
       // a launch of 192 workgroups leaves a quarter of the CUs idle: among 8 or 6 weight tiles per wavefront and
       // any K split (not only powers of two) take the fullest last round; ties go to 8 tiles, then to fewer K ranges
@@ -761,22 +808,22 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
       if (best_nt == 8) launch_bf16<8, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<6, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
     } else if (NT8 && nt % 8 == 0 && nt >= 8 * NT8) {
-      if (split) ks = pick_ksplit(nt / 8, KT, M, arena);
+      if (split) ks = pick_ksplit(nt / 8, KT, M, arena, c->k.gemm_target_wgs);
       ep.slab = (size_t)M * ep.ld;
       if (U >= 2) launch_bf16<8, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<8, 1, 1>(st, W, A, M, N, K, kepi, ep, ks);
     } else if (nt % 4 == 0) {
-      if (split) ks = pick_ksplit(nt / 4, KT, M, arena);
+      if (split) ks = pick_ksplit(nt / 4, KT, M, arena, c->k.gemm_target_wgs);
       ep.slab = (size_t)M * ep.ld;
       if (U >= 4) launch_bf16<4, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
       else if (U >= 2) launch_bf16<4, 1, 2>(st, W, A, M, N, K, kepi, ep, ks);
       else launch_bf16<4, 1, 1>(st, W, A, M, N, K, kepi, ep, ks);
     } else if (nt % 2 == 0) {
-      if (split) ks = pick_ksplit(nt / 2, KT, M, arena);
+      if (split) ks = pick_ksplit(nt / 2, KT, M, arena, c->k.gemm_target_wgs);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<2, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
     } else {
-      if (split) ks = pick_ksplit(nt, KT, M, arena);
+      if (split) ks = pick_ksplit(nt, KT, M, arena, c->k.gemm_target_wgs);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<1, 1, 4>(st, W, A, M, N, K, kepi, ep, ks);
     }
@@ -784,7 +831,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     // still bandwidth-bound: the same streaming kernel with two or four activation bands per weight tile.  As for a
     // single band, 8 or 6 weight tiles per wavefront and the K split are chosen for the fullest rounds of the 256 CUs
     // (gate/up of the 8B shape: 192 workgroups with 8 tiles, 256 with 6)
-    static const int FILL4 = env_int("DFLASH_GEMM_FILL4", 1);   // tuning knob: any other value = 8 tiles and power-of-two K splits only
+    const int FILL4 = c->k.gemm_fill4;   // any value but 1: 8 tiles and power-of-two K splits only
     int best_nt = 8;
     if (FILL4 == 1) {
       double best_fill = -1.0;
@@ -799,10 +846,10 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
         }
       }
     } else if (split) {
-      ks = pick_ksplit(nt / 8, KT, M, arena);
+      ks = pick_ksplit(nt / 8, KT, M, arena, c->k.gemm_target_wgs);
     }
     ep.slab = (size_t)M * ep.ld;
-    static const int U4 = env_int("DFLASH_GEMM_U4", 1);   // tuning knob: k-tiles per prefetch stage for 16 < M <= 64 (2 measured slower)
+    const int U4 = c->k.gemm_u4;   // k-tiles per prefetch stage for 16 < M <= 64 (2 measured slower)
     if (M <= 32) {
       if (best_nt == 6) launch_bf16<6, 2, 1>(st, W, A, M, N, K, kepi, ep, ks);
       else if (U4 >= 2) launch_bf16<8, 2, 2>(st, W, A, M, N, K, kepi, ep, ks);
@@ -825,28 +872,28 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     bool best_solo = false;
     double best = 1e30;
     for (const Cand& cd : cands) {
-      if (c->tile_force && cd.wn != c->tile_force) continue;
-      if (c->wm_force && cd.wm != c->wm_force) continue;
+      if (c->k.gemm_tile && cd.wn != c->k.gemm_tile) continue;
+      if (c->k.gemm_wm && cd.wm != c->k.gemm_wm) continue;
       const int mb = ((M + 15) / 16 + 2 * cd.wm - 1) / (2 * cd.wm);
       const int wgs = ((nt + 2 * cd.wn - 1) / (2 * cd.wn)) * mb;
       for (int k = 1; k <= kMaxKSplit; k *= 2) {
         if (k > 1 && (!split || KT / k < 8 || k * M > arena)) break;
-        if (c->ks_force && split && k != c->ks_force && c->ks_force * M <= arena && KT / c->ks_force >= 8) continue;
+        if (c->k.gemm_ks && split && k != c->k.gemm_ks && c->k.gemm_ks * M <= arena && KT / c->k.gemm_ks >= 8) continue;
         const int per_cu = (wgs * k + 255) / 256;
         const double mfma_us = 32.0 * cd.wn * cd.wm * ((KT + k - 1) / k) / 2400.0;   // MFMA issue time of one workgroup
         const double slab_us = k > 1 ? (double)k * M * N * 8 / 4e6 : 0.0;
         // a workgroup alone on its CU has nobody to hide its barriers behind; the 128-row tiles then run as a
         // three-slot direct-to-LDS ring (they have the LDS to themselves), which loses less
         const bool solo = per_cu == 1, solo_ring = solo && !split && cd.wm == 4 && cd.wn >= 6;   // measured: only pays where K is not split
-        static const double solo_pen = env_int("DFLASH_GEMM_SOLO_PCT", 120) / 100.0;   // tuning knob: percent; measured 120 against 140 and 100
+        const double solo_pen = c->k.gemm_solo_pct / 100.0;   // measured 120 against 140 and 100
         const bool small_ring = cd.wm == 2 || cd.wn == 4;   // tiles that run as a direct-to-LDS ring anyway
         const double t = per_cu * mfma_us / cd.eff * (solo ? (solo_ring ? 1.15 : (small_ring ? solo_pen : 1.4)) : 1.0) + slab_us;
         if (t < best) { best = t; best_wn = cd.wn; best_wm = cd.wm; ks = k; best_solo = solo_ring; }
       }
     }
     ep.slab = (size_t)M * ep.ld;
-    static const int PD = env_int("DFLASH_GEMM_PD", 2);   // tuning knob: k tiles in flight from global memory (192/128-row tiles)
-    static const int RING = env_int("DFLASH_GEMM_RING", 1) == 1;   // tuning knob: 2 (or any other value) = register-staged variant for the small tiles
+    const int PD = c->k.gemm_pd;              // k tiles in flight from global memory (192/128-row tiles)
+    const bool RING = c->k.gemm_ring == 1;    // any other value: register-staged variant for the small tiles
     if (best_wm == 2 && RING) {
       if (best_wn == 8) launch_tiled<8, 2, 1, 3>(st, W, A, M, N, K, kepi, ep, ks);
       else if (best_wn == 6) launch_tiled<6, 2, 1, 3>(st, W, A, M, N, K, kepi, ep, ks);
@@ -866,11 +913,11 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
   } else {
     const int my = ((M + 15) / 16 + 3) / 4;
     if (nt % 2 == 0) {
-      if (split && my == 1) ks = pick_ksplit(nt / 2, KT, M, arena);
+      if (split && my == 1) ks = pick_ksplit(nt / 2, KT, M, arena, c->k.gemm_target_wgs);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<2, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
     } else {
-      if (split && my == 1) ks = pick_ksplit(nt, KT, M, arena);
+      if (split && my == 1) ks = pick_ksplit(nt, KT, M, arena, c->k.gemm_target_wgs);
       ep.slab = (size_t)M * ep.ld;
       launch_bf16<1, 4, 2>(st, W, A, M, N, K, kepi, ep, ks);
     }
@@ -907,7 +954,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   // bands per work item: enough for the rows an expert gets on average plus two standard deviations of an even spread,
   // so that nearly every expert's matrix is streamed by one row of workgroups only
   const double avg = (double)M * k / E, want = avg + 2.0 * sqrt(avg);
-  static const int mt_force = env_int("DFLASH_MOE_MT", 0);   // tuning / testing knob: 1, 2, 4 or 8 forces the bands per work item
+  const int mt_force = c->k.moe_mt;   // 1, 2, 4 or 8 forces the bands per work item
   // from 64 rows per expert on (a many-row prefill pass) the items are 128-row blocks of the LDS-staged kernel: the
   // streaming kernel would need two or more 64-row items for many experts, each streaming the expert's matrices.
   // Measured on one-pass prefills of the 30B-A3B shape, whose rows crowd on about a quarter of the experts: 1024 rows
@@ -936,7 +983,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   float* y = ws<float>(c->ws.moe_y);
   // tuning knob: from this many rows on the listed rows are first copied into list order (the GEMM then reads whole
   // fragments); below, the GEMM reads them through the list
-  static const int gather_min = env_int("DFLASH_MOE_GATHER_MIN_ROWS", 64);
+  const int gather_min = c->k.moe_gather_min_rows;
   const bool gathered = M >= gather_min || MT == 8;   // the LDS-staged kernel copies whole fragments: list order only
   if (gathered) {
     hipLaunchKernelGGL(moe_gather_kernel, dim3((D / 32 + 3) / 4, n_pos / 16), dim3(256), 0, st, reinterpret_cast<const u32x4*>(a), r.row_of,
@@ -949,7 +996,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   // registers, 64 KB of LDS: two workgroups per CU cover each other's waits); 1 = the double-buffered form, one
   // workgroup per CU.  Measured at 512 rows: 91-95 us against 104-106.  The gate/up launch gains nothing from it (165-181
   // us from run to run against 167-176) and stays double-buffered.
-  static const int ph4 = env_int("DFLASH_MOE_PHASES", 2);
+  const int ph4 = c->k.moe_phases;
   {
     ProfScope prof(c, st, DFLASH_PROF_MOE_GATEUP, used * 2 * Fe * D * 2);
     EpiArgs ep{nullptr, 0, 0, act, Fe};
@@ -973,7 +1020,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     // tuning knob: k tiles per prefetch stage of the one-band down projection.  Its K is short (6 k tiles per wavefront
     // at the 30B-A3B shape): one tile per stage leaves registers for four workgroups per CU, whose prologues and
     // epilogues overlap (measured 48 us against 54 with two tiles per stage and 60 with four)
-    static const int down_u = env_int("DFLASH_MOE_DOWN_U", 1);
+    const int down_u = c->k.moe_down_u;
     if (MT == 8) launch_grouped_tiled<4, 1, EPI_STORE, 3>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (MT == 1 && down_u == 1) launch_grouped<1, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     else if (MT == 1) launch_grouped<1, 2, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
@@ -1021,7 +1068,7 @@ void Engine<bf16_t>::resid(const bf16_t* W, const bf16_t* A, int M, int N, int K
   ra.taps = tap >= 0 ? ws<bf16_t>(c->ws.taps) : nullptr;
   ra.tap_idx = tap;
   ra.tap_K = c->rt.n_taps * c->t.d_model;
-  const int nw = c->resid_nw, u = c->resid_u;
+  const int nw = c->k.resid_nw, u = c->k.resid_u;
   if (nw == 16) launch_resid<4, 16>(st, W, A, M, N, K, ra);
   else if (nw == 8 && u <= 4) launch_resid<4, 8>(st, W, A, M, N, K, ra);
   else if (nw == 8) launch_resid<8, 8>(st, W, A, M, N, K, ra);
@@ -1034,10 +1081,10 @@ void Engine<float>::resid(const float*, const float*, int, int, int, const float
 
 template <typename T>
 void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const dflash_batch* b, bool causal) {
-  const int S = b->n_seqs, B = c->rt.block_size, M = S * B;
+  const int S = b->n_seqs, B = blk(b), M = S * B;
   const int max_tokens = std::min(b->max_seq_len + B, c->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
   const int q_shift = attn_q_shift(m, B);
-  const SplitPlan p = plan_splits(S, m.n_kv_heads << q_shift, max_tokens);
+  const SplitPlan p = plan_splits(S, m.n_kv_heads << q_shift, max_tokens, c->k.attn_target_wgs);
   AttnArgs aa;
   aa.n_q_heads = m.n_q_heads; aa.n_kv_heads = m.n_kv_heads; aa.head_dim = m.head_dim; aa.layer = layer;
   aa.causal = causal ? 1 : 0; aa.chunk = p.chunk; aa.n_splits = p.n_splits; aa.scale = 1.0f / sqrtf((float)m.head_dim);
@@ -1047,7 +1094,7 @@ void Engine<T>::attention(const dflash_dims& m, const T* pool, int layer, const 
   {
     // algorithmic bytes: every cached K and V row of this layer once (upper bound from the host hint)
     ProfScope prof(c, st, DFLASH_PROF_ATTN, (double)S * max_tokens * 2 * m.n_kv_heads * m.head_dim * sizeof(T));
-    if (!attn_mfma_launch<T>(st, ws<T>(c->ws.q), pool, geom(b), aa, S, part_o, part_ml, c->attn_wide_min_chunk))
+    if (!attn_mfma_launch<T>(st, ws<T>(c->ws.q), pool, geom(b), aa, S, part_o, part_ml, c->k.attn_wide_min_chunk))
       hipLaunchKernelGGL(attn_partial_simple_kernel<T>, dim3(p.n_splits, m.n_kv_heads, S), dim3(256), 0, st, ws<T>(c->ws.q), pool,
                          geom(b), aa, part_o, part_ml);
     check();
@@ -1143,9 +1190,12 @@ int check_batch(dflash_ctx* ctx, const dflash_batch* b) {
   if (!b->seq_lens || !b->block_table || !b->anchor) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: null pointer");
   if (b->n_seqs < 0 || b->n_seqs > ctx->rt.max_seqs) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: n_seqs %d outside [0,%d]", b->n_seqs, ctx->rt.max_seqs);
   if (b->max_seq_len < 0) return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: negative max_seq_len");
-  if ((int64_t)b->max_seq_len + ctx->rt.block_size > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE)
+  if (b->block_size != 0 && (b->block_size < 2 || b->block_size > ctx->rt.block_size))
+    return CTX_FAIL(ctx, DFLASH_EINVAL, "batch: block_size %d outside [2,%d] (0 = the context's)", b->block_size, ctx->rt.block_size);
+  const int blk = b->block_size > 0 ? b->block_size : ctx->rt.block_size;
+  if ((int64_t)b->max_seq_len + blk > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE)
     return CTX_FAIL(ctx, DFLASH_ECAPACITY, "batch: max_seq_len %d + block %d exceeds the %d tokens a block-table row covers", b->max_seq_len,
-                    ctx->rt.block_size, ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
+                    blk, ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
   return DFLASH_OK;
 }
 
@@ -1170,16 +1220,6 @@ int timed(hipStream_t st, float* ms, F&& enqueue) {
 }
 }  // namespace
 
-namespace {
-template <int NR, int NF, int NM>
-void launch_lds_mix(hipStream_t st, int fill, const u32x4* in, int iters) {
-  if (fill == 0) hipLaunchKernelGGL((probe_lds_mix_kernel<NR, 0, NM, 0>), dim3(512), dim3(256), 0, st, in, iters);
-  else if (fill == 1) hipLaunchKernelGGL((probe_lds_mix_kernel<NR, NF, NM, 1>), dim3(512), dim3(256), 0, st, in, iters);
-  else if (fill == 2) hipLaunchKernelGGL((probe_lds_mix_kernel<NR, NF, NM, 2>), dim3(512), dim3(256), 0, st, in, iters);
-  else hipLaunchKernelGGL((probe_lds_mix_kernel<NR, NF, NM, 3>), dim3(512), dim3(256), 0, st, in, iters);
-}
-}  // namespace
-
 // =====================================================================================================
 extern "C" {
 
@@ -1197,7 +1237,7 @@ size_t dflash_kv_pool_bytes(const dflash_dims* m, int32_t n_pages) {
 }
 size_t dflash_workspace_bytes(const dflash_dims* target, const dflash_dims* draft, const dflash_runtime* rt) {
   if (check_dims(target, "target") || check_dims(draft, "draft") || check_runtime(target, draft, rt)) return 0;
-  return workspace_layout(*target, *draft, *rt).total;
+  return workspace_layout(*target, *draft, *rt, read_knobs()).total;
 }
 
 int dflash_pack_target_head(const dflash_dims* target, const void* embed, const void* lm_head, const float* final_gain, void* blob,
@@ -1264,7 +1304,8 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
       ((uintptr_t)target_blob & 255) || ((uintptr_t)draft_blob & 255))
     return fail(nullptr, DFLASH_EINVAL, "create: buffers must be 256-byte aligned");
   if ((draft->n_layers * 2 * draft->n_kv_heads * draft->head_dim) % 16) return fail(nullptr, DFLASH_EINVAL, "draft K/V width must be a multiple of 16");
-  const Workspace ws = workspace_layout(*target, *draft, *rt);
+  const Knobs knobs = read_knobs();
+  const Workspace ws = workspace_layout(*target, *draft, *rt, knobs);
   if (rt->workspace_bytes < ws.total) return fail(nullptr, DFLASH_EWORKSPACE, "create: workspace has %zu bytes, %zu needed", rt->workspace_bytes, ws.total);
   dflash_ctx* c = new (std::nothrow) dflash_ctx;
   if (!c) return fail(nullptr, DFLASH_EINVAL, "create: out of host memory");
@@ -1274,15 +1315,7 @@ int dflash_create(const dflash_dims* target, const void* target_blob, const dfla
   c->ws = ws;
   c->tblob = (const char*)target_blob; c->dblob = (const char*)draft_blob; c->wsp = (char*)rt->workspace;
   c->err[0] = 0;
-  c->tile_force = env_int("DFLASH_GEMM_TILE", 0);
-  c->wm_force = env_int("DFLASH_GEMM_WM", 0);
-  c->lm_stats = env_int("DFLASH_LM_STATS", 1) == 1;
-  c->ks_force = env_int("DFLASH_GEMM_KS", 0);
-  c->attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
-  c->fuse = env_int("DFLASH_FUSE", 1);   // 1, 2 as above; any other value: off
-  if (c->fuse != 1 && c->fuse != 2) c->fuse = 0;
-  c->resid_nw = env_int("DFLASH_RESID_NW", 4);
-  c->resid_u = env_int("DFLASH_RESID_U", 8);
+  c->k = knobs;
   if (hipMemset(c->wsp + ws.status, 0, 256) != hipSuccess) {
     delete c;
     return fail(nullptr, DFLASH_EHIP, "create: cannot clear the device status word");
@@ -1344,24 +1377,6 @@ int dflash_probe_mfma(int32_t shape, int32_t workgroups, int32_t iters, float* m
   return rc;
 }
 
-int dflash_probe_lds_mix(const void* buf, int32_t mix, int32_t fill, int32_t iters, float* ms, double* flops, void* stream) {
-  if (!buf || !ms || !flops || mix < 0 || mix > 3 || fill < 0 || fill > 3 || iters < 1)
-    return fail(nullptr, DFLASH_EINVAL, "probe_lds_mix: need a 32 KB buffer, outputs, mix 0..3, fill 0..2 and iters >= 1");
-  hipStream_t st = (hipStream_t)stream;
-  const u32x4* in = reinterpret_cast<const u32x4*>(buf);
-  static const int mfmas[4] = {48, 32, 24, 64};
-  const int rc = timed(st, ms, [&] {
-    switch (mix) {
-      case 0: launch_lds_mix<14, 7, 48>(st, fill, in, iters); break;   // 192 x 128 tile
-      case 1: launch_lds_mix<12, 6, 32>(st, fill, in, iters); break;   // 128 x 128 and 256 x 64
-      case 2: launch_lds_mix<10, 5, 24>(st, fill, in, iters); break;   // 192 x 64
-      default: launch_lds_mix<16, 8, 64>(st, fill, in, iters); break;  // 256 x 128
-    }
-  });
-  *flops = 512.0 * 4 * iters * mfmas[mix] * (2.0 * 16 * 16 * 32);
-  return rc;
-}
-
 const char* dflash_last_error(const dflash_ctx* ctx) { return ctx ? ctx->err : g_err; }
 
 int dflash_device_status(dflash_ctx* ctx, void* stream) {
@@ -1371,7 +1386,7 @@ int dflash_device_status(dflash_ctx* ctx, void* stream) {
   if (hipMemcpy(&v, ctx->wsp + ctx->ws.status, 4, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "status read failed");
   if (v) {
     if (hipMemset(ctx->wsp + ctx->ws.status, 0, 4) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "status clear failed");
-    return CTX_FAIL(ctx, DFLASH_ECAPACITY, "device: a row addressed a page outside the block table / pool, or a token id outside the vocabulary");
+    return CTX_FAIL(ctx, DFLASH_ECAPACITY, "device: a row addressed a page outside the block table / pool, a token id was outside the vocabulary, or a sequence was longer than the batch's max_seq_len");
   }
   return DFLASH_OK;
 }
@@ -1379,8 +1394,8 @@ int dflash_device_status(dflash_ctx* ctx, void* stream) {
 int dflash_moe_stats(dflash_ctx* ctx, void* stream, int64_t* out) {
   if (!ctx || !out) return fail(ctx ? ctx->err : nullptr, DFLASH_EINVAL, "moe_stats: null argument");
   if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "stream synchronise failed");
-  if (hipMemcpy(out, ctx->wsp + ctx->ws.status + 64, 32, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics read failed");
-  if (hipMemset(ctx->wsp + ctx->ws.status + 64, 0, 32) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics clear failed");
+  if (hipMemcpy(out, ctx->wsp + ctx->ws.status + 64, 40, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics read failed");
+  if (hipMemset(ctx->wsp + ctx->ws.status + 64, 0, 40) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics clear failed");
   return DFLASH_OK;
 }
 

@@ -15,7 +15,6 @@
 // Ring variant (NS >= 3): the k tiles arrive by direct-to-LDS loads, see the comment at the loop.  It is used where
 // NS slots fit next to a second workgroup on the CU (128 x 128 and the 64-row tiles) and for the 128-row tiles of
 // an unsplit GEMM whose workgroups each have a CU to themselves.
-// (The probe kernel probe_lds_mix_kernel runs the per-k-tile instruction mix of these loops in isolation.)
 //
 // Workgroup order: consecutive workgroup ids go to different XCDs (round-robin dispatch), so id = 8*j + x
 // is mapped to weight band block 8*(j / m_blocks) + x and activation block j % m_blocks: the workgroups that
@@ -156,7 +155,12 @@ __global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void g
       for (int i = 0; i < PER; ++i) {
         const u32x4* src = g_base[i] + g_off[i] + (size_t)kt * g_step[i];
         const unsigned dst = __builtin_amdgcn_readfirstlane(lds_base + (unsigned)((slot * FR + wave * PER + i) * 1024));
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(src) : "memory");
+        // m0 carries the LDS address; whatever the compiler keeps in it is put back, so the statement clobbers nothing
+        unsigned keep_m0;
+        asm volatile("s_mov_b32 %0, m0\n\ts_mov_b32 m0, %1\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %2, off\n\ts_nop 0\n\ts_mov_b32 m0, %0"
+                     : "=&s"(keep_m0)
+                     : "s"(dst), "v"(src)
+                     : "memory");
       }
     };
 #pragma unroll

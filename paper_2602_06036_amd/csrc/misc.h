@@ -21,7 +21,8 @@ struct RopeTab {
   int hd;
 };
 
-// h[m, :] = float(E[tokens[m], :]); ids outside the vocabulary raise the status flag and read row 0.
+// h[m, :] = float(E[tokens[m], :]); ids outside the vocabulary raise the status flag and read row 0; so does a sequence
+// longer than the host's hint.
 // The first two wavefronts also write the row's entries of up to two rotary tables.
 // With `fuse.a_out` the row is also handed on as the first layer's GEMM operand with the RMSNorm deferred (see
 // gemm_resid.h): a_out[m, :] = h * gain, ssq[m] = sum of squares of the row (one piece per row).
@@ -34,9 +35,12 @@ struct EmbedFuse {
 template <typename T>
 __global__ __launch_bounds__(256) void embed_kernel(const T* __restrict__ E, const int32_t* __restrict__ tokens,
                                                     float* __restrict__ h, int D, int vocab, int32_t* status,
-                                                    const int32_t* __restrict__ seq_lens, int B, RopeTab t0, RopeTab t1,
+                                                    const int32_t* __restrict__ seq_lens, int B, int len_hint, RopeTab t0, RopeTab t1,
                                                     EmbedFuse fuse = EmbedFuse{}) {
   const int m = blockIdx.x;
+  // the host sized the attention launches of this call for sequences of at most len_hint committed tokens: a longer
+  // one would have its last keys left out, so it is reported
+  if (threadIdx.x == 0 && seq_lens[m / B] > len_hint) atomicOr(status, DF_STATUS_CAPACITY);
   {
     const int w = threadIdx.x >> 6, lane = threadIdx.x & 63;
     const RopeTab rt = w == 0 ? t0 : t1;
@@ -585,66 +589,4 @@ __global__ __launch_bounds__(256) void probe_mfma32_kernel(int iters) {
 #pragma unroll
     for (int e = 0; e < 16; ++e) s += acc[i][e];
   if (s == 12345.678f) g_probe_sink = 1u;   // keeps the MFMAs alive
-}
-
-// Instruction mix of one k tile of the LDS-staged GEMM, per wavefront: NR fragment reads (1 KB per wavefront each),
-// NF fragment fills and NM MFMAs, one workgroup barrier per round, two workgroups of 4 wavefronts per CU.
-// FILL 0: no fills; 1: ds_write_b128 from registers; 2: global_load_lds_dwordx4 (straight from global memory, here
-// L2 hits, with one round of loads left in flight); 3: the same loads issued before the reads.  Otherwise the reads
-// are issued first, then the fills, then the MFMAs;
-// the fragments read in one round are consumed in the next (software pipeline pinned with scheduling barriers).
-template <int NR, int NF, int NM, int FILL>
-__global__ __launch_bounds__(256, 2) void probe_lds_mix_kernel(const u32x4* __restrict__ in, int iters) {
-  __shared__ u32x4 lds[32][64];
-  const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
-  for (int f = wave; f < 32; f += 4) lds[f][lane] = in[f * 64 + lane];
-  __syncthreads();
-  const u32x4 a = in[threadIdx.x], b = in[256 + threadIdx.x];
-  constexpr int NA = NM < 16 ? NM : 16;
-  f32x4 acc[NA];
-#pragma unroll
-  for (int i = 0; i < NA; ++i) acc[i] = (f32x4){0.f, 0.f, 0.f, 0.f};
-  u32x4 x = {0u, 0u, 0u, 0u};
-  const unsigned lbase = (unsigned)(size_t)&lds[0][lane];   // LDS byte address of this lane's 16 bytes in fragment 0
-  const unsigned wbase = (unsigned)(size_t)&lds[0][0];
-  u32x4 r[NR];
-#pragma unroll
-  for (int i = 0; i < NR; ++i) r[i] = (u32x4){0u, 0u, 0u, 0u};
-  for (int it = 0; it < iters; ++it) {
-    asm volatile("s_waitcnt lgkmcnt(0)" ::: "memory");
-    __builtin_amdgcn_s_barrier();
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < NR; ++i) { x[0] ^= r[i][0]; x[1] ^= r[i][1]; x[2] ^= r[i][2]; x[3] ^= r[i][3]; }
-    __builtin_amdgcn_sched_barrier(0);
-    auto reads = [&] {
-#pragma unroll
-      for (int i = 0; i < NR; ++i)
-        asm volatile("ds_read_b128 %0, %1" : "=v"(r[i]) : "v"(lbase + (((i + wave * 7 + it) & 31) << 10)) : "memory");
-    };
-    if (FILL != 3) reads();
-#pragma unroll
-    for (int i = 0; i < NF; ++i) {
-      if (FILL >= 2) {
-        const unsigned dst = __builtin_amdgcn_readfirstlane(wbase + (((i + wave * 8) & 31) << 10));
-        asm volatile("s_mov_b32 m0, %0\n\ts_nop 0\n\tglobal_load_lds_dwordx4 %1, off" ::"s"(dst), "v"(in + ((i + it) & 31) * 64 + lane) : "memory");
-      } else if (FILL == 1) {
-        asm volatile("ds_write_b128 %0, %1" ::"v"(lbase + (((i + wave * 8) & 31) << 10)), "v"(x) : "memory");
-      }
-    }
-    if (FILL == 3) reads();
-    if (FILL >= 2 && NF > 0) asm volatile("s_waitcnt vmcnt(%0)" ::"n"(NF) : "memory");
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int i = 0; i < NM; ++i)
-      acc[i % NA] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, a), __builtin_bit_cast(bf16x8, b), acc[i % NA], 0, 0, 0);
-    __builtin_amdgcn_sched_barrier(0);
-  }
-  asm volatile("s_waitcnt vmcnt(0) lgkmcnt(0)" ::: "memory");
-#pragma unroll
-  for (int i = 0; i < NR; ++i) x[0] ^= r[i][0];
-  float s = 0.f;
-#pragma unroll
-  for (int i = 0; i < NA; ++i) s += acc[i][0] + acc[i][1] + acc[i][2] + acc[i][3];
-  if (s == 12345.678f && x[0] == 0x12345677u) g_probe_sink = x[1] ^ x[2] ^ x[3];   // keeps the work alive; practically never true
 }

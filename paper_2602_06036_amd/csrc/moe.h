@@ -25,7 +25,7 @@ struct MoeRoute {
   int32_t* row_of;       // [n_pos_max] expert-sorted list: token row behind each position, -1 = padding
   int4* items;           // [max_items] (expert, first band, end band, 0), expert = -1: unused
   int max_items;
-  unsigned long long* counters;   // [4] running totals: routing launches, experts reached, 16-row bands, work items (statistics)
+  unsigned long long* counters;   // [5] running totals: routing launches, experts reached, 16-row bands, work items; [4] = bands per work item of the last launch (statistics)
   int32_t* n_bands_out;           // [1] bands of the list this launch built
 };
 
@@ -182,6 +182,7 @@ __global__ __launch_bounds__(1024) void moe_route_kernel(MoeRoute a) {
     a.counters[1] += (unsigned long long)n_used;
     a.counters[2] += (unsigned long long)n_bands;
     a.counters[3] += (unsigned long long)n_items;
+    a.counters[4] = (unsigned long long)a.MT;   // not a total: the bands per work item of this launch
   }
 }
 

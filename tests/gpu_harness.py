@@ -65,8 +65,8 @@ class GpuModel:
         self.logits_d = torch.zeros((self.S, self.Bk, V), dtype=torch.float32, device=self.dev)
         self.logits_t = torch.zeros_like(self.logits_d)
 
-    def batch(self):
-        return self.e.batch(self.seq_lens, self.block_table, self.anchor, int(self.host_lens.max()))
+    def batch(self, block: int = 0):
+        return self.e.batch(self.seq_lens, self.block_table, self.anchor, int(self.host_lens.max()), block)
 
     # ---- prefill by chunked verification with forced commits ---------------------------------------
     def prefill(self, prompts: Sequence[np.ndarray]) -> np.ndarray:
@@ -129,31 +129,43 @@ class GpuModel:
 
     # ---- one speculative step --------------------------------------------------------------------------
     def step(self, proposals: Optional[np.ndarray] = None, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None,
-             key: int = 0, want_logits: bool = True) -> Dict[str, np.ndarray]:
-        b = self.batch()
+             key: int = 0, want_logits: bool = True, block: int = 0) -> Dict[str, np.ndarray]:
+        """block: rows per sequence of this step when it is to differ from the context's block size (dflash_batch::block_size);
+        the step's [S, block] arrays are then separate tensors of that shape."""
+        b = self.batch(block)
+        if block and block != self.Bk:
+            V = self.w.target.vocab
+            draft_tokens = torch.zeros((self.S, block), dtype=torch.int32, device=self.dev)
+            tgt_argmax, out_tokens = torch.zeros_like(draft_tokens), torch.zeros_like(draft_tokens)
+            kv_slots = torch.zeros((self.S, block), dtype=torch.int64, device=self.dev)
+            logits_d = torch.zeros((self.S, block, V), dtype=torch.float32, device=self.dev) if want_logits else None
+            logits_t = torch.zeros_like(logits_d) if want_logits else None
+        else:
+            draft_tokens, tgt_argmax, out_tokens, kv_slots = self.draft_tokens, self.tgt_argmax, self.out_tokens, self.kv_slots
+            logits_d, logits_t = (self.logits_d, self.logits_t) if want_logits else (None, None)
         rng = torch.tensor([key], dtype=torch.int64, device=self.dev) if temperature > 0 else None
-        dfl.dflash_draft_block(self.e, b, self.draft_tokens, temperature, rng, self.logits_d if want_logits else None)
-        drafted = self.draft_tokens.cpu().numpy().copy()
+        dfl.dflash_draft_block(self.e, b, draft_tokens, temperature, rng, logits_d)
+        drafted = draft_tokens.cpu().numpy().copy()
         if proposals is not None:                 # entries < 0 keep the GPU's own draft for that slot
             blk = drafted.copy()
             blk[:, 1:] = np.where(proposals >= 0, proposals, drafted[:, 1:])
-            self.draft_tokens.copy_(torch.from_numpy(blk).to(self.dev))
-        dfl.dflash_verify(self.e, b, self.draft_tokens, self.tgt_argmax, self.logits_t if want_logits else None)
+            draft_tokens.copy_(torch.from_numpy(blk).to(self.dev))
+        dfl.dflash_verify(self.e, b, draft_tokens, tgt_argmax, logits_t)
         u = torch.from_numpy(np.ascontiguousarray(uniforms, dtype=np.float32)).to(self.dev) if uniforms is not None else None
-        dfl.dflash_accept(self.e, b, self.draft_tokens, self.tgt_argmax, self.accept_len, self.out_tokens, temperature, u, rng)
+        dfl.dflash_accept(self.e, b, draft_tokens, tgt_argmax, self.accept_len, out_tokens, temperature, u, rng)
         lens_before = self.host_lens.copy()
-        dfl.dflash_kv_commit(self.e, b, self.accept_len, self.out_tokens, self.kv_slots)
+        dfl.dflash_kv_commit(self.e, b, self.accept_len, out_tokens, kv_slots)
         torch.cuda.synchronize(self.dev)
         self.e.device_status()
         a = self.accept_len.cpu().numpy().copy()
         self.host_lens = lens_before + a + 1
         assert np.array_equal(self.seq_lens.cpu().numpy(), self.host_lens)
-        out = dict(drafted=drafted, block=self.draft_tokens.cpu().numpy().copy(), tgt_argmax=self.tgt_argmax.cpu().numpy().copy(),
-                   accept_len=a, out_tokens=self.out_tokens.cpu().numpy().copy(), kv_slots=self.kv_slots.cpu().numpy().copy(),
+        out = dict(drafted=drafted, block=draft_tokens.cpu().numpy().copy(), tgt_argmax=tgt_argmax.cpu().numpy().copy(),
+                   accept_len=a, out_tokens=out_tokens.cpu().numpy().copy(), kv_slots=kv_slots.cpu().numpy().copy(),
                    lens_before=lens_before, anchor=self.anchor.cpu().numpy().copy())
         if want_logits:
-            out["logits_d"] = self.logits_d.cpu().numpy().copy()
-            out["logits_t"] = self.logits_t.cpu().numpy().copy()
+            out["logits_d"] = logits_d.cpu().numpy().copy()
+            out["logits_t"] = logits_t.cpu().numpy().copy()
         return out
 
     # ---- cache state in canonical form -----------------------------------------------------------------------
@@ -206,9 +218,9 @@ class GpuModel:
                         dfl.dflash_kv_write(self.e, self.batch(), pid, l, s, 0, kv[0].contiguous(), kv[1].contiguous())
             torch.cuda.synchronize(self.dev)
 
-    def expected_slots(self, lens_before: np.ndarray, accept_len: np.ndarray) -> np.ndarray:
+    def expected_slots(self, lens_before: np.ndarray, accept_len: np.ndarray, block: int = 0) -> np.ndarray:
         """page*16 + offset from the page table (the definition of a KV slot id), -1 past the accepted prefix."""
-        out = -np.ones((self.S, self.Bk), dtype=np.int64)
+        out = -np.ones((self.S, block or self.Bk), dtype=np.int64)
         for s in range(self.S):
             for j in range(int(accept_len[s]) + 1):
                 pos = int(lens_before[s]) + j

@@ -32,7 +32,7 @@ def test_every_declared_symbol_is_exported(B):
 def test_struct_sizes_match_the_header(B):
     assert C.sizeof(B.Dims) == 14 * 4
     assert C.sizeof(B.LayerWeights) == 12 * 8
-    assert C.sizeof(B.Batch) == 8 + 3 * 8
+    assert C.sizeof(B.Batch) == 8 + 3 * 8 + 8          # block_size and the padding behind it
     assert C.sizeof(B.Runtime) == 4 * 4 + 4 + 8 * 4 + 4 + 4 * 8   # incl. no padding surprises
     
 

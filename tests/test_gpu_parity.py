@@ -80,16 +80,17 @@ class Lockstep:
             self.g.load_state(self.states)
         return first, got, mism
 
-    def step(self, plan=None, temperature=0.0, step_idx=0, key=0):
+    def step(self, plan=None, temperature=0.0, step_idx=0, key=0, block=0):
+        """block: this step's block size when it differs from the workload's (both sides then run the step with it)."""
         w, g = self.w, self.g
-        Bk = w.block_size
+        Bk = block or w.block_size
         proposals = None
         if plan is not None:      # k correct continuation tokens (from the oracle target), then a wrong one
             proposals = np.zeros((self.S, Bk - 1), dtype=np.int32)
             for s, st in enumerate(self.states):
-                proposals[s] = self._true_continuation(st, int(plan[s]))
-        uniforms = si.make_uniforms(replace(w, n_seqs=self.S), step_idx) if temperature > 0 else None
-        out = g.step(proposals, temperature, uniforms, key)
+                proposals[s] = self._true_continuation(st, int(plan[s]), Bk)
+        uniforms = si.make_uniforms(replace(w, n_seqs=self.S, block_size=Bk), step_idx) if temperature > 0 else None
+        out = g.step(proposals, temperature, uniforms, key, block=block)
         res = []
         diverged = False
         for s, st in enumerate(self.states):
@@ -138,16 +139,16 @@ class Lockstep:
                 assert out["anchor"][s] == r["emitted"][-1]
             self.emitted[s] += r["emitted"]
         # KV slot ids are pure page-table arithmetic: always bit-exact given the GPU's own accept lengths
-        assert np.array_equal(out["kv_slots"], g.expected_slots(out["lens_before"], out["accept_len"]))
+        assert np.array_equal(out["kv_slots"], g.expected_slots(out["lens_before"], out["accept_len"], Bk))
         if diverged:
             self.stats["reseeds"] += 1
             g.load_state(self.states)
         return out, res
 
-    def _true_continuation(self, st, k):
+    def _true_continuation(self, st, k, Bk=None):
         """B-1 proposals: the target's own greedy continuation after the anchor for k slots, then wrong."""
         w = self.w
-        Bk = w.block_size
+        Bk = Bk or w.block_size
         kv = O.KVList(w.target.n_layers, w.target.n_kv_heads, w.target.head_dim, st.n + Bk + 1)
         for l in range(w.target.n_layers):
             kv.k[l][: st.n] = st.kv.k[l][: st.n]
@@ -358,6 +359,29 @@ def test_small_bf16_other_block_sizes(block):
     assert ls.stats["reseeds"] <= 1
 
 
+def test_block_size_chosen_per_step():
+    """Section 5.5 discusses smaller blocks where verification is compute-bound: the block size is a field of the batch, so
+    one context (created for B = 16) runs steps of 16, 8, 5, 16, 2 and 10 rows per sequence on the same caches; every step
+    against the oracle's step of that block size, accept lengths forced through the whole range of each block."""
+    w = si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=150, seed=53)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=150 + 8 * 16)
+    ls.prefill()
+    for i, (block, plan) in enumerate([(16, [15, 0, 9]), (8, [7, 3, 0]), (5, None), (16, None), (2, [1, 0, 1]), (10, [9, 9, 2]), (8, [7, 7, 7])]):
+        out, res = ls.step(plan=plan, step_idx=i, block=block)
+        assert out["block"].shape == (3, block)
+        if plan is not None and ls.stats["reseeds"] == 0:
+            assert list(out["accept_len"]) == plan
+    ls.check_cache([0, 7], [0, 1])
+    print("per-step block size stats", ls.stats)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+    from paper_2602_06036_amd import binding as B
+    with pytest.raises(B.DFlashError) as ei:       # larger than the context's block size: refused on the host
+        ls.g.step(block=17)
+    assert ei.value.code == B.DFLASH_EINVAL
+
+
 @pytest.mark.parametrize("n_seqs,block,fuse,temperature", [(1, 16, "1", 0.0), (1, 16, "2", 0.0), (1, 16, "3", 0.0), (2, 8, "1", 0.0),
                                                           (2, 8, "2", 0.0), (1, 10, "1", 0.0), (1, 10, "2", 0.0), (1, 16, "1", 0.7),
                                                           (1, 16, "2", 0.7), (3, 5, "2", 0.0)])
@@ -484,8 +508,13 @@ def test_small_moe_target_with_128_row_expert_items(n_seqs, top_k, seed, monkeyp
     ls.prefill()
     assert min(ls.route_gaps) > ROUTE_CLEAR
     ls.check_cache([0, 3], [0, 1])
+    ls.g.e.moe_stats()
     for i, plan in enumerate([None, list(np.arange(n_seqs) % 16)]):
         ls.step(plan=plan, step_idx=i)
+    # the forced path really ran: 8 bands per work item (the context read the knob when it was created, whatever
+    # other tests of this process set before), hence one work item per reached expert
+    launches, reached, bands, items, per_item = ls.g.e.moe_stats()
+    assert per_item == 8 and launches == 2 * w.target.n_layers and items == reached and bands >= reached, (launches, reached, bands, items, per_item)
     ls.check_cache([1, 3], [1])
     assert ls.stats["route_ties"] <= 2 and ls.stats["reseeds"] <= 1 + ls.stats["route_ties"]
 
@@ -718,3 +747,18 @@ def test_device_status_reports_a_sequence_that_outgrew_its_pages():
         g.e.device_status()
     assert ei.value.code == B.DFLASH_ECAPACITY
     g.e.device_status()          # the flag is cleared by the read
+    # within the pages, but longer than the hint the launches were sized for: keys past the hint may be left out of
+    # attention, which must not pass silently
+    g.seq_lens.fill_(20)
+    for call in ("draft", "verify"):
+        b = g.e.batch(g.seq_lens, g.block_table, g.anchor, 4)
+        if call == "draft":
+            dfl.dflash_draft_block(g.e, b, g.draft_tokens, 0.0, None)
+        else:
+            dfl.dflash_verify(g.e, b, g.draft_tokens, g.tgt_argmax)
+        with pytest.raises(B.DFlashError) as ei:
+            g.e.device_status()
+        assert ei.value.code == B.DFLASH_ECAPACITY, call
+    b = g.e.batch(g.seq_lens, g.block_table, g.anchor, 20)      # an honest hint: no flag
+    dfl.dflash_verify(g.e, b, g.draft_tokens, g.tgt_argmax)
+    g.e.device_status()
