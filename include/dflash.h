@@ -190,6 +190,21 @@ int dflash_accept(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *dra
 int dflash_kv_commit(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *accept_len,
                      const int32_t *out_tokens, int64_t *kv_slots_out, void *stream);
 
+/* Prefill (Section 4.1: "Given a prompt, the target model first performs a standard prefill pass to generate the first
+ * token"; the hidden features of the tapped layers are taken for every prompt token and become the draft's context).
+ * prompt_lens (host) [S]: new tokens of each sequence (0 = none); tokens (device): those tokens of all sequences
+ * concatenated in sequence order.  batch->seq_lens[s] tokens are already cached (0 for a fresh prompt; more for a prompt
+ * that arrives in pieces or shares a cached prefix).  The new tokens run through the target causally, as passes of up to
+ * max_seqs * B rows (every block of B tokens of every prompt is one row block of a verification-shaped pass): their K/V
+ * rows go into the target pool, the tapped hidden states of ALL rows are fused and projected into the draft pool
+ * (as dflash_kv_commit does for a block), the LM head runs on each prompt's last row only.  Afterwards
+ * seq_lens[s] += prompt_lens[s] and, for every sequence with new tokens, anchor[s] = first_tokens[s] (device, nullable)
+ * = the greedy token after its last prompt token -- the state the first dflash_draft_block call starts from.
+ * The block table must cover seq_lens[s] + prompt_lens[s] rounded up to whole blocks (the padding rows of a prompt's last
+ * block are written too, invisibly); DFLASH_ECAPACITY otherwise.  prompt_lens is read before the call returns. */
+int dflash_prefill(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *tokens, const int32_t *prompt_lens,
+                   int32_t *first_tokens, void *stream);
+
 /* ---- per-launch timing (benchmarks) -------------------------------------------------------------
  * While enabled, every GEMM and attention launch is bracketed by a pair of HIP events on the caller's
  * stream (this slows the step down: time whole steps with profiling off).  dflash_profile_read

@@ -418,16 +418,23 @@ def _append_context(Wd, md, st: SeqState, taps: np.ndarray, start: int, rnd: "Ro
     st.ctx.n = start + taps.shape[0]
 
 
-def prefill(Wt, Wd, mt, md, tap_layers, prompt: Sequence[int], st: SeqState,
-            rnd: "Rounding" = identity) -> int:
+def prefill_with_logits(Wt, Wd, mt, md, tap_layers, prompt: Sequence[int], st: SeqState,
+                        rnd: "Rounding" = identity) -> Tuple[int, np.ndarray]:
     """Standard prefill (Section 4.1): target over the prompt, taps of every prompt token fused
-    and projected into the draft's context K/V; the first generated token becomes the anchor."""
+    and projected into the draft's context K/V; the first generated token becomes the anchor.
+    Returns (that token, the logits row it is the argmax of)."""
     T = len(prompt)
     logits, taps = target_forward_sequence(Wt, mt, prompt, st.kv, tap_layers, rnd, logit_rows=[T - 1])
     _append_context(Wd, md, st, taps, 0, rnd)
     st.n = T
     st.anchor = int(np.argmax(logits[0]))
-    return st.anchor
+    return st.anchor, logits[0]
+
+
+def prefill(Wt, Wd, mt, md, tap_layers, prompt: Sequence[int], st: SeqState,
+            rnd: "Rounding" = identity) -> int:
+    """prefill_with_logits without the logits."""
+    return prefill_with_logits(Wt, Wd, mt, md, tap_layers, prompt, st, rnd)[0]
 
 
 def spec_step(Wt, Wd, mt, md, tap_layers, st: SeqState, block_size: int, mask_id: int,

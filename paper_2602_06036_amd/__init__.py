@@ -3,4 +3,4 @@ plus a thin ctypes binding.  There is no CPU fallback: importing `binding` and c
 requires the built library libdflash.so."""
 from . import binding  # noqa: F401
 from .binding import (Engine, DFlashError, dflash_draft_block, dflash_verify, dflash_accept,  # noqa: F401
-                      dflash_kv_commit, dflash_kv_read, dflash_kv_write)
+                      dflash_kv_commit, dflash_prefill, dflash_kv_read, dflash_kv_write)

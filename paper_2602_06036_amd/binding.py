@@ -25,7 +25,7 @@ EXPORTS = [
     "dflash_pack_target_head", "dflash_pack_target_layer", "dflash_pack_draft_head", "dflash_pack_draft_layer",
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
-    "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats",
+    "dflash_prefill", "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats",
     "dflash_probe_hbm_read", "dflash_probe_mfma",
 ]
 
@@ -90,6 +90,7 @@ def lib() -> C.CDLL:
         l.dflash_verify.argtypes = [P, C.POINTER(Batch), P, P, P, P]
         l.dflash_accept.argtypes = [P, C.POINTER(Batch), P, P, F, P, P, P, P, P]
         l.dflash_kv_commit.argtypes = [P, C.POINTER(Batch), P, P, P, P]
+        l.dflash_prefill.argtypes = [P, C.POINTER(Batch), P, C.POINTER(C.c_int32), P, P]
         l.dflash_kv_read.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
         l.dflash_kv_write.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
         l.dflash_profile_enable.argtypes = [P, I]
@@ -254,6 +255,13 @@ def dflash_accept(e: Engine, batch: Batch, draft_tokens: torch.Tensor, tgt_argma
 def dflash_kv_commit(e: Engine, batch: Batch, accept_len: torch.Tensor, out_tokens: torch.Tensor,
                      kv_slots_out: Optional[torch.Tensor] = None):
     _check(e.l.dflash_kv_commit(e.ctx, C.byref(batch), _ptr(accept_len), _ptr(out_tokens), _ptr(kv_slots_out), _stream()), e.ctx)
+
+
+def dflash_prefill(e: Engine, batch: Batch, tokens: torch.Tensor, prompt_lens, first_tokens: Optional[torch.Tensor] = None):
+    """tokens: int32 device tensor, the new tokens of all sequences concatenated; prompt_lens: host ints, one per sequence."""
+    assert tokens.dtype == torch.int32 and tokens.is_contiguous() and int(tokens.numel()) == int(sum(prompt_lens))
+    lens = (C.c_int32 * len(prompt_lens))(*[int(x) for x in prompt_lens])
+    _check(e.l.dflash_prefill(e.ctx, C.byref(batch), _ptr(tokens), lens, _ptr(first_tokens), _stream()), e.ctx)
 
 
 def dflash_kv_read(e: Engine, batch: Batch, pool: int, layer: int, seq: int, start: int, count: int):

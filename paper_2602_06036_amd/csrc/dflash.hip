@@ -232,7 +232,7 @@ inline int arena_rows(int max_rows) { return std::max(1024, 4 * max_rows); }
 constexpr int ARGMAX_CHUNKS = 32;   // workgroups that share one vocabulary row in the argmax
 
 struct Workspace {
-  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, ssq, total;
+  size_t status, arena, h, a, q, o, act, taps, fuse, ht, logits_d, logits_t, part_o, part_ml, stats_p, stats_q, amax, lsep, rope_t, rope_d, ssq, pf_lens, pf_plens, pf_table, pf_tokens, pf_end_row, pf_end_seq, pf_first, pf_anchor, total;
   size_t moe_sel_e, moe_sel_w, moe_sel_pos, moe_row_of, moe_items, moe_a, moe_act, moe_y;   // routed-expert target only
 };
 Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dflash_runtime& rt, const Knobs& kn) {
@@ -284,6 +284,15 @@ Workspace workspace_layout(const dflash_dims& t, const dflash_dims& d, const dfl
   w.rope_t = take((size_t)M * (t.head_dim / 2) * 8);   // rotary tables of the call's rows (target, draft)
   w.rope_d = take((size_t)M * (d.head_dim / 2) * 8);
   w.ssq = take((size_t)M * (D / 16 + 1) * 4);          // pieces of the rows' sums of squares (deferred RMSNorm, few-row path)
+  // dflash_prefill: the prompts' lengths and the pseudo-sequence batch of a pass (see prefill_plan_kernel)
+  w.pf_lens = take((size_t)rt.max_seqs * 4);
+  w.pf_plens = take((size_t)rt.max_seqs * 4);
+  w.pf_table = take((size_t)rt.max_seqs * rt.max_pages_per_seq * 4);
+  w.pf_tokens = take((size_t)M * 4);
+  w.pf_end_row = take((size_t)rt.max_seqs * 4);
+  w.pf_end_seq = take((size_t)rt.max_seqs * 4);
+  w.pf_first = take((size_t)rt.max_seqs * 4);
+  w.pf_anchor = take((size_t)rt.max_seqs * 4);
   w.moe_sel_e = w.moe_sel_w = w.moe_sel_pos = w.moe_row_of = w.moe_items = w.moe_a = w.moe_act = w.moe_y = 0;
   if (t.n_experts) {
     const size_t mk = (size_t)M * t.top_k, np = moe_positions(t, M);
@@ -703,6 +712,17 @@ struct Engine {
   }
 
   int commit(const dflash_batch* b, const int32_t* accept_len, const int32_t* out_tokens, int64_t* kv_slots) {
+    const int S = b->n_seqs;
+    commit_project(b);
+    hipLaunchKernelGGL(commit_update_kernel, dim3((S + 63) / 64), dim3(64), 0, st, geom(b), b->seq_lens, b->anchor, accept_len,
+                       out_tokens, S, kv_slots);
+    check();
+    return hip_err ? DFLASH_EHIP : DFLASH_OK;
+  }
+
+  // H_t = RMSNorm(W_c [taps]) of the rows of the preceding verification pass, projected with every draft layer's W_K, W_V
+  // into the draft pool at the rows' positions (Appendix A.3)
+  void commit_project(const dflash_batch* b) {
     const int S = b->n_seqs, B = blk(b), M = S * B;
     const dflash_dims& d = c->d;
     const int D = d.d_model, kd = d.n_kv_heads * d.head_dim, nkv = d.n_layers * 2 * kd;
@@ -726,9 +746,78 @@ struct Engine {
                          geom(b), ra, kvs.ks, kvs.stride);
       check();
     }
-    hipLaunchKernelGGL(commit_update_kernel, dim3((S + 63) / 64), dim3(64), 0, st, geom(b), b->seq_lens, b->anchor, accept_len,
-                       out_tokens, S, kv_slots);
+  }
+
+  // Prefill of the prompts' new tokens as many-row passes of at most max_seqs pseudo-sequences (prefill_plan_kernel): the
+  // target's layers over all rows (K/V rows into the target pool, taps), the LM head on the last row of every prompt
+  // only, the taps of all rows fused and projected into the draft's context cache.  lens_host: new tokens per prompt.
+  int prefill(const dflash_batch* b, const int32_t* tokens, const int32_t* lens_host, int32_t* first_out) {
+    const int S = b->n_seqs, B = blk(b);
+    const dflash_dims& t = c->t;
+    int total_chunks = 0, max_len = 0;
+    for (int s = 0; s < S; ++s) {
+      total_chunks += (lens_host[s] + B - 1) / B;
+      max_len = std::max(max_len, lens_host[s]);
+    }
+    if (total_chunks == 0) return DFLASH_OK;
+    int32_t* d_lens = ws<int32_t>(c->ws.pf_lens);
+    if (hipMemcpyAsync(d_lens, lens_host, (size_t)S * 4, hipMemcpyHostToDevice, st) != hipSuccess) return CTX_FAIL(c, DFLASH_EHIP, "prefill: length upload failed");
+    for (int chunk0 = 0; chunk0 < total_chunks; chunk0 += c->rt.max_seqs) {
+      const int n = std::min(c->rt.max_seqs, total_chunks - chunk0), M = n * B;
+      // prompts whose last chunk lies in this pass (the host counts them from the same lengths as the kernel)
+      int n_end = 0, first = 0;
+      for (int s = 0; s < S; ++s) {
+        const int nc = (lens_host[s] + B - 1) / B;
+        if (nc > 0 && first + nc - 1 >= chunk0 && first + nc - 1 < chunk0 + n) ++n_end;
+        first += nc;
+      }
+      PrefillPlan pp;
+      pp.lens = d_lens; pp.seq_lens = b->seq_lens; pp.block_table = b->block_table; pp.tokens = tokens;
+      pp.S = S; pp.B = B; pp.mpps = c->rt.max_pages_per_seq; pp.chunk0 = chunk0; pp.n_chunks = n;
+      pp.p_lens = ws<int32_t>(c->ws.pf_plens); pp.p_table = ws<int32_t>(c->ws.pf_table); pp.p_tokens = ws<int32_t>(c->ws.pf_tokens);
+      pp.end_row = ws<int32_t>(c->ws.pf_end_row); pp.end_seq = ws<int32_t>(c->ws.pf_end_seq);
+      hipLaunchKernelGGL(prefill_plan_kernel, dim3(n), dim3(256), 0, st, pp);
+      check();
+      dflash_batch pb;
+      pb.n_seqs = n;
+      pb.max_seq_len = std::min(b->max_seq_len + max_len, c->rt.max_pages_per_seq * DFLASH_PAGE_SIZE - B);
+      pb.seq_lens = pp.p_lens; pb.block_table = pp.p_table; pb.anchor = ws<int32_t>(c->ws.pf_anchor);
+      pb.block_size = B;
+      hipLaunchKernelGGL(embed_kernel<T>, dim3(M), dim3(256), 0, st, reinterpret_cast<const T*>(c->tblob + c->tl.embed), pp.p_tokens,
+                         ws<float>(c->ws.h), t.d_model, t.vocab, status(), pb.seq_lens, B, pb.max_seq_len,
+                         RopeTab{ws<float2>(c->ws.rope_t), log((double)t.rope_theta), t.head_dim},
+                         RopeTab{ws<float2>(c->ws.rope_d), log((double)c->d.rope_theta), c->d.head_dim}, EmbedFuse{});
+      check();
+      int tap = 0;
+      for (int l = 0; l < t.n_layers; ++l) {
+        layer(t, c->tblob + c->tl.layer0 + c->tl.lo.end * l, c->tl.lo, reinterpret_cast<T*>(c->rt.target_kv_pool), l, &pb, true);
+        if (tap < c->rt.n_taps && c->rt.tap_layers[tap] == l) pending_tap = tap++;
+      }
+      if (n_end > 0 || pending_tap >= 0) norm_h(reinterpret_cast<const float*>(c->tblob + c->tl.gf), M, t.d_model, t.rms_eps);
+      pending = Slab{};
+      if (n_end > 0) {   // the first generated token of every prompt that ends here: LM head on those rows only
+        T* rows_a = ws<T>(c->ws.ht);   // free until the projection below
+        hipLaunchKernelGGL(gather_operand_rows_kernel<T>, dim3(n_end), dim3(256), 0, st, ws<T>(c->ws.a), pp.end_row, rows_a, t.d_model);
+        check();
+        float* logits = ws<float>(c->ws.logits_t);
+        EpiArgs ep{logits, t.vocab, 0, nullptr, 0};
+        ep.amax = ws<float2>(c->ws.amax);
+        ep.amax_B = 1;
+        lm_skip_store = true;
+        amax_parts = 0;
+        gemm(reinterpret_cast<const T*>(c->tblob + c->tl.lm), rows_a, n_end, t.vocab, t.d_model, EPI_STORE, ep, false);
+        lm_skip_store = false;
+        argmax(logits, t.vocab, n_end, 1, ws<int32_t>(c->ws.pf_first), 0, 0, 1.0f, (const uint64_t*)nullptr);
+        hipLaunchKernelGGL(prefill_first_kernel, dim3((n_end + 63) / 64), dim3(64), 0, st, ws<int32_t>(c->ws.pf_first), pp.end_seq, n_end, b->anchor,
+                           first_out);
+        check();
+      }
+      commit_project(&pb);
+    }
+    hipLaunchKernelGGL(prefill_advance_kernel, dim3((S + 63) / 64), dim3(64), 0, st, b->seq_lens, d_lens, S);
     check();
+    c->have_logits_t = c->have_logits_d = false;
+    c->stats_p_T = c->stats_q_T = 0.f;
     return hip_err ? DFLASH_EHIP : DFLASH_OK;
   }
 };
@@ -1442,6 +1531,25 @@ int dflash_kv_commit(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* 
   if (batch->n_seqs == 0) return DFLASH_OK;
   if (!accept_len || !out_tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "kv_commit: null pointer");
   return DISPATCH(ctx, commit(batch, accept_len, out_tokens, kv_slots_out));
+}
+
+int dflash_prefill(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* tokens, const int32_t* prompt_lens, int32_t* first_tokens,
+                   void* stream) {
+  int rc;
+  if ((rc = check_batch(ctx, batch))) return rc;
+  if (batch->n_seqs == 0) return DFLASH_OK;
+  if (!tokens || !prompt_lens) return CTX_FAIL(ctx, DFLASH_EINVAL, "prefill: null tokens or prompt_lens");
+  const int B = batch->block_size > 0 ? batch->block_size : ctx->rt.block_size;
+  int longest = 0;
+  for (int s = 0; s < batch->n_seqs; ++s) {
+    if (prompt_lens[s] < 0) return CTX_FAIL(ctx, DFLASH_EINVAL, "prefill: negative prompt length");
+    longest = std::max(longest, prompt_lens[s]);
+  }
+  // the last chunk of a prompt is padded to a whole block of rows, whose K/V rows are written too (invisible)
+  if ((int64_t)batch->max_seq_len + (longest + B - 1) / B * B > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE)
+    return CTX_FAIL(ctx, DFLASH_ECAPACITY, "prefill: max_seq_len %d + the longest prompt (%d, padded to whole blocks of %d) exceeds the %d tokens a block-table row covers",
+                    batch->max_seq_len, longest, B, ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
+  return DISPATCH(ctx, prefill(batch, tokens, prompt_lens, first_tokens));
 }
 
 static int kv_copy_checked(dflash_ctx* ctx, const dflash_batch* batch, int32_t pool, int32_t layer, int32_t seq, int32_t start, int32_t count,

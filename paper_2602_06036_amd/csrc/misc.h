@@ -590,3 +590,86 @@ __global__ __launch_bounds__(256) void probe_mfma32_kernel(int iters) {
     for (int e = 0; e < 16; ++e) s += acc[i][e];
   if (s == 12345.678f) g_probe_sink = 1u;   // keeps the MFMAs alive
 }
+
+// ---- prefill as a many-row pass (Section 4.1: the standard prefill gives the first token and the target's hidden
+// features of every prompt token) ------------------------------------------------------------------------------
+// The new tokens of all prompts are cut into chunks of B rows; chunk c (counted over all prompts, in order) becomes
+// pseudo-sequence c - chunk0 of one verification-shaped pass: committed length = the prompt's cached length + the
+// chunk's offset, block-table row = the prompt's.  Inside a layer every K/V row is in the pages before attention runs,
+// so the causal block attention of the chunks is a causal prefill.  One workgroup per pseudo-sequence.
+struct PrefillPlan {
+  const int32_t* lens;         // [S] new tokens per prompt (device copy of the host's array)
+  const int32_t* seq_lens;     // [S] tokens already cached
+  const int32_t* block_table;  // [S, mpps]
+  const int32_t* tokens;       // new tokens of all prompts, concatenated
+  int S, B, mpps, chunk0, n_chunks;
+  int32_t* p_lens;             // [n_chunks]
+  int32_t* p_table;            // [n_chunks, mpps]
+  int32_t* p_tokens;           // [n_chunks, B], zero-padded
+  int32_t* end_row;            // [.] row (in this pass) of the last token of every prompt that ends in this pass, in prompt order
+  int32_t* end_seq;            // [.] and that prompt's index
+};
+
+__global__ __launch_bounds__(256) void prefill_plan_kernel(PrefillPlan p) {
+  const int i = blockIdx.x, c = p.chunk0 + i;
+  __shared__ int sh[4];
+  if (threadIdx.x == 0) {
+    int first = 0, s = 0, n_end_before = 0;
+    for (; s < p.S; ++s) {
+      const int nc = (p.lens[s] + p.B - 1) / p.B;
+      if (c < first + nc) break;
+      // a prompt before ours whose last chunk lies in this pass takes an earlier place in the end list
+      if (nc > 0 && first + nc - 1 >= p.chunk0) ++n_end_before;
+      first += nc;
+    }
+    sh[0] = s;
+    sh[1] = (c - first) * p.B;       // offset of the chunk inside the prompt's new tokens
+    sh[2] = n_end_before;
+    int tok0 = 0;
+    for (int t = 0; t < s && t < p.S; ++t) tok0 += p.lens[t];
+    sh[3] = tok0;
+  }
+  __syncthreads();
+  const int s = sh[0], off = sh[1];
+  if (s >= p.S) return;              // cannot happen when the host counted the chunks from the same lengths
+  const int len = p.lens[s], rows = min(p.B, len - off);
+  for (int j = threadIdx.x; j < p.mpps; j += blockDim.x) p.p_table[(size_t)i * p.mpps + j] = p.block_table[(size_t)s * p.mpps + j];
+  for (int j = threadIdx.x; j < p.B; j += blockDim.x) p.p_tokens[(size_t)i * p.B + j] = j < rows ? p.tokens[sh[3] + off + j] : 0;
+  if (threadIdx.x == 0) {
+    p.p_lens[i] = p.seq_lens[s] + off;
+    if (off + rows == len) {
+      p.end_row[sh[2]] = i * p.B + rows - 1;
+      p.end_seq[sh[2]] = s;
+    }
+  }
+}
+
+// out row r (GEMM operand, row length K) = row rows[r] of `a`
+template <typename T>
+__global__ __launch_bounds__(256) void gather_operand_rows_kernel(const T* __restrict__ a, const int32_t* __restrict__ rows, T* __restrict__ out, int K) {
+  const int r = blockIdx.x, m = rows[r];
+  for (int k = threadIdx.x; k < K; k += blockDim.x) {
+    if constexpr (sizeof(T) == 2) {
+      const size_t src = Act<bf16_t>::index(m, k, K), dst = Act<bf16_t>::index(r, k, K);
+      out[dst] = a[src];
+      out[dst + 512] = a[src + 512];
+    } else {
+      out[(size_t)r * K + k] = a[(size_t)m * K + k];
+    }
+  }
+}
+
+// first generated token of the prompts that ended in a pass: anchor and (optionally) the caller's array
+__global__ void prefill_first_kernel(const int32_t* __restrict__ first, const int32_t* __restrict__ end_seq, int n_end, int32_t* anchor,
+                                     int32_t* first_out) {
+  const int r = blockIdx.x * blockDim.x + threadIdx.x;
+  if (r >= n_end) return;
+  const int s = end_seq[r];
+  anchor[s] = first[r];
+  if (first_out) first_out[s] = first[r];
+}
+
+__global__ void prefill_advance_kernel(int32_t* seq_lens, const int32_t* __restrict__ lens, int S) {
+  const int s = blockIdx.x * blockDim.x + threadIdx.x;
+  if (s < S) seq_lens[s] += lens[s];
+}

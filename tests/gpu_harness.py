@@ -127,6 +127,25 @@ class GpuModel:
         self.anchor.copy_(torch.from_numpy(first_tokens).to(dev))
         return first_tokens.copy()
 
+    def prefill_entry(self, prompts: Sequence[np.ndarray], pieces: int = 1) -> np.ndarray:
+        """Prefill through the library's own entry point (dflash_prefill): all prompts in one call, or, with pieces > 1,
+        every prompt cut into that many consecutive parts handed over in as many calls (a prompt that arrives in
+        pieces: the later calls find the earlier parts cached)."""
+        lens = np.array([len(p) for p in prompts])
+        first = torch.full((self.S,), -1, dtype=torch.int32, device=self.dev)
+        cuts = [np.linspace(0, n, pieces + 1).astype(int) for n in lens]
+        for k in range(pieces):
+            part = [np.asarray(p[c[k]: c[k + 1]], dtype=np.int32) for p, c in zip(prompts, cuts)]
+            toks = torch.from_numpy(np.concatenate(part) if sum(len(x) for x in part) else np.zeros(0, np.int32)).to(self.dev)
+            dfl.dflash_prefill(self.e, self.batch(), toks, [len(x) for x in part], first)
+            self.host_lens += np.array([len(x) for x in part])
+        torch.cuda.synchronize(self.dev)
+        self.e.device_status()
+        assert np.array_equal(self.seq_lens.cpu().numpy(), self.host_lens)
+        got = self.anchor.cpu().numpy().copy()
+        assert np.array_equal(got[lens > 0], first.cpu().numpy()[lens > 0])
+        return got
+
     # ---- one speculative step --------------------------------------------------------------------------
     def step(self, proposals: Optional[np.ndarray] = None, temperature: float = 0.0, uniforms: Optional[np.ndarray] = None,
              key: int = 0, want_logits: bool = True, block: int = 0) -> Dict[str, np.ndarray]:

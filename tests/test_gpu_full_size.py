@@ -34,6 +34,97 @@ def shared():
     return dict(golden=golden, wt=wt, wd=wd, blobs=None)
 
 
+def _compare_step(name, v, out, g, w, stats):
+    """One sequence's step against its stored oracle record (see the module docstring)."""
+    from paper_2602_06036_amd import binding as B
+    Bk = w.block_size
+    s, n, a = v["seq"], v["n"], v["accept_len"]
+    cols = np.array(v["cols"])
+    assert out["lens_before"][s] == n and out["block"][s, 0] == v["anchor"]
+    # draft: logits at the sampled columns, drafted tokens
+    err_d = np.abs(out["logits_d"][s, 1:][:, cols] - np.array(v["draft_logits_cols"])[1:]).max()
+    err_rows = np.abs(out["logits_t"][s][:, cols] - np.array(v["tgt_logits_cols"])).max(1)
+    # routed-expert target: a block row whose router logits nearly tie in some layer may take another expert there
+    # (both are correct evaluations), and the routed layers that follow amplify that difference -- the function is
+    # discontinuous at ties (tests/test_oracle_model.py shows it with the oracle alone).  With 48 routed layers
+    # nearly every row meets such a layer, so the rows are followed THROUGH the stack instead: layer l's K/V rows of
+    # the block (read back from the target pool) depend on the FFN outputs of the layers before l, so they must
+    # match the oracle's for every row until a near-tie of that row lies behind it.  Final logits are compared for
+    # rows without any near-tie whose predecessors in the block all stayed with the oracle; the others must stay sane.
+    clear = np.ones(Bk, dtype=bool)
+    if "router_gap_by_layer_row" in v:
+        gaps = np.array(v["router_gap_by_layer_row"])                       # [layers, Bk]
+        L = gaps.shape[0]
+        near = gaps < ROUTE_NEAR_TIE
+        first = np.where(near.any(0), near.argmax(0), L)                    # first layer with a near-tie, per row
+        ref_k, ref_v = np.array(v["blk_k"]), np.array(v["blk_v"])           # [layers, Bk, 8]
+        # every row is followed until its K/V rows leave the oracle's; that may only happen after a near-tie of
+        # that row (rows that took the oracle's expert at their near-ties are followed on, down to the last layer)
+        following = np.ones(Bk, dtype=bool)
+        left_at = np.full(Bk, L)
+        worst, compared = 0.0, 0
+        for l in range(L):
+            k, vv = g.read_kv(B.DFLASH_POOL_TARGET, l, s, n, Bk)
+            e = np.maximum(np.abs(k[:, 0, :8] - ref_k[l]).max(1), np.abs(vv[:, 0, :8] - ref_v[l]).max(1))   # per row
+            # a row attends to the block rows before it: once one of those has left, their changed K/V rows (about
+            # 1/2000 of the keys each) shift this row's values slightly without any router decision of its own
+            tol = np.where(np.cumsum(~following) - ~following > 0, 0.15, 0.05)
+            for r in np.flatnonzero(following & (e > tol)):
+                assert near[:l, r].any(), f"{name}: row {r} leaves the oracle at target layer {l} ({e[r]:.3f}) without a router near-tie before it"
+                following[r], left_at[r] = False, l
+            if following.any():
+                worst, compared = max(worst, float(e[following].max())), compared + int(following.sum())
+        stats["kv_trace_rows_compared"], stats["kv_trace_max_err"] = compared, worst
+        print(f"{name}: first near-tie layer per row {first}; rows followed until layer {left_at} (of {L}); {compared} (layer, row) "
+              f"K/V pairs matched, max err {worst:.4f}; per-row target logit error {np.round(err_rows, 3)}", flush=True)
+        assert compared >= L * Bk // 4 and left_at.max() >= L // 2, f"{name}: too little of the stack could be followed"
+        # final logits: strictly comparable only for a row without any near-tie whose predecessors all stayed
+        stayed = left_at == L
+        first = np.where(~near.any(0) & (np.cumsum(~stayed) == 0), L, 0)
+        clear = first == L
+        assert np.isfinite(out["logits_t"][s]).all() and err_rows.max() < 8 * v["logit_std"]
+        assert abs(out["logits_t"][s][:, cols].std() / np.array(v["tgt_logits_cols"]).std() - 1.0) < 0.1
+        if not clear.any():
+            err_rows = np.zeros(Bk)
+            clear[:] = False
+    err_t = err_rows[clear].max() if clear.any() else 0.0
+    stats["max_err_d"] = max(stats["max_err_d"], float(err_d))
+    stats["max_err_t"] = max(stats["max_err_t"], float(err_t))
+    assert err_d <= TOL, f"{name}: draft logits {err_d}"
+    assert err_t <= TOL, f"{name}: target logits {err_t}"
+    for j in range(1, Bk):
+        stats["rows"] += 1
+        if out["drafted"][s, j] != v["oracle_draft"][j - 1]:
+            assert v["draft_margin"][j - 1] < MARGIN, f"{name}: drafted token slot {j}"
+            stats["flips"] += 1
+    assert list(out["block"][s]) == v["block"]
+    flips = [j for j in range(Bk) if out["tgt_argmax"][s, j] != v["tgt_argmax"][j]]
+    for j in flips:
+        assert v["tgt_margin"][j] < MARGIN or not clear[j], f"{name}: target argmax row {j}"
+    stats["flips"] += len(flips)
+    stats["rows"] += Bk
+    same = out["accept_len"][s] == a and list(out["out_tokens"][s, : a + 1]) == v["emitted"]
+    if same and not clear[: a + 1].all():
+        return                         # same tokens, but the committed rows' features may differ: not compared
+    if not same:
+        near = bool(flips)
+        if w.temperature > 0:
+            near = near or v["final_margin"] < MARGIN or min(v["accept_test_margin"]) < 1e-3
+        assert near, f"{name}: accept {out['accept_len'][s]} {out['out_tokens'][s]} vs {a} {v['emitted']}"
+    else:
+        assert list(out["out_tokens"][s, a + 1:]) == [-1] * (Bk - 1 - a)
+        assert out["anchor"][s] == v["emitted"][-1]
+        # committed context-feature rows (first / last draft layer, head 0, 8 dims)
+        ref_k, ref_v = np.array(v["ctx_k_new"]), np.array(v["ctx_v_new"])
+        got_k, got_v = [], []
+        for l in (0, w.draft.n_layers - 1):
+            k, vv = g.read_kv(B.DFLASH_POOL_DRAFT, l, s, n, a + 1)
+            got_k += [k[j, 0, :8] for j in range(a + 1)]
+            got_v += [vv[j, 0, :8] for j in range(a + 1)]
+        assert np.abs(np.array(got_k) - ref_k).max() <= 0.05, f"{name}: committed context K"
+        assert np.abs(np.array(got_v) - ref_v).max() <= 0.05, f"{name}: committed context V"
+
+
 def _run_config(shared, cfg, w=None):
     from tests.gpu_harness import GpuModel
     from paper_2602_06036_amd import binding as B
@@ -73,91 +164,7 @@ def _run_config(shared, cfg, w=None):
     assert np.array_equal(out["tgt_argmax"], lt.argmax(-1).numpy()), "fused argmax is not the argmax of the stored logits"
     stats = dict(max_err_d=0.0, max_err_t=0.0, flips=0, rows=0)
     for name, v in golden.items():
-        s, n, a = v["seq"], v["n"], v["accept_len"]
-        cols = np.array(v["cols"])
-        assert out["lens_before"][s] == n and out["block"][s, 0] == v["anchor"]
-        # draft: logits at the sampled columns, drafted tokens
-        err_d = np.abs(out["logits_d"][s, 1:][:, cols] - np.array(v["draft_logits_cols"])[1:]).max()
-        err_rows = np.abs(out["logits_t"][s][:, cols] - np.array(v["tgt_logits_cols"])).max(1)
-        # routed-expert target: a block row whose router logits nearly tie in some layer may take another expert there
-        # (both are correct evaluations), and the routed layers that follow amplify that difference -- the function is
-        # discontinuous at ties (tests/test_oracle_model.py shows it with the oracle alone).  With 48 routed layers
-        # nearly every row meets such a layer, so the rows are followed THROUGH the stack instead: layer l's K/V rows of
-        # the block (read back from the target pool) depend on the FFN outputs of the layers before l, so they must
-        # match the oracle's for every row until a near-tie of that row lies behind it.  Final logits are compared for
-        # rows without any near-tie whose predecessors in the block all stayed with the oracle; the others must stay sane.
-        clear = np.ones(Bk, dtype=bool)
-        if "router_gap_by_layer_row" in v:
-            gaps = np.array(v["router_gap_by_layer_row"])                       # [layers, Bk]
-            L = gaps.shape[0]
-            near = gaps < ROUTE_NEAR_TIE
-            first = np.where(near.any(0), near.argmax(0), L)                    # first layer with a near-tie, per row
-            ref_k, ref_v = np.array(v["blk_k"]), np.array(v["blk_v"])           # [layers, Bk, 8]
-            # every row is followed until its K/V rows leave the oracle's; that may only happen after a near-tie of
-            # that row (rows that took the oracle's expert at their near-ties are followed on, down to the last layer)
-            following = np.ones(Bk, dtype=bool)
-            left_at = np.full(Bk, L)
-            worst, compared = 0.0, 0
-            for l in range(L):
-                k, vv = g.read_kv(B.DFLASH_POOL_TARGET, l, s, n, Bk)
-                e = np.maximum(np.abs(k[:, 0, :8] - ref_k[l]).max(1), np.abs(vv[:, 0, :8] - ref_v[l]).max(1))   # per row
-                # a row attends to the block rows before it: once one of those has left, their changed K/V rows (about
-                # 1/2000 of the keys each) shift this row's values slightly without any router decision of its own
-                tol = np.where(np.cumsum(~following) - ~following > 0, 0.15, 0.05)
-                for r in np.flatnonzero(following & (e > tol)):
-                    assert near[:l, r].any(), f"{name}: row {r} leaves the oracle at target layer {l} ({e[r]:.3f}) without a router near-tie before it"
-                    following[r], left_at[r] = False, l
-                if following.any():
-                    worst, compared = max(worst, float(e[following].max())), compared + int(following.sum())
-            stats["kv_trace_rows_compared"], stats["kv_trace_max_err"] = compared, worst
-            print(f"{name}: first near-tie layer per row {first}; rows followed until layer {left_at} (of {L}); {compared} (layer, row) "
-                  f"K/V pairs matched, max err {worst:.4f}; per-row target logit error {np.round(err_rows, 3)}", flush=True)
-            assert compared >= L * Bk // 4 and left_at.max() >= L // 2, f"{name}: too little of the stack could be followed"
-            # final logits: strictly comparable only for a row without any near-tie whose predecessors all stayed
-            stayed = left_at == L
-            first = np.where(~near.any(0) & (np.cumsum(~stayed) == 0), L, 0)
-            clear = first == L
-            assert np.isfinite(out["logits_t"][s]).all() and err_rows.max() < 8 * v["logit_std"]
-            assert abs(out["logits_t"][s][:, cols].std() / np.array(v["tgt_logits_cols"]).std() - 1.0) < 0.1
-            if not clear.any():
-                err_rows = np.zeros(Bk)
-                clear[:] = False
-        err_t = err_rows[clear].max() if clear.any() else 0.0
-        stats["max_err_d"] = max(stats["max_err_d"], float(err_d))
-        stats["max_err_t"] = max(stats["max_err_t"], float(err_t))
-        assert err_d <= TOL, f"{name}: draft logits {err_d}"
-        assert err_t <= TOL, f"{name}: target logits {err_t}"
-        for j in range(1, Bk):
-            stats["rows"] += 1
-            if out["drafted"][s, j] != v["oracle_draft"][j - 1]:
-                assert v["draft_margin"][j - 1] < MARGIN, f"{name}: drafted token slot {j}"
-                stats["flips"] += 1
-        assert list(out["block"][s]) == v["block"]
-        flips = [j for j in range(Bk) if out["tgt_argmax"][s, j] != v["tgt_argmax"][j]]
-        for j in flips:
-            assert v["tgt_margin"][j] < MARGIN or not clear[j], f"{name}: target argmax row {j}"
-        stats["flips"] += len(flips)
-        stats["rows"] += Bk
-        same = out["accept_len"][s] == a and list(out["out_tokens"][s, : a + 1]) == v["emitted"]
-        if same and not clear[: a + 1].all():
-            continue                       # same tokens, but the committed rows' features may differ: not compared
-        if not same:
-            near = bool(flips)
-            if w.temperature > 0:
-                near = near or v["final_margin"] < MARGIN or min(v["accept_test_margin"]) < 1e-3
-            assert near, f"{name}: accept {out['accept_len'][s]} {out['out_tokens'][s]} vs {a} {v['emitted']}"
-        else:
-            assert list(out["out_tokens"][s, a + 1:]) == [-1] * (Bk - 1 - a)
-            assert out["anchor"][s] == v["emitted"][-1]
-            # committed context-feature rows (first / last draft layer, head 0, 8 dims)
-            ref_k, ref_v = np.array(v["ctx_k_new"]), np.array(v["ctx_v_new"])
-            got_k, got_v = [], []
-            for l in (0, w.draft.n_layers - 1):
-                k, vv = g.read_kv(B.DFLASH_POOL_DRAFT, l, s, n, a + 1)
-                got_k += [k[j, 0, :8] for j in range(a + 1)]
-                got_v += [vv[j, 0, :8] for j in range(a + 1)]
-            assert np.abs(np.array(got_k) - ref_k).max() <= 0.05, f"{name}: committed context K"
-            assert np.abs(np.array(got_v) - ref_v).max() <= 0.05, f"{name}: committed context V"
+        _compare_step(name, v, out, g, w, stats)
     # properties that hold for every sequence of the batch, sampled or not
     a_all = out["accept_len"]
     assert ((a_all >= 0) & (a_all <= Bk - 1)).all()                       # tau = a+1 in [1, B]
@@ -210,6 +217,64 @@ def test_moe_30b_a3b_batch32_ctx2048(shared_moe):
 
 def test_config2_batch1_ctx2048(shared):
     _run_config(shared, 2)
+
+
+def test_config2_from_a_true_prefill(shared):
+    """Configuration 2 as the benchmark definition states it: the context is 2048 uniform-random tokens that really went
+    through the target.  dflash_prefill (two passes of 1024 rows) against the oracle's sequence-form prefill -- first token,
+    sampled K/V rows of four target layers, context K/V rows of the first and last draft layer -- then one speculative
+    step from THAT state against the oracle's step, and two more steps whose emitted tokens must continue the oracle's
+    plain token-by-token greedy decoding of the target (losslessness at the full 8B shape over three steps)."""
+    from tests.gpu_harness import GpuModel
+    from paper_2602_06036_amd import binding as B
+    v = shared["golden"].get("cfg2_prefill_seq0")
+    if v is None:
+        pytest.skip("no golden for the prefilled configuration 2")
+    w = si.workload(2)
+    Bk, V = w.block_size, w.target.vocab
+    prompt = si.make_prompts(w)[0]
+    n = len(prompt)
+    assert n == v["n"] == 2048
+    g = GpuModel(w, shared["wt"], shared["wd"], n + 6 * Bk, max_seqs=64, blobs=shared["blobs"])
+    shared["blobs"] = g.blobs()
+    got = g.prefill_entry([prompt])
+    assert int(got[0]) == v["anchor"], f"first token {got[0]} against {v['anchor']} (oracle margin {v['first_margin']})"
+    rows = v["kv_rows"]
+    worst = 0.0
+    for pool, layers, kk, vv, head in ((B.DFLASH_POOL_TARGET, v["kv_layers"], v["tgt_k"], v["tgt_v"], 3),
+                                       (B.DFLASH_POOL_DRAFT, v["ctx_layers"], v["ctx_k"], v["ctx_v"], 5)):
+        for li, l in enumerate(layers):
+            for ri, r in enumerate(rows):
+                k, vals = g.read_kv(pool, l, 0, r, 1)
+                e = max(np.abs(k[0, head, :8] - np.array(kk[li][ri])).max(), np.abs(vals[0, head, :8] - np.array(vv[li][ri])).max())
+                worst = max(worst, float(e))
+                assert e <= 0.05, f"pool {pool} layer {l} row {r}: {e}"
+    print(f"prefilled configuration 2: first token {got[0]}, sampled cache rows within {worst:.4f}", flush=True)
+    # one step from the prefilled state, against the oracle's step from ITS prefilled state
+    proposals = np.array([v["block"][1:]], dtype=np.int64)
+    out = g.step(proposals, 0.0, None, RNG_KEY)
+    stats = dict(max_err_d=0.0, max_err_t=0.0, flips=0, rows=0)
+    _compare_step("cfg2_prefill_seq0", v, out, g, w, stats)
+    print(f"prefilled configuration 2: step stats {stats}", flush=True)
+    # losslessness over the next steps: constructed proposals (k correct, then a wrong one) from the oracle's plain decoding
+    cont, margins = v["plain_greedy"], v["plain_greedy_margin"]
+    emitted = list(out["out_tokens"][0, : out["accept_len"][0] + 1])
+    for k in (1, 0):
+        done = len(emitted)
+        if emitted != cont[:done] or done + k + 1 > len(cont):
+            break
+        prop = -np.ones((1, Bk - 1), dtype=np.int64)
+        prop[0, :k] = cont[done: done + k]
+        prop[0, k] = (cont[done + k] + 1) % (V - 1)
+        o = g.step(prop, 0.0, None, RNG_KEY, want_logits=False)
+        emitted += list(o["out_tokens"][0, : o["accept_len"][0] + 1])
+    first_diff = next((i for i, (a, b) in enumerate(zip(emitted, cont)) if a != b), None)
+    print(f"prefilled configuration 2: emitted {emitted} plain greedy decoding {cont}", flush=True)
+    if first_diff is not None:
+        assert margins[first_diff] < MARGIN, f"token {first_diff} after the prompt: {emitted[first_diff]} against {cont[first_diff]} at a margin of {margins[first_diff]}"
+    else:
+        assert len(emitted) == 6
+    g.e.close()
 
 
 def test_config3_batch16_ragged_paged(shared):
