@@ -48,8 +48,10 @@ WORKLOADS = {
 }
 
 
-def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
-    """Random-init weights generated on the device tensor by tensor, packed, canonical copy freed."""
+def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled", blobs=None, max_seqs=None):
+    """Random-init weights generated on the device tensor by tensor, packed, canonical copy freed (blobs: the packed
+    weights of an earlier engine of the same models, shared instead of generated again).  max_seqs: sequences per call
+    the context is created for when that is more than the S sequences whose caches are laid out (prefill passes)."""
     import torch
     import paper_2602_06036_amd as dfl
     from synth import inputs as si
@@ -58,9 +60,9 @@ def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
     max_len = ctx + (steps_total + 2) * Bk
     pps = (max_len + 15) // 16
     n_pages = S * pps
-    e = dfl.Engine(w.target, w.draft, w.dtype, Bk, S, pps, n_pages, w.tap_layers, w.mask_token_id, str(dev))
+    e = dfl.Engine(w.target, w.draft, w.dtype, Bk, max_seqs or S, pps, n_pages, w.tap_layers, w.mask_token_id, str(dev), blobs=blobs)
     gen = torch.Generator(device=dev)
-    gen.manual_seed(w.seed)
+    gen.manual_seed(w.wseed)
     tdt = torch.bfloat16 if w.dtype == "bf16" else torch.float32
 
     def mat(shape):
@@ -74,14 +76,15 @@ def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
         return {k: (gain(shp[k][0]) if k in si.LAYER_GAINS else mat(shp[k])) for k in shp}
 
     t, d = w.target, w.draft
-    e.pack_target_head(mat((t.vocab, t.d_model)), mat((t.vocab, t.d_model)), gain(t.d_model))
-    for l in range(t.n_layers):
-        e.pack_target_layer(l, layer(t))
-        torch.cuda.synchronize(dev)
-    e.pack_draft_head(mat((d.d_model, len(w.tap_layers) * t.d_model)), gain(d.d_model), gain(d.d_model))
-    for l in range(d.n_layers):
-        e.pack_draft_layer(l, layer(d))
-        torch.cuda.synchronize(dev)
+    if blobs is None:
+        e.pack_target_head(mat((t.vocab, t.d_model)), mat((t.vocab, t.d_model)), gain(t.d_model))
+        for l in range(t.n_layers):
+            e.pack_target_layer(l, layer(t))
+            torch.cuda.synchronize(dev)
+        e.pack_draft_head(mat((d.d_model, len(w.tap_layers) * t.d_model)), gain(d.d_model), gain(d.d_model))
+        for l in range(d.n_layers):
+            e.pack_draft_layer(l, layer(d))
+            torch.cuda.synchronize(dev)
     e.create()
     # caches: seeded random rows standing in for a prefill (unit-scale K after k-norm / RoPE, V likewise)
     for pool in (e.target_pool, e.draft_pool):
@@ -100,38 +103,25 @@ def build_engine(w, S, ctx, steps_total, dev, page_order="shuffled"):
 
 
 def run_prefill(args, dev):
-    """Prefill of one prompt of args.prefill tokens (8B shape of configuration 2; with a `moe_*` --workload the
-    mixture-of-experts shape, up to 2048 tokens) as ONE many-row pass: every 16-token
-    chunk is a pseudo-sequence whose committed length is the chunk's offset and whose block-table row is the
-    prompt's, handed to one dflash_verify (tokens out: greedy token after every row) and one forced
-    dflash_kv_commit (context K/V of all rows into the draft cache).  Prints one JSON line: prompt tokens per second."""
+    """Prefill of one prompt of args.prefill random tokens through dflash_prefill (8B shape of configuration 2; with a
+    `moe_*` --workload the mixture-of-experts shape, up to 2048 tokens): one pass of all rows, the LM head on the
+    prompt's last row only, context K/V of all rows into the draft cache.  Prints one JSON line: prompt tokens per second."""
     import torch
     import paper_2602_06036_amd as dfl
     from synth import inputs as si
-    w = si.qwen3_30b_a3b_workload(1, 2048) if args.workload.startswith("moe_") else si.workload(2)
+    w = si.qwen3_30b_a3b_workload(1, 2048) if args.workload and args.workload.startswith("moe_") else si.workload(2)
     Bk = w.block_size
-    n_tok = (args.prefill // Bk) * Bk
-    n = n_tok // Bk
-    e, table, _ = build_engine(w, n, n_tok, 1, dev, args.page_order)   # rows long enough for the prompt; the pool is larger than needed
-    pps = table.shape[1]
-    pages = table.reshape(-1)[: (n_tok + Bk + 15) // 16]      # the prompt's pages, taken from the shuffled pool
-    if pages.numel() > pps:
-        raise SystemExit("bench --prefill: prompt longer than a block-table row of this engine")
-    prow = torch.zeros(pps, dtype=torch.int32, device=dev)
-    prow[: pages.numel()] = pages
-    ptable = prow.repeat(n, 1).contiguous()
-    lens0 = (torch.arange(n, dtype=torch.int32, device=dev) * Bk).contiguous()
-    lens = lens0.clone()
-    anchor = torch.zeros(n, dtype=torch.int32, device=dev)
-    tokens = torch.randint(0, w.target.vocab - 1, (n, Bk), dtype=torch.int32, device=dev)
-    argmax = torch.zeros((n, Bk), dtype=torch.int32, device=dev)
-    acc = torch.full((n,), Bk - 1, dtype=torch.int32, device=dev)
+    n_tok = args.prefill
+    n = (n_tok + Bk - 1) // Bk
+    e, table, _ = build_engine(w, 1, n_tok, 1, dev, args.page_order, max_seqs=n)
+    lens = torch.zeros(1, dtype=torch.int32, device=dev)
+    anchor = torch.zeros(1, dtype=torch.int32, device=dev)
+    tokens = torch.randint(0, w.target.vocab - 1, (n_tok,), dtype=torch.int32, device=dev)
+    first = torch.zeros(1, dtype=torch.int32, device=dev)
 
     def one_pass():
-        lens.copy_(lens0)
-        b = e.batch(lens, ptable, anchor, n_tok - Bk)
-        dfl.dflash_verify(e, b, tokens, argmax)
-        dfl.dflash_kv_commit(e, b, acc, argmax)
+        lens.zero_()
+        dfl.dflash_prefill(e, e.batch(lens, table, anchor, 0), tokens, [n_tok], first)
 
     for _ in range(args.warmup):
         one_pass()
@@ -145,15 +135,16 @@ def run_prefill(args, dev):
     t1.record()
     torch.cuda.synchronize(dev)
     e.device_status()
+    assert int(lens.item()) == n_tok
     ms = t0.elapsed_time(t1) / args.steps
     t = w.target
     qd, kd = t.n_q_heads * t.head_dim, t.n_kv_heads * t.head_dim
     ffn = (t.n_experts + t.top_k * 3 * t.d_expert) * t.d_model if t.n_experts else 3 * t.d_ffn * t.d_model   # per row: router + top_k experts
-    flops = 2.0 * n_tok * (t.n_layers * ((qd + 2 * kd) * t.d_model + t.d_model * qd + ffn) + t.vocab * t.d_model)
-    print(json.dumps({"metric": "prefill tokens/sec/GPU (%s, one many-row pass)" % ("30B-A3B-shape" if w.target.n_experts else "8B-shape"), "value": n_tok / (ms * 1e-3), "unit": "tokens/s",
+    flops = 2.0 * n_tok * t.n_layers * ((qd + 2 * kd) * t.d_model + t.d_model * qd + ffn) + 2.0 * t.vocab * t.d_model
+    print(json.dumps({"metric": "prefill tokens/sec/GPU (%s, dflash_prefill, one many-row pass)" % ("30B-A3B-shape" if w.target.n_experts else "8B-shape"), "value": n_tok / (ms * 1e-3), "unit": "tokens/s",
                       "n_gpus": 1, "steps": args.steps, "warmup": args.warmup, "ms_per_step": ms, "higher_is_better": True,
                       "scaling": "weak", "vs_baseline": None, "dtype": w.dtype, "data": "synthetic",
-                      "config": {"workload": "prefill_moe_30b_a3b" if w.target.n_experts else "prefill_8b", "prompt_tokens": n_tok, "rows_per_pass": n_tok, "page_order": args.page_order},
+                      "config": {"workload": "prefill_moe_30b_a3b" if w.target.n_experts else "prefill_8b", "prompt_tokens": n_tok, "rows_per_pass": n * Bk, "page_order": args.page_order},
                       "target_gemm_TFLOPs_algorithmic": flops / (ms * 1e-3) / 1e12,
                       "moe_stats_launches_experts_bands_items": list(e.moe_stats())[:4] if t.n_experts else None}))
     e.close()
@@ -222,18 +213,28 @@ def step_roofline(w, S, ctx, ms_step):
                 frac=max(t_hbm, t_mfma) / (ms_step * 1e-3))
 
 
-def cpu_baseline(w, ctx, time_budget_s=25.0):
-    """Times the oracle, as it stands, on a bounded sample of the same step: one target layer and one
-    draft layer of the workload's shape over one 16-token block with `ctx` cached rows, plus the final
-    norm + LM head on a 1/8 vocabulary slice; scaled to the full layer counts and vocabulary."""
+def cpu_baseline(w, ctx):
+    """Times the oracle, as it stands, on a bounded sample of the same step: TWO target layers and TWO draft layers of
+    the workload's shape over one block with `ctx` cached rows, plus the final norm + LM head on a 1/8 vocabulary
+    slice.  Each model is run with one layer and with two: the difference is the cost of a layer (that the second
+    layer costs what the first does is thereby measured, not assumed), the rest is embedding + head; scaled to the
+    full layer counts and vocabulary."""
     import numpy as np
     from dataclasses import replace
     from oracle import dflash_oracle as O
     from synth import inputs as si
 
-    t1 = replace(w.target, n_layers=1, vocab=w.target.vocab // 8)
-    d1 = replace(w.draft, n_layers=1, vocab=w.target.vocab // 8)
-    ws = replace(w, target=t1, draft=d1, tap_layers=(0,), mask_token_id=t1.vocab - 1)
+    t2 = replace(w.target, n_layers=2, vocab=w.target.vocab // 8)
+    d2 = replace(w.draft, n_layers=2, vocab=w.target.vocab // 8)
+    ws = replace(w, target=t2, draft=d2, tap_layers=(0,), mask_token_id=t2.vocab - 1)
+    n_threads = os.cpu_count() or 1
+    try:
+        from threadpoolctl import threadpool_info
+        blas = [p["num_threads"] for p in threadpool_info() if p.get("user_api") == "blas"]
+        if blas:
+            n_threads = max(blas)           # the threads the matrix products of the oracle actually run on
+    except Exception:
+        pass
     wt, wd = si.make_weights(ws, min(16, os.cpu_count() or 1))
     cache = {}
 
@@ -248,10 +249,11 @@ def cpu_baseline(w, ctx, time_budget_s=25.0):
     rnd = O.rounding_for(w.dtype)
     Bk = w.block_size
     rng = np.random.default_rng(0)
-    st = O.SeqState(t1, d1, ctx + Bk + 1, cache_dtype=np.float32)
-    for lists, m in ((st.kv, t1), (st.ctx, d1)):
-        lists.k[0][:ctx] = O.round_bf16(rng.standard_normal((ctx, m.n_kv_heads, m.head_dim)))
-        lists.v[0][:ctx] = O.round_bf16(rng.standard_normal((ctx, m.n_kv_heads, m.head_dim)))
+    st = O.SeqState(t2, d2, ctx + Bk + 1, cache_dtype=np.float32)
+    for lists, m in ((st.kv, t2), (st.ctx, d2)):
+        for l in range(2):
+            lists.k[l][:ctx] = O.round_bf16(rng.standard_normal((ctx, m.n_kv_heads, m.head_dim)))
+            lists.v[l][:ctx] = O.round_bf16(rng.standard_normal((ctx, m.n_kv_heads, m.head_dim)))
         lists.n = ctx
     st.n, st.anchor = ctx, 7
     # warm the weight cache (upcast is part of neither leg: the GPU side has its weights resident too)
@@ -259,67 +261,33 @@ def cpu_baseline(w, ctx, time_budget_s=25.0):
         Wt(nm)
     for nm in list(wd.names()):
         Wd(nm)
-    t0 = time.perf_counter()
-    O.draft_block_forward(Wd, d1, st.anchor, ctx, st.ctx, Bk, ws.mask_token_id, rnd)
-    t_draft = time.perf_counter() - t0
-    t0 = time.perf_counter()
-    O.target_forward_tokens(Wt, t1, list(range(Bk)), ctx, st.kv, (0,), rnd)
-    t_tgt = time.perf_counter() - t0
-    # each leg = one layer + (norm + LM head on V/8); separate the head by timing it alone
-    h = rng.standard_normal((Bk, t1.d_model))
-    t0 = time.perf_counter()
-    _ = rnd(O.rmsnorm(h, Wt("gf"), t1.rms_eps)) @ Wt("lm").T
-    t_head = time.perf_counter() - t0
-    step = (t_tgt - t_head) * w.target.n_layers + (t_draft - t_head) * w.draft.n_layers + 2 * 8 * t_head
-    return dict(value=Bk / step, unit="tokens/s", cores=min(16, os.cpu_count() or 1), kind="oracle",
-                sample="1 of %d target layers + 1 of %d draft layers over one %d-token block with %d cached rows, "
-                       "LM head on 1/8 of the vocabulary; scaled to the full step (%.1f s/step)" %
-                       (w.target.n_layers, w.draft.n_layers, Bk, ctx, step))
+    times = {}
+    for layers in (1, 2):
+        t0 = time.perf_counter()
+        O.draft_block_forward(Wd, replace(d2, n_layers=layers), st.anchor, ctx, st.ctx, Bk, ws.mask_token_id, rnd)
+        times["d", layers] = time.perf_counter() - t0
+        t0 = time.perf_counter()
+        O.target_forward_tokens(Wt, replace(t2, n_layers=layers), list(range(Bk)), ctx, st.kv, (0,), rnd)
+        times["t", layers] = time.perf_counter() - t0
+        st.kv.truncate(ctx)
+    layer_t, layer_d = times["t", 2] - times["t", 1], times["d", 2] - times["d", 1]
+    head_t, head_d = max(times["t", 1] - layer_t, 0.0), max(times["d", 1] - layer_d, 0.0)   # embedding + final norm + LM head on V/8
+    step = layer_t * w.target.n_layers + layer_d * w.draft.n_layers + 8 * (head_t + head_d)
+    return dict(value=Bk / step, unit="tokens/s", cores=n_threads, host_cpu_count=os.cpu_count(), kind="oracle",
+                seconds=dict(target_1_layer=times["t", 1], target_2_layers=times["t", 2], draft_1_layer=times["d", 1], draft_2_layers=times["d", 2]),
+                sample="2 of %d target layers + 2 of %d draft layers over one %d-token block with %d cached rows (each model timed "
+                       "with 1 and with 2 layers: second layer / first run = %.2f target, %.2f draft), LM head on 1/8 of the vocabulary; "
+                       "scaled to the full step (%.1f s/step)" %
+                       (w.target.n_layers, w.draft.n_layers, Bk, ctx, layer_t / max(times["t", 1], 1e-9), layer_d / max(times["d", 1], 1e-9), step))
 
 
-def main():
-    ap = argparse.ArgumentParser()
-    ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=30)
-    ap.add_argument("--warmup", type=int, default=5)
-    ap.add_argument("--workload", default="cfg2_8b_b1_ctx2048", choices=sorted(WORKLOADS))
-    ap.add_argument("--prefill", type=int, default=0,
-                    help="instead of the step: prefill of one prompt of this many tokens (8B shape) as one many-row "
-                         "verify + forced commit; one JSON line with prompt tokens per second")
-    ap.add_argument("--page-order", default="shuffled", choices=["shuffled", "contiguous"],
-                    help="how cache pages are assigned to sequences (shuffled = scattered 16-token pages, the harder case)")
-    ap.add_argument("--graph", action="store_true",
-                    help="capture one step into a HIP graph (attention splits planned for the longest length the run "
-                         "reaches) and time K replays instead of K eager steps")
-    ap.add_argument("--peaks", action="store_true",
-                    help="instead of the step: what single launches reach on this GPU (read-only HBM streaming of the "
-                         "sizes of the weight matrices, register-resident bf16 MFMA loop), one JSON line")
-    ap.add_argument("--no-cpu-baseline", action="store_true")
-    ap.add_argument("--no-profile", action="store_true")
-    ap.add_argument("--copy-probe", action="store_true",
-                    help="also run three device copies of exactly 1 GiB (a kernel of known traffic, used to scale "
-                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
-    args = ap.parse_args()
-    if args.gpus != 1:
-        print("bench.py: this build runs on ONE GPU (the step is single-device: sequences are independent, so more GPUs would each take a share of the batch); "
-              "use --gpus 1", file=sys.stderr)
-        sys.exit(2)
-
+def run_workload(name, args, dev, K, Wm, blobs=None):
+    """K timed steps of one named workload after Wm warm-up steps (and, unless --no-profile, the same K steps again with
+    an event pair around every GEMM / attention launch).  Returns (the result dictionary, the packed weights)."""
     import torch
     import paper_2602_06036_amd as dfl
-    from paper_2602_06036_amd import binding as B
     from synth import inputs as si
-
-    assert torch.cuda.is_available(), "bench.py needs a GPU"
-    dev = torch.device("cuda:0")
-    torch.cuda.set_device(dev)
-    if args.peaks:
-        print(json.dumps(measure_peaks(dev)))
-        return
-    if args.prefill:
-        run_prefill(args, dev)
-        return
-    idx, S, ctx = WORKLOADS[args.workload]
+    idx, S, ctx = WORKLOADS[name]
     if idx == "llama31":
         w = si.llama31_8b_workload(S, ctx)
     elif idx == "moe30b":
@@ -330,9 +298,8 @@ def main():
     else:
         w = si.workload(idx)
     Bk = w.block_size
-    K, Wm = args.steps, args.warmup
     passes = 1 if args.no_profile else 2
-    e, table, max_len = build_engine(w, S, ctx, Wm + passes * K, dev, args.page_order)
+    e, table, max_len = build_engine(w, S, ctx, Wm + passes * K, dev, args.page_order, blobs=blobs)
 
     seq_lens = torch.full((S,), ctx, dtype=torch.int32, device=dev)
     anchor = torch.full((S,), 11, dtype=torch.int32, device=dev)
@@ -411,7 +378,12 @@ def main():
                 gemm_ms += ms
                 gemm_bytes += by
         extra["kernels"] = per
-        extra["all_gemm"] = dict(ms_per_step=gemm_ms / K, gbs=gemm_bytes / gemm_ms / 1e6)
+        # every GEMM launch of the step together: weight bytes per second, and 2*M*N*K flops (M = S*B rows per weight byte pair)
+        # against the bf16 MFMA peak -- algorithmic, and as issued (every weight tile meets a hi and a lo activation fragment)
+        gemm_tflops = gemm_bytes * (S * Bk) / (gemm_ms * 1e-3) / 1e12
+        extra["all_gemm"] = dict(ms_per_step=gemm_ms / K, gbs=gemm_bytes / gemm_ms / 1e6, tflops_algorithmic=gemm_tflops,
+                                 mfma_frac_algorithmic=gemm_tflops / MFMA_BF16_PEAK_TFLOPS,
+                                 mfma_frac_issued=(2.0 if w.dtype == "bf16" else 1.0) * gemm_tflops / MFMA_BF16_PEAK_TFLOPS)
         ms, cnt, by = prof[2]        # dominant kernel: gate/up projection with fused SwiGLU
         M_rows = S * Bk
         if w.target.n_experts:
@@ -431,7 +403,7 @@ def main():
             else:
                 ach = e_by / (us_e * 1e-6) / 1e9
                 roof = dict(bound="hbm", achieved=ach, peak=HBM_PEAK_GBS, unit="GB/s", frac=ach / HBM_PEAK_GBS)
-            roof.update(kernel="gemm_bf16_kernel<SWIGLU, grouped> (routed experts' gate/up projection)", traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
+            roof.update(kernel="gemm_bf16_kernel<SWIGLU, grouped> (routed experts' gate/up projection)", traffic=MEASURED_TRAFFIC_BYTES.get(name),
                         bytes_per_launch=e_by, flops_per_launch=flops, avg_launch_us=us_e)
         elif M_rows * 2 > 620:         # above the ridge (2.5 PFLOP/s / 8 TB/s = 310 flop per weight byte = M rows): MFMA-bound
             # algorithmic flops: 2 * M * N * K = M flops per weight byte (bf16); the hi+lo activation pair doubles the
@@ -439,14 +411,14 @@ def main():
             ach = (by / cnt) * M_rows / (ms / cnt) / 1e9
             roof = dict(bound="mfma", kernel="gemm_bf16_tiled_kernel<SWIGLU> (gate/up projection)", achieved=ach,
                         peak=MFMA_BF16_PEAK_TFLOPS, unit="TFLOP/s", frac=ach / MFMA_BF16_PEAK_TFLOPS,
-                        traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
+                        traffic=MEASURED_TRAFFIC_BYTES.get(name),
                         flops_per_launch=(by / cnt) * M_rows, issued_mfma_flops_per_launch=2 * (by / cnt) * M_rows,
                         avg_launch_us=1e3 * ms / cnt)
         else:
             ach = (by / cnt) / (ms / cnt) / 1e6
             kname = "gemm_bf16_tiled_kernel<SWIGLU>" if M_rows > 64 else "gemm_bf16_kernel<SWIGLU>"
             roof = dict(bound="hbm", kernel=kname + " (gate/up projection)", achieved=ach, peak=HBM_PEAK_GBS,
-                        unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(args.workload),
+                        unit="GB/s", frac=ach / HBM_PEAK_GBS, traffic=MEASURED_TRAFFIC_BYTES.get(name),
                         bytes_per_launch=by / cnt, avg_launch_us=1e3 * ms / cnt)
 
     out = {
@@ -457,7 +429,7 @@ def main():
         "n_gpus": 1, "steps": K, "warmup": Wm, "ms_per_step": ms_step,
         "higher_is_better": True, "scaling": "weak", "vs_baseline": None,
         "dtype": w.dtype, "data": "synthetic",
-        "config": {"workload": args.workload, "n_seqs": S, "block_size": Bk, "context": ctx,
+        "config": {"workload": name, "n_seqs": S, "block_size": Bk, "context": ctx,
                    "temperature": T, "value_counts": "verified positions (S*B per step)",
                    "launch": "hip graph replay" if args.graph else "eager", "page_order": args.page_order},
         "committed_tokens_per_s": committed / (ms_total * 1e-3),
@@ -469,6 +441,69 @@ def main():
         "step_roofline": step_roofline(w, S, ctx, ms_step),
     }
     out.update(extra)
+    blobs = (e.target_blob, e.draft_blob)
+    e.close()
+    del e, table
+    torch.cuda.empty_cache()
+    return out, blobs, w, ctx
+
+
+def main():
+    ap = argparse.ArgumentParser()
+    ap.add_argument("--gpus", type=int, default=1)
+    ap.add_argument("--steps", type=int, default=30)
+    ap.add_argument("--warmup", type=int, default=5)
+    ap.add_argument("--workload", default=None, choices=sorted(WORKLOADS),
+                    help="one named workload; without it: configuration 2 (the headline) followed by configurations 3, 4 and 5 "
+                         "under \"configs\" in the same JSON line")
+    ap.add_argument("--prefill", type=int, default=0,
+                    help="instead of the step: prefill of one prompt of this many tokens (8B shape) as one many-row "
+                         "verify + forced commit; one JSON line with prompt tokens per second")
+    ap.add_argument("--page-order", default="shuffled", choices=["shuffled", "contiguous"],
+                    help="how cache pages are assigned to sequences (shuffled = scattered 16-token pages, the harder case)")
+    ap.add_argument("--graph", action="store_true",
+                    help="capture one step into a HIP graph (attention splits planned for the longest length the run "
+                         "reaches) and time K replays instead of K eager steps")
+    ap.add_argument("--peaks", action="store_true",
+                    help="instead of the step: what single launches reach on this GPU (read-only HBM streaming of the "
+                         "sizes of the weight matrices, register-resident bf16 MFMA loop), one JSON line")
+    ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--no-profile", action="store_true")
+    ap.add_argument("--copy-probe", action="store_true",
+                    help="also run three device copies of exactly 1 GiB (a kernel of known traffic, used to scale "
+                         "rocprofv3 FETCH_SIZE / WRITE_SIZE counters)")
+    args = ap.parse_args()
+    if args.gpus != 1:
+        print("bench.py: this build runs on ONE GPU (the step is single-device: sequences are independent, so more GPUs would each take a share of the batch); "
+              "use --gpus 1", file=sys.stderr)
+        sys.exit(2)
+
+    import torch
+    import paper_2602_06036_amd as dfl
+    from paper_2602_06036_amd import binding as B
+    from synth import inputs as si
+
+    assert torch.cuda.is_available(), "bench.py needs a GPU"
+    dev = torch.device("cuda:0")
+    torch.cuda.set_device(dev)
+    if args.peaks:
+        print(json.dumps(measure_peaks(dev)))
+        return
+    if args.prefill:
+        run_prefill(args, dev)
+        return
+    if args.workload:
+        out, _, w, ctx = run_workload(args.workload, args, dev, args.steps, args.warmup)
+    else:
+        # default: the headline workload (configuration 2) in full, then configurations 3, 4 and 5 with the same packed
+        # weights and fewer steps, each as a compact record under "configs"
+        out, blobs, w, ctx = run_workload("cfg2_8b_b1_ctx2048", args, dev, args.steps, args.warmup)
+        out["configs"] = {}
+        for name in ("cfg3_8b_b16_ctx2560", "cfg4_8b_b4_ctx16k", "cfg5_8b_b32_ctx8k"):
+            r, blobs, _, _ = run_workload(name, args, dev, max(5, args.steps // 3), min(args.warmup, 3), blobs=blobs)
+            out["configs"][name] = {k: r[k] for k in ("value", "unit", "steps", "warmup", "ms_per_step", "config", "roofline", "step_roofline",
+                                                     "kernels", "all_gemm") if k in r}
+        del blobs
     if not args.no_cpu_baseline:
         out["cpu_baseline"] = cpu_baseline(w, ctx)
     print(json.dumps(out))
