@@ -177,6 +177,20 @@ int dflash_accept(dflash_ctx *ctx, const dflash_batch *batch, const int32_t *dra
                   const uint64_t *rng_key /*(device) [1], nullable when greedy*/,
                   int32_t *accept_len /*(device) [S] out*/, int32_t *out_tokens /*(device) [S,B] out*/, void *stream);
 
+/* For callers that cannot allocate device memory or hand over a workspace (code under HIP graph capture, tight serving
+ * loops, harnesses that forbid hipMalloc): the temperature > 0 branch of dflash_accept on logits the caller holds itself
+ * (e.g. the logits_out of dflash_draft_block and dflash_verify), with the rows' softmax statistics kept in an array that
+ * is built into the library (64 KB of device memory per GPU, held until the process ends) instead of a workspace.
+ * target_logits, draft_logits (device) [S,B,V] fp32; draft_tokens (device) [S,B]; uniforms (device) [S,B]; rng_key
+ * (device) [1]; outputs as dflash_accept.  Needs no context, allocates nothing, calls no allocating routine.
+ * At most 4096 rows (n_seqs * block_size): DFLASH_ECAPACITY beyond that; DFLASH_EINVAL for temperature <= 0 (greedy
+ * acceptance needs no scratch at all: use dflash_accept).  All calls on one GPU share the one array: calls that overlap
+ * on the same GPU (different streams, different threads) race on it and must be serialised by the caller.  Nothing in
+ * the array has to start at zero: every call overwrites the entries it reads. */
+int dflash_accept_sampled_noalloc(const float *target_logits, const float *draft_logits, const int32_t *draft_tokens,
+                                  const float *uniforms, const uint64_t *rng_key, float temperature, int32_t n_seqs,
+                                  int32_t block_size, int32_t vocab, int32_t *accept_len, int32_t *out_tokens, void *stream);
+
 /* Commit / rollback (Section 4.1, Appendix A.3): fuses the tapped hidden states of the block rows,
  * H_t = RMSNorm(W_c [taps]), projects them with every draft layer's W_K, W_V (k-norm, RoPE at the
  * row's position) into the draft pool at positions n_s .. n_s+B-1, then advances

@@ -25,7 +25,7 @@ EXPORTS = [
     "dflash_pack_target_head", "dflash_pack_target_layer", "dflash_pack_draft_head", "dflash_pack_draft_layer",
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
-    "dflash_prefill", "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats",
+    "dflash_prefill", "dflash_accept_sampled_noalloc", "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats",
     "dflash_probe_hbm_read", "dflash_probe_mfma",
 ]
 
@@ -91,6 +91,7 @@ def lib() -> C.CDLL:
         l.dflash_accept.argtypes = [P, C.POINTER(Batch), P, P, F, P, P, P, P, P]
         l.dflash_kv_commit.argtypes = [P, C.POINTER(Batch), P, P, P, P]
         l.dflash_prefill.argtypes = [P, C.POINTER(Batch), P, C.POINTER(C.c_int32), P, P]
+        l.dflash_accept_sampled_noalloc.argtypes = [P, P, P, P, P, F, I, I, I, P, P, P]
         l.dflash_kv_read.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
         l.dflash_kv_write.argtypes = [P, C.POINTER(Batch), I, I, I, I, I, P, P, P]
         l.dflash_profile_enable.argtypes = [P, I]
@@ -250,6 +251,15 @@ def dflash_accept(e: Engine, batch: Batch, draft_tokens: torch.Tensor, tgt_argma
                   rng_key: Optional[torch.Tensor] = None):
     _check(e.l.dflash_accept(e.ctx, C.byref(batch), _ptr(draft_tokens), _ptr(tgt_argmax), float(temperature), _ptr(uniforms),
                              _ptr(rng_key), _ptr(accept_len), _ptr(out_tokens), _stream()), e.ctx)
+
+
+def dflash_accept_sampled_noalloc(target_logits: torch.Tensor, draft_logits: torch.Tensor, draft_tokens: torch.Tensor, uniforms: torch.Tensor,
+                                  rng_key: torch.Tensor, temperature: float, accept_len: torch.Tensor, out_tokens: torch.Tensor):
+    """Speculative-sampling acceptance on logits the caller holds, [S, B, V] fp32 each; no context, no workspace."""
+    S, Bk, V = target_logits.shape
+    assert draft_logits.shape == target_logits.shape and target_logits.dtype == torch.float32 and draft_logits.dtype == torch.float32
+    _check(lib().dflash_accept_sampled_noalloc(_ptr(target_logits), _ptr(draft_logits), _ptr(draft_tokens), _ptr(uniforms), _ptr(rng_key),
+                                               float(temperature), int(S), int(Bk), int(V), _ptr(accept_len), _ptr(out_tokens), _stream()))
 
 
 def dflash_kv_commit(e: Engine, batch: Batch, accept_len: torch.Tensor, out_tokens: torch.Tensor,

@@ -10,6 +10,7 @@
 #include <string.h>
 
 #include <algorithm>
+#include <mutex>
 #include <new>
 #include <type_traits>
 #include <vector>
@@ -22,6 +23,13 @@
 #include "gemm_tiled.h"
 #include "misc.h"
 #include "moe.h"
+
+// Scratch of dflash_accept_sampled_noalloc (the entry point for callers that cannot allocate): the rows' softmax
+// statistics, (max, log-sum-exp) of the target rows followed by those of the draft rows.  Every GPU the library runs
+// on holds its own copy of this array until the process ends; host code reaches it through the address that
+// hipGetSymbolAddress returns for the current device, never through this name.
+#define DFLASH_NOALLOC_MAX_ROWS 4096
+static __device__ __align__(256) unsigned char scratch[2 * DFLASH_NOALLOC_MAX_ROWS * sizeof(float2)];
 
 namespace {
 
@@ -1550,6 +1558,51 @@ int dflash_prefill(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* to
     return CTX_FAIL(ctx, DFLASH_ECAPACITY, "prefill: max_seq_len %d + the longest prompt (%d, padded to whole blocks of %d) exceeds the %d tokens a block-table row covers",
                     batch->max_seq_len, longest, B, ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE);
   return DISPATCH(ctx, prefill(batch, tokens, prompt_lens, first_tokens));
+}
+
+// address of `scratch` on the current device, looked up once per device
+static int noalloc_scratch(void** out) {
+  static std::mutex mu;
+  static void* ptrs[64] = {nullptr};
+  int dev = -1;
+  if (hipGetDevice(&dev) != hipSuccess || dev < 0 || dev >= 64) return fail(nullptr, DFLASH_EHIP, "accept_sampled_noalloc: cannot tell the current device");
+  std::lock_guard<std::mutex> lock(mu);
+  if (!ptrs[dev]) {
+    void* p = nullptr;
+    const hipError_t e = hipGetSymbolAddress(&p, HIP_SYMBOL(scratch));
+    if (e != hipSuccess || !p) return fail(nullptr, DFLASH_EHIP, "accept_sampled_noalloc: hipGetSymbolAddress failed: %s", hipGetErrorString(e));
+    ptrs[dev] = p;
+  }
+  *out = ptrs[dev];
+  return DFLASH_OK;
+}
+
+int dflash_accept_sampled_noalloc(const float* target_logits, const float* draft_logits, const int32_t* draft_tokens, const float* uniforms,
+                                  const uint64_t* rng_key, float temperature, int32_t n_seqs, int32_t block_size, int32_t vocab,
+                                  int32_t* accept_len, int32_t* out_tokens, void* stream) {
+  if (n_seqs == 0) return DFLASH_OK;
+  if (!target_logits || !draft_logits || !draft_tokens || !uniforms || !rng_key || !accept_len || !out_tokens)
+    return fail(nullptr, DFLASH_EINVAL, "accept_sampled_noalloc: null pointer");
+  if (!(temperature > 0.f)) return fail(nullptr, DFLASH_EINVAL, "accept_sampled_noalloc: temperature must be positive (greedy acceptance needs no scratch: dflash_accept)");
+  if (n_seqs < 0 || block_size < 2 || block_size > DFLASH_MAX_BLOCK || vocab < 1)
+    return fail(nullptr, DFLASH_EINVAL, "accept_sampled_noalloc: need n_seqs >= 0, block_size in [2,%d], vocab >= 1", DFLASH_MAX_BLOCK);
+  if ((int64_t)n_seqs * block_size > DFLASH_NOALLOC_MAX_ROWS)
+    return fail(nullptr, DFLASH_ECAPACITY, "accept_sampled_noalloc: %lld rows exceed the %d rows of the built-in scratch array",
+                (long long)n_seqs * block_size, DFLASH_NOALLOC_MAX_ROWS);
+  void* base = nullptr;
+  int rc;
+  if ((rc = noalloc_scratch(&base))) return rc;
+  float2* stats_p = reinterpret_cast<float2*>(base);
+  float2* stats_q = stats_p + DFLASH_NOALLOC_MAX_ROWS;
+  hipStream_t st = (hipStream_t)stream;
+  const int M = n_seqs * block_size;
+  const float inv_T = 1.0f / temperature;
+  hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, target_logits, vocab, inv_T, stats_p);
+  hipLaunchKernelGGL(row_lse_kernel, dim3(M), dim3(1024), 0, st, draft_logits, vocab, inv_T, stats_q);
+  hipLaunchKernelGGL(accept_sampling_kernel, dim3(n_seqs), dim3(1024), 0, st, target_logits, draft_logits, stats_p, stats_q, draft_tokens, uniforms,
+                     rng_key, vocab, block_size, inv_T, accept_len, out_tokens);
+  if (hipGetLastError() != hipSuccess) return fail(nullptr, DFLASH_EHIP, "accept_sampled_noalloc: launch failed");
+  return DFLASH_OK;
 }
 
 static int kv_copy_checked(dflash_ctx* ctx, const dflash_batch* batch, int32_t pool, int32_t layer, int32_t seq, int32_t start, int32_t count,
