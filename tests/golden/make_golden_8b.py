@@ -214,6 +214,22 @@ def main():
             json.dump(results, open(out_path, "w"), indent=0)
             print(f"[{time.time()-t0:7.1f}s]   accept_len {rec['accept_len']} emitted {rec['emitted']} "
                   f"min margins draft {min(rec['draft_margin']):.4f} target {min(rec['tgt_margin']):.4f}", flush=True)
+    if "--exact" in sys.argv and "cfg2_seq0" in results and ("tgt_logits_cols_exact" not in results["cfg2_seq0"] or "--redo" in sys.argv):
+        # configuration 2 once more in exact arithmetic (no storage rounding anywhere) on the same cached rows and the
+        # same block: what the GPU's distance from the unrounded model is measured against
+        w = si.workload(2)
+        if wt is None:
+            print(f"[{time.time()-t0:7.1f}s] generating weights (seed {w.wseed})", flush=True)
+            wt, wd = si.make_weights(w, 8)
+        rec = results["cfg2_seq0"]
+        st = load_state(w, 0, rec["n"])
+        print(f"[{time.time()-t0:7.1f}s] cfg 2 seq 0 in exact arithmetic", flush=True)
+        r = O.spec_step(getter(wt), getter(wd), w.target, w.draft, w.tap_layers, st, w.block_size, w.mask_token_id, O.identity,
+                        proposal=rec["block"][1:])
+        cols = np.array(rec["cols"])
+        rec["tgt_logits_cols_exact"] = [[float(x) for x in r["logits"][j][cols]] for j in range(w.block_size)]
+        rec["draft_logits_cols_exact"] = [[float(x) for x in r["draft_logits"][j][cols]] for j in range(w.block_size)]
+        json.dump(results, open(out_path, "w"), indent=0)
     print(f"[{time.time()-t0:7.1f}s] wrote {out_path}", flush=True)
 
 

@@ -92,6 +92,14 @@ def _compare_step(name, v, out, g, w, stats):
     stats["max_err_t"] = max(stats["max_err_t"], float(err_t))
     assert err_d <= TOL, f"{name}: draft logits {err_d}"
     assert err_t <= TOL, f"{name}: target logits {err_t}"
+    if "tgt_logits_cols_exact" in v:
+        # the same block in exact arithmetic (no storage rounding anywhere): the distance of the bf16 model as evaluated
+        # by the kernels from the unrounded model -- reported and bounded loosely; it is the oracle's own distance too
+        ex_t = np.abs(out["logits_t"][s][:, cols] - np.array(v["tgt_logits_cols_exact"])).max()
+        ex_o = np.abs(np.array(v["tgt_logits_cols"]) - np.array(v["tgt_logits_cols_exact"])).max()
+        stats["max_err_t_vs_exact"] = float(ex_t)
+        print(f"{name}: target logits against exact arithmetic: GPU {ex_t:.4f}, the oracle's bf16 model {ex_o:.4f} (logit spread {v['logit_std']:.3f})", flush=True)
+        assert ex_t < 0.1 * v["logit_std"]
     for j in range(1, Bk):
         stats["rows"] += 1
         if out["drafted"][s, j] != v["oracle_draft"][j - 1]:

@@ -167,3 +167,105 @@ def test_machine_probes_report_plausible_rates():
         B.dflash_probe_hbm_read(buf, 1000, 1)
     with pytest.raises(B.DFlashError):
         B.dflash_probe_mfma(2, 512, 10)
+
+
+@pytest.mark.parametrize("kind", ["small_bf16", "fp32"])
+def test_several_steps_in_one_graph_against_the_oracle(kind):
+    """The resident decode loop: THREE consecutive speculative steps captured into one HIP graph (lengths, anchors and
+    caches stay on the device between them; the proposals that force accept lengths through the range are copied in by
+    device-to-device copies inside the graph), replayed once, and every step compared with the CPU oracle's step --
+    draft and target logits, drafted tokens, target tokens, accept lengths, emitted tokens, slot ids -- not with an
+    eager run of the same kernels.  The oracle runs first: given equal states the two sides evolve identically, so its
+    proposals are the ones the captured steps verify."""
+    import torch
+    import paper_2602_06036_amd as dfl
+    from oracle import dflash_oracle as O
+    from tests.test_gpu_parity import Lockstep, MARGIN, TOL
+    n_steps = 3
+    if kind == "fp32":
+        w = tiny_workload(seed=25, n_layers=2, draft_layers=1, vocab=512, block=8, n_seqs=2, taps=(0,))
+        prompts = [p[:n] for p, n in zip(si.make_prompts(replace(w, ctx_min=40, ctx_max=40)), (40, 27))]
+        plans = [[7, 0], [2, 5], [0, 7]]
+    else:
+        w = si.small_bf16_workload(n_seqs=3, ctx_min=20, ctx_max=90, seed=37)
+        prompts = si.make_prompts(w)
+        plans = [[15, 0, 9], [3, 15, 1], [0, 6, 15]]
+    Bk, S, V = w.block_size, len(prompts), w.target.vocab
+    ls = Lockstep(w, prompts, max_len=max(len(p) for p in prompts) + (n_steps + 2) * Bk)
+    first, got, mism = ls.prefill()
+    assert not mism
+    g = ls.g
+    dev = g.dev
+    # the oracle's three steps (on copies of its states, which the comparison below steps again): proposals per step
+    import copy
+    states = copy.deepcopy(ls.states)
+    proposals = []
+    for k in range(n_steps):
+        prop = np.stack([ls._true_continuation(st, plans[k][s]) for s, st in enumerate(states)])
+        proposals.append(prop)
+        for s, st in enumerate(states):
+            O.spec_step(ls.Wt, ls.Wd, w.target, w.draft, w.tap_layers, st, Bk, w.mask_token_id, ls.rnd, proposal=prop[s])
+    prop_dev = [torch.from_numpy(p.astype(np.int32)).to(dev) for p in proposals]
+    outs = [dict(draft=torch.zeros((S, Bk), dtype=torch.int32, device=dev), block=torch.zeros((S, Bk), dtype=torch.int32, device=dev),
+                 tgt=torch.zeros((S, Bk), dtype=torch.int32, device=dev), acc=torch.zeros(S, dtype=torch.int32, device=dev),
+                 out=torch.zeros((S, Bk), dtype=torch.int32, device=dev), slots=torch.zeros((S, Bk), dtype=torch.int64, device=dev),
+                 ld=torch.zeros((S, Bk, V), dtype=torch.float32, device=dev), lt=torch.zeros((S, Bk, V), dtype=torch.float32, device=dev))
+            for _ in range(n_steps)]
+    bound = int(g.host_lens.max()) + n_steps * Bk
+    batch = g.e.batch(g.seq_lens, g.block_table, g.anchor, bound)
+
+    def enqueue():
+        for k in range(n_steps):
+            o = outs[k]
+            dfl.dflash_draft_block(g.e, batch, o["block"], 0.0, None, o["ld"])
+            o["draft"].copy_(o["block"])
+            o["block"][:, 1:].copy_(prop_dev[k])
+            dfl.dflash_verify(g.e, batch, o["block"], o["tgt"], o["lt"])
+            dfl.dflash_accept(g.e, batch, o["block"], o["tgt"], o["acc"], o["out"])
+            dfl.dflash_kv_commit(g.e, batch, o["acc"], o["out"], o["slots"])
+
+    snap = _snapshot(g)
+    side = torch.cuda.Stream()
+    side.wait_stream(torch.cuda.current_stream())
+    with torch.cuda.stream(side):
+        enqueue()                                               # warm-up on the capture stream, then undo it
+    torch.cuda.synchronize(dev)
+    _restore(g, snap)
+    torch.cuda.synchronize(dev)
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.graph(graph, stream=side):
+        enqueue()
+    torch.cuda.synchronize(dev)
+    _restore(g, snap)
+    for o in outs:
+        for t in o.values():
+            t.zero_()
+    torch.cuda.synchronize(dev)
+    graph.replay()
+    torch.cuda.synchronize(dev)
+    g.e.device_status()
+    tol = TOL[w.dtype]
+    lens = g.host_lens.copy()
+    for k in range(n_steps):
+        o = {n: t.cpu().numpy() for n, t in outs[k].items()}
+        assert np.array_equal(o["block"][:, 1:], proposals[k])
+        for s, st in enumerate(ls.states):
+            r = O.spec_step(ls.Wt, ls.Wd, w.target, w.draft, w.tap_layers, st, Bk, w.mask_token_id, ls.rnd, proposal=proposals[k][s])
+            assert o["block"][s, 0] == r["block"][0], f"step {k} seq {s}: anchor"
+            assert np.abs(o["ld"][s, 1:] - r["draft_logits"][1:]).max() <= tol, f"step {k} seq {s}: draft logits"
+            assert np.abs(o["lt"][s] - r["logits"]).max() <= tol, f"step {k} seq {s}: target logits"
+            for j in range(1, Bk):
+                assert o["draft"][s, j] == int(np.argmax(r["draft_scores"][j])) or O.top2_margin(r["draft_scores"][j]) < MARGIN
+            flips = [j for j in range(Bk) if o["tgt"][s, j] != r["tgt_argmax"][j]]
+            for j in flips:
+                assert O.top2_margin(r["logits"][j]) < MARGIN, f"step {k} seq {s}: target token row {j}"
+            a = r["accept_len"]
+            if flips:
+                pytest.skip("a near-tie of the target's two best logits makes the later captured steps differ from the oracle's (legitimately)")
+            assert o["acc"][s] == a == plans[k][s] and list(o["out"][s, : a + 1]) == r["emitted"] and (o["out"][s, a + 1:] == -1).all()
+        assert np.array_equal(o["slots"], g.expected_slots(lens, o["acc"]))
+        lens = lens + o["acc"] + 1
+    assert np.array_equal(g.seq_lens.cpu().numpy(), lens)
+    g.host_lens = lens
+    ls.check_cache([0, w.target.n_layers - 1], [0])
+    g.e.close()

@@ -255,8 +255,21 @@ def test_small_bf16_model_steps_and_cache():
     first, got, mism = ls.prefill()      # (a first-token flip is accepted on a near tie only: Lockstep.prefill checks)
     ls.check_cache([0, 3, 7], [0, 1])
     plans = [None, [15, 0, 9], [3, 15, 15], None, [8, 2, 0], [15, 15, 15]]
+    import copy
     for i, plan in enumerate(plans):
+        before = copy.deepcopy(ls.states) if i == 1 else None
         out, res = ls.step(plan=plan, step_idx=i)
+        if before is not None:
+            # the same step in exact arithmetic (no storage rounding anywhere) from the same cached rows: how far the bf16
+            # model as the kernels evaluate it is from the unrounded one -- reported, and bounded loosely (the parity bound
+            # above is against the oracle's model of the bf16 storage points, which this figure does not depend on)
+            worst = 0.0
+            for s, st in enumerate(before):
+                r = O.spec_step(ls.Wt, ls.Wd, w.target, w.draft, w.tap_layers, st, w.block_size, w.mask_token_id, O.identity,
+                                proposal=out["block"][s, 1:])
+                worst = max(worst, float(np.abs(out["logits_t"][s] - r["logits"]).max() / r["logits"].std()))
+            print(f"GPU target logits against the oracle in exact arithmetic: max abs difference {100 * worst:.2f} % of the logit spread")
+            assert worst < 0.08
     ls.check_cache([0, 7], [0, 1])
     print("small bf16 stats", ls.stats)
     assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2

@@ -21,6 +21,29 @@ def test_round_bf16_matches_torch_cast():
     assert O.round_bf16(np.array([1.01171875]))[0] == 1.015625     # tie -> even (up)
 
 
+def test_round_bf16_pair_is_two_bf16_numbers_with_sixteen_bits():
+    """hi + lo storage of a GEMM input: hi and lo are each representable in bf16 (checked against torch's cast, not
+    against the oracle's own rounding), hi is the nearest bf16 to x, lo the nearest bf16 to the fp32 remainder, and the
+    pair is within 2^-16 |x| of x (two 8-bit significands less the overlap); a value with at most 16 significant bits
+    that are split evenly is reproduced exactly."""
+    rng = np.random.default_rng(3)
+    x = np.concatenate([rng.standard_normal(4000) * 10.0 ** rng.integers(-6, 6, 4000), [0.0, 1.0, -1.0, 3.0e-5, 65280.0]])
+    x = x.astype(np.float32).astype(np.float64)
+    r = O.round_bf16_pair(x)
+    xt = torch.from_numpy(x.astype(np.float32))
+    hi = xt.to(torch.bfloat16).to(torch.float32)
+    lo = (xt - hi).to(torch.bfloat16).to(torch.float32)
+    assert np.array_equal(r, hi.double().numpy() + lo.double().numpy())
+    lo_o = torch.from_numpy((r - hi.double().numpy()).astype(np.float32))
+    assert torch.equal(lo_o.to(torch.bfloat16).to(torch.float32), lo_o)          # what is left beside hi is one bf16 number
+    assert (np.abs(x - r) <= 2.0 ** -16 * np.abs(x)).all()
+    assert np.abs(x - r).max() > 0                                               # and it is a rounding, not the identity
+    exact = np.array([1.0 + 2.0 ** -7 + 2.0 ** -14, 3.0 - 2.0 ** -13, -(2.0 ** 20 + 2.0 ** 6)])
+    assert np.array_equal(O.round_bf16_pair(exact), exact)
+    single = O.round_bf16(x)
+    assert np.abs(x - single).max() / np.abs(x - r).max() > 50                   # the pair is far finer than one bf16 number
+
+
 def test_rmsnorm_library_and_scale_invariance():
     rng = np.random.default_rng(2)
     x = rng.standard_normal((5, 96))
