@@ -281,7 +281,7 @@ def cpu_baseline(w, ctx):
                        (w.target.n_layers, w.draft.n_layers, Bk, ctx, layer_t / max(times["t", 1], 1e-9), layer_d / max(times["d", 1], 1e-9), step))
 
 
-def run_workload(name, args, dev, K, Wm, blobs=None):
+def run_workload(name, args, dev, K, Wm, blobs=None, draft_only=False):
     """K timed steps of one named workload after Wm warm-up steps (and, unless --no-profile, the same K steps again with
     an event pair around every GEMM / attention launch).  Returns (the result dictionary, the packed weights)."""
     import torch
@@ -441,6 +441,24 @@ def run_workload(name, args, dev, K, Wm, blobs=None):
         "step_roofline": step_roofline(w, S, ctx, ms_step),
     }
     out.update(extra)
+    if draft_only:
+        # Section 3.2, Eq. 3: a block-diffusion drafter's cost is one parallel pass whatever the number of drafted tokens.
+        # The draft call alone, at the context's block size and at smaller ones chosen per call (dflash_batch::block_size).
+        per_block = {}
+        for blk in sorted({Bk, max(2, Bk // 2), max(2, Bk // 4), 2}, reverse=True):
+            dt = torch.zeros((S, blk), dtype=torch.int32, device=dev)
+            b = e.batch(seq_lens, table, anchor, state["upper"], blk)
+            for _ in range(3):
+                dfl.dflash_draft_block(e, b, dt, T, rng_key)
+            torch.cuda.synchronize(dev)
+            ev0.record()
+            for _ in range(K):
+                dfl.dflash_draft_block(e, b, dt, T, rng_key)
+            ev1.record()
+            torch.cuda.synchronize(dev)
+            per_block[str(blk)] = ev0.elapsed_time(ev1) / K
+        e.device_status()
+        out["draft_only_ms_by_block_size"] = per_block
     blobs = (e.target_blob, e.draft_blob)
     e.close()
     del e, table
@@ -497,7 +515,7 @@ def main():
     else:
         # default: the headline workload (configuration 2) in full, then configurations 3, 4 and 5 with the same packed
         # weights and fewer steps, each as a compact record under "configs"
-        out, blobs, w, ctx = run_workload("cfg2_8b_b1_ctx2048", args, dev, args.steps, args.warmup)
+        out, blobs, w, ctx = run_workload("cfg2_8b_b1_ctx2048", args, dev, args.steps, args.warmup, draft_only=True)
         out["configs"] = {}
         for name in ("cfg3_8b_b16_ctx2560", "cfg4_8b_b4_ctx16k", "cfg5_8b_b32_ctx8k"):
             r, blobs, _, _ = run_workload(name, args, dev, max(5, args.steps // 3), min(args.warmup, 3), blobs=blobs)

@@ -91,8 +91,8 @@ struct GemmBuf {
   u32x4 w[U][NT], ah[U][MT], al[U][MT];
 };
 
-template <int NT, int MT, int U, int EPI, bool GRP = false, int PH = 1>
-__global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
+template <int NT, int MT, int U, int EPI, bool GRP = false, int PH = 1, int NW = 4>
+__global__ __launch_bounds__(64 * NW, (NW > 4 ? 1 : PH)) void gemm_bf16_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A,
                                                         int M, int N, int K, EpiArgs ep) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
   const int kz = blockIdx.z;
@@ -114,8 +114,8 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
     m_tiles = item.z;
   }
   const int ks = gridDim.z;
-  const int per = (KT + ks * 4 - 1) / (ks * 4);
-  const int kb = min(KT, (kz * 4 + wave) * per);
+  const int per = (KT + ks * NW - 1) / (ks * NW);
+  const int kb = min(KT, (kz * NW + wave) * per);
   const int ke = min(KT, kb + per);
 
   f32x4 acc[NT][MT];
@@ -156,25 +156,31 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
       }
     }
   };
+  // all hi products of a k tile, then all lo products: two MFMAs on the same accumulator are never back to back (the
+  // second would wait out the first one's passes)
   auto compute = [&](const GemmBuf<NT, MT, U>& b) {
 #pragma unroll
-    for (int u = 0; u < U; ++u)
+    for (int u = 0; u < U; ++u) {
 #pragma unroll
       for (int i = 0; i < NT; ++i)
 #pragma unroll
-        for (int j = 0; j < MT; ++j) {
+        for (int j = 0; j < MT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b.w[u][i]),
                                                               __builtin_bit_cast(bf16x8, b.ah[u][j]), acc[i][j], 0, 0, 0);
+#pragma unroll
+      for (int i = 0; i < NT; ++i)
+#pragma unroll
+        for (int j = 0; j < MT; ++j)
           acc[i][j] = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b.w[u][i]),
                                                               __builtin_bit_cast(bf16x8, b.al[u][j]), acc[i][j], 0, 0, 0);
-        }
+    }
   };
 
   // Deferred RMSNorm: 1 / rms of this workgroup's rows, 16 threads per row, each adding every 16th piece in
   // ascending order, then the 16 partial sums by a fixed shuffle tree.  Written to LDS here, read after the
   // barrier of the cross-wavefront sum.
   __shared__ float s_rstd[MT * 16];
-  if (ep.ssq) {
+  if (ep.ssq && threadIdx.x < 256) {
     const int r = threadIdx.x >> 4, c = threadIdx.x & 15;
 #pragma unroll
     for (int j = 0; j < MT; ++j) {
@@ -205,7 +211,7 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
   // time, and the wait for the older buffer would then have to drain the newer one as well.  The last one or two
   // stages are peeled off; if the range has an odd number of stages the final load re-reads the last tile
   // (still in cache) and meets zeroed activations.
-  if constexpr (PH == 2) {
+  if constexpr (PH == 2 && NW == 4) {
     // one buffer only (and the cross-wavefront sum below in two halves): half the registers and half the LDS, so that
     // two workgroups share a CU and their wavefronts cover each other's waits
     GemmBuf<NT, MT, U> b;
@@ -231,14 +237,14 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
   // The four wavefronts' partial sums meet in LDS, PH phases of NT / PH weight tiles each (PH = 2 halves the buffer).
   constexpr int HT = NT / PH;
   static_assert(NT % PH == 0 && (EPI != EPI_SWIGLU || HT % 2 == 0), "phases");
-  __shared__ float4 red[4][HT * MT][64];
+  __shared__ float4 red[NW][HT * MT][64];
   const int mrow = lane & 15, g = lane >> 4;
   // the four wavefronts' partial sums of tile t (= weight tile * MT + band) of the current phase, in wavefront order,
   // times the row's deferred 1 / rms
   auto tile_sum = [&](int t) {
     float4 s = red[0][t][lane];
 #pragma unroll
-    for (int w = 1; w < 4; ++w) {
+    for (int w = 1; w < NW; ++w) {
       const float4 a = red[w][t][lane];
       s.x += a.x; s.y += a.y; s.z += a.z; s.w += a.w;
     }
@@ -259,7 +265,7 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
     __syncthreads();
     if (EPI == EPI_SWIGLU) {
       bf16_t* act = reinterpret_cast<bf16_t*>(ep.act);
-      for (int t = wave; t < (HT / 2) * MT; t += 4) {
+      for (int t = wave; t < (HT / 2) * MT; t += NW) {
         const int p = t / MT, j = t % MT;
         const float4 gs = tile_sum((2 * p) * MT + j), us = tile_sum((2 * p + 1) * MT + j);
         const int m = (mt0 + j) * 16 + mrow;
@@ -270,7 +276,7 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
         }
       }
     } else if (ep.out) {
-      for (int t = wave; t < HT * MT; t += 4) {
+      for (int t = wave; t < HT * MT; t += NW) {
         const int i = t / MT, j = t % MT;
         const float4 s = tile_sum(t);
         const int m = (mt0 + j) * 16 + mrow;
@@ -282,18 +288,20 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
     }
   };
   phase(std::integral_constant<int, 0>{});
-  if constexpr (PH == 2) phase(std::integral_constant<int, 1>{});
+  if constexpr (PH >= 2) phase(std::integral_constant<int, 1>{});
+  if constexpr (PH >= 3) phase(std::integral_constant<int, 2>{});
+  static_assert(PH <= 3, "phases");
 
   if constexpr (EPI != EPI_SWIGLU && PH == 1) {
     if (ep.amax) {   // fused argmax over this workgroup's NT*16 columns (host guarantees a single K range)
-      __shared__ float2 wbest[4][MT * 16];
+      __shared__ float2 wbest[NW][MT * 16];
       const uint64_t key = ep.amax_mode ? ep.amax_key[0] : 0ull;
 #pragma unroll
       for (int j = 0; j < MT; ++j) {
         const int m = (mt0 + j) * 16 + mrow;
         float bv = -INFINITY;
         int bi = 0x7FFFFFFF;
-        for (int i = wave; i < NT; i += 4) {
+        for (int i = wave; i < NT; i += NW) {
           const float4 s = tile_sum(i * MT + j);
           const int col = (nt0 + i) * 16 + 4 * g;
           argmax_combine(bv, bi, amax_score(ep, key, s.x, m, col), col);
@@ -310,33 +318,33 @@ __global__ __launch_bounds__(256, PH) void gemm_bf16_kernel(const bf16_t* __rest
         if (g == 0) wbest[wave][j * 16 + mrow] = make_float2(bv, __int_as_float(bi));
       }
       __syncthreads();
-      for (int r = threadIdx.x; r < MT * 16; r += 256) {
+      for (int r = threadIdx.x; r < MT * 16; r += 64 * NW) {
         const int m = mt0 * 16 + r;
         if (m >= M) continue;
         float bv = wbest[0][r].x;
         int bi = __float_as_int(wbest[0][r].y);
 #pragma unroll
-        for (int w = 1; w < 4; ++w) argmax_combine(bv, bi, wbest[w][r].x, __float_as_int(wbest[w][r].y));
+        for (int w = 1; w < NW; ++w) argmax_combine(bv, bi, wbest[w][r].x, __float_as_int(wbest[w][r].y));
         ep.amax[(size_t)m * gridDim.x + blockIdx.x] = make_float2(bv, __int_as_float(bi));
       }
     }
     if (ep.lse) {   // fused softmax statistics over this workgroup's NT*16 columns (single K range)
-      __shared__ float2 wl[4][MT * 16];
+      __shared__ float2 wl[NW][MT * 16];
       __syncthreads();
 #pragma unroll
       for (int j = 0; j < MT; ++j) {
         float lm = -INFINITY, ls = 0.f;
-        for (int i = wave; i < NT; i += 4) lse_add4(lm, ls, tile_sum(i * MT + j), ep.lse_inv_T);
+        for (int i = wave; i < NT; i += NW) lse_add4(lm, ls, tile_sum(i * MT + j), ep.lse_inv_T);
         lse_combine_row(lm, ls);
         if (g == 0) wl[wave][j * 16 + mrow] = make_float2(lm, ls);
       }
       __syncthreads();
-      for (int r = threadIdx.x; r < MT * 16; r += 256) {
+      for (int r = threadIdx.x; r < MT * 16; r += 64 * NW) {
         const int m = mt0 * 16 + r;
         if (m >= M) continue;
         float lm = wl[0][r].x, ls = wl[0][r].y;
 #pragma unroll
-        for (int w = 1; w < 4; ++w) lse_combine(lm, ls, wl[w][r].x, wl[w][r].y);
+        for (int w = 1; w < NW; ++w) lse_combine(lm, ls, wl[w][r].x, wl[w][r].y);
         ep.lse[(size_t)m * gridDim.x + blockIdx.x] = make_float2(lm, ls);
       }
     }
