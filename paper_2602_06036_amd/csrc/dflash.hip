@@ -1546,13 +1546,15 @@ int dflash_prefill(dflash_ctx* ctx, const dflash_batch* batch, const int32_t* to
   int rc;
   if ((rc = check_batch(ctx, batch))) return rc;
   if (batch->n_seqs == 0) return DFLASH_OK;
-  if (!tokens || !prompt_lens) return CTX_FAIL(ctx, DFLASH_EINVAL, "prefill: null tokens or prompt_lens");
+  if (!prompt_lens) return CTX_FAIL(ctx, DFLASH_EINVAL, "prefill: null prompt_lens");
   const int B = batch->block_size > 0 ? batch->block_size : ctx->rt.block_size;
   int longest = 0;
   for (int s = 0; s < batch->n_seqs; ++s) {
     if (prompt_lens[s] < 0) return CTX_FAIL(ctx, DFLASH_EINVAL, "prefill: negative prompt length");
     longest = std::max(longest, prompt_lens[s]);
   }
+  if (longest == 0) return DFLASH_OK;   // no sequence has new tokens
+  if (!tokens) return CTX_FAIL(ctx, DFLASH_EINVAL, "prefill: null tokens");
   // the last chunk of a prompt is padded to a whole block of rows, whose K/V rows are written too (invisible)
   if ((int64_t)batch->max_seq_len + (longest + B - 1) / B * B > (int64_t)ctx->rt.max_pages_per_seq * DFLASH_PAGE_SIZE)
     return CTX_FAIL(ctx, DFLASH_ECAPACITY, "prefill: max_seq_len %d + the longest prompt (%d, padded to whole blocks of %d) exceeds the %d tokens a block-table row covers",

@@ -555,6 +555,43 @@ def test_prefill_entry_point(kind, max_seqs, pieces):
     assert ls.stats["reseeds"] <= 1 + ls.stats["route_ties"]
 
 
+def test_prefill_entry_point_edges():
+    """dflash_prefill: a sequence without new tokens is left untouched (length, anchor, caches), a call with no new tokens at
+    all is a no-op, a prompt whose padded length does not fit the block table is refused on the host, and a prompt exactly
+    one block long ends on the block's last row."""
+    import torch
+    import paper_2602_06036_amd as dfl
+    from paper_2602_06036_amd import binding as B
+    w = tiny_workload(seed=17, n_layers=2, draft_layers=1, vocab=256, block=8, n_seqs=3, taps=(0,))
+    prompts = [p[:n] for p, n in zip(si.make_prompts(replace(w, ctx_min=40, ctx_max=40)), (0, 8, 23))]
+    ls = Lockstep(w, prompts, max_len=48, max_seqs=4)
+    g = ls.g
+    g.anchor.fill_(77)
+    first = torch.full((3,), -5, dtype=torch.int32, device=g.dev)
+    dfl.dflash_prefill(g.e, g.batch(), torch.zeros(0, dtype=torch.int32, device=g.dev), [0, 0, 0], first)      # nothing to do
+    torch.cuda.synchronize(g.dev)
+    assert g.seq_lens.cpu().tolist() == [0, 0, 0] and first.cpu().tolist() == [-5, -5, -5]
+    toks = torch.from_numpy(np.concatenate(prompts).astype(np.int32)).to(g.dev)
+    dfl.dflash_prefill(g.e, g.batch(), toks, [0, 8, 23], first)
+    torch.cuda.synchronize(g.dev)
+    g.e.device_status()
+    assert g.seq_lens.cpu().tolist() == [0, 8, 23]
+    assert g.anchor.cpu().tolist()[0] == 77 and first.cpu().tolist()[0] == -5
+    g.host_lens[:] = [0, 8, 23]
+    for s in (1, 2):
+        st = ls.states[s]
+        tok, row = O.prefill_with_logits(ls.Wt, ls.Wd, w.target, w.draft, w.tap_layers, prompts[s], st, ls.rnd)
+        assert int(first[s]) == tok == int(g.anchor[s]) or O.top2_margin(row) < MARGIN
+    ls.check_cache([0, 1], [0], seqs=[1, 2])
+    with pytest.raises(B.DFlashError) as ei:                     # 23 cached + 26 new tokens, padded to 32: beyond the 48-token table
+        dfl.dflash_prefill(g.e, g.batch(), torch.zeros(26, dtype=torch.int32, device=g.dev), [0, 0, 26], first)
+    assert ei.value.code == B.DFLASH_ECAPACITY
+    with pytest.raises(B.DFlashError) as ei:
+        dfl.dflash_prefill(g.e, g.batch(), torch.zeros(1, dtype=torch.int32, device=g.dev), [0, -1, 2], first)
+    assert ei.value.code == B.DFLASH_EINVAL
+    g.e.close()
+
+
 @pytest.mark.parametrize("n_seqs,top_k,seed", [(10, 4, 72), (3, 2, 61)])
 def test_small_moe_target_with_128_row_expert_items(n_seqs, top_k, seed, monkeypatch):
     """The grouped launches of the LDS-staged GEMM (work items of up to 8 bands, used from about a hundred rows per expert
