@@ -109,6 +109,17 @@ def test_graph_replay_small_bf16_greedy_and_sampling():
     _run(replace(w, temperature=1.0), prompts, 1.0)
 
 
+@pytest.mark.parametrize("fuse", ["1", "2"])
+def test_graph_replay_single_band_of_rows(fuse, monkeypatch):
+    """Batch 1 at B = 16 (one band of rows: the unsplit projections with the residual update and the deferred RMSNorm) replays
+    like every other shape, greedy and sampled."""
+    monkeypatch.setenv("DFLASH_FUSE", fuse)
+    w = si.small_bf16_workload(n_seqs=1, ctx_min=40, ctx_max=90, seed=17)
+    prompts = si.make_prompts(w)
+    _run(w, prompts, 0.0)
+    _run(replace(w, temperature=1.0), prompts, 1.0)
+
+
 @pytest.mark.parametrize("n_seqs", [3, 10])
 def test_graph_replay_routed_expert_target(n_seqs):
     """The routed-expert step is graph-capturable too: routing, the expert-sorted row list and the work items live on the
