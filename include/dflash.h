@@ -246,6 +246,13 @@ int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count
  * GEMMs had to read.  Synchronises the stream and clears all five. */
 int dflash_moe_stats(dflash_ctx *ctx, void *stream, int64_t *out);
 
+/* Routed-expert targets, state export for tests and debugging: while `choices` (device, [n_layers, max_seqs * block_size,
+ * top_k] int32, caller-owned) is set, every routed target layer leaves the experts it chose for row m (by decreasing
+ * router logit) at choices[(layer * max_seqs * block_size + m) * top_k ..]; NULL switches the trace off again.  Rows
+ * beyond the call's S * B rows are not written.  The routing itself is unchanged (the kernels keep their choices there
+ * instead of in the workspace). */
+int dflash_moe_trace(dflash_ctx *ctx, int32_t *choices);
+
 /* ---- machine probes (benchmarks; not part of the method) -----------------------------------------
  * What one launch can reach on this GPU, to put the kernels' figures beside: neither needs a context.
  * dflash_probe_hbm_read: `launches` back-to-back kernels (256 workgroups of 256 threads, 8 non-temporal 1 KB

@@ -180,6 +180,7 @@ def _attend(m, q: np.ndarray, K: np.ndarray, V: np.ndarray) -> np.ndarray:
 
 ROUTE_MARGINS: Optional[List[float]] = None   # a test may set this to a list: every routing decision then appends
                                               # the gap between the last chosen and the best rejected router logit
+ROUTE_CHOICES: Optional[List[List[int]]] = None   # likewise: the chosen experts of every routing decision, ascending
 
 
 def moe_route(logits: np.ndarray, top_k: int):
@@ -202,6 +203,8 @@ def _ffn(W, m, pre: str, h: np.ndarray, rnd: "Rounding") -> np.ndarray:
             idx, wts = moe_route(router[t], m.top_k)
             if ROUTE_MARGINS is not None and m.top_k < m.n_experts:
                 ROUTE_MARGINS.append(float(router[t, idx[-1]] - np.delete(router[t], idx).max()))
+            if ROUTE_CHOICES is not None:
+                ROUTE_CHOICES.append(sorted(int(e) for e in idx))
             for e, wt in zip(idx, wts):
                 act = rnd.at("ffn_act")(silu(Wg[e] @ a[t]) * (Wu[e] @ a[t]))
                 out[t] += wt * (Wd[e] @ act)

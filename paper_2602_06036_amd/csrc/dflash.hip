@@ -352,6 +352,7 @@ struct dflash_ctx {
   char* wsp;
   char err[512];
   Knobs k;                                             // tuning / testing knobs as they stood when the context was created
+  int32_t* moe_trace = nullptr;                        // dflash_moe_trace: where the routed layers also leave their expert choices
   bool have_logits_d = false, have_logits_t = false;   // the workspace holds this step's draft / target logits
   float draft_temperature = 0.f;                       // of the last dflash_draft_block call
   float stats_q_T = 0.f, stats_p_T = 0.f;              // > 0: ws.stats_q / ws.stats_p hold this step's (max, log-sum-exp) rows at that temperature
@@ -436,6 +437,7 @@ struct Engine {
 
   // Few-row path: ws.a holds x * gain with the division by the row's rms deferred to the GEMM that reads it; the
   // pieces of the rows' sums of squares are in ws.ssq (see gemm_resid.h)
+  int cur_layer = 0;     // layer index of the layer() call in progress (routed experts: row of the choice trace)
   int defer_parts = 0;
   bool few_rows(const dflash_dims& m, int M, int level = 2) const {
     return std::is_same<T, bf16_t>::value && c->k.fuse >= level && !m.n_experts && M <= 16 && m.d_model % 16 == 0;
@@ -543,6 +545,7 @@ struct Engine {
     pending = gemm(reinterpret_cast<const T*>(lbase + lo.wo), o, M, D, qd, EPI_RESID, EpiArgs{h, D, 0, nullptr, 0});
     norm_h(reinterpret_cast<const float*>(lbase + lo.g2), M, D, m.rms_eps);
     if (m.n_experts) {
+      cur_layer = l;
       pending = moe_ffn(m, lbase, lo, M);
       return;
     }
@@ -1063,7 +1066,9 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
   MoeRoute r;
   r.logits = rs.p; r.ks = rs.ks; r.stride = rs.stride;
   r.M = M; r.E = E; r.k = k; r.MT = MT;
-  r.sel_e = ws<int32_t>(c->ws.moe_sel_e); r.sel_w = ws<float>(c->ws.moe_sel_w); r.sel_pos = ws<int32_t>(c->ws.moe_sel_pos);
+  // with a trace buffer the choices of this layer are kept there (the kernels write and re-read them in place)
+  r.sel_e = c->moe_trace ? c->moe_trace + (size_t)cur_layer * c->rt.max_seqs * c->rt.block_size * k : ws<int32_t>(c->ws.moe_sel_e);
+  r.sel_w = ws<float>(c->ws.moe_sel_w); r.sel_pos = ws<int32_t>(c->ws.moe_sel_pos);
   r.row_of = ws<int32_t>(c->ws.moe_row_of);
   r.items = ws<int4>(c->ws.moe_items); r.max_items = n_items;
   r.counters = reinterpret_cast<unsigned long long*>(c->wsp + c->ws.status + 64);
@@ -1493,6 +1498,13 @@ int dflash_moe_stats(dflash_ctx* ctx, void* stream, int64_t* out) {
   if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "stream synchronise failed");
   if (hipMemcpy(out, ctx->wsp + ctx->ws.status + 64, 40, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics read failed");
   if (hipMemset(ctx->wsp + ctx->ws.status + 64, 0, 40) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics clear failed");
+  return DFLASH_OK;
+}
+
+int dflash_moe_trace(dflash_ctx* ctx, int32_t* choices) {
+  if (!ctx) return fail(nullptr, DFLASH_EINVAL, "ctx: null");
+  if (choices && !ctx->t.n_experts) return CTX_FAIL(ctx, DFLASH_EINVAL, "moe_trace: the target has no routed experts");
+  ctx->moe_trace = choices;
   return DFLASH_OK;
 }
 

@@ -84,6 +84,18 @@ def _compare_step(name, v, out, g, w, stats):
         clear = first == L
         assert np.isfinite(out["logits_t"][s]).all() and err_rows.max() < 8 * v["logit_std"]
         assert abs(out["logits_t"][s][:, cols].std() / np.array(v["tgt_logits_cols"]).std() - 1.0) < 0.1
+        trace = getattr(g.e, "_moe_trace", None)
+        if "expert_choices" in v and trace is not None:
+            # rows that went to the oracle's experts in EVERY layer, as did every block row before them (which they attend
+            # to), are the same function evaluation as the oracle's: their final logits are compared strictly
+            got = np.sort(trace.cpu().numpy()[:, s * Bk:(s + 1) * Bk, :], axis=-1)          # [layers, Bk, top_k]
+            same = (got == np.array(v["expert_choices"])).all(-1).all(0)                     # per row: all layers
+            strict = same & (np.cumsum(~same) == 0)
+            stats["rows_with_the_oracles_experts"] = int(same.sum())
+            stats["rows_compared_strictly"] = int(strict.sum())
+            print(f"{name}: rows with the oracle's experts in every layer {np.flatnonzero(same)}, compared strictly {np.flatnonzero(strict)}: "
+                  f"logit error {np.round(err_rows[strict], 4)}", flush=True)
+            clear = clear | strict
         if not clear.any():
             err_rows = np.zeros(Bk)
             clear[:] = False
@@ -146,6 +158,8 @@ def _run_config(shared, cfg, w=None):
     g = GpuModel(w, shared["wt"], shared["wd"], int(lens.max()) + 2 * Bk, blobs=shared["blobs"])
     shared["blobs"] = g.blobs()
     sampled = sorted(v["seq"] for v in golden.values())
+    if w.target.n_experts:
+        g.e.moe_trace()              # the routed layers also leave their expert choices for the comparison below
     g.load_synthetic(sampled)
     print(f"cfg {cfg}: state loaded, sampled sequences {sampled}", flush=True)
     proposals = -np.ones((S, Bk - 1), dtype=np.int64)

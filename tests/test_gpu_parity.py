@@ -592,6 +592,32 @@ def test_prefill_entry_point_edges():
     g.e.close()
 
 
+def test_routed_expert_choices_can_be_traced():
+    """dflash_moe_trace: the experts every row of a verification pass went to, layer by layer, against the oracle's routing
+    of the same block (identical wherever no router logits nearly tie)."""
+    w = si.small_moe_workload(n_seqs=3, ctx_min=12, ctx_max=60, seed=61)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=60 + 3 * 16)
+    ls.prefill()
+    trace = ls.g.e.moe_trace()
+    O.ROUTE_CHOICES = []
+    try:
+        out, res = ls.step()
+        ref = np.array(O.ROUTE_CHOICES)
+    finally:
+        O.ROUTE_CHOICES = None
+    S, L, Bk, k = 3, w.target.n_layers, w.block_size, w.target.top_k
+    ref = ref.reshape(S, L, Bk, k).transpose(1, 0, 2, 3)                     # the oracle steps sequence after sequence
+    got = np.sort(trace.cpu().numpy()[:, : S * Bk], axis=-1).reshape(L, S, Bk, k)
+    same = (got == ref).all(-1)
+    print("routing decisions equal to the oracle's:", int(same.sum()), "of", same.size, "smallest router gap", min(ls.route_gaps))
+    assert (got >= 0).all() and (got < w.target.n_experts).all()
+    assert same.all() or min(ls.route_gaps) < ROUTE_TIE
+    assert same.mean() > 0.97
+    ls.g.e.moe_trace(False)
+    ls.step()                                                                 # and the step runs on without the trace
+
+
 @pytest.mark.parametrize("n_seqs,top_k,seed", [(10, 4, 72), (3, 2, 61)])
 def test_small_moe_target_with_128_row_expert_items(n_seqs, top_k, seed, monkeypatch):
     """The grouped launches of the LDS-staged GEMM (work items of up to 8 bands, used from about a hundred rows per expert
