@@ -522,7 +522,7 @@ def test_prefill_as_one_many_row_pass():
 
 
 @pytest.mark.parametrize("kind,max_seqs,pieces", [("small_bf16", 16, 1), ("small_bf16", 4, 1), ("small_bf16", 16, 3), ("fp32", 8, 1),
-                                                 ("fp32", 3, 2), ("moe", 16, 1)])
+                                                 ("fp32", 3, 2), ("moe", 16, 1), ("single", 1, 1), ("single", 1, 2)])
 def test_prefill_entry_point(kind, max_seqs, pieces):
     """dflash_prefill (Section 4.1: the standard prefill that yields the first token and the target features of every
     prompt token) against the oracle's sequence-form prefill: first tokens, target K/V rows and context K/V rows of all
@@ -537,6 +537,10 @@ def test_prefill_entry_point(kind, max_seqs, pieces):
         w = si.small_moe_workload(n_seqs=3, ctx_min=12, ctx_max=60, seed=61)
         prompts = si.make_prompts(w)
         layers_t, layers_d = [0, 3], [0, 1]
+    elif kind == "single":        # one prompt of 27 tokens through a context for ONE sequence: two passes of a single band of rows each
+        w = si.small_bf16_workload(n_seqs=1, ctx_min=27, ctx_max=27, seed=21)
+        prompts = si.make_prompts(w)
+        layers_t, layers_d = [0, 3, 7], [0, 1]
     else:
         w = si.small_bf16_workload(n_seqs=3, ctx_min=9, ctx_max=150, seed=19)
         prompts = si.make_prompts(w)
@@ -548,7 +552,7 @@ def test_prefill_entry_point(kind, max_seqs, pieces):
         assert min(ls.route_gaps) > ROUTE_CLEAR
     assert not mism, (first, got)
     ls.check_cache(layers_t, layers_d)
-    for i, plan in enumerate([None, [Bk - 1, 0, 3]]):
+    for i, plan in enumerate([None, [Bk - 1, 0, 3][: len(prompts)]]):
         ls.step(plan=plan, step_idx=i)
     ls.check_cache(layers_t[-1:], layers_d[-1:])
     print(f"prefill entry ({kind}, max_seqs {max_seqs}, pieces {pieces}) stats", ls.stats)
