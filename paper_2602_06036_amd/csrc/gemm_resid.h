@@ -26,9 +26,7 @@ struct ResidBuf {
   u32x4 w[U], ah[U], al[U];
 };
 
-// LAY: 0 = weight tiles k-tile-major (the layout of every other GEMM), 1 = band-major (a band's K / 32 tiles contiguous).
-// PL: activation planes (2 = hi + lo pair, 1 = hi only).
-template <int U, int NW, int LAY = 0, int PL = 2>
+template <int U, int NW>
 __global__ __launch_bounds__(64 * NW) void gemm_bf16_resid_kernel(const bf16_t* __restrict__ W, const bf16_t* __restrict__ A, int M,
                                                                   int N, int K, ResidArgs ra) {
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6);
@@ -47,8 +45,8 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_resid_kernel(const bf16_t* 
   }
 
   f32x4 acc = {0.f, 0.f, 0.f, 0.f};
-  const u32x4* Wp = reinterpret_cast<const u32x4*>(W) + (LAY ? (size_t)n * KT * 64 : (size_t)n * 64) + lane;
-  const size_t w_step = LAY ? 64 : (size_t)n_tiles * 64;
+  const u32x4* Wp = reinterpret_cast<const u32x4*>(W) + (size_t)n * 64 + lane;
+  const size_t w_step = (size_t)n_tiles * 64;   // weight tiles are k-tile-major
   const u32x4* Ap = reinterpret_cast<const u32x4*>(A) + lane;
   auto load = [&](ResidBuf<U>& b, int k0) {
 #pragma unroll
@@ -58,18 +56,15 @@ __global__ __launch_bounds__(64 * NW) void gemm_bf16_resid_kernel(const bf16_t* 
       b.w[u] = __builtin_nontemporal_load(Wp + (size_t)kt * w_step);
       const u32x4 hi = Ap[(size_t)kt * 128];
       b.ah[u] = in ? hi : (u32x4){0u, 0u, 0u, 0u};
-      if constexpr (PL == 2) {
-        const u32x4 lo = Ap[(size_t)kt * 128 + 64];
-        b.al[u] = in ? lo : (u32x4){0u, 0u, 0u, 0u};
-      }
+      const u32x4 lo = Ap[(size_t)kt * 128 + 64];
+      b.al[u] = in ? lo : (u32x4){0u, 0u, 0u, 0u};
     }
   };
   auto compute = [&](const ResidBuf<U>& b) {
 #pragma unroll
     for (int u = 0; u < U; ++u) {
       acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b.w[u]), __builtin_bit_cast(bf16x8, b.ah[u]), acc, 0, 0, 0);
-      if constexpr (PL == 2)
-        acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b.w[u]), __builtin_bit_cast(bf16x8, b.al[u]), acc, 0, 0, 0);
+      acc = __builtin_amdgcn_mfma_f32_16x16x32_bf16(__builtin_bit_cast(bf16x8, b.w[u]), __builtin_bit_cast(bf16x8, b.al[u]), acc, 0, 0, 0);
     }
   };
   // two register buffers; no load inside the loop is conditional (the tail is peeled), see gemm_bf16_kernel
