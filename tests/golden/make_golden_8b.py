@@ -32,7 +32,7 @@ CASES = {
     2: dict(seqs=[0], k=[3]),
     3: dict(seqs=list(range(16)), k=[0, 1, 3, 0, 4, 2, 1, 0, 5, 2, 0, 6, 1, 3, 0, 9]),
     4: dict(seqs=[0, 1, 2, 3], k=[0, 1, 2, 3]),
-    5: dict(seqs=[0, 17], k=None),
+    5: dict(seqs=[0, 3, 8, 12, 17, 21, 26, 31], k=None),
 }
 N_COLS = 64
 RNG_KEY = 20260206
