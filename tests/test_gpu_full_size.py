@@ -1,8 +1,9 @@
 """GPU parity at the full 8B shape (configurations 2-5), in the launch configuration bench.py times:
-one speculative step from a seeded synthetic cache state, compared for a few sampled sequences with
-the CPU oracle's stored results (tests/golden/golden_8b.json, written by tests/golden/make_golden_8b.py
-which calls only oracle/ and synth/).  The other sequences of each batch run along with the same kind of
-state; for them the properties that hold at any size are checked (tau range, slot ids, padding)."""
+one speculative step from a seeded synthetic cache state, compared with the CPU oracle's stored results
+(tests/golden/golden_8b.json, written by tests/golden/make_golden_8b.py which calls only oracle/ and synth/)
+for every sequence of configurations 2, 3 and 4 and for the stored sequences of configuration 5; its other
+sequences run along with the same kind of state, and for them the properties that hold at any size are
+checked (tau range, slot ids, padding).  Configuration 2 also from the oracle's own prefill of its prompt."""
 import json
 import os
 
