@@ -246,6 +246,20 @@ int dflash_profile_read(dflash_ctx *ctx, void *stream, float *ms, int32_t *count
  * GEMMs had to read.  Synchronises the stream and clears all five. */
 int dflash_moe_stats(dflash_ctx *ctx, void *stream, int64_t *out);
 
+/* State export for tests and tuning: GEMM launches per kernel family since the last call (or create) into
+ * out[0..DFLASH_GEMM_KINDS-1] (host), cleared by the call.  Says which kernel a shape, a row count or a tuning
+ * variable actually selected.  Host counters: no synchronisation, no device access. */
+#define DFLASH_GEMM_KINDS 6
+enum {
+  DFLASH_GEMM_STREAMING = 0, /* weight-streaming kernel, up to 64 rows (K split across workgroups and wavefronts) */
+  DFLASH_GEMM_TILED4 = 1,    /* LDS-staged tiles, four wavefronts */
+  DFLASH_GEMM_TILED8 = 2,    /* LDS-staged tiles, eight wavefronts (384 or 256 weight rows) */
+  DFLASH_GEMM_FEW_ROWS = 3,  /* unsplit projection with the residual update in its epilogue (one band of rows) */
+  DFLASH_GEMM_GROUPED = 4,   /* routed experts: grouped launches */
+  DFLASH_GEMM_F32 = 5        /* fp32 models */
+};
+int dflash_gemm_counts(dflash_ctx *ctx, int64_t *out);
+
 /* Routed-expert targets, state export for tests and debugging: while `choices` (device, [n_layers, max_seqs * block_size,
  * top_k] int32, caller-owned) is set, every routed target layer leaves the experts it chose for row m (by decreasing
  * router logit) at choices[(layer * max_seqs * block_size + m) * top_k ..]; NULL switches the trace off again.  Rows

@@ -25,7 +25,7 @@ EXPORTS = [
     "dflash_pack_target_head", "dflash_pack_target_layer", "dflash_pack_draft_head", "dflash_pack_draft_layer",
     "dflash_create", "dflash_destroy", "dflash_last_error", "dflash_device_status",
     "dflash_draft_block", "dflash_verify", "dflash_accept", "dflash_kv_commit",
-    "dflash_prefill", "dflash_accept_sampled_noalloc", "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats", "dflash_moe_trace",
+    "dflash_prefill", "dflash_accept_sampled_noalloc", "dflash_kv_read", "dflash_kv_write", "dflash_profile_enable", "dflash_profile_read", "dflash_moe_stats", "dflash_moe_trace", "dflash_gemm_counts",
     "dflash_probe_hbm_read", "dflash_probe_mfma",
 ]
 
@@ -98,6 +98,7 @@ def lib() -> C.CDLL:
         l.dflash_profile_read.argtypes = [P, P, C.POINTER(C.c_float), C.POINTER(C.c_int32), C.POINTER(C.c_double)]
         l.dflash_moe_stats.argtypes = [P, P, C.POINTER(C.c_int64)]
         l.dflash_moe_trace.argtypes = [P, P]
+        l.dflash_gemm_counts.argtypes = [P, P]
         for name in EXPORTS:
             if name not in ("dflash_target_blob_bytes", "dflash_draft_blob_bytes", "dflash_kv_pool_bytes",
                             "dflash_workspace_bytes", "dflash_last_error"):
@@ -230,6 +231,12 @@ class Engine:
         out = (C.c_int64 * 5)()
         _check(self.l.dflash_moe_stats(self.ctx, _stream(), out), self.ctx)
         return int(out[0]), int(out[1]), int(out[2]), int(out[3]), int(out[4])
+
+    def gemm_counts(self):
+        """GEMM launches per kernel family since the last call: (streaming, tiled4, tiled8, few_rows, grouped, f32)."""
+        out = (C.c_int64 * 6)()
+        _check(self.l.dflash_gemm_counts(self.ctx, out), self.ctx)
+        return tuple(int(v) for v in out)
 
     def moe_trace(self, on: bool = True):
         """Routed-expert targets: a [n_layers, max_seqs * B, top_k] int32 tensor that every following verify / prefill pass

@@ -58,6 +58,7 @@ inline int env_int(const char* name, int dflt) {
 // context keeps the values it was created with, so a test that sets one before dflash_create gets exactly that path
 // whatever ran earlier in the process.  Defaults are what the measurements in the documentation use.
 struct Knobs {
+  int gemm_wide;            // DFLASH_GEMM_WIDE: 1 = eight-wavefront tiles where they fill one round of the CUs (default), 2 = wherever one fits (tests), 0 = never
   int attn_target_wgs;      // DFLASH_ATTN_TARGET_WGS: workgroups an attention launch aims at
   int attn_wide_min_chunk;  // DFLASH_ATTN_WIDE_MIN_CHUNK: keys per workgroup from which the key-split attention kernel is used
   int gemm_target_wgs;      // DFLASH_GEMM_TARGET_WGS: workgroups a K-split streaming GEMM aims at
@@ -80,6 +81,7 @@ struct Knobs {
 };
 Knobs read_knobs() {
   Knobs k;
+  k.gemm_wide = env_int("DFLASH_GEMM_WIDE", 1);
   k.attn_target_wgs = env_int("DFLASH_ATTN_TARGET_WGS", 256);
   k.attn_wide_min_chunk = env_int("DFLASH_ATTN_WIDE_MIN_CHUNK", 512);
   k.gemm_target_wgs = env_int("DFLASH_GEMM_TARGET_WGS", 256);
@@ -352,6 +354,7 @@ struct dflash_ctx {
   char* wsp;
   char err[512];
   Knobs k;                                             // tuning / testing knobs as they stood when the context was created
+  int64_t gemm_counts[DFLASH_GEMM_KINDS] = {};         // dflash_gemm_counts: GEMM launches per kernel family since the last read
   int32_t* moe_trace = nullptr;                        // dflash_moe_trace: where the routed layers also leave their expert choices
   bool have_logits_d = false, have_logits_t = false;   // the workspace holds this step's draft / target logits
   float draft_temperature = 0.f;                       // of the last dflash_draft_block call
@@ -837,11 +840,13 @@ struct Engine {
 constexpr int kMaxKSplit = 16;
 
 thread_local int g_launch_parts = 0;   // column blocks of the last bf16 GEMM launch (= fused-argmax partials per row)
+thread_local int g_launch_kind = 0;    // kernel family of that launch (DFLASH_GEMM_* of dflash_gemm_counts)
 
 template <int NT, int MT, int U>
 void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
   const dim3 grid((N / 16) / NT, ((M + 15) / 16 + MT - 1) / MT, ks), block(256);
   g_launch_parts = (int)grid.x;
+  g_launch_kind = DFLASH_GEMM_STREAMING;
   if (epi == EPI_SWIGLU) {
     if constexpr (NT >= 2) hipLaunchKernelGGL((gemm_bf16_kernel<NT, MT, U, EPI_SWIGLU>), grid, block, 0, st, W, A, M, N, K, ep);
   } else {
@@ -849,15 +854,16 @@ void launch_bf16(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N,
   }
 }
 
-template <int WN, int WM, int PD, int NS = 2>
+template <int WN, int WM, int PD, int NS = 2, int WY = 2>
 void launch_tiled(hipStream_t st, const bf16_t* W, const bf16_t* A, int M, int N, int K, int epi, EpiArgs ep, int ks) {
-  const int n_blocks = (N / 16 + 2 * WN - 1) / (2 * WN), m_blocks = ((M + 15) / 16 + 2 * WM - 1) / (2 * WM);
-  const dim3 grid(((n_blocks + 7) / 8) * 8 * m_blocks, ks), block(256);
+  const int n_blocks = (N / 16 + WY * WN - 1) / (WY * WN), m_blocks = ((M + 15) / 16 + 2 * WM - 1) / (2 * WM);
+  const dim3 grid(((n_blocks + 7) / 8) * 8 * m_blocks, ks), block(128 * WY);
   g_launch_parts = n_blocks;
+  g_launch_kind = WY == 4 ? DFLASH_GEMM_TILED8 : DFLASH_GEMM_TILED4;
   if (epi == EPI_SWIGLU)
-    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_SWIGLU, NS>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_SWIGLU, NS, false, WY>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
   else
-    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_STORE, NS>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
+    hipLaunchKernelGGL((gemm_bf16_tiled_kernel<WN, WM, PD, EPI_STORE, NS, false, WY>), grid, block, 0, st, W, A, M, N, K, n_blocks, m_blocks, ep);
 }
 
 inline int gemm_class(int epi, int N, int vocab) { return (epi == EPI_STORE && N == vocab) ? DFLASH_PROF_GEMM_LMHEAD : epi; }
@@ -992,6 +998,43 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
       }
     }
     ep.slab = (size_t)M * ep.ld;
+    // Eight-wavefront tiles (four wavefronts along N: 384 or 256 weight rows x 128 or 64 activation rows, one workgroup
+    // per CU): two of the four-wavefront workgroups fused along N, so the activation stage is fetched once for twice
+    // the weight rows.  Taken when such a tiling with some K split gives one round that fills the CUs (225-256
+    // workgroups).  Isolated launches at 512 rows over random operands, against the best four-wavefront choice: gate/up
+    // 166 against 197 us, QKV 46 against 51.  Inside the step (kernel trace at 512 rows): QKV 50.2 against 59.0 us,
+    // O and down together 123.9 against 128.5, gate/up 154.6 against 152.1 -- and a step time that moves by 0.2 % at
+    // most, because the step's GEMMs run against the power limit (the same gate/up launch takes 149 us over constant
+    // operands and 197 us over random ones): what one launch saves, the clock takes back.
+    const bool forced = c->k.gemm_tile || c->k.gemm_wm || c->k.gemm_ks;   // a forced four-wavefront shape stays forced
+    // (inside the step the gate/up launch gains nothing from them -- 154.6 against 152.1 us at 512 rows -- and keeps its tiles)
+    if (c->k.gemm_wide == 2 || (c->k.gemm_wide == 1 && !forced && epi != EPI_SWIGLU)) {
+      const bool any_fill = c->k.gemm_wide == 2;   // 2: the first fitting eight-wavefront tile whatever the number of workgroups
+      static const int wide[4][2] = {{6, 4}, {4, 4}, {6, 2}, {4, 2}};
+      for (const auto& wd : wide) {
+        if (nt % (4 * wd[0])) continue;
+        if (any_fill && ((c->k.gemm_tile && c->k.gemm_tile != wd[0]) || (c->k.gemm_wm && c->k.gemm_wm != wd[1]))) continue;
+        const int mb = ((M + 15) / 16 + 2 * wd[1] - 1) / (2 * wd[1]);
+        const int wgs = nt / (4 * wd[0]) * mb;
+        for (int k = 1; k <= kMaxKSplit; k *= 2) {
+          if (k > 1 && (!split || KT / k < 8 || k * M > arena)) break;
+          if (any_fill ? (c->k.gemm_ks && split && k != c->k.gemm_ks && c->k.gemm_ks * M <= arena && KT / c->k.gemm_ks >= 8)
+                       : (wgs * k < 225 || wgs * k > 256))
+            continue;
+          ks = k;
+          if (wd[0] == 6 && wd[1] == 4) launch_tiled<6, 4, 1, 3, 4>(st, W, A, M, N, K, kepi, ep, ks);
+          else if (wd[0] == 4 && wd[1] == 4) launch_tiled<4, 4, 1, 3, 4>(st, W, A, M, N, K, kepi, ep, ks);
+          else if (wd[0] == 6) launch_tiled<6, 2, 1, 3, 4>(st, W, A, M, N, K, kepi, ep, ks);
+          else launch_tiled<4, 2, 1, 4, 4>(st, W, A, M, N, K, kepi, ep, ks);
+          check();
+          ++c->gemm_counts[g_launch_kind];
+          if (ep.amax) amax_parts = g_launch_parts;
+          if (ep.lse) lse_parts = g_launch_parts;
+          if (epi == EPI_SWIGLU) return Slab{};
+          return Slab{ep.out, ks, ep.slab};
+        }
+      }
+    }
     const int PD = c->k.gemm_pd;              // k tiles in flight from global memory (192/128-row tiles)
     const bool RING = c->k.gemm_ring == 1;    // any other value: register-staged variant for the small tiles
     if (best_wm == 2 && RING) {
@@ -1023,6 +1066,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     }
   }
   check();
+  ++c->gemm_counts[g_launch_kind];
   if (ep.amax) amax_parts = g_launch_parts;
   if (ep.lse) lse_parts = g_launch_parts;
   if (epi == EPI_SWIGLU) return Slab{};
@@ -1113,6 +1157,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     else if (MT == 2) launch_grouped<2, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
     else launch_grouped<4, 1, EPI_SWIGLU>(st, W, a, n_pos, 2 * Fe, D, ep, n_items);
     check();
+    ++c->gemm_counts[DFLASH_GEMM_GROUPED];
   }
   {
     ProfScope prof(c, st, DFLASH_PROF_MOE_DOWN, used * Fe * D * 2);
@@ -1130,6 +1175,7 @@ Engine<bf16_t>::Slab Engine<bf16_t>::moe_ffn(const dflash_dims& m, const char* l
     else if (ph4 == 2) launch_grouped<4, 1, EPI_STORE, 2>(st, W, act, n_pos, D, Fe, ep, n_items);
     else launch_grouped<4, 1, EPI_STORE>(st, W, act, n_pos, D, Fe, ep, n_items);
     check();
+    ++c->gemm_counts[DFLASH_GEMM_GROUPED];
   }
   // the weighted sum of a row's experts' outputs is taken by the next RMSNorm, which adds it to the residual stream
   Slab out{y, 1, 0};
@@ -1150,6 +1196,7 @@ Engine<float>::Slab Engine<float>::gemm(const float* W, const float* A, int M, i
     default: hipLaunchKernelGGL(gemm_f32_kernel<EPI_SWIGLU>, grid, block, 0, st, W, A, M, N, K, ep); break;
   }
   check();
+  ++c->gemm_counts[DFLASH_GEMM_F32];
   if (epi == EPI_STORE) return Slab{ep.out, 1, (size_t)M * ep.ld};
   return Slab{};
 }
@@ -1176,6 +1223,7 @@ void Engine<bf16_t>::resid(const bf16_t* W, const bf16_t* A, int M, int N, int K
   else if (nw == 8) launch_resid<8, 8>(st, W, A, M, N, K, ra);
   else launch_resid<8, 4>(st, W, A, M, N, K, ra);
   check();
+  ++c->gemm_counts[DFLASH_GEMM_FEW_ROWS];
   defer_parts = N / 16;
 }
 template <>
@@ -1498,6 +1546,15 @@ int dflash_moe_stats(dflash_ctx* ctx, void* stream, int64_t* out) {
   if (hipStreamSynchronize((hipStream_t)stream) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "stream synchronise failed");
   if (hipMemcpy(out, ctx->wsp + ctx->ws.status + 64, 40, hipMemcpyDeviceToHost) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics read failed");
   if (hipMemset(ctx->wsp + ctx->ws.status + 64, 0, 40) != hipSuccess) return CTX_FAIL(ctx, DFLASH_EHIP, "statistics clear failed");
+  return DFLASH_OK;
+}
+
+int dflash_gemm_counts(dflash_ctx* ctx, int64_t* out) {
+  if (!ctx || !out) return fail(ctx ? ctx->err : nullptr, DFLASH_EINVAL, "gemm_counts: null argument");
+  for (int i = 0; i < DFLASH_GEMM_KINDS; ++i) {
+    out[i] = ctx->gemm_counts[i];
+    ctx->gemm_counts[i] = 0;
+  }
   return DFLASH_OK;
 }
 

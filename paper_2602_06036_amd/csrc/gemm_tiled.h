@@ -1,11 +1,13 @@
 // Compute-bound GEMM for many activation rows (M > 64): y[M,N] = a[M,K] * W[N,K]^T, bf16 MFMA 16x16x32 with
 // hi+lo activation pairs, fp32 accumulation, the same operand layouts and epilogues as the streaming kernel.
 //
-// A workgroup of 4 wavefronts (2 along N x 2 along M) owns a tile of 2*WN weight row bands x 2*WM activation
-// row bands for one K range (grid.y).  Both operands already sit in HBM in MFMA fragment order (1 KB per
+// A workgroup of 2*WY wavefronts (WY = 2 or 4 along N x 2 along M) owns a tile of WY*WN weight row bands x 2*WM
+// activation row bands for one K range (grid.y).  Both operands already sit in HBM in MFMA fragment order (1 KB per
 // 16x32 fragment), so a k tile is staged by copying whole fragments: global -> registers (PD k tiles in flight)
-// -> one of two LDS slots; every wavefront reads the WN weight and 2*WM activation fragments of its quadrant
-// (each lane its own 16 bytes: conflict-free ds_read_b128) and issues WN*WM*2 MFMAs per k tile.
+// -> one of two LDS slots; every wavefront reads the WN weight and 2*WM activation fragments of its part of the tile
+// (each lane its own 16 bytes: conflict-free ds_read_b128) and issues WN*WM*2 MFMAs per k tile.  The eight-wavefront
+// form (WY = 4) is two four-wavefront workgroups fused along N: one activation stage for twice the weight rows,
+// i.e. a third less operand traffic from L2 per flop, at one workgroup per CU.
 // Schedule of a k tile, register-staged variant (NS = 2; one barrier per k tile, order pinned with scheduling
 // barriers): barrier -> all WN + 2*WM fragment reads of the k tile -> the LDS writes of the next k tile (from
 // registers loaded PD k tiles earlier) and the global loads of k tile t+1+PD -> the WN*WM*2 MFMAs.  LDS operations
@@ -22,13 +24,14 @@
 #pragma once
 #include "gemm.h"
 
-template <int WN, int WM, int PD, int EPI, int NS = 2, bool GRP = false>
-__global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void gemm_bf16_tiled_kernel(const bf16_t* __restrict__ W,
-                                                                                const bf16_t* __restrict__ A, int M, int N, int K,
-                                                                                int n_blocks, int m_blocks, EpiArgs ep) {
-  constexpr int BNT = 2 * WN, BMT = 2 * WM;        // fragments of a stage: BNT weight + 2*BMT activation (hi, lo)
-  constexpr int FR = BNT + 2 * BMT, PER = FR / 4;  // fragments copied by each wavefront
-  static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % 4 == 0 && (PD == 1 || PD == 2) && NS >= 2 && NS * FR <= 160, "tile shape");
+template <int WN, int WM, int PD, int EPI, int NS = 2, bool GRP = false, int WY = 2>
+__global__ __launch_bounds__(128 * WY, (WY == 2 && NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void gemm_bf16_tiled_kernel(
+    const bf16_t* __restrict__ W, const bf16_t* __restrict__ A, int M, int N, int K, int n_blocks, int m_blocks, EpiArgs ep) {
+  constexpr int NWV = 2 * WY;                       // wavefronts: WY along N x 2 along M
+  constexpr int BNT = WY * WN, BMT = 2 * WM;        // fragments of a stage: BNT weight + 2*BMT activation (hi, lo)
+  constexpr int FR = BNT + 2 * BMT, PER = FR / NWV; // fragments copied by each wavefront
+  static_assert(WN % 2 == 0 && WM % 2 == 0 && FR % NWV == 0 && (PD == 1 || PD == 2) && NS >= 2 && NS * FR <= 160 && (WY == 2 || WY == 4),
+                "tile shape");
   __shared__ u32x4 stage[NS][FR][64];
 
   const int lane = threadIdx.x & 63, wave = __builtin_amdgcn_readfirstlane(threadIdx.x >> 6), wy = wave >> 1, wx = wave & 1;
@@ -228,7 +231,7 @@ __global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void g
   }
   if (EPI == EPI_STORE && ep.amax) {   // fused argmax over this workgroup's columns (host guarantees a single K range)
     __syncthreads();                   // the staging slots are free now: reuse them for the two N halves' bests
-    float2* wbest = reinterpret_cast<float2*>(&stage[0][0][0]);   // [wy][BMT * 16 rows]
+    float2* wbest = reinterpret_cast<float2*>(&stage[0][0][0]);   // [wy][BMT * 16 rows]: the bests of the WY column groups
     const uint64_t key = ep.amax_mode ? ep.amax_key[0] : 0ull;
 #pragma unroll
     for (int jj = 0; jj < WM; ++jj) {
@@ -252,12 +255,13 @@ __global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void g
       if (gq == 0) wbest[wy * (BMT * 16) + (wx * WM + jj) * 16 + mrow] = make_float2(bv, __int_as_float(bi));
     }
     __syncthreads();
-    for (int r = threadIdx.x; r < BMT * 16; r += 256) {
+    for (int r = threadIdx.x; r < BMT * 16; r += 64 * NWV) {
       const int m = mt0 * 16 + r;
       if (m >= M) continue;
       float bv = wbest[r].x;
       int bi = __float_as_int(wbest[r].y);
-      argmax_combine(bv, bi, wbest[BMT * 16 + r].x, __float_as_int(wbest[BMT * 16 + r].y));
+#pragma unroll
+      for (int y = 1; y < WY; ++y) argmax_combine(bv, bi, wbest[y * BMT * 16 + r].x, __float_as_int(wbest[y * BMT * 16 + r].y));
       ep.amax[(size_t)m * n_blocks + nb] = make_float2(bv, __int_as_float(bi));
     }
   }
@@ -276,11 +280,12 @@ __global__ __launch_bounds__(256, (NS * (2 * WN + 4 * WM) <= 80 ? 2 : 1)) void g
       if (gq == 0) wl[wy * (BMT * 16) + (wx * WM + jj) * 16 + mrow] = make_float2(lm, ls);
     }
     __syncthreads();
-    for (int r = threadIdx.x; r < BMT * 16; r += 256) {
+    for (int r = threadIdx.x; r < BMT * 16; r += 64 * NWV) {
       const int m = mt0 * 16 + r;
       if (m >= M) continue;
       float lm = wl[r].x, ls = wl[r].y;
-      lse_combine(lm, ls, wl[BMT * 16 + r].x, wl[BMT * 16 + r].y);
+#pragma unroll
+      for (int y = 1; y < WY; ++y) lse_combine(lm, ls, wl[y * BMT * 16 + r].x, wl[y * BMT * 16 + r].y);
       ep.lse[(size_t)m * n_blocks + nb] = make_float2(lm, ls);
     }
   }

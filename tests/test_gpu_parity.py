@@ -357,7 +357,36 @@ def test_small_bf16_many_rows_tiled_gemm(tile, rows, monkeypatch):
     for i, plan in enumerate(plans):
         ls.step(plan=plan, step_idx=i)
     ls.check_cache([3], [1])
-    print("small bf16 (160 rows) stats", ls.stats)
+    counts = ls.g.e.gemm_counts()
+    print("small bf16 (160 rows) stats", ls.stats, "launches per kernel family", counts)
+    assert counts[1] > 0 and counts[2] == 0     # four-wavefront tiles for the 160-row steps (eight-wavefront ones need a full round of CUs)
+    assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
+    assert ls.stats["reseeds"] <= 1
+
+
+@pytest.mark.parametrize("tile,rows,ks", [("0", "0", "0"), ("6", "4", "0"), ("4", "4", "2"), ("6", "2", "0"), ("4", "2", "2")])
+def test_small_bf16_many_rows_eight_wavefront_tiles(tile, rows, ks, monkeypatch):
+    """The 160-row case through the eight-wavefront tiles of the LDS-staged GEMM (384 or 256 weight rows x 128 or 64
+    activation rows, four wavefronts along N), which the dispatcher takes at the 8B shape where they fill one round of
+    the CUs; here forced wherever the matrix height allows (a matrix whose height is no multiple of the tile keeps the
+    four-wavefront kernel), with and without a K split, including the LM head with its fused argmax."""
+    monkeypatch.setenv("DFLASH_GEMM_WIDE", "2")
+    monkeypatch.setenv("DFLASH_GEMM_TILE", tile)
+    monkeypatch.setenv("DFLASH_GEMM_WM", rows)
+    monkeypatch.setenv("DFLASH_GEMM_KS", ks)
+    w = si.small_bf16_workload(n_seqs=10, ctx_min=17, ctx_max=90, seed=23)
+    prompts = si.make_prompts(w)
+    ls = Lockstep(w, prompts, max_len=90 + 4 * 16)
+    ls.prefill()
+    ls.check_cache([0, 7], [0, 1])
+    for i, plan in enumerate([None, [15, 0, 9, 1, 2, 3, 4, 5, 15, 7]]):
+        ls.step(plan=plan, step_idx=i)
+    ls.check_cache([3], [1])
+    counts = ls.g.e.gemm_counts()
+    print("small bf16 (160 rows, eight-wavefront tiles) stats", ls.stats, "launches per kernel family", counts)
+    assert counts[2] > 0
+    if tile in ("0", "4"):
+        assert counts[1] == 0                   # every matrix height of this model is a multiple of 256 rows
     assert ls.stats["low_margin_flips"] <= 0.02 * ls.stats["rows"] + 2
     assert ls.stats["reseeds"] <= 1
 
