@@ -58,7 +58,7 @@ inline int env_int(const char* name, int dflt) {
 // context keeps the values it was created with, so a test that sets one before dflash_create gets exactly that path
 // whatever ran earlier in the process.  Defaults are what the measurements in the documentation use.
 struct Knobs {
-  int gemm_wide;            // DFLASH_GEMM_WIDE: 1 = eight-wavefront tiles where they fill one round of the CUs (default), 2 = wherever one fits (tests), 0 = never
+  int gemm_wide;            // DFLASH_GEMM_WIDE: 1 = eight-wavefront tiles where they fill one round of the CUs (default), 2 = wherever one fits (tests), any other value = never
   int attn_target_wgs;      // DFLASH_ATTN_TARGET_WGS: workgroups an attention launch aims at
   int attn_wide_min_chunk;  // DFLASH_ATTN_WIDE_MIN_CHUNK: keys per workgroup from which the key-split attention kernel is used
   int gemm_target_wgs;      // DFLASH_GEMM_TARGET_WGS: workgroups a K-split streaming GEMM aims at
@@ -1000,15 +1000,13 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     ep.slab = (size_t)M * ep.ld;
     // Eight-wavefront tiles (four wavefronts along N: 384 or 256 weight rows x 128 or 64 activation rows, one workgroup
     // per CU): two of the four-wavefront workgroups fused along N, so the activation stage is fetched once for twice
-    // the weight rows.  Taken when such a tiling with some K split gives one round that fills the CUs (225-256
+    // the weight rows.  Taken when such a tiling with some K split gives exactly one round that fills the CUs (225-256
     // workgroups).  Isolated launches at 512 rows over random operands, against the best four-wavefront choice: gate/up
-    // 166 against 197 us, QKV 46 against 51.  Inside the step (kernel trace at 512 rows): QKV 50.2 against 59.0 us,
-    // O and down together 123.9 against 128.5, gate/up 154.6 against 152.1 -- and a step time that moves by 0.2 % at
-    // most, because the step's GEMMs run against the power limit (the same gate/up launch takes 149 us over constant
-    // operands and 197 us over random ones): what one launch saves, the clock takes back.
+    // 166 against 197 us, QKV 46 against 51.  Whole step: 25.2 against 25.8 ms at 512 rows, 12.24 against 12.42 at 256.
+    // Over several rounds they lose (gate/up of a 1024-row prefill pass, two rounds: 49.8 against 48.8 ms per prefill).
     const bool forced = c->k.gemm_tile || c->k.gemm_wm || c->k.gemm_ks;   // a forced four-wavefront shape stays forced
     // (inside the step the gate/up launch gains nothing from them -- 154.6 against 152.1 us at 512 rows -- and keeps its tiles)
-    if (c->k.gemm_wide == 2 || (c->k.gemm_wide == 1 && !forced && epi != EPI_SWIGLU)) {
+    if (c->k.gemm_wide == 2 || (c->k.gemm_wide == 1 && !forced)) {
       const bool any_fill = c->k.gemm_wide == 2;   // 2: the first fitting eight-wavefront tile whatever the number of workgroups
       static const int wide[4][2] = {{6, 4}, {4, 4}, {6, 2}, {4, 2}};
       for (const auto& wd : wide) {
