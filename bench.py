@@ -21,8 +21,8 @@ HBM_PEAK_GBS = 8000.0
 # workload (FETCH_SIZE x 2.000 + WRITE_SIZE x 1.000, factors from a 1 GiB copy): profiles/cfg2_step_kernel_stats.md (configuration 2),
 # profiles/gateup_gemm_attention_hbm_traffic.md (the others)
 MFMA_BF16_PEAK_TFLOPS = 2500.0     # MI355X dense bf16 MFMA peak
-MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": int(99449.2 * 2 + 768) * 1024, "cfg3_8b_b16_ctx2560": int(114806.3 * 2 + 12288) * 1024,
-                          "cfg4_8b_b4_ctx16k": int(102485.9 * 2 + 3072) * 1024, "cfg5_8b_b32_ctx8k": int(131284.2 * 2 + 24576) * 1024,
+MEASURED_TRAFFIC_BYTES = {"cfg2_8b_b1_ctx2048": int(99449.2 * 2 + 768) * 1024, "cfg3_8b_b16_ctx2560": int(114750.8 * 2 + 12288) * 1024,
+                          "cfg4_8b_b4_ctx16k": int(102485.9 * 2 + 3072) * 1024, "cfg5_8b_b32_ctx8k": int(131169.8 * 2 + 24576) * 1024,
                           # grouped gate/up launch of the routed experts: profiles/moe_expert_gemm_hbm_traffic.md
                           "moe_30b_a3b_b1_ctx2048": int(230241.5 * 2 + 3588.2) * 1024, "moe_30b_a3b_b32_ctx2048": int(413442.9 * 2 + 15089.0) * 1024}
 
