@@ -1003,9 +1003,9 @@ Engine<bf16_t>::Slab Engine<bf16_t>::gemm(const bf16_t* W, const bf16_t* A, int 
     // the weight rows.  Taken when such a tiling with some K split gives exactly one round that fills the CUs (225-256
     // workgroups).  Isolated launches at 512 rows over random operands, against the best four-wavefront choice: gate/up
     // 166 against 197 us, QKV 46 against 51.  Whole step: 25.2 against 25.8 ms at 512 rows, 12.24 against 12.42 at 256.
-    // Over several rounds they lose (gate/up of a 1024-row prefill pass, two rounds: 49.8 against 48.8 ms per prefill).
+    // Over several rounds they lose (gate/up of a 1024-row prefill pass, two rounds: 49.8 against 48.8 ms per prefill; the LM
+    // head at 512 rows, five to seven rounds: 1157-1230 against 1090 us).
     const bool forced = c->k.gemm_tile || c->k.gemm_wm || c->k.gemm_ks;   // a forced four-wavefront shape stays forced
-    // (inside the step the gate/up launch gains nothing from them -- 154.6 against 152.1 us at 512 rows -- and keeps its tiles)
     if (c->k.gemm_wide == 2 || (c->k.gemm_wide == 1 && !forced)) {
       const bool any_fill = c->k.gemm_wide == 2;   // 2: the first fitting eight-wavefront tile whatever the number of workgroups
       static const int wide[4][2] = {{6, 4}, {4, 4}, {6, 2}, {4, 2}};
