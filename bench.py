@@ -316,7 +316,7 @@ def run_workload(name, args, dev, K, Wm, blobs=None, draft_only=False):
     state = {"upper": ctx}
 
     def step():
-        b = e.batch(seq_lens, table, anchor, state["upper"])
+        b = e.batch(seq_lens, table, anchor, min(state["upper"], max_len - Bk))   # (the bound a captured step was planned for is the table's)
         dfl.dflash_draft_block(e, b, draft_tokens, T, rng_key)
         dfl.dflash_verify(e, b, draft_tokens, tgt_argmax)
         dfl.dflash_accept(e, b, draft_tokens, tgt_argmax, accept_len, out_tokens, T, uniforms, rng_key)
