@@ -148,4 +148,7 @@ def test_step_calls_reject_null_handles_before_touching_the_device(B):
     assert l.dflash_accept(None, C.byref(batch), None, None, C.c_float(0.0), None, None, None, None, None) == B.DFLASH_EINVAL
     assert l.dflash_kv_commit(None, C.byref(batch), None, None, None, None) == B.DFLASH_EINVAL
     assert b"ctx" in l.dflash_last_error(None)
+    counts = (C.c_int64 * 6)()
+    assert l.dflash_gemm_counts(None, counts) == B.DFLASH_EINVAL
+    assert l.dflash_moe_trace(None, None) == B.DFLASH_EINVAL
     assert l.dflash_destroy(None) in (B.DFLASH_OK, B.DFLASH_EINVAL)
