@@ -310,3 +310,54 @@ def test_config4_batch4_ctx16k(shared):
 
 def test_config5_batch32_ctx8k_sampling(shared):
     _run_config(shared, 5)
+
+
+def test_long_context_131072_tokens_under_two_split_plans(shared, monkeypatch):
+    """Maximum-size edge of the 8B shape on one GPU: ONE sequence with 131 072 cached tokens (8192 pages per layer and
+    pool, 19 GB of target cache, 2.7 GB of context features, table and position arithmetic far beyond the other
+    configurations).  No oracle can hold that state, so the step is run twice from the same seeded state under two
+    different attention plans -- the dispatcher's own (key-split kernel, 32 chunks of 4096 keys per kv head) and one forced
+    to the row-split kernel with 256 chunks of 512 keys -- which share no indexing beyond the page layout; their logits
+    have to agree like two summation orders of one computation, and the properties that hold at any size are checked."""
+    import torch
+    from dataclasses import replace
+    from tests.gpu_harness import GpuModel
+    n_ctx = 131072
+    w = replace(si.workload(2), n_seqs=1, ctx_min=n_ctx, ctx_max=n_ctx)
+    Bk = w.block_size
+    outs = []
+    for plan in ("default", "row-split, 256 chunks"):
+        if plan != "default":
+            monkeypatch.setenv("DFLASH_ATTN_WIDE_MIN_CHUNK", "100000000")
+            monkeypatch.setenv("DFLASH_ATTN_TARGET_WGS", "2048")
+        g = GpuModel(w, shared["wt"], shared["wd"], n_ctx + 2 * Bk, blobs=shared["blobs"])
+        shared["blobs"] = g.blobs()
+        g.load_synthetic([])
+        assert int(g.host_lens[0]) == n_ctx
+        # the second run verifies the block the first one drafted (a near-tie in the draft would otherwise change the inputs)
+        out = g.step(outs[0]["block"][:, 1:] if outs else None, 0.0, None, 0)
+        print(f"131072 tokens, plan {plan}: accept_len {list(out['accept_len'])}, block {list(out['block'][0][:6])}", flush=True)
+        assert np.isfinite(out["logits_t"]).all() and np.isfinite(out["logits_d"]).all()
+        assert np.array_equal(out["tgt_argmax"], torch.from_numpy(out["logits_t"]).argmax(-1).numpy())
+        a = int(out["accept_len"][0])
+        assert 0 <= a <= Bk - 1
+        assert np.array_equal(out["kv_slots"], g.expected_slots(out["lens_before"], out["accept_len"]))
+        assert (out["out_tokens"][0, : a + 1] >= 0).all() and (out["out_tokens"][0, a + 1:] == -1).all()
+        assert out["out_tokens"][0, a] == out["tgt_argmax"][0, a]
+        assert all(out["block"][0, j + 1] == out["tgt_argmax"][0, j] for j in range(a))
+        # the block's own K rows landed behind the 131 072 cached ones (last page of the table row)
+        k_new, _ = g.read_kv(__import__("paper_2602_06036_amd").binding.DFLASH_POOL_TARGET, 35, 0, n_ctx, a + 1)
+        assert np.isfinite(k_new).all() and np.abs(k_new).max() > 0
+        outs.append(out)
+        g.e.close()
+        del g
+        torch.cuda.empty_cache()
+    a, b = outs
+    err_d = np.abs(a["logits_d"] - b["logits_d"]).max()
+    err_t = np.abs(a["logits_t"] - b["logits_t"]).max()
+    print(f"131072 tokens: the two plans differ by {err_d:.2e} (draft logits) and {err_t:.2e} (target logits)", flush=True)
+    assert err_d <= 5e-3 and err_t <= 5e-3
+    for j in range(Bk):
+        if a["tgt_argmax"][0, j] != b["tgt_argmax"][0, j]:
+            top = np.sort(a["logits_t"][0, j])[-2:]
+            assert top[1] - top[0] < MARGIN, f"row {j}: different target tokens without a near-tie"
